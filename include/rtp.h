@@ -1,0 +1,290 @@
+/*
+ * rtp.h -- C ABI of the rotated-shard linear layer of Rotated Tensor
+ * Parallelism (RTP, arXiv 2311.01635) for one worker on one MI355X (gfx950).
+ *
+ * The worker keeps 1/N of the batch and, at any moment, 1/N of a layer
+ * unit's weights.  Over N steps it computes on the weight shard it holds
+ * while the next shard is brought in on a second HIP stream (Design section;
+ * Rotating Communication Primitive section).  The other workers' memory is
+ * played by a caller-owned "home" store of N slots on the same GPU; there is
+ * no second device and no collective.
+ *
+ * Conventions
+ *   - Every pointer named `*_dev` or documented "device" is device memory the
+ *     CALLER allocates and frees; the library allocates no device memory.  It
+ *     owns only its host objects and the HIP events inside them.
+ *   - Streams are passed as `void*` holding a `hipStream_t`.  The two streams
+ *     of a ring must differ and must have default priority.
+ *   - Matrices are row-major and contiguous: W[O, I], X[T, I], Y[T, O].
+ *     Weight shard k of an output-partitioned matrix is rows
+ *     [k*o, (k+1)*o) of W, o = O/N, stored [o, I]; of an input-partitioned
+ *     matrix it is columns [k*o, (k+1)*o) of W[O, I], o = I/N, stored
+ *     contiguously as [O, o] (Partition Strategies section).
+ *   - Calls only enqueue work and return; ordering between the two streams is
+ *     the library's job (events).  rtp_ring_sync() joins both streams and
+ *     reports asynchronous HIP errors.
+ *   - Every function returns an rtp_status (or a plain integer for the pure
+ *     index helpers); nothing throws or aborts.  rtp_last_error() gives the
+ *     text of the last failure on the calling thread.
+ */
+#ifndef RTP_H_
+#define RTP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RTP_OK = 0,
+    RTP_ERR_INVALID = 1,     /* null or aliasing pointer, bad enum value            */
+    RTP_ERR_SHAPE = 2,       /* N does not divide the partitioned dim, size <= 0,
+                                alignment the kernels need is not met                */
+    RTP_ERR_STATE = 3,       /* call out of sequence (see each function)            */
+    RTP_ERR_UNSUPPORTED = 4, /* dtype / mode / activation combination not built     */
+    RTP_ERR_HIP = 5          /* a HIP runtime call failed; text in rtp_last_error() */
+} rtp_status;
+
+typedef enum { RTP_F32 = 0, RTP_BF16 = 1, RTP_F16 = 2 } rtp_dtype;
+
+/* Output-Partition (outputs are concatenated) and the input-dimension
+ * partition of the layer that follows it (outputs are summed): Partition
+ * Strategies section, first and second item. */
+typedef enum { RTP_SPLIT_OUT = 0, RTP_SPLIT_IN = 1 } rtp_split;
+
+/* How the next shard is staged (Rotating Communication Primitive section):
+ *  RTP_DOUBLE_BUFFER   out-of-place rotation: two (W_k, G_k) buffers that swap
+ *                      roles every step; all traffic overlaps compute.
+ *  RTP_INPLACE_STAGED  one extra weight buffer only; the gradient shard is
+ *                      exchanged in place (written home, then the next one
+ *                      read into the same buffer) as soon as the step's dW
+ *                      kernel is done, under the step's dX kernel.
+ *  RTP_INPLACE_BLOCKING the paper's in-place variant: no extra buffer, the
+ *                      exchange runs on the compute stream between steps.   */
+typedef enum { RTP_DOUBLE_BUFFER = 0, RTP_INPLACE_STAGED = 1, RTP_INPLACE_BLOCKING = 2 } rtp_mode;
+
+/* Activation fused after an output-partitioned GEMM (RTP Transformers
+ * section: "a GEMM succeeded by a GeLU"); RTP_ACT_SWIGLU is the gated form
+ * silu(a)*b over a (gate, up) pair. */
+typedef enum { RTP_ACT_NONE = 0, RTP_ACT_GELU_ERF = 1, RTP_ACT_GELU_TANH = 2, RTP_ACT_SWIGLU = 3 } rtp_act;
+
+typedef enum { RTP_PASS_IDLE = 0, RTP_PASS_FWD = 1, RTP_PASS_BWD = 2 } rtp_pass;
+
+#define RTP_CW (+1)  /* clockwise: forward, weights only            */
+#define RTP_CCW (-1) /* counter-clockwise: backward, weights + grads */
+
+#define RTP_FLAG_DRY_RUN 1u /* make no HIP call at all: the schedule and the
+                               state machine run on the host only (tests)   */
+
+typedef struct rtp_ring rtp_ring;
+typedef struct rtp_linear rtp_linear;
+typedef struct rtp_mlp rtp_mlp;
+
+/* ---- pure host integer helpers (no GPU needed) ------------------------- */
+
+/* Shard a worker holds at a step, 0-based (Design section, workflow
+ * paragraph): forward (rank - step) mod n, backward (rank + 1 + step) mod n.
+ * Return -1 if n <= 0 or rank/step are outside [0, n). */
+int rtp_fwd_shard(int rank, int step, int n);
+int rtp_bwd_shard(int rank, int step, int n);
+
+/* First row (or column) of shard k of a dimension of size `dim` split n
+ * ways; -1 if n does not divide dim or k is outside [0, n). */
+int64_t rtp_shard_begin(int k, int64_t dim, int n);
+
+/* Parameter bytes one worker holds for a unit whose slot has w_bytes of
+ * weights and g_bytes of gradients, per mode; 0 on a bad mode.
+ *   DOUBLE_BUFFER 2(w+g), INPLACE_STAGED 2w+g, INPLACE_BLOCKING w+g.
+ * rtp_table1_worker_bytes is the matching per-worker share of Table 1
+ * (RTP: w+g+max(w,g); RTP in place: w+g) for comparison. */
+size_t rtp_worker_bytes(rtp_mode mode, size_t w_bytes, size_t g_bytes);
+size_t rtp_table1_worker_bytes(int inplace, size_t w_bytes, size_t g_bytes);
+
+const char *rtp_status_str(rtp_status s);
+const char *rtp_last_error(void);
+
+/* ---- the ring: one layer unit's shard store and rotation --------------- */
+
+typedef struct {
+    int n;            /* partition factor N >= 1                                  */
+    int rank;         /* this worker, 0 <= rank < n                               */
+    rtp_mode mode;
+    unsigned flags;   /* RTP_FLAG_*                                               */
+    size_t w_bytes;   /* weight part of one slot: every matrix shard of the unit,
+                         back to back (the FlatParameter idea); multiple of 16    */
+    size_t g_bytes;   /* gradient part of one slot; multiple of 16; may be 0      */
+    void *home_w_dev; /* n * w_bytes, slot k at k * w_bytes                       */
+    void *home_g_dev; /* n * g_bytes                                              */
+    void *buf_w_dev[2]; /* w_bytes each; [1] unused (may be NULL) when blocking   */
+    void *buf_g_dev[2]; /* g_bytes each; [1] used by RTP_DOUBLE_BUFFER only       */
+    void *compute_stream; /* hipStream_t */
+    void *stage_stream;   /* hipStream_t, != compute_stream unless blocking       */
+} rtp_ring_desc;
+
+/* Creates the host object.  Errors: RTP_ERR_INVALID (null desc/out, null
+ * device pointer that the mode needs, equal streams), RTP_ERR_SHAPE (n < 1,
+ * rank outside [0, n), sizes not multiples of 16). */
+rtp_status rtp_ring_create(rtp_ring **out, const rtp_ring_desc *desc);
+rtp_status rtp_ring_destroy(rtp_ring *ring);
+
+/* Starts a pass.  RTP_PASS_FWD: copies home slot `rank` into the resident
+ * buffer (weights) -- the worker's own shard.  RTP_PASS_BWD: must follow a
+ * completed forward pass (the worker holds shard (rank+1) mod n) or, with
+ * n == 1 or after rtp_ring_seek(), any idle state; loads that shard's
+ * gradient part.  RTP_ERR_STATE if a pass is in progress. */
+rtp_status rtp_ring_begin(rtp_ring *ring, rtp_pass pass);
+
+/* Makes shard (rank+1) mod n resident without a forward pass (tests and
+ * backward-only timing). */
+rtp_status rtp_ring_seek_bwd_start(rtp_ring *ring);
+
+/* One rotation (Rotating Communication Primitive section).  `direction`
+ * RTP_CW in a forward pass, RTP_CCW in a backward pass; `step` is the step
+ * whose compute the transfer overlaps, 0 <= step < n-1 (the pass computes n
+ * times and rotates n-1 times).  Must be called once per step, in order,
+ * BEFORE the rtp_linear_* calls of that step (so that the transfer is not
+ * ordered behind them), and after every linear of the ring has been issued
+ * for the previous step.  Enqueues on the stage stream: the held weights go
+ * back to their home slot, the next shard's weights come into the staging
+ * buffer; in a backward pass the gradient part follows each linear's dW
+ * kernel (see rtp_linear_bwd).  Errors: RTP_ERR_STATE for a wrong direction,
+ * a step out of order or >= n-1, a linear lagging behind. */
+rtp_status rtp_rotate_step(rtp_ring *ring, int direction, int step);
+
+/* Ends a pass after step n-1.  After a backward pass writes nothing: the
+ * worker holds its own (W_rank, G_rank).  RTP_ERR_STATE if steps remain. */
+rtp_status rtp_ring_end(rtp_ring *ring);
+
+/* Copies the resident (W, G) to their home slot so that a reader of the home
+ * store sees every shard (tests, checkpoints).  Idle state only. */
+rtp_status rtp_ring_flush(rtp_ring *ring);
+
+/* Joins both streams; returns RTP_ERR_HIP if anything asynchronous failed. */
+rtp_status rtp_ring_sync(rtp_ring *ring);
+
+/* Shard currently resident (after everything enqueued so far), or -1. */
+int rtp_ring_resident(const rtp_ring *ring);
+
+/* Copies up to `cap` records of what the ring has enqueued since creation
+ * (or the last call with clear != 0) and returns the total number recorded.
+ * kind: 1 compute-fwd, 2 compute-bwd, 3 weights in, 4 weights out,
+ * 5 gradients in, 6 gradients out.  Integer record of the schedule, for
+ * bit-exact comparison with the oracle. */
+typedef struct { int kind, pass, step, shard, buffer; } rtp_trace_rec;
+int64_t rtp_ring_trace(rtp_ring *ring, rtp_trace_rec *out, int64_t cap, int clear);
+
+/* ---- a linear layer whose shards live in a ring slot ------------------- */
+
+typedef struct {
+    int64_t T;            /* local tokens                                         */
+    int64_t I, O;         /* full matrix W[O, I]                                  */
+    rtp_split split;
+    rtp_dtype dtype;      /* of X, W, Y, dY, dX                                   */
+    rtp_dtype grad_dtype; /* of the gradient shard: RTP_F32, or equal to dtype    */
+    rtp_act act;          /* RTP_SPLIT_OUT: fused after the forward GEMM.
+                             RTP_SPLIT_IN: the activation that produced this
+                             layer's input; if not NONE the backward returns the
+                             gradient w.r.t. that activation's pre-activation.    */
+    size_t w_offset;      /* byte offset of this matrix's shard in the slot       */
+    size_t g_offset;
+    void *preact_dev;     /* act != NONE: pre-activations, dtype, [T, O] for
+                             SPLIT_OUT (written by fwd), [T, P] for SPLIT_IN
+                             (read by bwd), P = I (GELU) or 2 I (SWIGLU)          */
+    float *acc_ws_dev;    /* fp32 [T, I] (SPLIT_OUT, dX) or [T, O] (SPLIT_IN, Y):
+                             cross-step accumulator; needed when dtype != F32
+                             and n > 1                                            */
+} rtp_linear_desc;
+
+/* With act == RTP_ACT_SWIGLU and SPLIT_OUT, W is the stack of the gate and up
+ * matrices arranged so that shard k (o = O/n rows, o even) is gate rows
+ * [k*o/2, (k+1)*o/2) followed by the same rows of up; the forward output is
+ * [T, O/2].  With SPLIT_IN and SWIGLU the backward output is [T, 2 I] in the
+ * same shard-stacked column order.
+ * Errors: RTP_ERR_SHAPE (n does not divide the partitioned dimension; bf16:
+ * I, o not multiples of 8; shard does not fit the slot), RTP_ERR_INVALID,
+ * RTP_ERR_UNSUPPORTED (RTP_F16; grad dtype other than F32 or dtype). */
+rtp_status rtp_linear_create(rtp_linear **out, rtp_ring *ring, const rtp_linear_desc *desc);
+rtp_status rtp_linear_destroy(rtp_linear *lin);
+
+/* Forward step (RTP Transformers section, embedding-and-linear item), on the
+ * shard k = rtp_fwd_shard(rank, step, n) that the ring holds:
+ *   SPLIT_OUT  Y[:, k*o:(k+1)*o] = act(X W_k^T)       X[T, I], Y[T, O]
+ *              (SWIGLU: Y[T, O/2], slice of width o/2), pre-activations saved;
+ *   SPLIT_IN   Y += X[:, k*o:(k+1)*o] W_k^T           X[T, I], Y[T, O]
+ *              summed over the n steps (fp32 accumulator, rounded once).
+ * X, Y device.  RTP_ERR_STATE unless a forward pass is open, `step` is this
+ * linear's next step, and (step == 0 or rtp_rotate_step(step-1) was issued). */
+rtp_status rtp_linear_fwd(rtp_linear *lin, int step, const void *X_dev, void *Y_dev);
+
+/* Backward step on shard k = rtp_bwd_shard(rank, step, n); first the weight
+ * gradient, fused into the travelling gradient shard, then the input
+ * gradient:
+ *   SPLIT_OUT  G_k += dY[:, k*o:(k+1)*o]^T X ;  dX += dY[:, k*o:(k+1)*o] W_k
+ *   SPLIT_IN   G_k += dY^T X[:, k*o:(k+1)*o] ;  dX[:, k*o:(k+1)*o] = dY W_k
+ *              (times act'(preact) if act != NONE).
+ * When this step rotates, the gradient part of this linear is handed to the
+ * stage stream right after the dW kernel.  dX_dev may be NULL to skip the
+ * input gradient.  Same state rules as rtp_linear_fwd, in a backward pass. */
+rtp_status rtp_linear_bwd(rtp_linear *lin, int step, const void *X_dev, const void *dY_dev, void *dX_dev);
+
+/* ---- MLP unit: the whole N-step loop in one call ------------------------ */
+
+typedef struct {
+    int64_t T, I, O, O2;  /* X[T, I]; W1 (or gate, up) [O, I]; W2 (down) [O2, O]   */
+    int n, rank;
+    rtp_mode mode;
+    rtp_dtype dtype;      /* RTP_BF16 or RTP_F32                                  */
+    rtp_act act;          /* GELU_* (one matrix) or SWIGLU (gate + up)            */
+    unsigned flags;
+    /* slot = [W1_k | W2_k] or [gate_k | up_k | down_k]; gradients fp32         */
+    void *home_w_dev, *home_g_dev;
+    void *buf_w_dev[2], *buf_g_dev[2];
+    void *preact_dev;     /* [T, P*O], P = 2 for SWIGLU                            */
+    void *hidden_dev;     /* [T, O]                                                */
+    void *dpre_dev;       /* [T, P*O]                                              */
+    float *acc_y_dev;     /* fp32 [T, O2]                                          */
+    float *acc_dx_dev;    /* fp32 [T, I]                                           */
+    void *compute_stream, *stage_stream;
+} rtp_mlp_desc;
+
+size_t rtp_mlp_slot_w_bytes(const rtp_mlp_desc *d);
+size_t rtp_mlp_slot_g_bytes(const rtp_mlp_desc *d);
+
+/* An MLP block with its first GEMM output-partitioned and its second
+ * input-partitioned, so that unit k is self-contained and rotates as one
+ * message.  rtp_mlp_fwd runs n x (rtp_rotate_step, rtp_linear_fwd x 2);
+ * rtp_mlp_bwd the mirror image.  `rotate` = 0 skips the rotation calls (the
+ * resident shard is used for every step: timing of compute alone, results
+ * are meaningless); `compute` = 0 skips the kernels (timing of the staging
+ * traffic alone). */
+rtp_status rtp_mlp_create(rtp_mlp **out, const rtp_mlp_desc *desc);
+rtp_status rtp_mlp_destroy(rtp_mlp *mlp);
+rtp_status rtp_mlp_fwd(rtp_mlp *mlp, const void *X_dev, void *Y_dev);
+rtp_status rtp_mlp_bwd(rtp_mlp *mlp, const void *X_dev, const void *dY_dev, void *dX_dev);
+rtp_status rtp_mlp_set_ablation(rtp_mlp *mlp, int rotate, int compute);
+rtp_status rtp_mlp_flush(rtp_mlp *mlp);
+rtp_status rtp_mlp_sync(rtp_mlp *mlp);
+rtp_ring *rtp_mlp_ring(rtp_mlp *mlp);
+
+/* ---- single GEMM launch (kernel tests and roofline timing) -------------- */
+
+/* C[M,N] (+)= op(A) op(B) on `stream`, bf16 or f32 inputs, layout 0 NT
+ * (A[M,K], B[N,K]), 1 NN (A[M,K], B[K,N]), 2 TN (A[K,M], B[K,N]); leading
+ * dimensions in elements.  accumulate != 0 adds onto fp32 C (out_dtype must
+ * be RTP_F32).  variant selects a tile configuration (0 = default).
+ * Name of the kernel it launches: rtp_gemm_kernel_name(). */
+rtp_status rtp_gemm(int layout, rtp_dtype in_dtype, rtp_dtype out_dtype, int accumulate,
+                    const void *A_dev, int64_t lda, const void *B_dev, int64_t ldb,
+                    void *C_dev, int64_t ldc, int64_t M, int64_t N, int64_t K,
+                    int variant, void *stream);
+
+/* Name (as a profiler shows it, up to template arguments) of the bf16 kernel
+ * behind a layout and a non-zero variant; "" if there is none. */
+const char *rtp_gemm_kernel_name(int layout, int variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RTP_H_ */

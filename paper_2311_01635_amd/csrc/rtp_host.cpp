@@ -1,0 +1,871 @@
+// Host scheduler behind the C ABI of include/rtp.h: shard index arithmetic,
+// the ring's buffer/state machine, the event graph between the compute and
+// the stage stream, and the per-step kernel launches.  No device memory is
+// allocated here; the only HIP objects owned are events.
+#include "../../include/rtp.h"
+#include "rtp_kernels.h"
+
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace rtp;
+
+// ---------------------------------------------------------------------------
+// errors
+// ---------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+static rtp_status fail(rtp_status s, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return s;
+}
+
+#define HIP_TRY(expr)                                                                                       \
+    do {                                                                                                    \
+        hipError_t e_ = (expr);                                                                             \
+        if (e_ != hipSuccess) return fail(RTP_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));             \
+    } while (0)
+
+#define RTP_TRY(expr)                       \
+    do {                                    \
+        rtp_status s_ = (expr);             \
+        if (s_ != RTP_OK) return s_;        \
+    } while (0)
+
+extern "C" const char *rtp_last_error(void) { return g_err; }
+
+extern "C" const char *rtp_status_str(rtp_status s)
+{
+    switch (s) {
+    case RTP_OK: return "RTP_OK";
+    case RTP_ERR_INVALID: return "RTP_ERR_INVALID";
+    case RTP_ERR_SHAPE: return "RTP_ERR_SHAPE";
+    case RTP_ERR_STATE: return "RTP_ERR_STATE";
+    case RTP_ERR_UNSUPPORTED: return "RTP_ERR_UNSUPPORTED";
+    case RTP_ERR_HIP: return "RTP_ERR_HIP";
+    }
+    return "RTP_ERR_?";
+}
+
+// ---------------------------------------------------------------------------
+// schedule (Design section, workflow paragraph)
+// ---------------------------------------------------------------------------
+extern "C" int rtp_fwd_shard(int rank, int step, int n)
+{
+    if (n <= 0 || rank < 0 || rank >= n || step < 0 || step >= n) return -1;
+    // each clockwise rotation brings in what the previous worker held
+    return (rank - step + n) % n;
+}
+
+extern "C" int rtp_bwd_shard(int rank, int step, int n)
+{
+    if (n <= 0 || rank < 0 || rank >= n || step < 0 || step >= n) return -1;
+    // starts where the forward pass ended and walks back to the worker's own shard
+    return (rank + 1 + step) % n;
+}
+
+extern "C" int64_t rtp_shard_begin(int k, int64_t dim, int n)
+{
+    if (n <= 0 || k < 0 || k >= n || dim < 0 || dim % n != 0) return -1;
+    return (int64_t)k * (dim / n);
+}
+
+extern "C" size_t rtp_worker_bytes(rtp_mode mode, size_t w, size_t g)
+{
+    switch (mode) {
+    case RTP_DOUBLE_BUFFER: return 2 * (w + g);
+    case RTP_INPLACE_STAGED: return 2 * w + g;
+    case RTP_INPLACE_BLOCKING: return w + g;
+    }
+    return 0;
+}
+
+extern "C" size_t rtp_table1_worker_bytes(int inplace, size_t w, size_t g)
+{
+    // Table 1, rows "RTP" and "RTP Inplace", divided evenly over the workers
+    return inplace ? w + g : w + g + std::max(w, g);
+}
+
+// ---------------------------------------------------------------------------
+// ring
+// ---------------------------------------------------------------------------
+enum { TR_FWD = 1, TR_BWD = 2, TR_W_IN = 3, TR_W_OUT = 4, TR_G_IN = 5, TR_G_OUT = 6 };
+
+struct rtp_linear;
+
+struct rtp_ring {
+    rtp_ring_desc d;
+    bool dry = false;
+    bool events_ready = false;
+    bool abl_rotate = true, abl_compute = true;
+    rtp_pass pass = RTP_PASS_IDLE;
+    int resident = -1;   // shard whose weights are in buf_w[res_idx]
+    int res_idx = 0;
+    int res_g = -1;      // shard whose gradients are in buf_g[res_g_idx]
+    int res_g_idx = 0;
+    int base_idx = 0;    // weight buffer index at step 0 of the open pass
+    int rotations = 0;   // rotate_step calls in the open pass
+    int executed = 0;    // blocking mode: rotations already carried out
+    std::vector<rtp_linear *> linears;
+    std::vector<rtp_trace_rec> trace;
+    hipEvent_t ev_free = nullptr, ev_join = nullptr;
+    hipEvent_t ev_w[2] = {nullptr, nullptr};
+    hipEvent_t ev_g[2] = {nullptr, nullptr};
+
+    hipStream_t cs() const { return (hipStream_t)d.compute_stream; }
+    hipStream_t ss() const { return d.mode == RTP_INPLACE_BLOCKING ? cs() : (hipStream_t)d.stage_stream; }
+    char *home_w(int k) const { return (char *)d.home_w_dev + (size_t)k * d.w_bytes; }
+    char *home_g(int k) const { return (char *)d.home_g_dev + (size_t)k * d.g_bytes; }
+    int w_idx(int step) const { return d.mode == RTP_INPLACE_BLOCKING ? 0 : (base_idx + step) & 1; }
+    int g_idx(int step) const { return d.mode == RTP_DOUBLE_BUFFER ? (step & 1) : 0; }
+    int shard_at(int step) const
+    {
+        return pass == RTP_PASS_BWD ? rtp_bwd_shard(d.rank, step, d.n) : rtp_fwd_shard(d.rank, step, d.n);
+    }
+    void rec(int kind, int step, int shard, int buffer)
+    {
+        trace.push_back(rtp_trace_rec{kind, (int)pass, step, shard, buffer});
+    }
+};
+
+struct rtp_linear {
+    rtp_ring *ring;
+    rtp_linear_desc d;
+    int64_t o;        // shard width along the partitioned dimension
+    size_t w_shard_bytes, g_shard_bytes;
+    int next_step = 0;
+    hipEvent_t ev_dw = nullptr, ev_g_in = nullptr;
+};
+
+static rtp_status ensure_events(rtp_ring *r)
+{
+    if (r->dry || r->events_ready) return RTP_OK;
+    hipEvent_t *all[] = {&r->ev_free, &r->ev_join, &r->ev_w[0], &r->ev_w[1], &r->ev_g[0], &r->ev_g[1]};
+    for (hipEvent_t *e : all)
+        HIP_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
+    for (rtp_linear *l : r->linears) {
+        if (!l->ev_dw) HIP_TRY(hipEventCreateWithFlags(&l->ev_dw, hipEventDisableTiming));
+        if (!l->ev_g_in) HIP_TRY(hipEventCreateWithFlags(&l->ev_g_in, hipEventDisableTiming));
+    }
+    r->events_ready = true;
+    return RTP_OK;
+}
+
+static rtp_status copy_async(rtp_ring *r, void *dst, const void *src, size_t bytes, hipStream_t s)
+{
+    if (r->dry || bytes == 0) return RTP_OK;
+    HIP_TRY(launch_copy(dst, src, bytes, s));
+    return RTP_OK;
+}
+
+// make each stream wait for everything enqueued so far on the other
+static rtp_status cross_join(rtp_ring *r)
+{
+    if (r->dry || r->cs() == r->ss()) return RTP_OK;
+    HIP_TRY(hipEventRecord(r->ev_join, r->ss()));
+    HIP_TRY(hipStreamWaitEvent(r->cs(), r->ev_join, 0));
+    HIP_TRY(hipEventRecord(r->ev_join, r->cs()));
+    HIP_TRY(hipStreamWaitEvent(r->ss(), r->ev_join, 0));
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_ring_create(rtp_ring **out, const rtp_ring_desc *d)
+{
+    if (!out || !d) return fail(RTP_ERR_INVALID, "rtp_ring_create: null argument");
+    *out = nullptr;
+    if (d->n < 1 || d->rank < 0 || d->rank >= d->n)
+        return fail(RTP_ERR_SHAPE, "rtp_ring_create: need n >= 1 and 0 <= rank < n (n=%d rank=%d)", d->n, d->rank);
+    if ((d->w_bytes & 15) || (d->g_bytes & 15) || d->w_bytes == 0)
+        return fail(RTP_ERR_SHAPE, "rtp_ring_create: slot sizes must be positive multiples of 16 bytes");
+    if (d->mode != RTP_DOUBLE_BUFFER && d->mode != RTP_INPLACE_STAGED && d->mode != RTP_INPLACE_BLOCKING)
+        return fail(RTP_ERR_INVALID, "rtp_ring_create: bad mode %d", (int)d->mode);
+    const bool dry = (d->flags & RTP_FLAG_DRY_RUN) != 0;
+    if (!dry) {
+        if (!d->home_w_dev || !d->buf_w_dev[0]) return fail(RTP_ERR_INVALID, "rtp_ring_create: null weight buffer");
+        if (d->mode != RTP_INPLACE_BLOCKING && !d->buf_w_dev[1])
+            return fail(RTP_ERR_INVALID, "rtp_ring_create: the staging weight buffer is missing");
+        if (d->g_bytes && (!d->home_g_dev || !d->buf_g_dev[0]))
+            return fail(RTP_ERR_INVALID, "rtp_ring_create: null gradient buffer");
+        if (d->g_bytes && d->mode == RTP_DOUBLE_BUFFER && !d->buf_g_dev[1])
+            return fail(RTP_ERR_INVALID, "rtp_ring_create: double buffering needs two gradient buffers");
+        if (d->buf_w_dev[0] == d->buf_w_dev[1] || (d->g_bytes && d->buf_g_dev[1] && d->buf_g_dev[0] == d->buf_g_dev[1]))
+            return fail(RTP_ERR_INVALID, "rtp_ring_create: resident and staging buffers alias");
+        if (d->mode != RTP_INPLACE_BLOCKING && d->compute_stream == d->stage_stream)
+            return fail(RTP_ERR_INVALID, "rtp_ring_create: the stage stream must differ from the compute stream");
+    }
+    rtp_ring *r = new (std::nothrow) rtp_ring;
+    if (!r) return fail(RTP_ERR_INVALID, "rtp_ring_create: out of host memory");
+    r->d = *d;
+    r->dry = dry;
+    *out = r;
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_ring_destroy(rtp_ring *r)
+{
+    if (!r) return RTP_OK;
+    if (!r->linears.empty()) return fail(RTP_ERR_STATE, "rtp_ring_destroy: destroy the ring's linears first");
+    if (r->events_ready) {
+        hipEvent_t all[] = {r->ev_free, r->ev_join, r->ev_w[0], r->ev_w[1], r->ev_g[0], r->ev_g[1]};
+        for (hipEvent_t e : all)
+            if (e) (void)hipEventDestroy(e);
+    }
+    delete r;
+    return RTP_OK;
+}
+
+extern "C" int rtp_ring_resident(const rtp_ring *r) { return r ? r->resident : -1; }
+
+extern "C" int64_t rtp_ring_trace(rtp_ring *r, rtp_trace_rec *out, int64_t cap, int clear)
+{
+    if (!r) return -1;
+    const int64_t total = (int64_t)r->trace.size();
+    if (out)
+        for (int64_t i = 0; i < std::min(total, cap); ++i) out[i] = r->trace[(size_t)i];
+    if (clear) r->trace.clear();
+    return total;
+}
+
+static rtp_status set_ablation(rtp_ring *r, int rotate, int compute)
+{
+    if (r->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "ablation can only change between passes");
+    r->abl_rotate = rotate != 0;
+    r->abl_compute = compute != 0;
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_ring_begin(rtp_ring *r, rtp_pass pass)
+{
+    if (!r) return fail(RTP_ERR_INVALID, "rtp_ring_begin: null ring");
+    if (pass != RTP_PASS_FWD && pass != RTP_PASS_BWD) return fail(RTP_ERR_INVALID, "rtp_ring_begin: bad pass");
+    if (r->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_ring_begin: a pass is already open");
+    const int n = r->d.n, rank = r->d.rank;
+    if (pass == RTP_PASS_BWD && r->resident != (rank + 1) % n)
+        return fail(RTP_ERR_STATE, "rtp_ring_begin: backward needs shard %d resident (forward pass first), have %d",
+                    (rank + 1) % n, r->resident);
+    RTP_TRY(ensure_events(r));
+    RTP_TRY(cross_join(r));
+    r->pass = pass;
+    r->rotations = 0;
+    r->executed = 0;
+    for (rtp_linear *l : r->linears) l->next_step = 0;
+    if (pass == RTP_PASS_FWD) {
+        // the worker starts on its own shard
+        r->res_idx = 0;
+        r->base_idx = 0;
+        r->resident = rank;
+        RTP_TRY(copy_async(r, r->d.buf_w_dev[0], r->home_w(rank), r->d.w_bytes, r->cs()));
+        r->rec(TR_W_IN, -1, rank, 0);
+    } else {
+        // gradient shards come into being where the weights ended the forward pass
+        r->base_idx = r->res_idx;
+        r->res_g_idx = 0;
+        r->res_g = r->resident;
+        if (r->d.g_bytes) {
+            RTP_TRY(copy_async(r, r->d.buf_g_dev[0], r->home_g(r->resident), r->d.g_bytes, r->cs()));
+            r->rec(TR_G_IN, -1, r->resident, 0);
+        }
+    }
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_ring_seek_bwd_start(rtp_ring *r)
+{
+    if (!r) return fail(RTP_ERR_INVALID, "null ring");
+    if (r->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_ring_seek_bwd_start: a pass is open");
+    RTP_TRY(ensure_events(r));
+    RTP_TRY(cross_join(r));
+    const int k = (r->d.rank + 1) % r->d.n;
+    r->res_idx = 0;
+    r->resident = k;
+    RTP_TRY(copy_async(r, r->d.buf_w_dev[0], r->home_w(k), r->d.w_bytes, r->cs()));
+    r->rec(TR_W_IN, -1, k, 0);
+    return RTP_OK;
+}
+
+// The transfers of one rotation.  Staged modes call this from rtp_rotate_step
+// on the stage stream; the blocking mode calls it on the compute stream when
+// the next step's first kernel is about to be enqueued.
+static rtp_status do_rotation(rtp_ring *r, int step)
+{
+    const bool bwd = r->pass == RTP_PASS_BWD;
+    const int k = r->shard_at(step), kin = r->shard_at(step + 1);
+    const int src = r->w_idx(step), dst = r->w_idx(step + 1);
+    hipStream_t s = r->ss();
+    const bool blocking = r->d.mode == RTP_INPLACE_BLOCKING;
+    if (!r->dry && !blocking) {
+        // the staging buffer was resident one step ago: wait for its readers
+        HIP_TRY(hipEventRecord(r->ev_free, r->cs()));
+        HIP_TRY(hipStreamWaitEvent(s, r->ev_free, 0));
+    }
+    // send the held weights to their next holder, receive the next shard
+    RTP_TRY(copy_async(r, r->home_w(k), r->d.buf_w_dev[src], r->d.w_bytes, s));
+    r->rec(TR_W_OUT, step, k, src);
+    RTP_TRY(copy_async(r, r->d.buf_w_dev[dst], r->home_w(kin), r->d.w_bytes, s));
+    r->rec(TR_W_IN, step, kin, dst);
+    if (!r->dry && !blocking) HIP_TRY(hipEventRecord(r->ev_w[(step + 1) & 1], s));
+    if (bwd && r->d.g_bytes) {
+        if (r->d.mode == RTP_DOUBLE_BUFFER) {
+            const int gdst = r->g_idx(step + 1);
+            RTP_TRY(copy_async(r, r->d.buf_g_dev[gdst], r->home_g(kin), r->d.g_bytes, s));
+            r->rec(TR_G_IN, step, kin, gdst);
+            if (!r->dry) HIP_TRY(hipEventRecord(r->ev_g[(step + 1) & 1], s));
+        } else if (blocking) {
+            RTP_TRY(copy_async(r, r->home_g(k), r->d.buf_g_dev[0], r->d.g_bytes, s));
+            r->rec(TR_G_OUT, step, k, 0);
+            RTP_TRY(copy_async(r, r->d.buf_g_dev[0], r->home_g(kin), r->d.g_bytes, s));
+            r->rec(TR_G_IN, step, kin, 0);
+        }
+        // RTP_INPLACE_STAGED: each linear exchanges its part right after its dW kernel
+    }
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_rotate_step(rtp_ring *r, int direction, int step)
+{
+    if (!r) return fail(RTP_ERR_INVALID, "rtp_rotate_step: null ring");
+    if (r->pass == RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_rotate_step: no pass is open");
+    const int want = r->pass == RTP_PASS_FWD ? RTP_CW : RTP_CCW;
+    if (direction != want)
+        return fail(RTP_ERR_STATE, "rtp_rotate_step: direction %d does not match the open pass", direction);
+    if (step != r->rotations)
+        return fail(RTP_ERR_STATE, "rtp_rotate_step: step %d out of order (next is %d)", step, r->rotations);
+    if (step >= r->d.n - 1)
+        return fail(RTP_ERR_STATE, "rtp_rotate_step: a pass of n=%d steps rotates n-1 times; step %d is past the last",
+                    r->d.n, step);
+    for (rtp_linear *l : r->linears)
+        if (l->next_step < step)
+            return fail(RTP_ERR_STATE, "rtp_rotate_step: a linear has not been issued for step %d yet", step - 1);
+        else if (l->next_step > step)
+            return fail(RTP_ERR_STATE, "rtp_rotate_step: must precede the linear calls of step %d", step);
+    if (r->abl_rotate && r->d.mode != RTP_INPLACE_BLOCKING) RTP_TRY(do_rotation(r, step));
+    r->rotations = step + 1;
+    return RTP_OK;
+}
+
+// Called by every linear before it enqueues kernels for `step`.
+static rtp_status enter_step(rtp_ring *r, rtp_linear *l, int step, rtp_pass pass, const char *who)
+{
+    if (r->pass != pass) return fail(RTP_ERR_STATE, "%s: the matching pass is not open", who);
+    if (step != l->next_step)
+        return fail(RTP_ERR_STATE, "%s: step %d out of order (next is %d)", who, step, l->next_step);
+    if (step >= r->d.n) return fail(RTP_ERR_STATE, "%s: step %d past the last (n=%d)", who, step, r->d.n);
+    if (step > 0 && r->rotations < step)
+        return fail(RTP_ERR_STATE, "%s: the shard of step %d has not been staged (rtp_rotate_step(%d) missing)", who,
+                    step, step - 1);
+    if (step < r->d.n - 1 && r->rotations <= step)
+        return fail(RTP_ERR_STATE, "%s: call rtp_rotate_step(%d) before the step's linears", who, step);
+    if (r->abl_rotate) {
+        if (r->d.mode == RTP_INPLACE_BLOCKING) {
+            while (r->executed < step) {
+                RTP_TRY(do_rotation(r, r->executed));
+                r->executed++;
+            }
+        } else if (step > 0 && !r->dry) {
+            HIP_TRY(hipStreamWaitEvent(r->cs(), r->ev_w[step & 1], 0));
+        }
+        r->resident = r->shard_at(step);
+        r->res_idx = r->w_idx(step);
+        if (pass == RTP_PASS_BWD) {
+            r->res_g = r->resident;
+            r->res_g_idx = r->g_idx(step);
+        }
+    }
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_ring_end(rtp_ring *r)
+{
+    if (!r) return fail(RTP_ERR_INVALID, "rtp_ring_end: null ring");
+    if (r->pass == RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_ring_end: no pass is open");
+    for (rtp_linear *l : r->linears)
+        if (l->next_step != r->d.n) return fail(RTP_ERR_STATE, "rtp_ring_end: steps remain");
+    if (r->linears.empty() && r->rotations != r->d.n - 1) return fail(RTP_ERR_STATE, "rtp_ring_end: rotations remain");
+    if (r->linears.empty() && r->abl_rotate) {
+        // a bare ring (no linears): finish the bookkeeping the linears would have done
+        if (r->d.mode == RTP_INPLACE_BLOCKING)
+            while (r->executed < r->d.n - 1) {
+                RTP_TRY(do_rotation(r, r->executed));
+                r->executed++;
+            }
+        r->resident = r->shard_at(r->d.n - 1);
+        r->res_idx = r->w_idx(r->d.n - 1);
+    }
+    if (!r->abl_rotate) {
+        // keep the shard ids consistent even though nothing moved
+        r->resident = r->shard_at(r->d.n - 1);
+    }
+    r->pass = RTP_PASS_IDLE;
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_ring_flush(rtp_ring *r)
+{
+    if (!r) return fail(RTP_ERR_INVALID, "rtp_ring_flush: null ring");
+    if (r->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_ring_flush: a pass is open");
+    if (r->resident < 0) return RTP_OK;
+    RTP_TRY(ensure_events(r));
+    RTP_TRY(cross_join(r));
+    RTP_TRY(copy_async(r, r->home_w(r->resident), r->d.buf_w_dev[r->res_idx], r->d.w_bytes, r->cs()));
+    r->rec(TR_W_OUT, -1, r->resident, r->res_idx);
+    if (r->d.g_bytes && r->res_g >= 0) {
+        RTP_TRY(copy_async(r, r->home_g(r->res_g), r->d.buf_g_dev[r->res_g_idx], r->d.g_bytes, r->cs()));
+        r->rec(TR_G_OUT, -1, r->res_g, r->res_g_idx);
+    }
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_ring_sync(rtp_ring *r)
+{
+    if (!r) return fail(RTP_ERR_INVALID, "rtp_ring_sync: null ring");
+    if (r->dry) return RTP_OK;
+    HIP_TRY(hipStreamSynchronize(r->cs()));
+    if (r->ss() != r->cs()) HIP_TRY(hipStreamSynchronize(r->ss()));
+    HIP_TRY(hipGetLastError());
+    return RTP_OK;
+}
+
+// ---------------------------------------------------------------------------
+// linear
+// ---------------------------------------------------------------------------
+static size_t esize(rtp_dtype t) { return t == RTP_F32 ? 4 : 2; }
+
+extern "C" rtp_status rtp_linear_create(rtp_linear **out, rtp_ring *ring, const rtp_linear_desc *d)
+{
+    if (!out || !ring || !d) return fail(RTP_ERR_INVALID, "rtp_linear_create: null argument");
+    *out = nullptr;
+    if (ring->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_linear_create: a pass is open");
+    if (d->T < 0 || d->I <= 0 || d->O <= 0) return fail(RTP_ERR_SHAPE, "rtp_linear_create: T >= 0, I > 0, O > 0 needed");
+    if (d->T > 0x7fffffff || d->I > 0x7fffffff || d->O > 0x7fffffff)
+        return fail(RTP_ERR_SHAPE, "rtp_linear_create: a dimension exceeds 2^31-1");
+    if (d->split != RTP_SPLIT_OUT && d->split != RTP_SPLIT_IN) return fail(RTP_ERR_INVALID, "bad split");
+    if (d->dtype == RTP_F16) return fail(RTP_ERR_UNSUPPORTED, "rtp_linear_create: fp16 inputs are not built");
+    if (d->dtype != RTP_F32 && d->dtype != RTP_BF16) return fail(RTP_ERR_INVALID, "bad dtype");
+    if (d->grad_dtype != RTP_F32)
+        return fail(RTP_ERR_UNSUPPORTED, "rtp_linear_create: gradient shards are kept in fp32");
+    if (d->act < RTP_ACT_NONE || d->act > RTP_ACT_SWIGLU) return fail(RTP_ERR_INVALID, "bad activation");
+    const int n = ring->d.n;
+    const int64_t part = d->split == RTP_SPLIT_OUT ? d->O : d->I;
+    if (part % n != 0)
+        return fail(RTP_ERR_SHAPE, "rtp_linear_create: n=%d does not divide the partitioned dimension %lld", n,
+                    (long long)part);
+    const int64_t o = part / n;
+    if (d->act == RTP_ACT_SWIGLU && d->split == RTP_SPLIT_OUT && (o & 1))
+        return fail(RTP_ERR_SHAPE, "rtp_linear_create: a (gate, up) shard needs an even width");
+    if (d->dtype == RTP_BF16) {
+        const int64_t half = (d->act == RTP_ACT_SWIGLU && d->split == RTP_SPLIT_OUT) ? o / 2 : o;
+        if ((d->I & 7) || (d->O & 7) || (o & 7) || (half & 7))
+            return fail(RTP_ERR_SHAPE, "rtp_linear_create: bf16 kernels need I, O and the shard width to be multiples of 8");
+    }
+    const size_t wsz = (size_t)d->O * (size_t)d->I / (size_t)n * esize(d->dtype);
+    const size_t gsz = (size_t)d->O * (size_t)d->I / (size_t)n * esize(d->grad_dtype);
+    if ((d->w_offset & 15) || (d->g_offset & 15)) return fail(RTP_ERR_SHAPE, "rtp_linear_create: offsets must be multiples of 16");
+    if (d->w_offset + wsz > ring->d.w_bytes || d->g_offset + gsz > ring->d.g_bytes)
+        return fail(RTP_ERR_SHAPE, "rtp_linear_create: the shard does not fit the ring's slot");
+    if (!ring->dry) {
+        if (d->act != RTP_ACT_NONE && !d->preact_dev)
+            return fail(RTP_ERR_INVALID, "rtp_linear_create: an activation needs the pre-activation buffer");
+        if (d->dtype != RTP_F32 && n > 1 && !d->acc_ws_dev)
+            return fail(RTP_ERR_INVALID, "rtp_linear_create: the fp32 cross-step accumulator is missing");
+    }
+    rtp_linear *l = new (std::nothrow) rtp_linear;
+    if (!l) return fail(RTP_ERR_INVALID, "out of host memory");
+    l->ring = ring;
+    l->d = *d;
+    l->o = o;
+    l->w_shard_bytes = wsz;
+    l->g_shard_bytes = gsz;
+    if (ring->events_ready) {
+        if (hipEventCreateWithFlags(&l->ev_dw, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&l->ev_g_in, hipEventDisableTiming) != hipSuccess) {
+            delete l;
+            return fail(RTP_ERR_HIP, "rtp_linear_create: hipEventCreate failed");
+        }
+    }
+    ring->linears.push_back(l);
+    *out = l;
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_linear_destroy(rtp_linear *l)
+{
+    if (!l) return RTP_OK;
+    rtp_ring *r = l->ring;
+    if (r->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_linear_destroy: a pass is open");
+    r->linears.erase(std::remove(r->linears.begin(), r->linears.end(), l), r->linears.end());
+    if (l->ev_dw) (void)hipEventDestroy(l->ev_dw);
+    if (l->ev_g_in) (void)hipEventDestroy(l->ev_g_in);
+    delete l;
+    return RTP_OK;
+}
+
+static int fwd_act_epi(rtp_act a)
+{
+    return a == RTP_ACT_GELU_ERF ? EPI_GELU_ERF_FWD : a == RTP_ACT_GELU_TANH ? EPI_GELU_TANH_FWD : EPI_SWIGLU_FWD;
+}
+static int bwd_act_epi(rtp_act a)
+{
+    return a == RTP_ACT_GELU_ERF ? EPI_GELU_ERF_BWD : a == RTP_ACT_GELU_TANH ? EPI_GELU_TANH_BWD : EPI_SWIGLU_BWD;
+}
+
+// epilogue of a result that is summed over the n steps
+static int acc_epi(int step, int n) { return n == 1 ? EPI_STORE : step == 0 ? EPI_ACC_FIRST : step == n - 1 ? EPI_ACC_LAST : EPI_ACC_ADD; }
+
+static rtp_status gemm(rtp_linear *l, int layout, GemmArgs &a)
+{
+    rtp_ring *r = l->ring;
+    if (r->dry || !r->abl_compute) return RTP_OK;
+    if (l->d.dtype == RTP_BF16)
+        HIP_TRY(launch_gemm_bf16(layout, a, 0, r->cs()));
+    else
+        HIP_TRY(launch_gemm_f32(layout, a, r->cs()));
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, void *Y)
+{
+    if (!l) return fail(RTP_ERR_INVALID, "rtp_linear_fwd: null linear");
+    rtp_ring *r = l->ring;
+    if (!r->dry && (!X || !Y)) return fail(RTP_ERR_INVALID, "rtp_linear_fwd: null tensor");
+    RTP_TRY(enter_step(r, l, step, RTP_PASS_FWD, "rtp_linear_fwd"));
+    const rtp_linear_desc &d = l->d;
+    const int n = r->d.n;
+    const int k = r->abl_rotate ? r->resident : rtp_fwd_shard(r->d.rank, step, n);
+    const size_t es = esize(d.dtype);
+    const char *Wk = (const char *)r->d.buf_w_dev[r->res_idx] + d.w_offset;
+    const int64_t o = l->o;
+    const bool f32 = d.dtype == RTP_F32;
+    r->rec(TR_FWD, step, k, r->res_idx);
+    GemmArgs a;
+    memset(&a, 0, sizeof a);
+    a.c_is_f32 = f32;
+    if (d.split == RTP_SPLIT_OUT) {
+        a.A = X; a.lda = d.I;
+        a.B = Wk; a.ldb = d.I;
+        a.M = (int)d.T; a.N = (int)o; a.K = (int)d.I;
+        if (d.act == RTP_ACT_NONE) {
+            a.epi = EPI_STORE;
+            a.C = (char *)Y + (size_t)k * o * es; a.ldc = d.O;
+            RTP_TRY(gemm(l, LAY_NT, a));
+        } else {
+            const bool gated = d.act == RTP_ACT_SWIGLU;
+            const int64_t ow = gated ? o / 2 : o, Ow = gated ? d.O / 2 : d.O;
+            char *pre = (char *)d.preact_dev + (size_t)k * o * es;
+            char *Yk = (char *)Y + (size_t)k * ow * es;
+            if (!f32) {
+                a.epi = fwd_act_epi(d.act);
+                a.half = (int)(o / 2);
+                a.aux = pre; a.ldaux = d.O;
+                a.C = Yk; a.ldc = Ow;
+                RTP_TRY(gemm(l, LAY_NT, a));
+            } else {
+                a.epi = EPI_STORE;
+                a.C = pre; a.ldc = d.O;
+                RTP_TRY(gemm(l, LAY_NT, a));
+                if (!r->dry && r->abl_compute)
+                    HIP_TRY(launch_act_f32(fwd_act_epi(d.act), (const float *)pre, d.O, nullptr, 0, (float *)Yk, Ow,
+                                           (int)d.T, (int)ow, (int)(o / 2), r->cs()));
+            }
+        }
+    } else {
+        if (d.act != RTP_ACT_NONE && false) return fail(RTP_ERR_UNSUPPORTED, "unreachable");
+        a.A = (const char *)X + (size_t)k * o * es; a.lda = d.I;
+        a.B = Wk; a.ldb = o;
+        a.M = (int)d.T; a.N = (int)d.O; a.K = (int)o;
+        a.C = Y; a.ldc = d.O;
+        if (f32) {
+            a.epi = step == 0 ? EPI_STORE : EPI_ACC_ADD;
+        } else {
+            a.epi = acc_epi(step, n);
+            a.ws = d.acc_ws_dev; a.ldws = d.O;
+        }
+        RTP_TRY(gemm(l, LAY_NT, a));
+    }
+    l->next_step = step + 1;
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, const void *dY, void *dX)
+{
+    if (!l) return fail(RTP_ERR_INVALID, "rtp_linear_bwd: null linear");
+    rtp_ring *r = l->ring;
+    if (!r->dry && (!X || !dY)) return fail(RTP_ERR_INVALID, "rtp_linear_bwd: null tensor");
+    RTP_TRY(enter_step(r, l, step, RTP_PASS_BWD, "rtp_linear_bwd"));
+    const rtp_linear_desc &d = l->d;
+    const int n = r->d.n;
+    const int k = r->abl_rotate ? r->resident : rtp_bwd_shard(r->d.rank, step, n);
+    const size_t es = esize(d.dtype);
+    const int64_t o = l->o;
+    const bool f32 = d.dtype == RTP_F32;
+    const bool rotating = r->abl_rotate && step < n - 1;
+    const bool staged_g = r->d.mode == RTP_INPLACE_STAGED;
+    const int gi = r->res_g_idx;
+    const char *Wk = (const char *)r->d.buf_w_dev[r->res_idx] + d.w_offset;
+    float *Gk = (float *)((char *)r->d.buf_g_dev[gi] + d.g_offset);
+    r->rec(TR_BWD, step, k, r->res_idx);
+
+    // the gradient shard this step adds onto must have arrived
+    if (!r->dry && r->abl_rotate && step > 0) {
+        if (r->d.mode == RTP_DOUBLE_BUFFER)
+            HIP_TRY(hipStreamWaitEvent(r->cs(), r->ev_g[step & 1], 0));
+        else if (staged_g)
+            HIP_TRY(hipStreamWaitEvent(r->cs(), l->ev_g_in, 0));
+    }
+
+    GemmArgs a;
+    // ---- weight gradient, fused into the travelling gradient shard -----------
+    memset(&a, 0, sizeof a);
+    a.c_is_f32 = 1;
+    a.epi = EPI_ACC_ADD;
+    a.K = (int)d.T;
+    if (d.split == RTP_SPLIT_OUT) {
+        a.A = (const char *)dY + (size_t)k * o * es; a.lda = d.O;
+        a.B = X; a.ldb = d.I;
+        a.M = (int)o; a.N = (int)d.I;
+        a.ws = Gk; a.ldws = d.I;
+    } else {
+        a.A = dY; a.lda = d.O;
+        a.B = (const char *)X + (size_t)k * o * es; a.ldb = d.I;
+        a.M = (int)d.O; a.N = (int)o;
+        a.ws = Gk; a.ldws = o;
+    }
+    a.C = a.ws; a.ldc = a.ldws;
+    if (d.T > 0) RTP_TRY(gemm(l, LAY_TN, a));
+
+    // ---- hand the gradient part to the stage stream ---------------------------
+    if (rotating && r->d.g_bytes && r->d.mode != RTP_INPLACE_BLOCKING) {
+        const int kin = rtp_bwd_shard(r->d.rank, step + 1, n);
+        if (!r->dry) {
+            HIP_TRY(hipEventRecord(l->ev_dw, r->cs()));
+            HIP_TRY(hipStreamWaitEvent(r->ss(), l->ev_dw, 0));
+        }
+        RTP_TRY(copy_async(r, r->home_g(k) + d.g_offset, (char *)r->d.buf_g_dev[gi] + d.g_offset, l->g_shard_bytes, r->ss()));
+        r->rec(TR_G_OUT, step, k, gi);
+        if (staged_g) {
+            RTP_TRY(copy_async(r, (char *)r->d.buf_g_dev[gi] + d.g_offset, r->home_g(kin) + d.g_offset, l->g_shard_bytes, r->ss()));
+            r->rec(TR_G_IN, step, kin, gi);
+            if (!r->dry) HIP_TRY(hipEventRecord(l->ev_g_in, r->ss()));
+        }
+    }
+
+    // ---- input gradient ----------------------------------------------------------
+    if (dX || r->dry) {
+        memset(&a, 0, sizeof a);
+        a.c_is_f32 = f32;
+        if (d.split == RTP_SPLIT_OUT) {
+            a.A = (const char *)dY + (size_t)k * o * es; a.lda = d.O;
+            a.B = Wk; a.ldb = d.I;
+            a.M = (int)d.T; a.N = (int)d.I; a.K = (int)o;
+            a.C = dX; a.ldc = d.I;
+            if (f32) {
+                a.epi = step == 0 ? EPI_STORE : EPI_ACC_ADD;
+            } else {
+                a.epi = acc_epi(step, n);
+                a.ws = d.acc_ws_dev; a.ldws = d.I;
+            }
+            RTP_TRY(gemm(l, LAY_NN, a));
+        } else {
+            a.A = dY; a.lda = d.O;
+            a.B = Wk; a.ldb = o;
+            a.M = (int)d.T; a.N = (int)o; a.K = (int)d.O;
+            if (d.act == RTP_ACT_NONE) {
+                a.epi = EPI_STORE;
+                a.C = (char *)dX + (size_t)k * o * es; a.ldc = d.I;
+                RTP_TRY(gemm(l, LAY_NN, a));
+            } else {
+                const bool gated = d.act == RTP_ACT_SWIGLU;
+                const int64_t P = gated ? 2 * d.I : d.I, po = gated ? 2 * o : o;
+                char *out = (char *)dX + (size_t)k * po * es;
+                const char *pre = (const char *)d.preact_dev + (size_t)k * po * es;
+                if (!f32) {
+                    a.epi = bwd_act_epi(d.act);
+                    a.half = (int)o;
+                    a.aux = (void *)pre; a.ldaux = P;
+                    a.C = out; a.ldc = P;
+                    RTP_TRY(gemm(l, LAY_NN, a));
+                } else {
+                    // the plain product lands in the last o columns of the slice, then the
+                    // activation's derivative is applied elementwise, in place
+                    float *tmp = (float *)out + (gated ? o : 0);
+                    a.epi = EPI_STORE;
+                    a.C = tmp; a.ldc = P;
+                    RTP_TRY(gemm(l, LAY_NN, a));
+                    if (!r->dry && r->abl_compute)
+                        HIP_TRY(launch_act_f32(bwd_act_epi(d.act), (const float *)pre, P, tmp, P, (float *)out, P,
+                                               (int)d.T, (int)o, (int)o, r->cs()));
+                }
+            }
+        }
+    }
+    l->next_step = step + 1;
+    return RTP_OK;
+}
+
+// ---------------------------------------------------------------------------
+// MLP unit
+// ---------------------------------------------------------------------------
+struct rtp_mlp {
+    rtp_mlp_desc d;
+    rtp_ring *ring = nullptr;
+    rtp_linear *l1 = nullptr, *l2 = nullptr;
+};
+
+static bool mlp_gated(const rtp_mlp_desc *d) { return d->act == RTP_ACT_SWIGLU; }
+
+extern "C" size_t rtp_mlp_slot_w_bytes(const rtp_mlp_desc *d)
+{
+    if (!d || d->n < 1) return 0;
+    const size_t p = mlp_gated(d) ? 2 : 1;
+    return (p * (size_t)d->O * d->I + (size_t)d->O2 * d->O) / (size_t)d->n * esize(d->dtype);
+}
+
+extern "C" size_t rtp_mlp_slot_g_bytes(const rtp_mlp_desc *d)
+{
+    if (!d || d->n < 1) return 0;
+    const size_t p = mlp_gated(d) ? 2 : 1;
+    return (p * (size_t)d->O * d->I + (size_t)d->O2 * d->O) / (size_t)d->n * 4;
+}
+
+extern "C" rtp_status rtp_mlp_create(rtp_mlp **out, const rtp_mlp_desc *d)
+{
+    if (!out || !d) return fail(RTP_ERR_INVALID, "rtp_mlp_create: null argument");
+    *out = nullptr;
+    if (d->act == RTP_ACT_NONE) return fail(RTP_ERR_INVALID, "rtp_mlp_create: an MLP block has an activation");
+    if (d->n < 1 || d->O <= 0 || d->I <= 0 || d->O2 <= 0 || d->O % d->n != 0)
+        return fail(RTP_ERR_SHAPE, "rtp_mlp_create: n must divide the hidden width");
+    const bool gated = mlp_gated(d);
+    const size_t p = gated ? 2 : 1;
+    rtp_ring_desc rd;
+    memset(&rd, 0, sizeof rd);
+    rd.n = d->n; rd.rank = d->rank; rd.mode = d->mode; rd.flags = d->flags;
+    rd.w_bytes = rtp_mlp_slot_w_bytes(d);
+    rd.g_bytes = rtp_mlp_slot_g_bytes(d);
+    rd.home_w_dev = d->home_w_dev; rd.home_g_dev = d->home_g_dev;
+    rd.buf_w_dev[0] = d->buf_w_dev[0]; rd.buf_w_dev[1] = d->buf_w_dev[1];
+    rd.buf_g_dev[0] = d->buf_g_dev[0]; rd.buf_g_dev[1] = d->buf_g_dev[1];
+    rd.compute_stream = d->compute_stream; rd.stage_stream = d->stage_stream;
+    rtp_mlp *m = new (std::nothrow) rtp_mlp;
+    if (!m) return fail(RTP_ERR_INVALID, "out of host memory");
+    m->d = *d;
+    rtp_status s = rtp_ring_create(&m->ring, &rd);
+    if (s != RTP_OK) { delete m; return s; }
+    const size_t w1 = p * (size_t)d->O * d->I / (size_t)d->n;
+    rtp_linear_desc l1;
+    memset(&l1, 0, sizeof l1);
+    l1.T = d->T; l1.I = d->I; l1.O = (int64_t)p * d->O;
+    l1.split = RTP_SPLIT_OUT; l1.dtype = d->dtype; l1.grad_dtype = RTP_F32; l1.act = d->act;
+    l1.w_offset = 0; l1.g_offset = 0;
+    l1.preact_dev = d->preact_dev; l1.acc_ws_dev = d->acc_dx_dev;
+    rtp_linear_desc l2;
+    memset(&l2, 0, sizeof l2);
+    l2.T = d->T; l2.I = d->O; l2.O = d->O2;
+    l2.split = RTP_SPLIT_IN; l2.dtype = d->dtype; l2.grad_dtype = RTP_F32; l2.act = d->act;
+    l2.w_offset = w1 * esize(d->dtype); l2.g_offset = w1 * 4;
+    l2.preact_dev = d->preact_dev; l2.acc_ws_dev = d->acc_y_dev;
+    s = rtp_linear_create(&m->l1, m->ring, &l1);
+    if (s == RTP_OK) s = rtp_linear_create(&m->l2, m->ring, &l2);
+    if (s == RTP_OK && !(d->flags & RTP_FLAG_DRY_RUN) && (!d->hidden_dev || !d->dpre_dev))
+        s = fail(RTP_ERR_INVALID, "rtp_mlp_create: hidden/dpre buffers are missing");
+    if (s != RTP_OK) {
+        rtp_linear_destroy(m->l2);
+        rtp_linear_destroy(m->l1);
+        rtp_ring_destroy(m->ring);
+        delete m;
+        return s;
+    }
+    *out = m;
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_mlp_destroy(rtp_mlp *m)
+{
+    if (!m) return RTP_OK;
+    RTP_TRY(rtp_linear_destroy(m->l2));
+    RTP_TRY(rtp_linear_destroy(m->l1));
+    RTP_TRY(rtp_ring_destroy(m->ring));
+    delete m;
+    return RTP_OK;
+}
+
+extern "C" rtp_ring *rtp_mlp_ring(rtp_mlp *m) { return m ? m->ring : nullptr; }
+
+extern "C" rtp_status rtp_mlp_set_ablation(rtp_mlp *m, int rotate, int compute)
+{
+    if (!m) return fail(RTP_ERR_INVALID, "null mlp");
+    return set_ablation(m->ring, rotate, compute);
+}
+
+extern "C" rtp_status rtp_mlp_fwd(rtp_mlp *m, const void *X, void *Y)
+{
+    if (!m) return fail(RTP_ERR_INVALID, "rtp_mlp_fwd: null mlp");
+    const int n = m->d.n;
+    RTP_TRY(rtp_ring_begin(m->ring, RTP_PASS_FWD));
+    for (int t = 0; t < n; ++t) {
+        if (t < n - 1) RTP_TRY(rtp_rotate_step(m->ring, RTP_CW, t));
+        RTP_TRY(rtp_linear_fwd(m->l1, t, X, m->d.hidden_dev));
+        RTP_TRY(rtp_linear_fwd(m->l2, t, m->d.hidden_dev, Y));
+    }
+    return rtp_ring_end(m->ring);
+}
+
+extern "C" rtp_status rtp_mlp_bwd(rtp_mlp *m, const void *X, const void *dY, void *dX)
+{
+    if (!m) return fail(RTP_ERR_INVALID, "rtp_mlp_bwd: null mlp");
+    const int n = m->d.n;
+    RTP_TRY(rtp_ring_begin(m->ring, RTP_PASS_BWD));
+    for (int s = 0; s < n; ++s) {
+        if (s < n - 1) RTP_TRY(rtp_rotate_step(m->ring, RTP_CCW, s));
+        RTP_TRY(rtp_linear_bwd(m->l2, s, m->d.hidden_dev, dY, m->d.dpre_dev));
+        RTP_TRY(rtp_linear_bwd(m->l1, s, X, m->d.dpre_dev, dX));
+    }
+    return rtp_ring_end(m->ring);
+}
+
+extern "C" rtp_status rtp_mlp_flush(rtp_mlp *m) { return m ? rtp_ring_flush(m->ring) : fail(RTP_ERR_INVALID, "null mlp"); }
+extern "C" rtp_status rtp_mlp_sync(rtp_mlp *m) { return m ? rtp_ring_sync(m->ring) : fail(RTP_ERR_INVALID, "null mlp"); }
+
+// ---------------------------------------------------------------------------
+// single GEMM launch
+// ---------------------------------------------------------------------------
+extern "C" rtp_status rtp_gemm(int layout, rtp_dtype in_dtype, rtp_dtype out_dtype, int accumulate, const void *A,
+                               int64_t lda, const void *B, int64_t ldb, void *C, int64_t ldc, int64_t M, int64_t N,
+                               int64_t K, int variant, void *stream)
+{
+    if (!A || !B || !C) return fail(RTP_ERR_INVALID, "rtp_gemm: null pointer");
+    if (layout < 0 || layout > 2) return fail(RTP_ERR_INVALID, "rtp_gemm: bad layout");
+    if (M < 0 || N < 0 || K <= 0 || M > 0x7fffffff || N > 0x7fffffff || K > 0x7fffffff)
+        return fail(RTP_ERR_SHAPE, "rtp_gemm: bad sizes");
+    if (accumulate && out_dtype != RTP_F32) return fail(RTP_ERR_UNSUPPORTED, "rtp_gemm: accumulation is fp32 only");
+    GemmArgs a;
+    memset(&a, 0, sizeof a);
+    a.A = A; a.lda = lda; a.B = B; a.ldb = ldb;
+    a.M = (int)M; a.N = (int)N; a.K = (int)K;
+    a.C = C; a.ldc = ldc; a.ws = (float *)C; a.ldws = ldc;
+    a.epi = accumulate ? EPI_ACC_ADD : EPI_STORE;
+    a.c_is_f32 = out_dtype == RTP_F32;
+    if (in_dtype == RTP_BF16) {
+        if (out_dtype != RTP_F32 && out_dtype != RTP_BF16) return fail(RTP_ERR_UNSUPPORTED, "rtp_gemm: bad output type");
+        hipError_t e = launch_gemm_bf16(layout, a, variant, (hipStream_t)stream);
+        if (e == hipErrorInvalidValue) return fail(RTP_ERR_SHAPE, "rtp_gemm: sizes/alignment the bf16 kernels need are not met");
+        HIP_TRY(e);
+    } else if (in_dtype == RTP_F32) {
+        if (out_dtype != RTP_F32) return fail(RTP_ERR_UNSUPPORTED, "rtp_gemm: fp32 inputs give fp32 outputs");
+        HIP_TRY(launch_gemm_f32(layout, a, (hipStream_t)stream));
+    } else {
+        return fail(RTP_ERR_UNSUPPORTED, "rtp_gemm: input type not built");
+    }
+    return RTP_OK;
+}
+
+extern "C" const char *rtp_gemm_kernel_name(int layout, int variant) { return gemm_bf16_kernel_name(layout, variant); }

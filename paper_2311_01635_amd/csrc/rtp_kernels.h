@@ -1,0 +1,56 @@
+// Internal launch interface between the host scheduler and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rtp {
+
+enum : int { LAY_NT = 0, LAY_NN = 1, LAY_TN = 2 };
+
+// What happens to the fp32 accumulator tile when the K loop is done.
+enum : int {
+    EPI_STORE = 0,        // C = acc                         (C in the output dtype)
+    EPI_ACC_FIRST = 1,    // ws = acc                        (fp32 workspace)
+    EPI_ACC_ADD = 2,      // ws += acc
+    EPI_ACC_LAST = 3,     // C = ws + acc                    (rounded once)
+    EPI_GELU_ERF_FWD = 4, // aux = acc ; C = gelu(acc)
+    EPI_GELU_TANH_FWD = 5,
+    EPI_SWIGLU_FWD = 6,   // B is [gate rows | up rows]; aux = (a | b); C = silu(a) * b
+    EPI_GELU_ERF_BWD = 7, // C = acc * gelu'(aux)
+    EPI_GELU_TANH_BWD = 8,
+    EPI_SWIGLU_BWD = 9    // C[:, n] = acc * b * silu'(a) ; C[:, half + n] = acc * silu(a)
+};
+
+struct GemmArgs {
+    const void *A;
+    const void *B;
+    int64_t lda, ldb;   // elements
+    int M, N, K;        // N counts both halves for EPI_SWIGLU_FWD
+    int epi;
+    void *C;            // output-dtype result
+    int64_t ldc;
+    float *ws;          // fp32 accumulator (EPI_ACC_*)
+    int64_t ldws;
+    void *aux;          // pre-activations, in the input dtype
+    int64_t ldaux;
+    int half;           // EPI_SWIGLU_FWD: N/2 ; EPI_SWIGLU_BWD: N
+    int c_is_f32;       // EPI_STORE / EPI_ACC_LAST write fp32 instead of the input dtype
+};
+
+// bf16 inputs, fp32 MFMA accumulation.  variant: 0 = pick by shape.
+hipError_t launch_gemm_bf16(int layout, const GemmArgs &a, int variant, hipStream_t s);
+const char *gemm_bf16_kernel_name(int layout, int variant);
+
+// fp32 inputs and outputs (epi: EPI_STORE, EPI_ACC_ADD with ws == C).
+hipError_t launch_gemm_f32(int layout, const GemmArgs &a, hipStream_t s);
+
+// elementwise pieces of the fp32 path (the bf16 path fuses them into the GEMMs)
+// kind: EPI_GELU_ERF_FWD / EPI_GELU_TANH_FWD / EPI_SWIGLU_FWD / *_BWD
+hipError_t launch_act_f32(int kind, const float *pre, int64_t ldpre, const float *in, int64_t ldin,
+                          float *out, int64_t ldout, int rows, int cols, int half, hipStream_t s);
+
+// device-to-device staging copy with a bounded number of workgroups
+hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
+hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s);
+
+} // namespace rtp

@@ -1,0 +1,202 @@
+// fp32 path of the partition GEMM (the small fp32 configuration), the
+// elementwise activation kernels that path uses, and the shard-staging copy.
+#include "rtp_kernels.h"
+
+namespace rtp {
+
+// ---- fp32 GEMM: 64x64 tile, 256 threads, 4x4 outputs per thread -------------------
+// LDS holds A as [BK][64] and B as [BK][64] whatever the HBM layout, so the
+// inner product reads both with unit stride.
+constexpr int FT = 64, FK = 16;
+
+template <int LAY>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs p)
+{
+    __shared__ float sA[FK][FT + 4];
+    __shared__ float sB[FK][FT + 4];
+    const float *A = (const float *)p.A, *B = (const float *)p.B;
+    const int tid = threadIdx.x;
+    const int m0 = blockIdx.y * FT, n0 = blockIdx.x * FT;
+    const int tx = tid & 15, ty = tid >> 4;
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < p.K; k0 += FK) {
+        // 64*16 = 1024 elements per operand, 4 per thread
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = tid + 256 * i;
+            int k, r;
+            if (LAY == LAY_TN) { r = e & 63; k = e >> 6; } else { k = e & 15; r = e >> 4; }
+            const int gm = m0 + r, gk = k0 + k;
+            float v = 0.0f;
+            if (gm < p.M && gk < p.K)
+                v = (LAY == LAY_TN) ? A[(int64_t)gk * p.lda + gm] : A[(int64_t)gm * p.lda + gk];
+            sA[k][r] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = tid + 256 * i;
+            int k, r;
+            if (LAY == LAY_NT) { k = e & 15; r = e >> 4; } else { r = e & 63; k = e >> 6; }
+            const int gn = n0 + r, gk = k0 + k;
+            float v = 0.0f;
+            if (gn < p.N && gk < p.K)
+                v = (LAY == LAY_NT) ? B[(int64_t)gn * p.ldb + gk] : B[(int64_t)gk * p.ldb + gn];
+            sB[k][r] = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < FK; ++k) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = sA[k][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = sB[k][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+    float *C = (float *)p.C;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = m0 + ty * 4 + i;
+        if (row >= p.M) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int col = n0 + tx * 4 + j;
+            if (col >= p.N) continue;
+            if (p.epi == EPI_ACC_ADD)
+                C[(int64_t)row * p.ldc + col] += acc[i][j];
+            else
+                C[(int64_t)row * p.ldc + col] = acc[i][j];
+        }
+    }
+}
+
+hipError_t launch_gemm_f32(int layout, const GemmArgs &a, hipStream_t s)
+{
+    if (a.M <= 0 || a.N <= 0) return hipSuccess;
+    if (a.K <= 0 || (a.epi != EPI_STORE && a.epi != EPI_ACC_ADD)) return hipErrorInvalidValue;
+    const dim3 grid((a.N + FT - 1) / FT, (a.M + FT - 1) / FT), block(256);
+    switch (layout) {
+    case LAY_NT: hipLaunchKernelGGL(gemm_f32_kernel<LAY_NT>, grid, block, 0, s, a); break;
+    case LAY_NN: hipLaunchKernelGGL(gemm_f32_kernel<LAY_NN>, grid, block, 0, s, a); break;
+    case LAY_TN: hipLaunchKernelGGL(gemm_f32_kernel<LAY_TN>, grid, block, 0, s, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// ---- elementwise activations for the fp32 path --------------------------------------
+__device__ __forceinline__ float act_gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+__device__ __forceinline__ float act_gelu_erf_grad(float x)
+{
+    return 0.5f * (1.0f + erff(x * 0.70710678118654752f)) + x * 0.3989422804014327f * expf(-0.5f * x * x);
+}
+__device__ __forceinline__ float act_gelu_tanh(float x)
+{
+    return 0.5f * x * (1.0f + tanhf(0.7978845608028654f * (x + 0.044715f * x * x * x)));
+}
+__device__ __forceinline__ float act_gelu_tanh_grad(float x)
+{
+    const float th = tanhf(0.7978845608028654f * (x + 0.044715f * x * x * x));
+    const float du = 0.7978845608028654f * (1.0f + 3.0f * 0.044715f * x * x);
+    return 0.5f * (1.0f + th) + 0.5f * x * (1.0f - th * th) * du;
+}
+__device__ __forceinline__ float act_sigmoid(float x) { return 1.0f / (1.0f + expf(-x)); }
+
+// forward kinds: out[r, c] = act(pre[r, c])            (SWIGLU: silu(pre[r,c]) * pre[r, half+c])
+// backward kinds: out[r, c] = in[r, c] * act'(pre[r, c])
+//   SWIGLU_BWD: out[r, c] = in*b*silu'(a), out[r, half+c] = in*silu(a)
+__global__ void act_f32_kernel(int kind, const float *pre, int64_t ldpre, const float *in, int64_t ldin, float *out,
+                               int64_t ldout, int rows, int cols, int half)
+{
+    const int64_t n = (int64_t)rows * cols;
+    for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x) {
+        const int r = (int)(e / cols), c = (int)(e % cols);
+        const float z = pre[r * ldpre + c];
+        switch (kind) {
+        case EPI_GELU_ERF_FWD: out[r * ldout + c] = act_gelu_erf(z); break;
+        case EPI_GELU_TANH_FWD: out[r * ldout + c] = act_gelu_tanh(z); break;
+        case EPI_SWIGLU_FWD: out[r * ldout + c] = z * act_sigmoid(z) * pre[r * ldpre + half + c]; break;
+        case EPI_GELU_ERF_BWD: out[r * ldout + c] = in[r * ldin + c] * act_gelu_erf_grad(z); break;
+        case EPI_GELU_TANH_BWD: out[r * ldout + c] = in[r * ldin + c] * act_gelu_tanh_grad(z); break;
+        case EPI_SWIGLU_BWD: {
+            const float sg = act_sigmoid(z), b = pre[r * ldpre + half + c], g = in[r * ldin + c];
+            out[r * ldout + c] = g * b * sg * (1.0f + z * (1.0f - sg));
+            out[r * ldout + half + c] = g * z * sg;
+            break;
+        }
+        default: break;
+        }
+    }
+}
+
+hipError_t launch_act_f32(int kind, const float *pre, int64_t ldpre, const float *in, int64_t ldin, float *out,
+                          int64_t ldout, int rows, int cols, int half, hipStream_t s)
+{
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    const int64_t n = (int64_t)rows * cols;
+    const int blocks = (int)((n + 255) / 256 > 2048 ? 2048 : (n + 255) / 256);
+    hipLaunchKernelGGL(act_f32_kernel, dim3(blocks), dim3(256), 0, s, kind, pre, ldpre, in, ldin, out, ldout, rows,
+                       cols, half);
+    return hipGetLastError();
+}
+
+// ---- staging copy ---------------------------------------------------------------------
+// Each workgroup moves one 64 KB piece with 16-byte accesses and exits, so the
+// copy slips into whatever wave slots the GEMM running beside it leaves free
+// instead of holding compute units for the whole transfer.
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+constexpr int COPY_THREADS = 256;
+constexpr int COPY_PER_THREAD = 16; // x 16 bytes
+
+__global__ __launch_bounds__(COPY_THREADS) void copy_kernel(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src,
+                                                            int64_t n16)
+{
+    const int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_PER_THREAD) + threadIdx.x;
+    u32x4 v[COPY_PER_THREAD];
+#pragma unroll
+    for (int i = 0; i < COPY_PER_THREAD; ++i) {
+        const int64_t e = base + (int64_t)i * COPY_THREADS;
+        if (e < n16) v[i] = __builtin_nontemporal_load(src + e);
+    }
+#pragma unroll
+    for (int i = 0; i < COPY_PER_THREAD; ++i) {
+        const int64_t e = base + (int64_t)i * COPY_THREADS;
+        if (e < n16) __builtin_nontemporal_store(v[i], dst + e);
+    }
+}
+
+hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s)
+{
+    if (bytes == 0) return hipSuccess;
+    if ((bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return hipErrorInvalidValue;
+    const int64_t n16 = (int64_t)(bytes >> 4);
+    const int64_t per = COPY_THREADS * COPY_PER_THREAD;
+    const unsigned blocks = (unsigned)((n16 + per - 1) / per);
+    hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(COPY_THREADS), 0, s, (u32x4 *)dst, (const u32x4 *)src, n16);
+    return hipGetLastError();
+}
+
+__global__ void fill_zero_kernel(u32x4 *dst, int64_t n16)
+{
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n16; e += (int64_t)gridDim.x * blockDim.x)
+        dst[e] = z;
+}
+
+hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s)
+{
+    if (bytes == 0) return hipSuccess;
+    if ((bytes & 15) || ((uintptr_t)dst & 15)) return hipErrorInvalidValue;
+    const int64_t n16 = (int64_t)(bytes >> 4);
+    const int blocks = (int)((n16 + 255) / 256 > 4096 ? 4096 : (n16 + 255) / 256);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, (u32x4 *)dst, n16);
+    return hipGetLastError();
+}
+
+} // namespace rtp

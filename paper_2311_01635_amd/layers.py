@@ -1,0 +1,204 @@
+"""Torch-side plumbing: device buffers, streams and the packing of full
+matrices into the ring store.  No arithmetic of the method happens here; the
+forward and backward steps are calls into librtp.so."""
+import ctypes as C
+
+import torch
+
+from . import binding as B
+
+_TORCH_DT = {B.RTP_F32: torch.float32, B.RTP_BF16: torch.bfloat16}
+
+
+def _esize(dtype):
+    return 4 if dtype == B.RTP_F32 else 2
+
+
+def pack_out_split(W, n):
+    """[O, I] -> [n, o*I]: shard k is rows [k o, (k+1) o)."""
+    O, I = W.shape
+    return W.reshape(n, (O // n) * I)
+
+
+def pack_in_split(W, n):
+    """[O, I] -> [n, O*o]: shard k is columns [k o, (k+1) o), stored [O, o]."""
+    O, I = W.shape
+    o = I // n
+    return W.reshape(O, n, o).permute(1, 0, 2).contiguous().reshape(n, O * o)
+
+
+def unpack_out_split(P, n, O, I):
+    return P.reshape(O, I)
+
+
+def unpack_in_split(P, n, O, I):
+    o = I // n
+    return P.reshape(n, O, o).permute(1, 0, 2).contiguous().reshape(O, I)
+
+
+def stack_gate_up(Wg, Wu, n):
+    """[O, I] x 2 -> [2 O, I] with shard k = gate rows k followed by up rows k."""
+    O, I = Wg.shape
+    o = O // n
+    return torch.stack((Wg.reshape(n, o, I), Wu.reshape(n, o, I)), dim=1).reshape(2 * O, I).contiguous()
+
+
+def unstack_gate_up(Wgu, n):
+    O2, I = Wgu.shape
+    o = O2 // (2 * n)
+    v = Wgu.reshape(n, 2, o, I)
+    return v[:, 0].reshape(n * o, I).contiguous(), v[:, 1].reshape(n * o, I).contiguous()
+
+
+class RtpLinear:
+    """One rotated linear layer: the N-step loop issued call by call through
+    rtp_rotate_step / rtp_linear_fwd / rtp_linear_bwd."""
+
+    def __init__(self, W, T, n, rank, split=B.RTP_SPLIT_OUT, mode=B.RTP_DOUBLE_BUFFER, dtype=B.RTP_BF16,
+                 act=B.RTP_ACT_NONE, G0=None, preact=None, device="cuda:0"):
+        self.dev = torch.device(device)
+        self.n, self.rank, self.T, self.split, self.mode, self.dtype, self.act = n, rank, T, split, mode, dtype, act
+        td = _TORCH_DT[dtype]
+        W = W.to(self.dev, td).contiguous()
+        self.O, self.I = W.shape
+        pack = pack_out_split if split == B.RTP_SPLIT_OUT else pack_in_split
+        self.home_w = pack(W, n).contiguous()
+        G0 = torch.zeros(self.O, self.I, device=self.dev, dtype=torch.float32) if G0 is None else \
+            G0.to(self.dev, torch.float32)
+        self.home_g = pack(G0, n).contiguous()
+        wb = self.home_w.shape[1] * _esize(dtype)
+        gb = self.home_g.shape[1] * 4
+        self.buf_w = [torch.empty(wb, dtype=torch.uint8, device=self.dev) for _ in range(2)]
+        self.buf_g = [torch.empty(gb, dtype=torch.uint8, device=self.dev) for _ in range(2)]
+        self.compute_stream = torch.cuda.Stream(self.dev)
+        self.stage_stream = torch.cuda.Stream(self.dev)
+        self.ring = B.Ring(n, rank, mode, wb, gb, self.home_w, self.home_g, self.buf_w, self.buf_g,
+                           self.compute_stream, self.stage_stream)
+        acc_cols = self.I if split == B.RTP_SPLIT_OUT else self.O
+        self.acc_ws = torch.empty(T, acc_cols, dtype=torch.float32, device=self.dev)
+        self.preact = preact
+        self.lin = B.Linear(self.ring, T, self.I, self.O, split, dtype, act, 0, 0, preact, self.acc_ws)
+        torch.cuda.synchronize(self.dev)
+
+    def forward(self, X, Y):
+        r, n = self.ring, self.n
+        r.begin(B.RTP_PASS_FWD)
+        for t in range(n):
+            if t < n - 1:
+                r.rotate_step(B.RTP_CW, t)
+            self.lin.fwd(t, X, Y)
+        r.end()
+
+    def backward(self, X, dY, dX):
+        r, n = self.ring, self.n
+        r.begin(B.RTP_PASS_BWD)
+        for s in range(n):
+            if s < n - 1:
+                r.rotate_step(B.RTP_CCW, s)
+            self.lin.bwd(s, X, dY, dX)
+        r.end()
+
+    def sync(self):
+        self.ring.sync()
+
+    def gathered(self):
+        """(W, G) as full matrices, read back from the home store."""
+        self.ring.flush()
+        self.ring.sync()
+        un = unpack_out_split if self.split == B.RTP_SPLIT_OUT else unpack_in_split
+        return un(self.home_w, self.n, self.O, self.I), un(self.home_g, self.n, self.O, self.I)
+
+    def close(self):
+        self.ring.close()
+
+
+class RtpMlp:
+    """MLP unit (first GEMM output-partitioned, second input-partitioned) run
+    by rtp_mlp_fwd / rtp_mlp_bwd: one library call per pass."""
+
+    def __init__(self, weights, T, n, rank, act, mode=B.RTP_INPLACE_STAGED, dtype=B.RTP_BF16, G0=None,
+                 device="cuda:0"):
+        self.dev = torch.device(device)
+        td = _TORCH_DT[dtype]
+        self.n, self.rank, self.T, self.act, self.mode, self.dtype = n, rank, T, act, mode, dtype
+        self.gated = act == B.RTP_ACT_SWIGLU
+        ws = [w.to(self.dev, td).contiguous() for w in weights]
+        if self.gated:
+            Wg, Wu, Wd = ws
+            W1 = stack_gate_up(Wg, Wu, n)
+        else:
+            W1, Wd = ws
+        self.O, self.I = (W1.shape[0] // 2 if self.gated else W1.shape[0]), W1.shape[1]
+        self.O2 = Wd.shape[0]
+        self.p = 2 if self.gated else 1
+        self.home_w = torch.cat((pack_out_split(W1, n), pack_in_split(Wd, n)), dim=1).contiguous()
+        self.n1 = self.p * self.O * self.I // n           # elements of the first matrix's shard
+        self.n2 = self.O2 * self.O // n
+        if G0 is None:
+            self.home_g = torch.zeros(n, self.n1 + self.n2, dtype=torch.float32, device=self.dev)
+        else:
+            g = [x.to(self.dev, torch.float32) for x in G0]
+            G1 = stack_gate_up(g[0], g[1], n) if self.gated else g[0]
+            self.home_g = torch.cat((pack_out_split(G1, n), pack_in_split(g[-1], n)), dim=1).contiguous()
+        d = B.rtp_mlp_desc()
+        d.T, d.I, d.O, d.O2 = T, self.I, self.O, self.O2
+        d.n, d.rank, d.mode, d.dtype, d.act, d.flags = n, rank, mode, dtype, act, 0
+        wb, gb = B.lib.rtp_mlp_slot_w_bytes(C.byref(d)), B.lib.rtp_mlp_slot_g_bytes(C.byref(d))
+        assert wb == self.home_w.shape[1] * _esize(dtype) and gb == self.home_g.shape[1] * 4
+        self.w_bytes, self.g_bytes = wb, gb
+        self.buf_w = [torch.empty(wb, dtype=torch.uint8, device=self.dev) for _ in range(2)]
+        ng = 2 if mode == B.RTP_DOUBLE_BUFFER else 1
+        self.buf_g = [torch.empty(gb, dtype=torch.uint8, device=self.dev) for _ in range(ng)] + [None] * (2 - ng)
+        self.preact = torch.empty(T, self.p * self.O, dtype=td, device=self.dev)
+        self.hidden = torch.empty(T, self.O, dtype=td, device=self.dev)
+        self.dpre = torch.empty(T, self.p * self.O, dtype=td, device=self.dev)
+        self.acc_y = torch.empty(T, self.O2, dtype=torch.float32, device=self.dev)
+        self.acc_dx = torch.empty(T, self.I, dtype=torch.float32, device=self.dev)
+        self.compute_stream = torch.cuda.Stream(self.dev)
+        self.stage_stream = torch.cuda.Stream(self.dev)
+        d.home_w_dev, d.home_g_dev = B._ptr(self.home_w), B._ptr(self.home_g)
+        d.buf_w_dev[0], d.buf_w_dev[1] = B._ptr(self.buf_w[0]), B._ptr(self.buf_w[1])
+        d.buf_g_dev[0], d.buf_g_dev[1] = B._ptr(self.buf_g[0]), B._ptr(self.buf_g[1])
+        d.preact_dev, d.hidden_dev, d.dpre_dev = B._ptr(self.preact), B._ptr(self.hidden), B._ptr(self.dpre)
+        d.acc_y_dev, d.acc_dx_dev = B._ptr(self.acc_y), B._ptr(self.acc_dx)
+        d.compute_stream, d.stage_stream = B._stream(self.compute_stream), B._stream(self.stage_stream)
+        self.desc = d
+        self.handle = C.c_void_p()
+        B.check(B.lib.rtp_mlp_create(C.byref(self.handle), C.byref(d)), "rtp_mlp_create")
+        torch.cuda.synchronize(self.dev)
+
+    def forward(self, X, Y):
+        B.check(B.lib.rtp_mlp_fwd(self.handle, B._ptr(X), B._ptr(Y)), "rtp_mlp_fwd")
+
+    def backward(self, X, dY, dX):
+        B.check(B.lib.rtp_mlp_bwd(self.handle, B._ptr(X), B._ptr(dY), B._ptr(dX)), "rtp_mlp_bwd")
+
+    def set_ablation(self, rotate=True, compute=True):
+        B.check(B.lib.rtp_mlp_set_ablation(self.handle, int(rotate), int(compute)), "rtp_mlp_set_ablation")
+
+    def sync(self):
+        B.check(B.lib.rtp_mlp_sync(self.handle), "rtp_mlp_sync")
+
+    def zero_grads(self):
+        self.home_g.zero_()
+
+    def worker_bytes(self):
+        return B.rtp_worker_bytes(self.mode, self.w_bytes, self.g_bytes)
+
+    def gathered(self):
+        """Full matrices read back from the home store: (weights, gradients)
+        in the order they were given."""
+        B.check(B.lib.rtp_mlp_flush(self.handle), "rtp_mlp_flush")
+        self.sync()
+        out = []
+        for home in (self.home_w, self.home_g):
+            P1, P2 = home[:, :self.n1].contiguous(), home[:, self.n1:].contiguous()
+            M1 = unpack_out_split(P1, self.n, self.p * self.O, self.I)
+            M2 = unpack_in_split(P2, self.n, self.O2, self.O)
+            out.append((*unstack_gate_up(M1, self.n), M2) if self.gated else (M1, M2))
+        return out
+
+    def close(self):
+        if self.handle:
+            B.check(B.lib.rtp_mlp_destroy(self.handle), "rtp_mlp_destroy")
+            self.handle = C.c_void_p()

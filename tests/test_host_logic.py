@@ -1,0 +1,214 @@
+"""Host-side checks that need no GPU: the library loads and exports what
+include/rtp.h declares, the integer schedule is bit-exact against the oracle,
+the ring's state machine orders transfers as the paper describes and rejects
+calls out of sequence."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import oracle as orc
+from paper_2311_01635_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "rtp.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(rtp_[a-z0-9_]+)\s*\(", hdr))
+    assert len(declared) >= 30
+    lib = C.CDLL(B.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} is declared in rtp.h but not exported"
+    assert declared == set(B.SYMBOLS), "binding and header must list the same entry points"
+
+
+@pytest.mark.parametrize("n", list(range(1, 65)))
+def test_schedule_bit_exact_vs_oracle(n):
+    for r in range(n):
+        for t in range(n):
+            assert B.rtp_fwd_shard(r, t, n) == orc.fwd_shard(r, t, n)
+            assert B.rtp_bwd_shard(r, t, n) == orc.bwd_shard(r, t, n)
+
+
+def test_schedule_rejects_bad_arguments():
+    assert B.rtp_fwd_shard(0, 0, 0) == -1
+    assert B.rtp_fwd_shard(4, 0, 4) == -1
+    assert B.rtp_bwd_shard(0, 4, 4) == -1
+    assert B.rtp_bwd_shard(-1, 0, 4) == -1
+    assert B.rtp_shard_begin(0, 10, 4) == -1
+    assert B.rtp_shard_begin(4, 16, 4) == -1
+
+
+@pytest.mark.parametrize("dim,n", [(512, 4), (11008, 8), (28672, 16), (12, 12), (7, 1)])
+def test_shard_begin_vs_oracle(dim, n):
+    for k in range(n):
+        assert B.rtp_shard_begin(k, dim, n) == orc.shard_rows(k, dim, n)[0]
+
+
+@pytest.mark.parametrize("w,g", [(100 * 16, 100 * 16), (58720256, 117440512), (64, 32)])
+def test_worker_bytes_against_table1(w, g):
+    n = 16
+    # Table 1 is system-wide: hand the oracle the totals and compare one worker's share
+    assert B.rtp_table1_worker_bytes(False, w, g) == orc.worker_param_bytes("rtp", w * n, g * n, n)
+    assert B.rtp_table1_worker_bytes(True, w, g) == orc.worker_param_bytes("rtp_inplace", w * n, g * n, n)
+    assert B.rtp_worker_bytes(B.RTP_INPLACE_BLOCKING, w, g) == orc.worker_param_bytes("rtp_inplace", w * n, g * n, n)
+    # one staging buffer for the weights only: never above the out-of-place row of the table
+    assert B.rtp_worker_bytes(B.RTP_INPLACE_STAGED, w, g) <= B.rtp_table1_worker_bytes(False, w, g)
+    assert B.rtp_worker_bytes(B.RTP_INPLACE_STAGED, w, g) == 2 * w + g
+    assert B.rtp_worker_bytes(B.RTP_DOUBLE_BUFFER, w, g) == 2 * (w + g)
+    assert B.rtp_worker_bytes(7, w, g) == 0
+
+
+def _dry_ring(n, rank, mode, w=1024, g=2048):
+    return B.Ring(n, rank, mode, w, g, flags=B.RTP_FLAG_DRY_RUN)
+
+
+def _run_dry(n, rank, mode, split=B.RTP_SPLIT_OUT):
+    ring = _dry_ring(n, rank, mode, w=16 * 8 * n * 4 // n * n, g=16 * 8 * n * 4 // n * n)
+    lin = B.Linear(ring, 4, 8 * n if split == B.RTP_SPLIT_IN else 8, 8 * n if split == B.RTP_SPLIT_OUT else 8, split,
+                   B.RTP_F32)
+    ring.begin(B.RTP_PASS_FWD)
+    for t in range(n):
+        if t < n - 1:
+            ring.rotate_step(B.RTP_CW, t)
+        lin.fwd(t, None, None)
+    ring.end()
+    after_fwd = ring.resident()
+    ring.begin(B.RTP_PASS_BWD)
+    for s in range(n):
+        if s < n - 1:
+            ring.rotate_step(B.RTP_CCW, s)
+        lin.bwd(s, None, None, None)
+    ring.end()
+    tr = ring.trace()
+    after_bwd = ring.resident()
+    ring.close()
+    return tr, after_fwd, after_bwd
+
+
+@pytest.mark.parametrize("mode", [B.RTP_DOUBLE_BUFFER, B.RTP_INPLACE_STAGED, B.RTP_INPLACE_BLOCKING])
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 8, 16])
+def test_dry_run_trace_matches_oracle_schedule(n, mode):
+    """The integer record of what the ring enqueues equals the oracle's log:
+    which shard each step computes on, which shard is sent and received at
+    every rotation, N-1 rotations per pass, and where the worker ends."""
+    import numpy as np
+    X, W, dY = np.zeros((2, 3)), np.zeros((2 * n, 3)), np.zeros((2, 2 * n))
+    for rank in range(n):
+        tr, after_fwd, after_bwd = _run_dry(n, rank, mode)
+        ref = orc.rtp_linear_out(X, W, dY, n, rank)
+        assert [(s, k) for (kind, p, s, k, b) in tr if kind == "fwd"] == ref["fwd_log"]
+        assert [(s, k) for (kind, p, s, k, b) in tr if kind == "bwd"] == ref["bwd_log"]
+        w_out = [k for (kind, p, s, k, b) in tr if kind == "w_out" and s >= 0]
+        w_in = [k for (kind, p, s, k, b) in tr if kind == "w_in" and s >= 0]
+        assert w_out == ref["sent"] and w_in == ref["received"]
+        assert len(w_out) == 2 * (n - 1)
+        g_out = [k for (kind, p, s, k, b) in tr if kind == "g_out" and s >= 0]
+        g_in = [k for (kind, p, s, k, b) in tr if kind == "g_in" and s >= 0]
+        assert g_out == ref["sent"][n - 1:] and g_in == ref["received"][n - 1:], "gradients travel in the backward pass only"
+        assert after_fwd == ref["resident_after_fwd"] and after_bwd == ref["resident_after_bwd"] == rank
+        # the transfer that overlaps step s never targets the buffer step s computes on,
+        # and lands in the buffer step s+1 computes on
+        if mode != B.RTP_INPLACE_BLOCKING:
+            comp = {(p, s): b for (kind, p, s, k, b) in tr if kind in ("fwd", "bwd")}
+            for (kind, p, s, k, b) in tr:
+                if kind == "w_in" and s >= 0:
+                    assert b != comp[(p, s)] and b == comp[(p, s + 1)]
+
+
+def test_state_machine_rejects_out_of_sequence_calls():
+    n = 4
+    ring = _dry_ring(n, 1, B.RTP_DOUBLE_BUFFER, w=16 * 32, g=16 * 32)
+    lin = B.Linear(ring, 4, 8, 32, B.RTP_SPLIT_OUT, B.RTP_F32)
+
+    def status(fn, *a):
+        with pytest.raises(B.RtpError) as e:
+            fn(*a)
+        return e.value.status
+
+    assert status(ring.rotate_step, B.RTP_CW, 0) == B.RTP_ERR_STATE          # no pass open
+    assert status(lin.fwd, 0, None, None) == B.RTP_ERR_STATE
+    assert status(ring.begin, B.RTP_PASS_BWD) == B.RTP_ERR_STATE             # backward before forward
+    ring.begin(B.RTP_PASS_FWD)
+    assert status(ring.begin, B.RTP_PASS_FWD) == B.RTP_ERR_STATE             # pass already open
+    assert status(ring.rotate_step, B.RTP_CCW, 0) == B.RTP_ERR_STATE         # wrong direction
+    assert status(ring.rotate_step, B.RTP_CW, 1) == B.RTP_ERR_STATE          # out of order
+    assert status(lin.fwd, 0, None, None) == B.RTP_ERR_STATE                 # rotate first
+    ring.rotate_step(B.RTP_CW, 0)
+    assert status(ring.rotate_step, B.RTP_CW, 0) == B.RTP_ERR_STATE          # twice
+    assert status(ring.rotate_step, B.RTP_CW, 1) == B.RTP_ERR_STATE          # linear lags behind
+    assert status(lin.fwd, 1, None, None) == B.RTP_ERR_STATE                 # skips step 0
+    assert status(lin.bwd, 0, None, None, None) == B.RTP_ERR_STATE           # wrong pass
+    lin.fwd(0, None, None)
+    assert status(lin.fwd, 1, None, None) == B.RTP_ERR_STATE                 # shard 1 not staged yet
+    assert status(ring.end) == B.RTP_ERR_STATE                               # steps remain
+    ring.rotate_step(B.RTP_CW, 1)
+    lin.fwd(1, None, None)
+    ring.rotate_step(B.RTP_CW, 2)
+    lin.fwd(2, None, None)
+    assert status(ring.rotate_step, B.RTP_CW, 3) == B.RTP_ERR_STATE          # only n-1 rotations
+    lin.fwd(3, None, None)
+    assert status(lin.fwd, 4, None, None) == B.RTP_ERR_STATE
+    ring.end()
+    assert ring.resident() == 2
+    assert status(ring.end) == B.RTP_ERR_STATE
+    ring.close()
+
+
+def test_create_rejects_bad_descriptions():
+    def ring_status(**kw):
+        args = dict(n=4, rank=0, mode=B.RTP_DOUBLE_BUFFER, w_bytes=64, g_bytes=64, flags=B.RTP_FLAG_DRY_RUN)
+        args.update(kw)
+        try:
+            B.Ring(**args).close()
+            return B.RTP_OK
+        except B.RtpError as e:
+            return e.status
+
+    assert ring_status() == B.RTP_OK
+    assert ring_status(n=0) == B.RTP_ERR_SHAPE
+    assert ring_status(rank=4) == B.RTP_ERR_SHAPE
+    assert ring_status(w_bytes=24) == B.RTP_ERR_SHAPE
+    assert ring_status(mode=9) == B.RTP_ERR_INVALID
+    assert ring_status(flags=0) == B.RTP_ERR_INVALID           # real run with null device buffers
+
+    ring = _dry_ring(4, 0, B.RTP_DOUBLE_BUFFER, w=16 * 1024, g=32 * 1024)
+
+    def lin_status(**kw):
+        args = dict(T=8, I=64, O=64, split=B.RTP_SPLIT_OUT, dtype=B.RTP_BF16)
+        args.update(kw)
+        try:
+            B.Linear(ring, **args).close()
+            return B.RTP_OK
+        except B.RtpError as e:
+            return e.status
+
+    assert lin_status() == B.RTP_OK
+    assert lin_status(O=66) == B.RTP_ERR_SHAPE                 # 4 does not divide 66
+    assert lin_status(O=48) == B.RTP_ERR_SHAPE                 # shard width 12 is not a multiple of 8
+    assert lin_status(I=60) == B.RTP_ERR_SHAPE
+    assert lin_status(I=0) == B.RTP_ERR_SHAPE
+    assert lin_status(dtype=B.RTP_F16) == B.RTP_ERR_UNSUPPORTED
+    assert lin_status(grad_dtype=B.RTP_BF16) == B.RTP_ERR_UNSUPPORTED
+    assert lin_status(O=4096) == B.RTP_ERR_SHAPE               # shard larger than the slot
+    assert lin_status(w_offset=8) == B.RTP_ERR_SHAPE
+    assert lin_status(split=5) == B.RTP_ERR_INVALID
+    assert lin_status(dtype=B.RTP_F32, O=12, I=3) == B.RTP_OK  # fp32 has no alignment rule
+    ring.close()
+    assert B.lib.rtp_status_str(B.RTP_ERR_STATE) == b"RTP_ERR_STATE"
+
+
+def test_mlp_slot_sizes():
+    d = B.rtp_mlp_desc()
+    d.T, d.I, d.O, d.O2, d.n, d.dtype, d.act = 4096, 4096, 11008, 4096, 8, B.RTP_BF16, B.RTP_ACT_SWIGLU
+    assert B.lib.rtp_mlp_slot_w_bytes(C.byref(d)) == 3 * 1376 * 4096 * 2
+    assert B.lib.rtp_mlp_slot_g_bytes(C.byref(d)) == 3 * 1376 * 4096 * 4
+    d.act, d.I, d.O, d.O2, d.n, d.T = B.RTP_ACT_GELU_ERF, 8192, 28672, 8192, 16, 2048
+    w, g = B.lib.rtp_mlp_slot_w_bytes(C.byref(d)), B.lib.rtp_mlp_slot_g_bytes(C.byref(d))
+    assert (w, g) == (58720256, 117440512)
+    # the large config's footprint against the table's per-worker bound
+    assert B.rtp_worker_bytes(B.RTP_INPLACE_STAGED, w, g) == 234881024
+    assert B.rtp_table1_worker_bytes(False, w, g) == orc.worker_param_bytes("rtp", 939524096, 1879048192, 16)
