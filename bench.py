@@ -1,0 +1,168 @@
+"""Benchmark of the rotated-shard MLP unit on one MI355X.
+
+A "step" is one whole pass of the hot path over one batch: the forward
+rotation (N steps) and the backward rotation (N steps) of the Llama-7B-shaped
+SwiGLU MLP unit with N = 8 virtual shards staged in place on a second stream.
+Inputs are synthetic, seeded and resident in HBM before the timed region.
+
+Prints ONE JSON line: whole-job TFLOP/s (6 T I O flops per matrix), the
+roofline of the dominant kernel (per-launch HIP-event timing in an
+instrumented repeat of the same steps), the fraction of shard staging hidden
+under compute (three-run method), and the CPU oracle timed on a bounded
+token sample on this host.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published)
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg4_llama7b_swiglu")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true", help="skip the three-run staging-overlap measurement")
+    ap.add_argument("--cpu-tokens", type=int, default=48, help="tokens in the oracle's timed sample")
+    return ap.parse_args()
+
+
+def build_inputs(w, torch, dev):
+    import numpy as np
+    import rtp_workloads as wl
+    inp = wl.make_inputs(w, seed=0)
+    bf = torch.bfloat16
+    to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev, bf)
+    if w.kind == "swiglu":
+        weights = [to(inp[k]) for k in ("Wg", "Wu", "Wd")]
+    else:
+        weights = [to(inp[k]) for k in ("W1", "W2")]
+    return inp, weights, to(inp["X"]), to(inp["dY"])
+
+
+def timed(torch, mlp, X, Y, dY, dX, steps, fwd=True, bwd=True):
+    """ms for `steps` fwd+bwd passes, HIP events on the compute stream."""
+    s = mlp.compute_stream
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(s)
+    for _ in range(steps):
+        mlp.forward(X, Y)
+        mlp.backward(X, dY, dX)
+    e1.record(s)
+    mlp.sync()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1)
+
+
+def cpu_baseline(w, inp, tokens):
+    """The oracle as it stands, one worker's full rotated fwd+bwd over a token
+    sample (the first `tokens` rows), timed on this host's cores."""
+    import numpy as np
+    import oracle as orc
+    f64 = lambda a: np.ascontiguousarray(a, dtype=np.float64)
+    X, dY = f64(inp["X"][:tokens]), f64(inp["dY"][:tokens])
+    if w.kind == "swiglu":
+        Ws = [f64(inp[k]) for k in ("Wg", "Wu", "Wd")]
+        t0 = time.perf_counter()
+        orc.rtp_swiglu(X, *Ws, dY, w.n, 0)
+        dt = time.perf_counter() - t0
+        flops = 6.0 * tokens * (2 * w.I * w.O + w.O * w.O2)
+    else:
+        Ws = [f64(inp[k]) for k in ("W1", "W2")]
+        t0 = time.perf_counter()
+        orc.rtp_mlp(X, *Ws, dY, w.n, 0)
+        dt = time.perf_counter() - t0
+        flops = 6.0 * tokens * (w.I * w.O + w.O * w.O2)
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"first {tokens} of {w.T} tokens, full weights, all {w.n} rotation steps fwd+bwd, "
+                      f"{dt:.1f} s, fp64 triple loops"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs one worker on one GPU (N virtual shards on the same device); "
+              "--gpus above 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import rtp_workloads as wl
+    from paper_2311_01635_amd import binding as B
+    from paper_2311_01635_amd.layers import RtpMlp
+
+    dev = torch.device("cuda:0")
+    w = wl.CONFIGS[a.workload]
+    inp, weights, X, dY = build_inputs(w, torch, dev)
+    act = B.RTP_ACT_SWIGLU if w.kind == "swiglu" else B.RTP_ACT_GELU_ERF
+    mode = {"double_buffer": B.RTP_DOUBLE_BUFFER, "inplace_staged": B.RTP_INPLACE_STAGED}[w.mode]
+    mlp = RtpMlp(weights, w.T, w.n, 0, act, mode, B.RTP_BF16)
+    Y = torch.empty(w.T, w.O2, device=dev, dtype=torch.bfloat16)
+    dX = torch.empty(w.T, w.I, device=dev, dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+
+    timed(torch, mlp, X, Y, dY, dX, a.warmup)
+    ms = timed(torch, mlp, X, Y, dY, dX, a.steps)
+    ms_step = ms / a.steps
+    tflops = w.flops / (ms_step * 1e-3) / 1e12
+
+    # ---- dominant kernel, instrumented repeat of the same steps --------------------
+    B.rtp_prof_begin()
+    timed(torch, mlp, X, Y, dY, dX, a.steps)
+    prof = B.rtp_prof_end()
+    dom = max(prof, key=lambda k: prof[k][1])
+    launches, tot_ms, tot_flops = prof[dom]
+    achieved = tot_flops / (tot_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": B.rtp_gemm_kernel_name({"nt": 0, "nn": 1, "tn": 2}[dom], 1),
+                "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                "avg_launch_us": tot_ms * 1e3 / launches, "launches_per_step": launches / a.steps,
+                "flops_per_launch": tot_flops / launches, "traffic": None,
+                "per_kernel": {k: {"launches_per_step": v[0] / a.steps, "avg_us": v[1] * 1e3 / max(v[0], 1),
+                                   "tflops": v[2] / max(v[1], 1e-9) / 1e9} for k, v in prof.items()}}
+
+    # ---- how much of the shard staging hides under compute -------------------------
+    overlap = None
+    if not a.no_overlap and w.n > 1:
+        k = max(3, a.steps // 2)
+        mlp.set_ablation(rotate=False, compute=True)
+        timed(torch, mlp, X, Y, dY, dX, 2)
+        t_c = timed(torch, mlp, X, Y, dY, dX, k) / k
+        mlp.set_ablation(rotate=True, compute=False)
+        timed(torch, mlp, X, Y, dY, dX, 2)
+        t_s = timed(torch, mlp, X, Y, dY, dX, k) / k
+        mlp.set_ablation(rotate=True, compute=True)
+        timed(torch, mlp, X, Y, dY, dX, 2)
+        t_b = timed(torch, mlp, X, Y, dY, dX, k) / k
+        hidden = 1.0 - max(0.0, t_b - t_c) / t_s if t_s > 0 else None
+        overlap = {"ms_compute_only": t_c, "ms_staging_only": t_s, "ms_both": t_b, "rotation_hidden_frac": hidden}
+
+    cpu = None
+    if not a.no_cpu_baseline:
+        cpu = cpu_baseline(w, inp, a.cpu_tokens)
+
+    out = {
+        "metric": "TFLOP/s rotated-shard linear fwd+bwd per GPU", "value": tflops, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "T": w.T, "I": w.I, "O": w.O, "O2": w.O2, "n_shards": w.n, "mode": w.mode,
+                   "grad_dtype": "f32", "flops_per_step": w.flops,
+                   "worker_param_bytes": mlp.worker_bytes(),
+                   "table1_rtp_worker_bytes": B.rtp_table1_worker_bytes(False, mlp.w_bytes, mlp.g_bytes)},
+        "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
+        "roofline": roofline, "overlap": overlap, "cpu_baseline": cpu,
+    }
+    mlp.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

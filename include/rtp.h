@@ -284,6 +284,18 @@ rtp_status rtp_gemm(int layout, rtp_dtype in_dtype, rtp_dtype out_dtype, int acc
  * behind a layout and a non-zero variant; "" if there is none. */
 const char *rtp_gemm_kernel_name(int layout, int variant);
 
+/* ---- per-launch timing of the bf16 GEMM kernels -------------------------- */
+
+/* Between rtp_prof_begin() and rtp_prof_end() every bf16 GEMM launch the
+ * library makes (from any entry point) is bracketed by HIP events on the
+ * stream it is launched on.  rtp_prof_end() waits for them and fills
+ * out[layout] (0 NT, 1 NN, 2 TN) with the number of launches, the sum of
+ * their durations and the sum of their flops (2 M N K each).  Process-wide,
+ * not thread-safe; meant for benchmarks. */
+typedef struct { int64_t launches; double total_ms; double total_flops; } rtp_prof_result;
+rtp_status rtp_prof_begin(void);
+rtp_status rtp_prof_end(rtp_prof_result out[3]);
+
 #ifdef __cplusplus
 }
 #endif

@@ -50,6 +50,10 @@ class rtp_mlp_desc(C.Structure):
                 ("compute_stream", C.c_void_p), ("stage_stream", C.c_void_p)]
 
 
+class rtp_prof_result(C.Structure):
+    _fields_ = [("launches", C.c_int64), ("total_ms", C.c_double), ("total_flops", C.c_double)]
+
+
 class rtp_trace_rec(C.Structure):
     _fields_ = [("kind", C.c_int), ("pass_", C.c_int), ("step", C.c_int), ("shard", C.c_int), ("buffer", C.c_int)]
 
@@ -91,6 +95,8 @@ SYMBOLS = {
     "rtp_gemm": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, _P, C.c_int64, _P, C.c_int64, _P, C.c_int64,
                            C.c_int64, C.c_int64, C.c_int64, C.c_int, _P]),
     "rtp_gemm_kernel_name": (C.c_char_p, [C.c_int, C.c_int]),
+    "rtp_prof_begin": (C.c_int, []),
+    "rtp_prof_end": (C.c_int, [C.POINTER(rtp_prof_result)]),
 }
 
 
@@ -246,3 +252,14 @@ def rtp_gemm(layout, in_dtype, out_dtype, accumulate, A, lda, B, ldb, Cmat, ldc,
 
 def rtp_gemm_kernel_name(layout, variant):
     return lib.rtp_gemm_kernel_name(layout, variant).decode()
+
+
+def rtp_prof_begin():
+    check(lib.rtp_prof_begin(), "rtp_prof_begin")
+
+
+def rtp_prof_end():
+    """{layout name: (launches, total_ms, total_flops)}"""
+    out = (rtp_prof_result * 3)()
+    check(lib.rtp_prof_end(out), "rtp_prof_end")
+    return {name: (out[i].launches, out[i].total_ms, out[i].total_flops) for i, name in enumerate(("nt", "nn", "tn"))}

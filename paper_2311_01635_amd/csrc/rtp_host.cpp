@@ -59,6 +59,68 @@ extern "C" const char *rtp_status_str(rtp_status s)
 }
 
 // ---------------------------------------------------------------------------
+// per-launch timing of the GEMM kernels (opt-in, for the roofline figures)
+// ---------------------------------------------------------------------------
+struct ProfRec {
+    int layout;
+    double flops;
+    hipEvent_t start, stop;
+};
+static bool g_prof_on = false;
+static std::vector<ProfRec> g_prof;
+
+extern "C" rtp_status rtp_prof_begin(void)
+{
+    if (g_prof_on) return fail(RTP_ERR_STATE, "rtp_prof_begin: already collecting");
+    g_prof.clear();
+    g_prof_on = true;
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_prof_end(rtp_prof_result out[3])
+{
+    if (!g_prof_on) return fail(RTP_ERR_STATE, "rtp_prof_end: not collecting");
+    g_prof_on = false;
+    if (out) memset(out, 0, 3 * sizeof(rtp_prof_result));
+    rtp_status st = RTP_OK;
+    for (ProfRec &r : g_prof) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(r.stop);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.start, r.stop);
+        if (e != hipSuccess && st == RTP_OK) st = fail(RTP_ERR_HIP, "rtp_prof_end: %s", hipGetErrorString(e));
+        if (out && e == hipSuccess) {
+            out[r.layout].launches += 1;
+            out[r.layout].total_ms += ms;
+            out[r.layout].total_flops += r.flops;
+        }
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    g_prof.clear();
+    return st;
+}
+
+// brackets one launch with events on its own stream when collecting
+template <class F>
+static hipError_t timed_launch(int layout, double flops, hipStream_t s, F launch)
+{
+    if (!g_prof_on) return launch();
+    ProfRec r{layout, flops, nullptr, nullptr};
+    hipError_t e = hipEventCreate(&r.start);
+    if (e != hipSuccess) return e;
+    e = hipEventCreate(&r.stop);
+    if (e != hipSuccess) return e;
+    e = hipEventRecord(r.start, s);
+    if (e != hipSuccess) return e;
+    e = launch();
+    if (e != hipSuccess) return e;
+    e = hipEventRecord(r.stop, s);
+    if (e != hipSuccess) return e;
+    g_prof.push_back(r);
+    return hipSuccess;
+}
+
+// ---------------------------------------------------------------------------
 // schedule (Design section, workflow paragraph)
 // ---------------------------------------------------------------------------
 extern "C" int rtp_fwd_shard(int rank, int step, int n)
@@ -473,7 +535,7 @@ extern "C" rtp_status rtp_linear_create(rtp_linear **out, rtp_ring *ring, const 
     if ((d->w_offset & 15) || (d->g_offset & 15)) return fail(RTP_ERR_SHAPE, "rtp_linear_create: offsets must be multiples of 16");
     if (d->w_offset + wsz > ring->d.w_bytes || d->g_offset + gsz > ring->d.g_bytes)
         return fail(RTP_ERR_SHAPE, "rtp_linear_create: the shard does not fit the ring's slot");
-    if (!ring->dry) {
+    if (!ring->dry && d->T > 0) {
         if (d->act != RTP_ACT_NONE && !d->preact_dev)
             return fail(RTP_ERR_INVALID, "rtp_linear_create: an activation needs the pre-activation buffer");
         if (d->dtype != RTP_F32 && n > 1 && !d->acc_ws_dev)
@@ -527,7 +589,8 @@ static rtp_status gemm(rtp_linear *l, int layout, GemmArgs &a)
     rtp_ring *r = l->ring;
     if (r->dry || !r->abl_compute) return RTP_OK;
     if (l->d.dtype == RTP_BF16)
-        HIP_TRY(launch_gemm_bf16(layout, a, 0, r->cs()));
+        HIP_TRY(timed_launch(layout, 2.0 * a.M * a.N * a.K, r->cs(),
+                             [&] { return launch_gemm_bf16(layout, a, 0, r->cs()); }));
     else
         HIP_TRY(launch_gemm_f32(layout, a, r->cs()));
     return RTP_OK;
@@ -537,7 +600,7 @@ extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, voi
 {
     if (!l) return fail(RTP_ERR_INVALID, "rtp_linear_fwd: null linear");
     rtp_ring *r = l->ring;
-    if (!r->dry && (!X || !Y)) return fail(RTP_ERR_INVALID, "rtp_linear_fwd: null tensor");
+    if (!r->dry && l->d.T > 0 && (!X || !Y)) return fail(RTP_ERR_INVALID, "rtp_linear_fwd: null tensor");
     RTP_TRY(enter_step(r, l, step, RTP_PASS_FWD, "rtp_linear_fwd"));
     const rtp_linear_desc &d = l->d;
     const int n = r->d.n;
@@ -579,7 +642,6 @@ extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, voi
             }
         }
     } else {
-        if (d.act != RTP_ACT_NONE && false) return fail(RTP_ERR_UNSUPPORTED, "unreachable");
         a.A = (const char *)X + (size_t)k * o * es; a.lda = d.I;
         a.B = Wk; a.ldb = o;
         a.M = (int)d.T; a.N = (int)d.O; a.K = (int)o;
@@ -600,7 +662,7 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
 {
     if (!l) return fail(RTP_ERR_INVALID, "rtp_linear_bwd: null linear");
     rtp_ring *r = l->ring;
-    if (!r->dry && (!X || !dY)) return fail(RTP_ERR_INVALID, "rtp_linear_bwd: null tensor");
+    if (!r->dry && l->d.T > 0 && (!X || !dY)) return fail(RTP_ERR_INVALID, "rtp_linear_bwd: null tensor");
     RTP_TRY(enter_step(r, l, step, RTP_PASS_BWD, "rtp_linear_bwd"));
     const rtp_linear_desc &d = l->d;
     const int n = r->d.n;
@@ -660,7 +722,7 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
     }
 
     // ---- input gradient ----------------------------------------------------------
-    if (dX || r->dry) {
+    if ((dX && d.T > 0) || r->dry) {
         memset(&a, 0, sizeof a);
         a.c_is_f32 = f32;
         if (d.split == RTP_SPLIT_OUT) {
@@ -856,7 +918,8 @@ extern "C" rtp_status rtp_gemm(int layout, rtp_dtype in_dtype, rtp_dtype out_dty
     a.c_is_f32 = out_dtype == RTP_F32;
     if (in_dtype == RTP_BF16) {
         if (out_dtype != RTP_F32 && out_dtype != RTP_BF16) return fail(RTP_ERR_UNSUPPORTED, "rtp_gemm: bad output type");
-        hipError_t e = launch_gemm_bf16(layout, a, variant, (hipStream_t)stream);
+        hipError_t e = timed_launch(layout, 2.0 * a.M * a.N * a.K, (hipStream_t)stream,
+                                    [&] { return launch_gemm_bf16(layout, a, variant, (hipStream_t)stream); });
         if (e == hipErrorInvalidValue) return fail(RTP_ERR_SHAPE, "rtp_gemm: sizes/alignment the bf16 kernels need are not met");
         HIP_TRY(e);
     } else if (in_dtype == RTP_F32) {

@@ -63,10 +63,13 @@ CONFIGS = {
 def round_to_bf16(x):
     """fp32 array -> fp32 array holding the nearest bf16 values (ties to even)."""
     x = np.ascontiguousarray(x, dtype=np.float32)
-    u = x.view(np.uint32).astype(np.uint64)
-    bias = ((u >> 16) & 1) + 0x7FFF
-    u = ((u + bias) & 0xFFFF0000).astype(np.uint32)
-    return u.view(np.float32).reshape(x.shape)
+    u = x.view(np.uint32)
+    # finite inputs only: the carry of the rounding add never reaches the sign bit
+    r = (u >> np.uint32(16)) & np.uint32(1)
+    r += np.uint32(0x7FFF)
+    r += u
+    r &= np.uint32(0xFFFF0000)
+    return r.view(np.float32).reshape(x.shape)
 
 
 def _store(x, dtype):
