@@ -15,51 +15,15 @@
 // accumulators stay in registers (v_mfma_f32_32x32x16_bf16, fp32) and the
 // epilogue writes straight into the column slice / accumulator the step
 // targets, which is how the paper's concat and add layers disappear.
-#include "rtp_kernels.h"
+#include "rtp_gemm_epilogue.h"
 
 namespace rtp {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
-typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
-
 constexpr int BK = 64;      // K extent of one LDS stage
-constexpr int MC_PAD = 16;  // elements of padding per K-row of an M/N-contiguous tile:
-                            // 32 bytes, so the 4 rows one transposing read touches
-                            // fall in different banks
-
-// ---- activations (fp32) ---------------------------------------------------
-__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
-__device__ __forceinline__ float gelu_erf_grad(float x)
-{
-    const float Phi = 0.5f * (1.0f + erff(x * 0.70710678118654752f));
-    const float phi = 0.3989422804014327f * __expf(-0.5f * x * x);
-    return Phi + x * phi;
-}
-__device__ __forceinline__ float gelu_tanh(float x)
-{
-    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    return 0.5f * x * (1.0f + tanhf(u));
-}
-__device__ __forceinline__ float gelu_tanh_grad(float x)
-{
-    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    const float th = tanhf(u);
-    const float du = 0.7978845608028654f * (1.0f + 3.0f * 0.044715f * x * x);
-    return 0.5f * (1.0f + th) + 0.5f * x * (1.0f - th * th) * du;
-}
-__device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + __expf(-x)); }
-__device__ __forceinline__ float silu(float x) { return x * sigmoidf_(x); }
-__device__ __forceinline__ float silu_grad(float x)
-{
-    const float s = sigmoidf_(x);
-    return s * (1.0f + x * (1.0f - s));
-}
-
-__device__ __forceinline__ float bf2f(__bf16 v) { return (float)v; }
+constexpr int MC_PAD = 32;  // elements of padding per K-row of an M/N-contiguous tile:
+                            // 64 bytes, so that the 4 K-rows x 2 column groups one
+                            // transposing read touches cover all 64 banks once
+                            // (row length mod 256 bytes must be 64 or 192)
 
 // ---- tile geometry ----------------------------------------------------------
 template <int BM, int BN, int WM, int WN, int LAY>
@@ -79,6 +43,7 @@ struct Cfg {
     static_assert(FM >= 1 && FN >= 1 && A_CH >= 1 && B_CH >= 1, "tile too small for the wave grid");
     static_assert(FN % 2 == 0 || LAY != LAY_NT, "paired epilogue needs an even fragment count");
     static_assert(2 * STAGE <= 160 * 1024, "two stages must fit the 160 KB LDS");
+    static_assert((A_LD * 2) % 128 == 64 && (B_LD * 2) % 128 == 64, "padded rows must shift by half the bank space");
 };
 
 // One operand's HBM -> LDS path for a stage.  R = rows (K-contiguous) or
@@ -102,7 +67,7 @@ struct Loader {
             if (KC) {
                 const int row = c >> 3, kc = c & 7;
                 gp[i] = (const char *)base + ((int64_t)rowmap(row) * ld + kc * 8) * 2;
-                lds_off[i] = row * 128 + ((kc ^ (row & 7)) << 4);
+                lds_off[i] = row * 128 + ((kc ^ ((row >> 1) & 7)) << 4);
                 kpos[i] = kc * 8;
             } else {
                 constexpr int CPR = R / 8; // chunks per K-row
@@ -142,8 +107,11 @@ struct Loader {
     }
 };
 
-// Fragment of a K-contiguous stage: 8 consecutive k of one row per lane.
-// rowbyte = row * 128, sw = (row & 7) ^ (lane >> 5) packed as the chunk xor.
+// Fragment of a K-contiguous stage: 8 consecutive k of one row per lane.  A
+// row is 128 bytes (8 chunks of 16); chunk c of row r sits at chunk slot
+// c ^ ((r >> 1) & 7), which spreads the 32 rows one ds_read_b128 touches over
+// all 64 banks.  base_off already holds the slot of K-step 0; K-step ks
+// flips chunk bits 1..2.
 __device__ __forceinline__ bf16x8 frag_kc(const char *stage, int base_off, int ks)
 {
     return *(const bf16x8 *)(stage + (base_off ^ (ks << 5)));
@@ -230,7 +198,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(const GemmArgs p
         const int rb = wm * (BM / WM) + f * 32;
         if (C::A_KC) {
             const int row = rb + (lane & 31);
-            a_off[f] = row * 128 + ((((lane >> 5)) ^ (row & 7)) << 4);
+            a_off[f] = row * 128 + ((((lane >> 5)) ^ ((row >> 1) & 7)) << 4);
         } else {
             const int q = lane >> 4, i = lane & 15;
             const int col = rb + (q & 1) * 16 + (i & 3) * 4;
@@ -243,7 +211,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(const GemmArgs p
         const int rb = f * (WN * 32) + wn * 32;
         if (C::B_KC) {
             const int row = rb + (lane & 31);
-            b_off[f] = row * 128 + ((((lane >> 5)) ^ (row & 7)) << 4);
+            b_off[f] = row * 128 + ((((lane >> 5)) ^ ((row >> 1) & 7)) << 4);
         } else {
             const int q = lane >> 4, i = lane & 15;
             const int col = rb + (q & 1) * 16 + (i & 3) * 4;
@@ -314,111 +282,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(const GemmArgs p
     }
 
     // ---- epilogue -------------------------------------------------------------------
-    // acc[i][j][v] is C[row, col] with
-    //   row = m0 + wm*(BM/WM) + i*32 + 8*(v/4) + 4*(lane/32) + v%4
-    //   col = n0 + j*(WN*32) + wn*32 + lane%32          (tile-local for the paired form)
-    const int rbase = m0 + wm * (BM / WM) + 4 * (lane >> 5);
-    const int cl = wn * 32 + (lane & 31);
-    __bf16 *Cb = (__bf16 *)p.C;
-    float *Cf = (float *)p.C;
-    const __bf16 *auxr = (const __bf16 *)p.aux;
-    __bf16 *auxw = (__bf16 *)p.aux;
-
-    if (paired) {
-        const int half = p.half;
-#pragma unroll
-        for (int i = 0; i < C::FM; ++i)
-#pragma unroll
-            for (int j = 0; j < C::FN / 2; ++j) {
-                const int col = n0 + j * (WN * 32) + cl;
-                if (col >= half) continue;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = rbase + i * 32 + 8 * (v >> 2) + (v & 3);
-                    if (row >= M) continue;
-                    const float a = acc[i][j][v], b = acc[i][j + C::FN / 2][v];
-                    auxw[(int64_t)row * p.ldaux + col] = (__bf16)a;
-                    auxw[(int64_t)row * p.ldaux + half + col] = (__bf16)b;
-                    Cb[(int64_t)row * p.ldc + col] = (__bf16)(silu(a) * b);
-                }
-            }
-        return;
-    }
-
-    // visit every valid element of the tile; the branch on the epilogue kind
-    // stays outside the unrolled loops
-    auto each = [&](auto fn) {
-#pragma unroll
-        for (int i = 0; i < C::FM; ++i)
-#pragma unroll
-            for (int j = 0; j < C::FN; ++j) {
-                const int col = n0 + j * (WN * 32) + cl;
-                if (col >= N) continue;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = rbase + i * 32 + 8 * (v >> 2) + (v & 3);
-                    if (row < M) fn(row, col, acc[i][j][v]);
-                }
-            }
-    };
-    const int64_t ldc = p.ldc, ldws = p.ldws, ldaux = p.ldaux;
-    float *ws = p.ws;
-    switch (p.epi) {
-    case EPI_STORE:
-        if (p.c_is_f32)
-            each([&](int row, int col, float x) { Cf[(int64_t)row * ldc + col] = x; });
-        else
-            each([&](int row, int col, float x) { Cb[(int64_t)row * ldc + col] = (__bf16)x; });
-        break;
-    case EPI_ACC_FIRST:
-        each([&](int row, int col, float x) { ws[(int64_t)row * ldws + col] = x; });
-        break;
-    case EPI_ACC_ADD:
-        each([&](int row, int col, float x) { ws[(int64_t)row * ldws + col] += x; });
-        break;
-    case EPI_ACC_LAST:
-        if (p.c_is_f32)
-            each([&](int row, int col, float x) { Cf[(int64_t)row * ldc + col] = ws[(int64_t)row * ldws + col] + x; });
-        else
-            each([&](int row, int col, float x) {
-                Cb[(int64_t)row * ldc + col] = (__bf16)(ws[(int64_t)row * ldws + col] + x);
-            });
-        break;
-    case EPI_GELU_ERF_FWD:
-        each([&](int row, int col, float x) {
-            auxw[(int64_t)row * ldaux + col] = (__bf16)x;
-            Cb[(int64_t)row * ldc + col] = (__bf16)gelu_erf(x);
-        });
-        break;
-    case EPI_GELU_TANH_FWD:
-        each([&](int row, int col, float x) {
-            auxw[(int64_t)row * ldaux + col] = (__bf16)x;
-            Cb[(int64_t)row * ldc + col] = (__bf16)gelu_tanh(x);
-        });
-        break;
-    case EPI_GELU_ERF_BWD:
-        each([&](int row, int col, float x) {
-            Cb[(int64_t)row * ldc + col] = (__bf16)(x * gelu_erf_grad(bf2f(auxr[(int64_t)row * ldaux + col])));
-        });
-        break;
-    case EPI_GELU_TANH_BWD:
-        each([&](int row, int col, float x) {
-            Cb[(int64_t)row * ldc + col] = (__bf16)(x * gelu_tanh_grad(bf2f(auxr[(int64_t)row * ldaux + col])));
-        });
-        break;
-    case EPI_SWIGLU_BWD: {
-        const int half = p.half;
-        each([&](int row, int col, float x) {
-            const float a = bf2f(auxr[(int64_t)row * ldaux + col]);
-            const float b = bf2f(auxr[(int64_t)row * ldaux + half + col]);
-            Cb[(int64_t)row * ldc + col] = (__bf16)(x * b * silu_grad(a));
-            Cb[(int64_t)row * ldc + half + col] = (__bf16)(x * silu(a));
-        });
-        break;
-    }
-    default:
-        break;
-    }
+    gemm_epilogue<C::FM, C::FN, WN * 32>(p, acc, m0 + wm * (BM / WM) + 4 * (lane >> 5), n0, wn * 32 + (lane & 31));
 }
 
 // ---- host side ------------------------------------------------------------------------
@@ -433,8 +297,10 @@ static const Variant kVariants[] = {
     {0, 0, 0, 0, {"", "", ""}},
     {256, 256, 2, 4, {"gemm_bf16_256x256_nt", "gemm_bf16_256x256_nn", "gemm_bf16_256x256_tn"}},
     {128, 128, 2, 2, {"gemm_bf16_128x128_nt", "gemm_bf16_128x128_nn", "gemm_bf16_128x128_tn"}},
+    {256, 256, 2, 2, {"gemm_bf16_256x256w4_nt", "gemm_bf16_256x256w4_nn", "gemm_bf16_256x256w4_tn"}},
+    {256, 256, 2, 4, {"gemm_bf16_pp_kernel<0>", "gemm_bf16_pp_kernel<1>", "gemm_bf16_pp_kernel<2>"}},
 };
-constexpr int kNumVariants = 2;
+constexpr int kNumVariants = 4;
 
 const char *gemm_bf16_kernel_name(int layout, int variant)
 {
@@ -442,8 +308,10 @@ const char *gemm_bf16_kernel_name(int layout, int variant)
     return kVariants[variant].name[layout];
 }
 
-static int pick_variant(const GemmArgs &a)
+static int pick_variant(int layout, const GemmArgs &a)
 {
+    // the ping-pong kernel whenever its shape rules hold and there is at least a tile's worth of work
+    if (gemm_bf16_pp_supported(layout, a) && a.M >= 64 && a.N >= 64) return 4;
     // the large tile when it yields at least ~one workgroup per CU, else the small one
     const int ncols = a.epi == EPI_SWIGLU_FWD ? a.half : a.N;
     const int bn = a.epi == EPI_SWIGLU_FWD ? 128 : 256;
@@ -486,12 +354,18 @@ hipError_t launch_gemm_bf16(int layout, const GemmArgs &a, int variant, hipStrea
     if (layout == LAY_TN && ((a.M & 7) || a.M < 8)) return hipErrorInvalidValue;
     if (layout != LAY_NT && ((a.N & 7) || a.N < 8)) return hipErrorInvalidValue;
     if (a.epi == EPI_SWIGLU_FWD && (layout != LAY_NT || a.half * 2 != a.N)) return hipErrorInvalidValue;
-    if (variant == 0) variant = pick_variant(a);
+    if (variant == 0) variant = pick_variant(layout, a);
+    if (variant == 4) {
+        if (!gemm_bf16_pp_supported(layout, a)) return hipErrorInvalidValue;
+        return launch_gemm_bf16_pp(layout, a, s);
+    }
     switch (variant) {
     case 1:
         return launch_cfg<256, 256, 2, 4>(layout, a, s);
     case 2:
         return launch_cfg<128, 128, 2, 2>(layout, a, s);
+    case 3:
+        return launch_cfg<256, 256, 2, 2>(layout, a, s);
     default:
         return hipErrorInvalidValue;
     }

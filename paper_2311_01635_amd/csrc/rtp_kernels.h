@@ -37,8 +37,12 @@ struct GemmArgs {
     int c_is_f32;       // EPI_STORE / EPI_ACC_LAST write fp32 instead of the input dtype
 };
 
-// bf16 inputs, fp32 MFMA accumulation.  variant: 0 = pick by shape.
+// bf16 inputs, fp32 MFMA accumulation.  variant: 0 = pick by shape; 1, 2, 3 = register-staged
+// tiles (256x256/8 waves, 128x128/4 waves, 256x256/4 waves); 4 = the ping-pong kernel.
 hipError_t launch_gemm_bf16(int layout, const GemmArgs &a, int variant, hipStream_t s);
+// the ping-pong kernel (rtp_gemm_pp.hip): needs K % 32 == 0
+bool gemm_bf16_pp_supported(int layout, const GemmArgs &a);
+hipError_t launch_gemm_bf16_pp(int layout, const GemmArgs &a, hipStream_t s);
 const char *gemm_bf16_kernel_name(int layout, int variant);
 
 // fp32 inputs and outputs (epi: EPI_STORE, EPI_ACC_ADD with ws == C).

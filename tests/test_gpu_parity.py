@@ -77,13 +77,17 @@ GEMM_SHAPES = [
     (1000, 1376, 320),
 ]
 # row counts that are not multiples of 8 are legal wherever the operand is contiguous along K
-GEMM_ODD = {B.LAYOUT_NT: [(301, 77, 72)], B.LAYOUT_NN: [(301, 72, 72)], B.LAYOUT_TN: [(72, 72, 301)]}
+GEMM_ODD = {B.LAYOUT_NT: [(301, 77, 72), (301, 77, 96)], B.LAYOUT_NN: [(301, 72, 72), (301, 72, 96)],
+            B.LAYOUT_TN: [(72, 72, 301), (72, 520, 320)]}
 
 
-@pytest.mark.parametrize("variant", [1, 2])
+# variants 1-3: register-staged tiles; variant 4: the ping-pong kernel (K must be a multiple of 32)
+@pytest.mark.parametrize("variant", [1, 2, 4])
 @pytest.mark.parametrize("layout", [B.LAYOUT_NT, B.LAYOUT_NN, B.LAYOUT_TN])
 def test_gemm_bf16_layouts_and_tails(layout, variant):
     for i, (M, N, K) in enumerate(GEMM_SHAPES + GEMM_ODD[layout]):
+        if variant == 4 and K % 32:
+            continue
         for accumulate, out_f32 in ((False, True), (True, True), (False, False)):
             say(f"gemm layout={layout} variant={variant} M={M} N={N} K={K} acc={accumulate} f32out={out_f32}")
             err = _gemm_case(layout, M, N, K, variant, accumulate, out_f32, seed=100 * layout + i)
