@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--workload", default="cfg4_llama7b_swiglu")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true", help="skip the three-run staging-overlap measurement")
-    ap.add_argument("--cpu-tokens", type=int, default=48, help="tokens in the oracle's timed sample")
+    ap.add_argument("--cpu-tokens", type=int, default=64, help="tokens in the oracle's timed sample")
     return ap.parse_args()
 
 
@@ -63,6 +63,19 @@ def timed(torch, mlp, X, Y, dY, dX, steps, fwd=True, bwd=True):
     mlp.sync()
     torch.cuda.synchronize()
     return e0.elapsed_time(e1)
+
+
+def measured_traffic(workload, layout):
+    """HBM bytes per launch of a GEMM kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs whose
+    summary is kept under profiles/ (counters cannot be read from inside this process); None if absent."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 2 and parts[0] == f"{layout}_bytes_per_launch":
+            return float(parts[1])
+    return None
 
 
 def cpu_baseline(w, inp, tokens):
@@ -122,10 +135,10 @@ def main():
     dom = max(prof, key=lambda k: prof[k][1])
     launches, tot_ms, tot_flops = prof[dom]
     achieved = tot_flops / (tot_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": B.rtp_gemm_kernel_name({"nt": 0, "nn": 1, "tn": 2}[dom], 1),
+    roofline = {"bound": "mfma", "kernel": B.rtp_gemm_kernel_name({"nt": 0, "nn": 1, "tn": 2}[dom], 4),
                 "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                 "avg_launch_us": tot_ms * 1e3 / launches, "launches_per_step": launches / a.steps,
-                "flops_per_launch": tot_flops / launches, "traffic": None,
+                "flops_per_launch": tot_flops / launches, "traffic": measured_traffic(w.name, dom),
                 "per_kernel": {k: {"launches_per_step": v[0] / a.steps, "avg_us": v[1] * 1e3 / max(v[0], 1),
                                    "tflops": v[2] / max(v[1], 1e-9) / 1e9} for k, v in prof.items()}}
 

@@ -154,4 +154,178 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, f32x16 (&acc)[F
     }
 }
 
+
+// ---- the same epilogue with 16-byte global accesses -----------------------------------
+// The accumulator layout gives a lane one column and 16 scattered rows, which
+// turns every fp32 read-modify-write or bf16 store into 2- or 4-byte accesses.
+// Here a wave first parks one 32-row fragment row of its tile in its own LDS
+// region (row pitch 288 bytes, so that the two half-waves of a ds_write_b32
+// fall into different banks), then reads it back four consecutive columns per
+// lane and touches global memory with float4 / 4 x bf16 accesses: whole 128-byte
+// lines per row segment.  Needs every leading dimension to be a multiple of 4
+// elements and 16-byte aligned bases; callers fall back to gemm_epilogue()
+// otherwise.  No workgroup barrier: a wave only reads what it wrote.
+constexpr int EPI_LDS_PITCH = 72;                       // floats per staged row (64 columns + pad)
+constexpr int EPI_LDS_BYTES_PER_WAVE = 32 * EPI_LDS_PITCH * 4;
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+
+__device__ __forceinline__ bf16x4 to_bf16x4(f32x4 x)
+{
+    bf16x4 r;
+    r.x = (__bf16)x.x; r.y = (__bf16)x.y; r.z = (__bf16)x.z; r.w = (__bf16)x.w;
+    return r;
+}
+__device__ __forceinline__ f32x4 from_bf16x4(bf16x4 x)
+{
+    f32x4 r;
+    r.x = (float)x.x; r.y = (float)x.y; r.z = (float)x.z; r.w = (float)x.w;
+    return r;
+}
+template <class F>
+__device__ __forceinline__ f32x4 map4(f32x4 x, F f)
+{
+    f32x4 r;
+    r.x = f(x.x); r.y = f(x.y); r.z = f(x.z); r.w = f(x.w);
+    return r;
+}
+
+__host__ __device__ inline bool gemm_epilogue_vec_ok(const GemmArgs &p)
+{
+    auto al = [](const void *q, int a) { return ((uintptr_t)q & (uintptr_t)(a - 1)) == 0; };
+    bool ok = (p.ldc & 3) == 0 && al(p.C, 16);
+    if (p.epi == EPI_ACC_FIRST || p.epi == EPI_ACC_ADD || p.epi == EPI_ACC_LAST) ok = ok && (p.ldws & 3) == 0 && al(p.ws, 16);
+    if (p.epi >= EPI_GELU_ERF_FWD) ok = ok && (p.ldaux & 3) == 0 && al(p.aux, 8) && (p.half & 3) == 0;
+    return ok && (p.N & 3) == 0;
+}
+
+template <int FM, int FN, int NSTRIDE>
+__device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (&acc)[FM][FN], float *wlds,
+                                                     int rbase_wave, int n0, int wn32, int lane)
+{
+    static_assert(FN == 2, "staging layout is written for two 32-column fragments per wave");
+    const int M = p.M, N = p.N;
+    const int64_t ldc = p.ldc, ldws = p.ldws, ldaux = p.ldaux;
+    const int half = p.half;
+    __bf16 *Cb = (__bf16 *)p.C;
+    float *Cf = (float *)p.C;
+    __bf16 *aux = (__bf16 *)p.aux;
+    float *ws = p.ws;
+    const int wrow = 4 * (lane >> 5), wcol = lane & 31;
+
+    // park fragment row i: rows 8*(v/4) + 4*(lane/32) + v%4, columns j*32 + lane%32
+    auto park = [&](int i) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                wlds[(8 * (v >> 2) + wrow + (v & 3)) * EPI_LDS_PITCH + j * 32 + wcol] = acc[i][j][v];
+        __builtin_amdgcn_s_waitcnt(0xc07f); // lgkmcnt(0): the wave's own writes have landed
+        __builtin_amdgcn_wave_barrier();
+    };
+
+    if (p.epi == EPI_SWIGLU_FWD) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            park(i);
+            // a lane takes the gate and the up value of the same 4 columns
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = 8 * r + (lane >> 3), c = (lane & 7) * 4;
+                const f32x4 a = *(const f32x4 *)(wlds + row * EPI_LDS_PITCH + c);
+                const f32x4 b = *(const f32x4 *)(wlds + row * EPI_LDS_PITCH + 32 + c);
+                const int grow = rbase_wave + i * 32 + row, col = n0 + wn32 + c;
+                if (grow < M && col < half) {
+                    *(bf16x4 *)(aux + (int64_t)grow * ldaux + col) = to_bf16x4(a);
+                    *(bf16x4 *)(aux + (int64_t)grow * ldaux + half + col) = to_bf16x4(b);
+                    f32x4 h;
+                    h.x = silu(a.x) * b.x; h.y = silu(a.y) * b.y; h.z = silu(a.z) * b.z; h.w = silu(a.w) * b.w;
+                    *(bf16x4 *)(Cb + (int64_t)grow * ldc + col) = to_bf16x4(h);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        return;
+    }
+
+    // every valid group of 4 consecutive columns; the branch on the kind stays outside the loops
+    auto each = [&](auto op) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            park(i);
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const int row = 4 * r + (lane >> 4), c4 = lane & 15;
+                const f32x4 x = *(const f32x4 *)(wlds + row * EPI_LDS_PITCH + c4 * 4);
+                const int grow = rbase_wave + i * 32 + row;
+                const int col = n0 + (c4 >> 3) * NSTRIDE + wn32 + (c4 & 7) * 4;
+                if (grow < M && col < N) op(grow, col, x);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    };
+    switch (p.epi) {
+    case EPI_STORE:
+        if (p.c_is_f32)
+            each([&](int r, int c, f32x4 x) { *(f32x4 *)(Cf + (int64_t)r * ldc + c) = x; });
+        else
+            each([&](int r, int c, f32x4 x) { *(bf16x4 *)(Cb + (int64_t)r * ldc + c) = to_bf16x4(x); });
+        break;
+    case EPI_ACC_FIRST:
+        each([&](int r, int c, f32x4 x) { *(f32x4 *)(ws + (int64_t)r * ldws + c) = x; });
+        break;
+    case EPI_ACC_ADD:
+        each([&](int r, int c, f32x4 x) {
+            f32x4 *q = (f32x4 *)(ws + (int64_t)r * ldws + c);
+            *q = *q + x;
+        });
+        break;
+    case EPI_ACC_LAST:
+        if (p.c_is_f32)
+            each([&](int r, int c, f32x4 x) {
+                *(f32x4 *)(Cf + (int64_t)r * ldc + c) = *(const f32x4 *)(ws + (int64_t)r * ldws + c) + x;
+            });
+        else
+            each([&](int r, int c, f32x4 x) {
+                *(bf16x4 *)(Cb + (int64_t)r * ldc + c) = to_bf16x4(*(const f32x4 *)(ws + (int64_t)r * ldws + c) + x);
+            });
+        break;
+    case EPI_GELU_ERF_FWD:
+        each([&](int r, int c, f32x4 x) {
+            *(bf16x4 *)(aux + (int64_t)r * ldaux + c) = to_bf16x4(x);
+            *(bf16x4 *)(Cb + (int64_t)r * ldc + c) = to_bf16x4(map4(x, [](float t) { return gelu_erf(t); }));
+        });
+        break;
+    case EPI_GELU_TANH_FWD:
+        each([&](int r, int c, f32x4 x) {
+            *(bf16x4 *)(aux + (int64_t)r * ldaux + c) = to_bf16x4(x);
+            *(bf16x4 *)(Cb + (int64_t)r * ldc + c) = to_bf16x4(map4(x, [](float t) { return gelu_tanh(t); }));
+        });
+        break;
+    case EPI_GELU_ERF_BWD:
+        each([&](int r, int c, f32x4 x) {
+            const f32x4 z = from_bf16x4(*(const bf16x4 *)(aux + (int64_t)r * ldaux + c));
+            *(bf16x4 *)(Cb + (int64_t)r * ldc + c) = to_bf16x4(x * map4(z, [](float t) { return gelu_erf_grad(t); }));
+        });
+        break;
+    case EPI_GELU_TANH_BWD:
+        each([&](int r, int c, f32x4 x) {
+            const f32x4 z = from_bf16x4(*(const bf16x4 *)(aux + (int64_t)r * ldaux + c));
+            *(bf16x4 *)(Cb + (int64_t)r * ldc + c) = to_bf16x4(x * map4(z, [](float t) { return gelu_tanh_grad(t); }));
+        });
+        break;
+    case EPI_SWIGLU_BWD:
+        each([&](int r, int c, f32x4 x) {
+            const f32x4 a = from_bf16x4(*(const bf16x4 *)(aux + (int64_t)r * ldaux + c));
+            const f32x4 b = from_bf16x4(*(const bf16x4 *)(aux + (int64_t)r * ldaux + half + c));
+            *(bf16x4 *)(Cb + (int64_t)r * ldc + c) = to_bf16x4(x * b * map4(a, [](float t) { return silu_grad(t); }));
+            *(bf16x4 *)(Cb + (int64_t)r * ldc + half + c) = to_bf16x4(x * map4(a, [](float t) { return silu(t); }));
+        });
+        break;
+    default:
+        break;
+    }
+}
+
 } // namespace rtp

@@ -50,7 +50,8 @@ typedef __attribute__((address_space(1))) const void *glb_vp;
 } // namespace pp
 
 template <int LAY>
-__global__ __launch_bounds__(pp::NTHR) void gemm_bf16_pp_kernel(const GemmArgs p, const int tiles_m, const int tiles_n)
+__global__ __launch_bounds__(pp::NTHR) void gemm_bf16_pp_kernel(const GemmArgs p, const int tiles_m, const int tiles_n,
+                                                                 const int vec_epilogue)
 {
     using namespace pp;
     constexpr bool A_KC = (LAY != LAY_TN), B_KC = (LAY == LAY_NT);
@@ -239,9 +240,14 @@ __global__ __launch_bounds__(pp::NTHR) void gemm_bf16_pp_kernel(const GemmArgs p
         __builtin_amdgcn_sched_barrier(0);
     }
     if (group == 0) asm volatile("s_barrier" ::: "memory"); // every wave passes the same number of barriers
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // nothing may still be writing LDS when the wave ends
+    // the refetches past the end may still be landing in LDS: drain everybody's before LDS is reused
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
 
-    gemm_epilogue<FM, FN, WN * 32>(p, acc, m0 + wm * (BM / WM) + 4 * (lane >> 5), n0, wn * 32 + (lane & 31));
+    if (vec_epilogue)
+        gemm_epilogue_staged<FM, FN, WN * 32>(p, acc, (float *)(smem + wave * EPI_LDS_BYTES_PER_WAVE),
+                                              m0 + wm * (BM / WM), n0, wn * 32, lane);
+    else
+        gemm_epilogue<FM, FN, WN * 32>(p, acc, m0 + wm * (BM / WM) + 4 * (lane >> 5), n0, wn * 32 + (lane & 31));
 }
 
 bool gemm_bf16_pp_supported(int layout, const GemmArgs &a)
@@ -261,10 +267,11 @@ hipError_t launch_gemm_bf16_pp(int layout, const GemmArgs &a, hipStream_t s)
     const int bn = a.epi == EPI_SWIGLU_FWD ? BN / 2 : BN;
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (ncols + bn - 1) / bn;
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(NTHR);
+    const int vec = gemm_epilogue_vec_ok(a) ? 1 : 0;
     switch (layout) {
-    case LAY_NT: hipLaunchKernelGGL(gemm_bf16_pp_kernel<LAY_NT>, grid, block, 0, s, a, tiles_m, tiles_n); break;
-    case LAY_NN: hipLaunchKernelGGL(gemm_bf16_pp_kernel<LAY_NN>, grid, block, 0, s, a, tiles_m, tiles_n); break;
-    case LAY_TN: hipLaunchKernelGGL(gemm_bf16_pp_kernel<LAY_TN>, grid, block, 0, s, a, tiles_m, tiles_n); break;
+    case LAY_NT: hipLaunchKernelGGL(gemm_bf16_pp_kernel<LAY_NT>, grid, block, 0, s, a, tiles_m, tiles_n, vec); break;
+    case LAY_NN: hipLaunchKernelGGL(gemm_bf16_pp_kernel<LAY_NN>, grid, block, 0, s, a, tiles_m, tiles_n, vec); break;
+    case LAY_TN: hipLaunchKernelGGL(gemm_bf16_pp_kernel<LAY_TN>, grid, block, 0, s, a, tiles_m, tiles_n, vec); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
