@@ -7,7 +7,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librtp.so")
-SOURCES = ["rtp_gemm_bf16.hip", "rtp_gemm_pp.hip", "rtp_misc_kernels.hip", "rtp_host.cpp"]
+SOURCES = ["rtp_gemm_bf16.hip", "rtp_gemm_pp.hip", "rtp_gemm_pp_256.hip", "rtp_gemm_pp_192.hip", "rtp_gemm_pp_128.hip",
+           "rtp_misc_kernels.hip", "rtp_host.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -packed-fp32-ops off: the compiler must not form packed fp32 arithmetic from scalar code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -20,7 +21,7 @@ def _newer(dst, srcs):
 
 def build(force: bool = True, verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    headers = [os.path.join(CSRC, "rtp_kernels.h"), os.path.join(CSRC, "rtp_gemm_epilogue.h"), os.path.join(HERE, "..", "include", "rtp.h")]
+    headers = [os.path.join(CSRC, "rtp_kernels.h"), os.path.join(CSRC, "rtp_gemm_epilogue.h"), os.path.join(CSRC, "rtp_gemm_pp.h"), os.path.join(HERE, "..", "include", "rtp.h")]
 
     def compile_one(src):
         s = os.path.join(CSRC, src)
@@ -32,7 +33,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
             subprocess.run(cmd, check=True)
         return o
 
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=7) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     if force or not _newer(LIB, objs):
         subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs, check=True)

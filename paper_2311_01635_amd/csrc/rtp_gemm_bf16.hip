@@ -298,9 +298,12 @@ static const Variant kVariants[] = {
     {256, 256, 2, 4, {"gemm_bf16_256x256_nt", "gemm_bf16_256x256_nn", "gemm_bf16_256x256_tn"}},
     {128, 128, 2, 2, {"gemm_bf16_128x128_nt", "gemm_bf16_128x128_nn", "gemm_bf16_128x128_tn"}},
     {256, 256, 2, 2, {"gemm_bf16_256x256w4_nt", "gemm_bf16_256x256w4_nn", "gemm_bf16_256x256w4_tn"}},
-    {256, 256, 2, 4, {"gemm_bf16_pp_kernel<0>", "gemm_bf16_pp_kernel<1>", "gemm_bf16_pp_kernel<2>"}},
+    {256, 256, 2, 4, {"gemm_bf16_pp_kernel<0, *>", "gemm_bf16_pp_kernel<1, *>", "gemm_bf16_pp_kernel<2, *>"}},
+    {256, 256, 2, 4, {"gemm_bf16_pp_kernel<0, 256>", "gemm_bf16_pp_kernel<1, 256>", "gemm_bf16_pp_kernel<2, 256>"}},
+    {192, 256, 2, 4, {"gemm_bf16_pp_kernel<0, 192>", "gemm_bf16_pp_kernel<1, 192>", "gemm_bf16_pp_kernel<2, 192>"}},
+    {128, 256, 2, 4, {"gemm_bf16_pp_kernel<0, 128>", "gemm_bf16_pp_kernel<1, 128>", "gemm_bf16_pp_kernel<2, 128>"}},
 };
-constexpr int kNumVariants = 4;
+constexpr int kNumVariants = 7;
 
 const char *gemm_bf16_kernel_name(int layout, int variant)
 {
@@ -355,9 +358,10 @@ hipError_t launch_gemm_bf16(int layout, const GemmArgs &a, int variant, hipStrea
     if (layout != LAY_NT && ((a.N & 7) || a.N < 8)) return hipErrorInvalidValue;
     if (a.epi == EPI_SWIGLU_FWD && (layout != LAY_NT || a.half * 2 != a.N)) return hipErrorInvalidValue;
     if (variant == 0) variant = pick_variant(layout, a);
-    if (variant == 4) {
+    if (variant >= 4 && variant <= 7) {
         if (!gemm_bf16_pp_supported(layout, a)) return hipErrorInvalidValue;
-        return launch_gemm_bf16_pp(layout, a, s);
+        const int bm[4] = {0, 256, 192, 128};
+        return launch_gemm_bf16_pp(layout, a, bm[variant - 4], s);
     }
     switch (variant) {
     case 1:

@@ -1,0 +1,290 @@
+// bf16 partition GEMM for gfx950, "ping-pong" form: the kernel the rotated
+// linear layer uses whenever the contraction length is a multiple of 32.
+// (Template; instantiated per tile height in rtp_gemm_pp_<BM>.hip.)
+//
+// One workgroup of 8 waves owns a BM x 256 tile of C, BM = 256, 192 or 128
+// (wave tile BM/2 x 64, 32x32x16 bf16 MFMA, fp32 accumulators in registers).
+// K advances in sub-tiles of 32 through a ring of four LDS stages
+// (96 to 128 KB of the 160 KB LDS).
+//
+//  * HBM -> LDS goes through the direct load (global_load_lds_dwordx4): no
+//    staging registers and no ds_write; three sub-tiles are always in flight.
+//  * The two waves that share a SIMD run half an iteration apart.  Every
+//    iteration of a wave is a "memory" slot (read the MFMA fragments of the
+//    sub-tile out of LDS, issue the loads for the far end of the ring) and a
+//    "compute" slot (the MFMAs, back to back), and a workgroup barrier ends
+//    each slot.  Because one group of four waves starts one slot late, one
+//    wave of every SIMD is always in its compute slot while the other is in
+//    its memory slot, so the LDS pipeline and the MFMA pipeline stay busy at
+//    the same time instead of taking turns.
+//  * LDS layouts are chosen so that every fragment read is bank-conflict
+//    free on the 64-bank LDS: operands contiguous along K are stored as
+//    64-byte rows with the 16-byte chunk index xor-ed with (row/4)%4;
+//    operands contiguous along M or N are stored as K-rows of the tile's
+//    width with the chunk index xor-ed with (or, for 384-byte rows, rotated
+//    by) 4*(k%4) and read back with the transposing ds_read_b64_tr_b16.  The
+//    direct load writes 64 lanes x 16 bytes to consecutive LDS addresses, so
+//    the permutation is applied on the global address each lane fetches.
+//  * Why three tile heights: a shard GEMM rarely yields a multiple of 256
+//    tiles at 256 x 256 (176 or 96 on the Llama-shaped unit), which would
+//    leave a third to two thirds of the compute units idle -- the occupancy
+//    loss the paper's Analysis section predicts for N small kernels.  A
+//    shorter tile that fills the machine in one round wins; the launcher
+//    picks the height with the smallest (rounds x height) product.
+//    (Splitting tiles along K over all compute units, "stream-K", was built
+//    and measured slower: workgroups at different K offsets stop sharing
+//    operand panels in L2, the hit rate fell from 86 % to 43 %.)
+//
+// Layouts and epilogues are those of rtp_gemm_bf16.hip; ragged M and N are
+// handled by clamping the fetched row/column (the clamped results are never
+// stored), K must be a multiple of 32.
+#pragma once
+#include "rtp_gemm_epilogue.h"
+
+namespace rtp {
+
+namespace pp {
+constexpr int BN = 256, BK = 32;
+constexpr int WM = 2, WN = 4, NTHR = 512;
+constexpr int FN = BN / (WN * 32);   // 2 fragments of 32 columns per wave
+constexpr int B_BYTES = BN * BK * 2; // 16 KB of B per stage
+typedef __attribute__((address_space(3))) void *lds_vp;
+typedef __attribute__((address_space(1))) const void *glb_vp;
+} // namespace pp
+
+template <int LAY, int BM>
+__global__ __launch_bounds__(pp::NTHR) void gemm_bf16_pp_kernel(const GemmArgs p, const int tiles_m, const int tiles_n,
+                                                                 const int vec_epilogue)
+{
+    using namespace pp;
+    static_assert(BM == 256 || BM == 192 || BM == 128, "tile heights built");
+    constexpr bool A_KC = (LAY != LAY_TN), B_KC = (LAY == LAY_NT);
+    constexpr int FM = BM / (WM * 32);       // 4, 3 or 2 fragments of 32 rows per wave
+    constexpr int A_BYTES = BM * BK * 2;     // 16, 12 or 8 KB of A per stage
+    constexpr int STAGE = A_BYTES + B_BYTES;
+#ifdef PP_FORCE_STAGES
+    constexpr int STAGES = PP_FORCE_STAGES;
+#else
+    constexpr int STAGES = 4; // deeper rings (5 or 6 stages fit the 160 KB LDS) measured no faster
+#endif
+    constexpr int PF = STAGES - 1;               // sub-tiles in flight
+    constexpr int A_PIECES = A_BYTES / 1024; // 1 KB direct-load pieces of A per stage: 16, 12, 8
+    constexpr int A_PW = (A_PIECES + 7) / 8; // ... per wave (the second one only on waves 0-3 when BM = 192)
+    constexpr int A_CPR = BM / 8;            // 16-byte chunks per K-row of an M-contiguous A stage
+    constexpr int A_ROWB = BM * 2;           // bytes per K-row of an M-contiguous A stage
+    __shared__ __attribute__((aligned(1024))) char smem[STAGES * STAGE];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int group = wave >> 2; // waves 0-3 and 4-7 sit on SIMDs 0-3 respectively
+
+    // ---- which tile: workgroup ids are dealt round-robin to the 8 XCDs; renumber them so
+    // that an XCD owns a contiguous 4 x 8 block of tiles that share operand panels in its L2
+    int pid = blockIdx.x;
+    {
+        const int total = gridDim.x;
+        const int per = (total + 7) >> 3;
+        int tall = total & 7;
+        if (tall == 0) tall = 8;
+        const int xcd = pid & 7, local = pid >> 3;
+        pid = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
+    }
+    constexpr int GROUP_M = 4;
+    const int group_sz = GROUP_M * tiles_n;
+    const int grp = pid / group_sz;
+    const int first_m = grp * GROUP_M;
+    const int gm = min(tiles_m - first_m, GROUP_M);
+    const int tm = first_m + (pid % group_sz) % gm;
+    const int tn = (pid % group_sz) / gm;
+
+    const bool paired = (p.epi == EPI_SWIGLU_FWD);
+    const int m0 = tm * BM;
+    const int n0 = paired ? tn * (BN / 2) : tn * BN;
+    const int M = p.M, N = p.N, K = p.K;
+    const int half = p.half;
+
+    // chunk permutation of an M-contiguous A stage: slot of logical chunk c in K-row kr
+    auto a_slot = [](int c, int kr) { return BM == 192 ? (c + 4 * (kr & 3)) % A_CPR : c ^ (4 * (kr & 3)); };
+    auto a_unslot = [](int pc, int kr) { return BM == 192 ? (pc + A_CPR - 4 * (kr & 3)) % A_CPR : pc ^ (4 * (kr & 3)); };
+
+    // ---- direct-load addresses --------------------------------------------------------
+    // A: piece j (1 KB) of a K-contiguous stage holds rows 16j..16j+15 (64 bytes each); of an
+    //    M-contiguous stage it holds chunks 64j..64j+63 of the K-rows laid end to end.  Wave w
+    //    fetches pieces w and w + 8.
+    // B: pieces 2w and 2w + 1, rows 16j.. or K-rows 2j, 2j+1 (512 bytes each).
+    auto a_row = [&](int r) { return min(m0 + r, M - 1); };
+    auto a_col = [&](int c) { return min(m0 + c, M - 8); };
+    auto b_row = [&](int r) {
+        if (paired) return r < BN / 2 ? min(n0 + r, half - 1) : half + min(n0 + r - BN / 2, half - 1);
+        return min(n0 + r, N - 1);
+    };
+    auto b_col = [&](int c) { return min(n0 + c, N - 8); };
+
+    const char *ga[A_PW], *gb[2];
+    const int a_pieces_mine = (A_PIECES - wave + 7) / 8; // 2, or 1 on waves 4-7 when BM = 192, or 1 when BM = 128
+#pragma unroll
+    for (int i = 0; i < A_PW; ++i) {
+        const int j = min(wave + 8 * i, A_PIECES - 1);
+        if (A_KC) {
+            const int row = 16 * j + (lane >> 2), pc = lane & 3, c = pc ^ ((row >> 2) & 3);
+            ga[i] = (const char *)p.A + ((int64_t)a_row(row) * p.lda + c * 8) * 2;
+        } else {
+            const int L = 64 * j + lane, kr = L / A_CPR, c = a_unslot(L % A_CPR, kr);
+            ga[i] = (const char *)p.A + ((int64_t)kr * p.lda + a_col(c * 8)) * 2;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int j = 2 * wave + i;
+        if (B_KC) {
+            const int row = 16 * j + (lane >> 2), pc = lane & 3, c = pc ^ ((row >> 2) & 3);
+            gb[i] = (const char *)p.B + ((int64_t)b_row(row) * p.ldb + c * 8) * 2;
+        } else {
+            const int kr = 2 * j + (lane >> 5), pc = lane & 31, c = pc ^ (4 * (kr & 3));
+            gb[i] = (const char *)p.B + ((int64_t)kr * p.ldb + b_col(c * 8)) * 2;
+        }
+    }
+    const int64_t stepA = A_KC ? (int64_t)BK * 2 : (int64_t)BK * p.lda * 2;
+    const int64_t stepB = B_KC ? (int64_t)BK * 2 : (int64_t)BK * p.ldb * 2;
+    const int KT = K / BK;
+
+    auto issue = [&](int kt) {
+        const int kk = min(kt, KT - 1); // past the end: refetch the last sub-tile into a stage nobody reads
+        char *st = smem + (kt % STAGES) * STAGE;
+        __builtin_amdgcn_global_load_lds((glb_vp)(ga[0] + kk * stepA), (lds_vp)(st + wave * 1024), 16, 0, 0);
+        if (A_PW == 2 && a_pieces_mine == 2)
+            __builtin_amdgcn_global_load_lds((glb_vp)(ga[A_PW - 1] + kk * stepA), (lds_vp)(st + (wave + 8) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            __builtin_amdgcn_global_load_lds((glb_vp)(gb[i] + kk * stepB), (lds_vp)(st + A_BYTES + (2 * wave + i) * 1024), 16, 0, 0);
+    };
+    // ends a slot: all but this wave's PF-1 newest sub-tiles of direct loads have landed, its LDS
+    // reads have returned, and everybody is here
+    auto end_slot_after_loads = [&]() {
+        if (a_pieces_mine == 2)
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((PF - 1) * 4) : "memory"); // 4 loads per sub-tile
+        else
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((PF - 1) * 3) : "memory"); // 3 loads per sub-tile
+    };
+    static_assert(PF >= 2 && (PF - 1) * 4 < 64, "vmcnt is a 6-bit counter");
+
+    // ---- fragment addresses -----------------------------------------------------------
+    int a_off[FM], b_off[FN];
+    {
+        const int q = lane >> 4, i16 = lane & 15;
+#pragma unroll
+        for (int f = 0; f < FM; ++f) {
+            const int rb = wm * (BM / WM) + f * 32;
+            if (A_KC) {
+                const int row = rb + (lane & 31);
+                a_off[f] = row * 64 + (((lane >> 5) ^ ((row >> 2) & 3)) << 4);
+            } else {
+                const int col = rb + (q & 1) * 16 + (i16 & 3) * 4;
+                const int kr = (q >> 1) * 8 + (i16 >> 2);
+                a_off[f] = kr * A_ROWB + (a_slot(col >> 3, kr) << 4) + (col & 7) * 2;
+            }
+        }
+#pragma unroll
+        for (int f = 0; f < FN; ++f) {
+            const int rb = f * (WN * 32) + wn * 32;
+            if (B_KC) {
+                const int row = rb + (lane & 31);
+                b_off[f] = row * 64 + (((lane >> 5) ^ ((row >> 2) & 3)) << 4);
+            } else {
+                const int col = rb + (q & 1) * 16 + (i16 & 3) * 4;
+                const int kr = (q >> 1) * 8 + (i16 >> 2);
+                b_off[f] = kr * 512 + (((col >> 3) ^ (4 * (i16 >> 2))) << 4) + (col & 7) * 2;
+            }
+        }
+    }
+    // 8 consecutive k of one row (K-contiguous stage) ...
+    auto frag_kc = [](const char *opnd, int off, int ks) { return *(const bf16x8 *)(opnd + (off ^ (ks << 5))); };
+    // ... or the same 8 k of one column through two transposing reads of 4 K-rows x 16 columns
+    // (K-rows 16*ks + 8*(lane/32) + 0..3 and + 4..7: the row index changes by multiples of 4, so
+    // the chunk permutation of the lane's row stays the one a_off / b_off were built with)
+    auto frag_mc = [](const char *opnd, int off, int ks, int rowb) {
+        typedef s16x4 __attribute__((address_space(3))) * lp;
+        const char *q = opnd + off + ks * 16 * rowb;
+        union {
+            s16x4 h[2];
+            bf16x8 v;
+        } u;
+        u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(q));
+        u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(q + 4 * rowb));
+        return u.v;
+    };
+
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                acc[i][j][v] = 0.0f;
+
+    // ---- prologue: PF sub-tiles in flight, the first one landed -------------------------
+#pragma unroll
+    for (int i = 0; i < PF; ++i) issue(i);
+    end_slot_after_loads();
+    if (group == 1) asm volatile("s_barrier" ::: "memory"); // start one slot late
+
+    bf16x8 af[2][FM], bf[2][FN];
+    for (int kt = 0; kt < KT; ++kt) {
+        // ---- memory slot ------------------------------------------------------------------
+        const char *sa = smem + (kt % STAGES) * STAGE;
+        const char *sb = sa + A_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+            for (int f = 0; f < FM; ++f) af[ks][f] = A_KC ? frag_kc(sa, a_off[f], ks) : frag_mc(sa, a_off[f], ks, A_ROWB);
+#pragma unroll
+            for (int f = 0; f < FN; ++f) bf[ks][f] = B_KC ? frag_kc(sb, b_off[f], ks) : frag_mc(sb, b_off[f], ks, 512);
+        }
+        issue(kt + PF);
+        // own loads of sub-tile kt+1 have landed, fragments are in registers
+        end_slot_after_loads();
+        __builtin_amdgcn_sched_barrier(0); // nothing may drift across a slot boundary
+        // ---- compute slot -------------------------------------------------------------------
+        __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][i], bf[ks][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_s_setprio(0);
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_barrier" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (group == 0) asm volatile("s_barrier" ::: "memory"); // every wave passes the same number of barriers
+    // the refetches past the end may still be landing in LDS: drain everybody's before LDS is reused
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+
+    if (vec_epilogue)
+        gemm_epilogue_staged<FM, FN, WN * 32>(p, acc, (float *)(smem + wave * EPI_LDS_BYTES_PER_WAVE),
+                                              m0 + wm * (BM / WM), n0, wn * 32, lane);
+    else
+        gemm_epilogue<FM, FN, WN * 32>(p, acc, m0 + wm * (BM / WM) + 4 * (lane >> 5), n0, wn * 32 + (lane & 31));
+}
+
+template <int BM>
+static hipError_t launch_gemm_bf16_pp_bm(int layout, const GemmArgs &a, int tiles_n, hipStream_t s)
+{
+    const int tiles_m = (a.M + BM - 1) / BM;
+    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(pp::NTHR);
+    const int vec = gemm_epilogue_vec_ok(a) ? 1 : 0;
+    switch (layout) {
+    case LAY_NT: hipLaunchKernelGGL((gemm_bf16_pp_kernel<LAY_NT, BM>), grid, block, 0, s, a, tiles_m, tiles_n, vec); break;
+    case LAY_NN: hipLaunchKernelGGL((gemm_bf16_pp_kernel<LAY_NN, BM>), grid, block, 0, s, a, tiles_m, tiles_n, vec); break;
+    case LAY_TN: hipLaunchKernelGGL((gemm_bf16_pp_kernel<LAY_TN, BM>), grid, block, 0, s, a, tiles_m, tiles_n, vec); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+} // namespace rtp

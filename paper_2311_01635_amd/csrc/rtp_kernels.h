@@ -38,11 +38,13 @@ struct GemmArgs {
 };
 
 // bf16 inputs, fp32 MFMA accumulation.  variant: 0 = pick by shape; 1, 2, 3 = register-staged
-// tiles (256x256/8 waves, 128x128/4 waves, 256x256/4 waves); 4 = the ping-pong kernel.
+// tiles (256x256/8 waves, 128x128/4 waves, 256x256/4 waves); 4 = the ping-pong kernel with the
+// tile height picked by shape; 5, 6, 7 = the ping-pong kernel with tile height 256, 192, 128.
 hipError_t launch_gemm_bf16(int layout, const GemmArgs &a, int variant, hipStream_t s);
-// the ping-pong kernel (rtp_gemm_pp.hip): needs K % 32 == 0
+// the ping-pong kernel (rtp_gemm_pp.h): needs K % 32 == 0; bm_override 0 = pick the tile height
 bool gemm_bf16_pp_supported(int layout, const GemmArgs &a);
-hipError_t launch_gemm_bf16_pp(int layout, const GemmArgs &a, hipStream_t s);
+int gemm_bf16_pp_pick_bm(const GemmArgs &a, int bm_override);
+hipError_t launch_gemm_bf16_pp(int layout, const GemmArgs &a, int bm_override, hipStream_t s);
 const char *gemm_bf16_kernel_name(int layout, int variant);
 
 // fp32 inputs and outputs (epi: EPI_STORE, EPI_ACC_ADD with ws == C).

@@ -81,12 +81,13 @@ GEMM_ODD = {B.LAYOUT_NT: [(301, 77, 72), (301, 77, 96)], B.LAYOUT_NN: [(301, 72,
             B.LAYOUT_TN: [(72, 72, 301), (72, 520, 320)]}
 
 
-# variants 1-3: register-staged tiles; variant 4: the ping-pong kernel (K must be a multiple of 32)
-@pytest.mark.parametrize("variant", [1, 2, 4])
+# variants 1-2: register-staged tiles; 4: the ping-pong kernel with the tile height picked by shape;
+# 5, 6, 7: ping-pong with tile height 256, 192, 128 (K must be a multiple of 32)
+@pytest.mark.parametrize("variant", [1, 2, 4, 5, 6, 7])
 @pytest.mark.parametrize("layout", [B.LAYOUT_NT, B.LAYOUT_NN, B.LAYOUT_TN])
 def test_gemm_bf16_layouts_and_tails(layout, variant):
     for i, (M, N, K) in enumerate(GEMM_SHAPES + GEMM_ODD[layout]):
-        if variant == 4 and K % 32:
+        if variant >= 4 and K % 32:
             continue
         for accumulate, out_f32 in ((False, True), (True, True), (False, False)):
             say(f"gemm layout={layout} variant={variant} M={M} N={N} K={K} acc={accumulate} f32out={out_f32}")
