@@ -121,6 +121,11 @@ typedef struct {
     void *buf_g_dev[2]; /* g_bytes each; [1] used by RTP_DOUBLE_BUFFER only       */
     void *compute_stream; /* hipStream_t */
     void *stage_stream;   /* hipStream_t, != compute_stream unless blocking       */
+    void *aux_stream;     /* optional second compute stream (hipStream_t, distinct):
+                             the weight-gradient kernels run there, beside the
+                             input-gradient kernels, since one shard GEMM seldom fills
+                             the machine.  Everything is joined back into the compute
+                             stream when a pass ends.  NULL = one compute stream.      */
 } rtp_ring_desc;
 
 /* Creates the host object.  Errors: RTP_ERR_INVALID (null desc/out, null
@@ -247,6 +252,7 @@ typedef struct {
     float *acc_y_dev;     /* fp32 [T, O2]                                          */
     float *acc_dx_dev;    /* fp32 [T, I]                                           */
     void *compute_stream, *stage_stream;
+    void *aux_stream;     /* optional, as in rtp_ring_desc                           */
 } rtp_mlp_desc;
 
 size_t rtp_mlp_slot_w_bytes(const rtp_mlp_desc *d);

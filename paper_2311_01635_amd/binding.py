@@ -29,7 +29,7 @@ class rtp_ring_desc(C.Structure):
                 ("w_bytes", C.c_size_t), ("g_bytes", C.c_size_t),
                 ("home_w_dev", C.c_void_p), ("home_g_dev", C.c_void_p),
                 ("buf_w_dev", C.c_void_p * 2), ("buf_g_dev", C.c_void_p * 2),
-                ("compute_stream", C.c_void_p), ("stage_stream", C.c_void_p)]
+                ("compute_stream", C.c_void_p), ("stage_stream", C.c_void_p), ("aux_stream", C.c_void_p)]
 
 
 class rtp_linear_desc(C.Structure):
@@ -47,7 +47,7 @@ class rtp_mlp_desc(C.Structure):
                 ("buf_w_dev", C.c_void_p * 2), ("buf_g_dev", C.c_void_p * 2),
                 ("preact_dev", C.c_void_p), ("hidden_dev", C.c_void_p), ("dpre_dev", C.c_void_p),
                 ("acc_y_dev", C.c_void_p), ("acc_dx_dev", C.c_void_p),
-                ("compute_stream", C.c_void_p), ("stage_stream", C.c_void_p)]
+                ("compute_stream", C.c_void_p), ("stage_stream", C.c_void_p), ("aux_stream", C.c_void_p)]
 
 
 class rtp_prof_result(C.Structure):
@@ -169,7 +169,7 @@ class Ring:
     """rtp_ring with its caller-owned buffers kept alive."""
 
     def __init__(self, n, rank, mode, w_bytes, g_bytes, home_w=None, home_g=None, buf_w=(None, None),
-                 buf_g=(None, None), compute_stream=None, stage_stream=None, flags=0):
+                 buf_g=(None, None), compute_stream=None, stage_stream=None, flags=0, aux_stream=None):
         d = rtp_ring_desc()
         d.n, d.rank, d.mode, d.flags = n, rank, mode, flags
         d.w_bytes, d.g_bytes = w_bytes, g_bytes
@@ -177,7 +177,8 @@ class Ring:
         d.buf_w_dev[0], d.buf_w_dev[1] = _ptr(buf_w[0]), _ptr(buf_w[1])
         d.buf_g_dev[0], d.buf_g_dev[1] = _ptr(buf_g[0]), _ptr(buf_g[1])
         d.compute_stream, d.stage_stream = _stream(compute_stream), _stream(stage_stream)
-        self._keep = (home_w, home_g, buf_w, buf_g, compute_stream, stage_stream)
+        d.aux_stream = _stream(aux_stream)
+        self._keep = (home_w, home_g, buf_w, buf_g, compute_stream, stage_stream, aux_stream)
         self.desc = d
         self.handle = C.c_void_p()
         check(lib.rtp_ring_create(C.byref(self.handle), C.byref(d)), "rtp_ring_create")

@@ -1,6 +1,8 @@
 // Launcher of the ping-pong bf16 GEMM: shape rules and the choice of tile height.
 #include "rtp_kernels.h"
 
+#include <algorithm>
+
 namespace rtp {
 
 hipError_t launch_gemm_bf16_pp_256(int layout, const GemmArgs &a, int tiles_n, hipStream_t s);
@@ -38,7 +40,7 @@ int gemm_bf16_pp_pick_bm(const GemmArgs &a, int bm_override)
     const int ncols = a.epi == EPI_SWIGLU_FWD ? a.half : a.N;
     const int bn = a.epi == EPI_SWIGLU_FWD ? 128 : 256;
     const long tiles_n = (ncols + bn - 1) / bn;
-    const int cus = compute_units();
+    const int cus = std::max(1, compute_units() / std::max(1, a.cu_share));
     const int heights[3] = {256, 192, 128};
     const double handicap[3] = {1.0, 1.04, 1.12};
     int best = 256;

@@ -181,12 +181,14 @@ struct rtp_ring {
     int executed = 0;    // blocking mode: rotations already carried out
     std::vector<rtp_linear *> linears;
     std::vector<rtp_trace_rec> trace;
-    hipEvent_t ev_free = nullptr, ev_join = nullptr;
+    hipEvent_t ev_free = nullptr, ev_free2 = nullptr, ev_join = nullptr, ev_aux = nullptr;
     hipEvent_t ev_w[2] = {nullptr, nullptr};
     hipEvent_t ev_g[2] = {nullptr, nullptr};
 
     hipStream_t cs() const { return (hipStream_t)d.compute_stream; }
     hipStream_t ss() const { return d.mode == RTP_INPLACE_BLOCKING ? cs() : (hipStream_t)d.stage_stream; }
+    // second compute stream (weight-gradient kernels); the compute stream itself when none was given
+    hipStream_t as() const { return d.aux_stream ? (hipStream_t)d.aux_stream : cs(); }
     char *home_w(int k) const { return (char *)d.home_w_dev + (size_t)k * d.w_bytes; }
     char *home_g(int k) const { return (char *)d.home_g_dev + (size_t)k * d.g_bytes; }
     int w_idx(int step) const { return d.mode == RTP_INPLACE_BLOCKING ? 0 : (base_idx + step) & 1; }
@@ -213,7 +215,7 @@ struct rtp_linear {
 static rtp_status ensure_events(rtp_ring *r)
 {
     if (r->dry || r->events_ready) return RTP_OK;
-    hipEvent_t *all[] = {&r->ev_free, &r->ev_join, &r->ev_w[0], &r->ev_w[1], &r->ev_g[0], &r->ev_g[1]};
+    hipEvent_t *all[] = {&r->ev_free, &r->ev_free2, &r->ev_join, &r->ev_aux, &r->ev_w[0], &r->ev_w[1], &r->ev_g[0], &r->ev_g[1]};
     for (hipEvent_t *e : all)
         HIP_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
     for (rtp_linear *l : r->linears) {
@@ -234,11 +236,18 @@ static rtp_status copy_async(rtp_ring *r, void *dst, const void *src, size_t byt
 // make each stream wait for everything enqueued so far on the other
 static rtp_status cross_join(rtp_ring *r)
 {
-    if (r->dry || r->cs() == r->ss()) return RTP_OK;
-    HIP_TRY(hipEventRecord(r->ev_join, r->ss()));
-    HIP_TRY(hipStreamWaitEvent(r->cs(), r->ev_join, 0));
+    if (r->dry) return RTP_OK;
+    if (r->as() != r->cs()) {
+        HIP_TRY(hipEventRecord(r->ev_join, r->as()));
+        HIP_TRY(hipStreamWaitEvent(r->cs(), r->ev_join, 0));
+    }
+    if (r->ss() != r->cs()) {
+        HIP_TRY(hipEventRecord(r->ev_join, r->ss()));
+        HIP_TRY(hipStreamWaitEvent(r->cs(), r->ev_join, 0));
+    }
     HIP_TRY(hipEventRecord(r->ev_join, r->cs()));
-    HIP_TRY(hipStreamWaitEvent(r->ss(), r->ev_join, 0));
+    if (r->ss() != r->cs()) HIP_TRY(hipStreamWaitEvent(r->ss(), r->ev_join, 0));
+    if (r->as() != r->cs()) HIP_TRY(hipStreamWaitEvent(r->as(), r->ev_join, 0));
     return RTP_OK;
 }
 
@@ -265,6 +274,8 @@ extern "C" rtp_status rtp_ring_create(rtp_ring **out, const rtp_ring_desc *d)
             return fail(RTP_ERR_INVALID, "rtp_ring_create: resident and staging buffers alias");
         if (d->mode != RTP_INPLACE_BLOCKING && d->compute_stream == d->stage_stream)
             return fail(RTP_ERR_INVALID, "rtp_ring_create: the stage stream must differ from the compute stream");
+        if (d->aux_stream && (d->aux_stream == d->compute_stream || d->aux_stream == d->stage_stream))
+            return fail(RTP_ERR_INVALID, "rtp_ring_create: the auxiliary stream must differ from the other two");
     }
     rtp_ring *r = new (std::nothrow) rtp_ring;
     if (!r) return fail(RTP_ERR_INVALID, "rtp_ring_create: out of host memory");
@@ -279,7 +290,7 @@ extern "C" rtp_status rtp_ring_destroy(rtp_ring *r)
     if (!r) return RTP_OK;
     if (!r->linears.empty()) return fail(RTP_ERR_STATE, "rtp_ring_destroy: destroy the ring's linears first");
     if (r->events_ready) {
-        hipEvent_t all[] = {r->ev_free, r->ev_join, r->ev_w[0], r->ev_w[1], r->ev_g[0], r->ev_g[1]};
+        hipEvent_t all[] = {r->ev_free, r->ev_free2, r->ev_join, r->ev_aux, r->ev_w[0], r->ev_w[1], r->ev_g[0], r->ev_g[1]};
         for (hipEvent_t e : all)
             if (e) (void)hipEventDestroy(e);
     }
@@ -370,6 +381,17 @@ static rtp_status do_rotation(rtp_ring *r, int step)
         // the staging buffer was resident one step ago: wait for its readers
         HIP_TRY(hipEventRecord(r->ev_free, r->cs()));
         HIP_TRY(hipStreamWaitEvent(s, r->ev_free, 0));
+        if (r->as() != r->cs()) {
+            // ... on the auxiliary stream too (the input-partitioned forward GEMM runs there)
+            HIP_TRY(hipEventRecord(r->ev_free2, r->as()));
+            HIP_TRY(hipStreamWaitEvent(s, r->ev_free2, 0));
+        }
+    }
+    if (!r->dry && blocking && r->as() != r->cs()) {
+        // the exchange runs on the compute stream: the weight-gradient kernels of the step that
+        // just ended (auxiliary stream) must be done with the gradient shard first
+        HIP_TRY(hipEventRecord(r->ev_join, r->as()));
+        HIP_TRY(hipStreamWaitEvent(r->cs(), r->ev_join, 0));
     }
     // send the held weights to their next holder, receive the next shard
     RTP_TRY(copy_async(r, r->home_w(k), r->d.buf_w_dev[src], r->d.w_bytes, s));
@@ -469,6 +491,18 @@ extern "C" rtp_status rtp_ring_end(rtp_ring *r)
         r->resident = r->shard_at(r->d.n - 1);
     }
     r->pass = RTP_PASS_IDLE;
+    // the pass is complete on the compute stream only once the stage stream's last transfers are:
+    // a caller that waits on (or captures) the compute stream alone then sees the whole pass
+    if (!r->dry && r->events_ready) {
+        if (r->cs() != r->ss()) {
+            HIP_TRY(hipEventRecord(r->ev_join, r->ss()));
+            HIP_TRY(hipStreamWaitEvent(r->cs(), r->ev_join, 0));
+        }
+        if (r->cs() != r->as()) {
+            HIP_TRY(hipEventRecord(r->ev_join, r->as()));
+            HIP_TRY(hipStreamWaitEvent(r->cs(), r->ev_join, 0));
+        }
+    }
     return RTP_OK;
 }
 
@@ -494,6 +528,7 @@ extern "C" rtp_status rtp_ring_sync(rtp_ring *r)
     if (r->dry) return RTP_OK;
     HIP_TRY(hipStreamSynchronize(r->cs()));
     if (r->ss() != r->cs()) HIP_TRY(hipStreamSynchronize(r->ss()));
+    if (r->as() != r->cs()) HIP_TRY(hipStreamSynchronize(r->as()));
     HIP_TRY(hipGetLastError());
     return RTP_OK;
 }
@@ -584,15 +619,14 @@ static int bwd_act_epi(rtp_act a)
 // epilogue of a result that is summed over the n steps
 static int acc_epi(int step, int n) { return n == 1 ? EPI_STORE : step == 0 ? EPI_ACC_FIRST : step == n - 1 ? EPI_ACC_LAST : EPI_ACC_ADD; }
 
-static rtp_status gemm(rtp_linear *l, int layout, GemmArgs &a)
+static rtp_status gemm(rtp_linear *l, int layout, GemmArgs &a, hipStream_t st)
 {
     rtp_ring *r = l->ring;
     if (r->dry || !r->abl_compute) return RTP_OK;
     if (l->d.dtype == RTP_BF16)
-        HIP_TRY(timed_launch(layout, 2.0 * a.M * a.N * a.K, r->cs(),
-                             [&] { return launch_gemm_bf16(layout, a, 0, r->cs()); }));
+        HIP_TRY(timed_launch(layout, 2.0 * a.M * a.N * a.K, st, [&] { return launch_gemm_bf16(layout, a, 0, st); }));
     else
-        HIP_TRY(launch_gemm_f32(layout, a, r->cs()));
+        HIP_TRY(launch_gemm_f32(layout, a, st));
     return RTP_OK;
 }
 
@@ -613,6 +647,9 @@ extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, voi
     GemmArgs a;
     memset(&a, 0, sizeof a);
     a.c_is_f32 = f32;
+    // with an auxiliary stream and a second linear on the ring, two forward GEMMs share the machine
+    const int fwd_share = (r->as() != r->cs() && r->linears.size() > 1) ? 2 : 1;
+    a.cu_share = fwd_share;
     if (d.split == RTP_SPLIT_OUT) {
         a.A = X; a.lda = d.I;
         a.B = Wk; a.ldb = d.I;
@@ -620,7 +657,7 @@ extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, voi
         if (d.act == RTP_ACT_NONE) {
             a.epi = EPI_STORE;
             a.C = (char *)Y + (size_t)k * o * es; a.ldc = d.O;
-            RTP_TRY(gemm(l, LAY_NT, a));
+            RTP_TRY(gemm(l, LAY_NT, a, r->cs()));
         } else {
             const bool gated = d.act == RTP_ACT_SWIGLU;
             const int64_t ow = gated ? o / 2 : o, Ow = gated ? d.O / 2 : d.O;
@@ -631,11 +668,11 @@ extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, voi
                 a.half = (int)(o / 2);
                 a.aux = pre; a.ldaux = d.O;
                 a.C = Yk; a.ldc = Ow;
-                RTP_TRY(gemm(l, LAY_NT, a));
+                RTP_TRY(gemm(l, LAY_NT, a, r->cs()));
             } else {
                 a.epi = EPI_STORE;
                 a.C = pre; a.ldc = d.O;
-                RTP_TRY(gemm(l, LAY_NT, a));
+                RTP_TRY(gemm(l, LAY_NT, a, r->cs()));
                 if (!r->dry && r->abl_compute)
                     HIP_TRY(launch_act_f32(fwd_act_epi(d.act), (const float *)pre, d.O, nullptr, 0, (float *)Yk, Ow,
                                            (int)d.T, (int)ow, (int)(o / 2), r->cs()));
@@ -652,7 +689,18 @@ extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, voi
             a.epi = acc_epi(step, n);
             a.ws = d.acc_ws_dev; a.ldws = d.O;
         }
-        RTP_TRY(gemm(l, LAY_NT, a));
+        // The partial products of the N steps only meet in the accumulator, so this GEMM can run
+        // on the auxiliary stream beside the next step's output-partitioned GEMM.  It starts after
+        // everything enqueued so far on the compute stream (its input may just have been produced
+        // there) and after this step's shard has been staged.
+        hipStream_t fs = r->as();
+        if (!r->dry && fs != r->cs()) {
+            HIP_TRY(hipEventRecord(r->ev_aux, r->cs()));
+            HIP_TRY(hipStreamWaitEvent(fs, r->ev_aux, 0));
+            if (r->abl_rotate && step > 0 && r->d.mode != RTP_INPLACE_BLOCKING)
+                HIP_TRY(hipStreamWaitEvent(fs, r->ev_w[step & 1], 0));
+        }
+        RTP_TRY(gemm(l, LAY_NT, a, fs));
     }
     l->next_step = step + 1;
     return RTP_OK;
@@ -677,12 +725,21 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
     float *Gk = (float *)((char *)r->d.buf_g_dev[gi] + d.g_offset);
     r->rec(TR_BWD, step, k, r->res_idx);
 
+    // The weight-gradient kernel runs on the auxiliary stream when there is one, beside the
+    // input-gradient kernels: shard GEMMs seldom fill the machine alone.  It starts after
+    // everything enqueued so far on the compute stream (its dY may just have been produced there).
+    hipStream_t ws = r->as();
+    const bool split = ws != r->cs();
+    if (!r->dry && split) {
+        HIP_TRY(hipEventRecord(r->ev_aux, r->cs()));
+        HIP_TRY(hipStreamWaitEvent(ws, r->ev_aux, 0));
+    }
     // the gradient shard this step adds onto must have arrived
     if (!r->dry && r->abl_rotate && step > 0) {
         if (r->d.mode == RTP_DOUBLE_BUFFER)
-            HIP_TRY(hipStreamWaitEvent(r->cs(), r->ev_g[step & 1], 0));
+            HIP_TRY(hipStreamWaitEvent(ws, r->ev_g[step & 1], 0));
         else if (staged_g)
-            HIP_TRY(hipStreamWaitEvent(r->cs(), l->ev_g_in, 0));
+            HIP_TRY(hipStreamWaitEvent(ws, l->ev_g_in, 0));
     }
 
     GemmArgs a;
@@ -703,13 +760,14 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
         a.ws = Gk; a.ldws = o;
     }
     a.C = a.ws; a.ldc = a.ldws;
-    if (d.T > 0) RTP_TRY(gemm(l, LAY_TN, a));
+    a.cu_share = split ? 2 : 1;
+    if (d.T > 0) RTP_TRY(gemm(l, LAY_TN, a, ws));
 
     // ---- hand the gradient part to the stage stream ---------------------------
     if (rotating && r->d.g_bytes && r->d.mode != RTP_INPLACE_BLOCKING) {
         const int kin = rtp_bwd_shard(r->d.rank, step + 1, n);
         if (!r->dry) {
-            HIP_TRY(hipEventRecord(l->ev_dw, r->cs()));
+            HIP_TRY(hipEventRecord(l->ev_dw, ws));
             HIP_TRY(hipStreamWaitEvent(r->ss(), l->ev_dw, 0));
         }
         RTP_TRY(copy_async(r, r->home_g(k) + d.g_offset, (char *)r->d.buf_g_dev[gi] + d.g_offset, l->g_shard_bytes, r->ss()));
@@ -725,6 +783,7 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
     if ((dX && d.T > 0) || r->dry) {
         memset(&a, 0, sizeof a);
         a.c_is_f32 = f32;
+        a.cu_share = split ? 2 : 1;
         if (d.split == RTP_SPLIT_OUT) {
             a.A = (const char *)dY + (size_t)k * o * es; a.lda = d.O;
             a.B = Wk; a.ldb = d.I;
@@ -736,7 +795,7 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
                 a.epi = acc_epi(step, n);
                 a.ws = d.acc_ws_dev; a.ldws = d.I;
             }
-            RTP_TRY(gemm(l, LAY_NN, a));
+            RTP_TRY(gemm(l, LAY_NN, a, r->cs()));
         } else {
             a.A = dY; a.lda = d.O;
             a.B = Wk; a.ldb = o;
@@ -744,7 +803,7 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
             if (d.act == RTP_ACT_NONE) {
                 a.epi = EPI_STORE;
                 a.C = (char *)dX + (size_t)k * o * es; a.ldc = d.I;
-                RTP_TRY(gemm(l, LAY_NN, a));
+                RTP_TRY(gemm(l, LAY_NN, a, r->cs()));
             } else {
                 const bool gated = d.act == RTP_ACT_SWIGLU;
                 const int64_t P = gated ? 2 * d.I : d.I, po = gated ? 2 * o : o;
@@ -755,14 +814,14 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
                     a.half = (int)o;
                     a.aux = (void *)pre; a.ldaux = P;
                     a.C = out; a.ldc = P;
-                    RTP_TRY(gemm(l, LAY_NN, a));
+                    RTP_TRY(gemm(l, LAY_NN, a, r->cs()));
                 } else {
                     // the plain product lands in the last o columns of the slice, then the
                     // activation's derivative is applied elementwise, in place
                     float *tmp = (float *)out + (gated ? o : 0);
                     a.epi = EPI_STORE;
                     a.C = tmp; a.ldc = P;
-                    RTP_TRY(gemm(l, LAY_NN, a));
+                    RTP_TRY(gemm(l, LAY_NN, a, r->cs()));
                     if (!r->dry && r->abl_compute)
                         HIP_TRY(launch_act_f32(bwd_act_epi(d.act), (const float *)pre, P, tmp, P, (float *)out, P,
                                                (int)d.T, (int)o, (int)o, r->cs()));
@@ -816,7 +875,7 @@ extern "C" rtp_status rtp_mlp_create(rtp_mlp **out, const rtp_mlp_desc *d)
     rd.home_w_dev = d->home_w_dev; rd.home_g_dev = d->home_g_dev;
     rd.buf_w_dev[0] = d->buf_w_dev[0]; rd.buf_w_dev[1] = d->buf_w_dev[1];
     rd.buf_g_dev[0] = d->buf_g_dev[0]; rd.buf_g_dev[1] = d->buf_g_dev[1];
-    rd.compute_stream = d->compute_stream; rd.stage_stream = d->stage_stream;
+    rd.compute_stream = d->compute_stream; rd.stage_stream = d->stage_stream; rd.aux_stream = d->aux_stream;
     rtp_mlp *m = new (std::nothrow) rtp_mlp;
     if (!m) return fail(RTP_ERR_INVALID, "out of host memory");
     m->d = *d;

@@ -35,6 +35,8 @@ struct GemmArgs {
     int64_t ldaux;
     int half;           // EPI_SWIGLU_FWD: N/2 ; EPI_SWIGLU_BWD: N
     int c_is_f32;       // EPI_STORE / EPI_ACC_LAST write fp32 instead of the input dtype
+    int cu_share;       // > 1: this launch runs beside cu_share - 1 others of similar size, so the
+                        // tile height is picked for 1/cu_share of the compute units (0, 1: all)
 };
 
 // bf16 inputs, fp32 MFMA accumulation.  variant: 0 = pick by shape; 1, 2, 3 = register-staged

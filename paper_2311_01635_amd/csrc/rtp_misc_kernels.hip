@@ -173,6 +173,7 @@ __global__ __launch_bounds__(COPY_THREADS) void copy_kernel(u32x4 *__restrict__ 
 
 hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s)
 {
+
     if (bytes == 0) return hipSuccess;
     if ((bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return hipErrorInvalidValue;
     const int64_t n16 = (int64_t)(bytes >> 4);

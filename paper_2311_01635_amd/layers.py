@@ -55,7 +55,7 @@ class RtpLinear:
     rtp_rotate_step / rtp_linear_fwd / rtp_linear_bwd."""
 
     def __init__(self, W, T, n, rank, split=B.RTP_SPLIT_OUT, mode=B.RTP_DOUBLE_BUFFER, dtype=B.RTP_BF16,
-                 act=B.RTP_ACT_NONE, G0=None, preact=None, device="cuda:0"):
+                 act=B.RTP_ACT_NONE, G0=None, preact=None, device="cuda:0", aux_stream=True):
         self.dev = torch.device(device)
         self.n, self.rank, self.T, self.split, self.mode, self.dtype, self.act = n, rank, T, split, mode, dtype, act
         td = _TORCH_DT[dtype]
@@ -72,8 +72,9 @@ class RtpLinear:
         self.buf_g = [torch.empty(gb, dtype=torch.uint8, device=self.dev) for _ in range(2)]
         self.compute_stream = torch.cuda.Stream(self.dev)
         self.stage_stream = torch.cuda.Stream(self.dev)
+        self.aux_stream = torch.cuda.Stream(self.dev) if aux_stream else None
         self.ring = B.Ring(n, rank, mode, wb, gb, self.home_w, self.home_g, self.buf_w, self.buf_g,
-                           self.compute_stream, self.stage_stream)
+                           self.compute_stream, self.stage_stream, aux_stream=self.aux_stream)
         acc_cols = self.I if split == B.RTP_SPLIT_OUT else self.O
         self.acc_ws = torch.empty(T, acc_cols, dtype=torch.float32, device=self.dev)
         self.preact = preact
@@ -117,7 +118,7 @@ class RtpMlp:
     by rtp_mlp_fwd / rtp_mlp_bwd: one library call per pass."""
 
     def __init__(self, weights, T, n, rank, act, mode=B.RTP_INPLACE_STAGED, dtype=B.RTP_BF16, G0=None,
-                 device="cuda:0"):
+                 device="cuda:0", aux_stream=True):
         self.dev = torch.device(device)
         td = _TORCH_DT[dtype]
         self.n, self.rank, self.T, self.act, self.mode, self.dtype = n, rank, T, act, mode, dtype
@@ -162,6 +163,8 @@ class RtpMlp:
         d.preact_dev, d.hidden_dev, d.dpre_dev = B._ptr(self.preact), B._ptr(self.hidden), B._ptr(self.dpre)
         d.acc_y_dev, d.acc_dx_dev = B._ptr(self.acc_y), B._ptr(self.acc_dx)
         d.compute_stream, d.stage_stream = B._stream(self.compute_stream), B._stream(self.stage_stream)
+        self.aux_stream = torch.cuda.Stream(self.dev) if aux_stream else None
+        d.aux_stream = B._stream(self.aux_stream)
         self.desc = d
         self.handle = C.c_void_p()
         B.check(B.lib.rtp_mlp_create(C.byref(self.handle), C.byref(d)), "rtp_mlp_create")
