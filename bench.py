@@ -33,7 +33,9 @@ def parse():
     ap.add_argument("--workload", default="cfg4_llama7b_swiglu")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true", help="skip the three-run staging-overlap measurement")
-    ap.add_argument("--cpu-tokens", type=int, default=64, help="tokens in the oracle's timed sample")
+    ap.add_argument("--stepwise", action="store_true", help="one launch per linear and step instead of grouped launches")
+    ap.add_argument("--no-aux-stream", action="store_true", help="no second compute stream")
+    ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens in the oracle's timed sample (0: sized for ~15 s)")
     return ap.parse_args()
 
 
@@ -80,23 +82,28 @@ def measured_traffic(workload, layout):
 
 def cpu_baseline(w, inp, tokens):
     """The oracle as it stands, one worker's full rotated fwd+bwd over a token
-    sample (the first `tokens` rows), timed on this host's cores."""
+    sample (the first `tokens` rows), timed on this host's cores.  tokens = 0:
+    a 16-token probe sizes the sample for roughly 15 s of CPU work."""
     import numpy as np
     import oracle as orc
     f64 = lambda a: np.ascontiguousarray(a, dtype=np.float64)
-    X, dY = f64(inp["X"][:tokens]), f64(inp["dY"][:tokens])
-    if w.kind == "swiglu":
-        Ws = [f64(inp[k]) for k in ("Wg", "Wu", "Wd")]
+    gated = w.kind == "swiglu"
+    Ws = [f64(inp[k]) for k in (("Wg", "Wu", "Wd") if gated else ("W1", "W2"))]
+
+    def run(nt):
+        X, dY = f64(inp["X"][:nt]), f64(inp["dY"][:nt])
         t0 = time.perf_counter()
-        orc.rtp_swiglu(X, *Ws, dY, w.n, 0)
-        dt = time.perf_counter() - t0
-        flops = 6.0 * tokens * (2 * w.I * w.O + w.O * w.O2)
-    else:
-        Ws = [f64(inp[k]) for k in ("W1", "W2")]
-        t0 = time.perf_counter()
-        orc.rtp_mlp(X, *Ws, dY, w.n, 0)
-        dt = time.perf_counter() - t0
-        flops = 6.0 * tokens * (w.I * w.O + w.O * w.O2)
+        if gated:
+            orc.rtp_swiglu(X, *Ws, dY, w.n, 0)
+        else:
+            orc.rtp_mlp(X, *Ws, dY, w.n, 0)
+        return time.perf_counter() - t0
+
+    if tokens <= 0:
+        probe = run(16)
+        tokens = int(min(w.T, max(16, 15.0 / (probe / 16.0)))) // 16 * 16
+    dt = run(tokens)
+    flops = 6.0 * tokens * ((2 if gated else 1) * w.I * w.O + w.O * w.O2)
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
             "sample": f"first {tokens} of {w.T} tokens, full weights, all {w.n} rotation steps fwd+bwd, "
                       f"{dt:.1f} s, fp64 triple loops"}
@@ -118,7 +125,7 @@ def main():
     inp, weights, X, dY = build_inputs(w, torch, dev)
     act = B.RTP_ACT_SWIGLU if w.kind == "swiglu" else B.RTP_ACT_GELU_ERF
     mode = {"double_buffer": B.RTP_DOUBLE_BUFFER, "inplace_staged": B.RTP_INPLACE_STAGED}[w.mode]
-    mlp = RtpMlp(weights, w.T, w.n, 0, act, mode, B.RTP_BF16)
+    mlp = RtpMlp(weights, w.T, w.n, 0, act, mode, B.RTP_BF16, stepwise=a.stepwise, aux_stream=not a.no_aux_stream)
     Y = torch.empty(w.T, w.O2, device=dev, dtype=torch.bfloat16)
     dX = torch.empty(w.T, w.I, device=dev, dtype=torch.bfloat16)
     torch.cuda.synchronize()
@@ -139,6 +146,9 @@ def main():
                 "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                 "avg_launch_us": tot_ms * 1e3 / launches, "launches_per_step": launches / a.steps,
                 "flops_per_launch": tot_flops / launches, "traffic": measured_traffic(w.name, dom),
+                # launches on the compute and the auxiliary stream overlap, so a launch's duration includes the
+                # time it shares the compute units with another GEMM: per-launch rates understate the kernel
+                "launches_overlap": (not a.no_aux_stream),
                 "per_kernel": {k: {"launches_per_step": v[0] / a.steps, "avg_us": v[1] * 1e3 / max(v[0], 1),
                                    "tflops": v[2] / max(v[1], 1e-9) / 1e9} for k, v in prof.items()}}
 
@@ -168,6 +178,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "T": w.T, "I": w.I, "O": w.O, "O2": w.O2, "n_shards": w.n, "mode": w.mode,
                    "grad_dtype": "f32", "flops_per_step": w.flops,
+                   "schedule": "stepwise" if a.stepwise else "grouped", "aux_stream": not a.no_aux_stream,
                    "worker_param_bytes": mlp.worker_bytes(),
                    "table1_rtp_worker_bytes": B.rtp_table1_worker_bytes(False, mlp.w_bytes, mlp.g_bytes)},
         "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,

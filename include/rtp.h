@@ -77,6 +77,9 @@ typedef enum { RTP_PASS_IDLE = 0, RTP_PASS_FWD = 1, RTP_PASS_BWD = 2 } rtp_pass;
 
 #define RTP_FLAG_DRY_RUN 1u /* make no HIP call at all: the schedule and the
                                state machine run on the host only (tests)   */
+#define RTP_FLAG_STEPWISE 2u /* rtp_mlp_*: one kernel launch per linear and step,
+                                exactly the rtp_rotate_step / rtp_linear_* call
+                                sequence (no grouped launches)                 */
 
 typedef struct rtp_ring rtp_ring;
 typedef struct rtp_linear rtp_linear;
@@ -261,7 +264,14 @@ size_t rtp_mlp_slot_g_bytes(const rtp_mlp_desc *d);
 /* An MLP block with its first GEMM output-partitioned and its second
  * input-partitioned, so that unit k is self-contained and rotates as one
  * message.  rtp_mlp_fwd runs n x (rtp_rotate_step, rtp_linear_fwd x 2);
- * rtp_mlp_bwd the mirror image.  `rotate` = 0 skips the rotation calls (the
+ * rtp_mlp_bwd the mirror image.  For bf16 units in a staged mode whose shapes
+ * the tiled kernel takes (all contraction lengths multiples of 32), the
+ * forward pass instead issues the same GEMMs as grouped launches with the
+ * second linear one step behind the first ({Z_t, down_{t-1}}), the shard
+ * parts moving accordingly; so does the backward pass when no auxiliary
+ * stream was given ({dX_{s-1}, dPre_s} and {dW1_s, dW2_s}).  Results, buffers
+ * and bytes moved are the same.  RTP_FLAG_STEPWISE in `flags` keeps the
+ * step-by-step sequence everywhere.  `rotate` = 0 skips the rotation calls (the
  * resident shard is used for every step: timing of compute alone, results
  * are meaningless); `compute` = 0 skips the kernels (timing of the staging
  * traffic alone). */

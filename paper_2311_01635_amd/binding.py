@@ -19,6 +19,7 @@ RTP_ACT_NONE, RTP_ACT_GELU_ERF, RTP_ACT_GELU_TANH, RTP_ACT_SWIGLU = 0, 1, 2, 3
 RTP_PASS_IDLE, RTP_PASS_FWD, RTP_PASS_BWD = 0, 1, 2
 RTP_CW, RTP_CCW = 1, -1
 RTP_FLAG_DRY_RUN = 1
+RTP_FLAG_STEPWISE = 2
 LAYOUT_NT, LAYOUT_NN, LAYOUT_TN = 0, 1, 2
 
 TRACE_KINDS = {1: "fwd", 2: "bwd", 3: "w_in", 4: "w_out", 5: "g_in", 6: "g_out"}

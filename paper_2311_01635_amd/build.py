@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librtp.so")
-SOURCES = ["rtp_gemm_bf16.hip", "rtp_gemm_pp.hip", "rtp_gemm_pp_256.hip", "rtp_gemm_pp_192.hip", "rtp_gemm_pp_128.hip",
+SOURCES = ["rtp_gemm_bf16.hip", "rtp_gemm_pp.hip", "rtp_gemm_pp_nt.hip", "rtp_gemm_pp_nn.hip", "rtp_gemm_pp_tn.hip",
            "rtp_misc_kernels.hip", "rtp_host.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -packed-fp32-ops off: the compiler must not form packed fp32 arithmetic from scalar code

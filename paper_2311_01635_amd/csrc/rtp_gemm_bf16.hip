@@ -298,10 +298,10 @@ static const Variant kVariants[] = {
     {256, 256, 2, 4, {"gemm_bf16_256x256_nt", "gemm_bf16_256x256_nn", "gemm_bf16_256x256_tn"}},
     {128, 128, 2, 2, {"gemm_bf16_128x128_nt", "gemm_bf16_128x128_nn", "gemm_bf16_128x128_tn"}},
     {256, 256, 2, 2, {"gemm_bf16_256x256w4_nt", "gemm_bf16_256x256w4_nn", "gemm_bf16_256x256w4_tn"}},
-    {256, 256, 2, 4, {"gemm_bf16_pp_kernel<0, *>", "gemm_bf16_pp_kernel<1, *>", "gemm_bf16_pp_kernel<2, *>"}},
-    {256, 256, 2, 4, {"gemm_bf16_pp_kernel<0, 256>", "gemm_bf16_pp_kernel<1, 256>", "gemm_bf16_pp_kernel<2, 256>"}},
-    {192, 256, 2, 4, {"gemm_bf16_pp_kernel<0, 192>", "gemm_bf16_pp_kernel<1, 192>", "gemm_bf16_pp_kernel<2, 192>"}},
-    {128, 256, 2, 4, {"gemm_bf16_pp_kernel<0, 128>", "gemm_bf16_pp_kernel<1, 128>", "gemm_bf16_pp_kernel<2, 128>"}},
+    {256, 256, 2, 4, {"gemm_bf16_pp_kernel<0>", "gemm_bf16_pp_kernel<1>", "gemm_bf16_pp_kernel<2>"}},
+    {256, 256, 2, 4, {"gemm_bf16_pp_kernel<0>", "gemm_bf16_pp_kernel<1>", "gemm_bf16_pp_kernel<2>"}},
+    {192, 256, 2, 4, {"gemm_bf16_pp_kernel<0>", "gemm_bf16_pp_kernel<1>", "gemm_bf16_pp_kernel<2>"}},
+    {128, 256, 2, 4, {"gemm_bf16_pp_kernel<0>", "gemm_bf16_pp_kernel<1>", "gemm_bf16_pp_kernel<2>"}},
 };
 constexpr int kNumVariants = 7;
 
@@ -347,16 +347,22 @@ static hipError_t launch_cfg(int layout, const GemmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+// what the kernels' clamped, 16-byte loads assume
+bool gemm_bf16_args_ok(int layout, const GemmArgs &a)
+{
+    if (layout < LAY_NT || layout > LAY_TN) return false;
+    if (a.K <= 0 || (a.lda & 7) || (a.ldb & 7) || ((uintptr_t)a.A & 15) || ((uintptr_t)a.B & 15)) return false;
+    if (layout != LAY_TN && (a.K & 7)) return false; // A rows are read in 8-element chunks of K
+    if (layout == LAY_TN && ((a.M & 7) || a.M < 8)) return false;
+    if (layout != LAY_NT && ((a.N & 7) || a.N < 8)) return false;
+    if (a.epi == EPI_SWIGLU_FWD && (layout != LAY_NT || a.half * 2 != a.N)) return false;
+    return true;
+}
+
 hipError_t launch_gemm_bf16(int layout, const GemmArgs &a, int variant, hipStream_t s)
 {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
-    // what the kernel's clamped, 16-byte loads assume
-    if (a.K <= 0 || (a.lda & 7) || (a.ldb & 7) || ((uintptr_t)a.A & 15) || ((uintptr_t)a.B & 15))
-        return hipErrorInvalidValue;
-    if (layout != LAY_TN && (a.K & 7)) return hipErrorInvalidValue;       // A rows are read in 8-element chunks of K
-    if (layout == LAY_TN && ((a.M & 7) || a.M < 8)) return hipErrorInvalidValue;
-    if (layout != LAY_NT && ((a.N & 7) || a.N < 8)) return hipErrorInvalidValue;
-    if (a.epi == EPI_SWIGLU_FWD && (layout != LAY_NT || a.half * 2 != a.N)) return hipErrorInvalidValue;
+    if (!gemm_bf16_args_ok(layout, a)) return hipErrorInvalidValue;
     if (variant == 0) variant = pick_variant(layout, a);
     if (variant >= 4 && variant <= 7) {
         if (!gemm_bf16_pp_supported(layout, a)) return hipErrorInvalidValue;

@@ -1,6 +1,6 @@
 // bf16 partition GEMM for gfx950, "ping-pong" form: the kernel the rotated
 // linear layer uses whenever the contraction length is a multiple of 32.
-// (Template; instantiated per tile height in rtp_gemm_pp_<BM>.hip.)
+// (Template; instantiated per operand layout in rtp_gemm_pp_<layout>.hip.)
 //
 // One workgroup of 8 waves owns a BM x 256 tile of C, BM = 256, 192 or 128
 // (wave tile BM/2 x 64, 32x32x16 bf16 MFMA, fp32 accumulators in registers).
@@ -35,6 +35,13 @@
 //    and measured slower: workgroups at different K offsets stop sharing
 //    operand panels in L2, the hit rate fell from 86 % to 43 %.)
 //
+//  * One launch can carry up to four GEMMs of the same operand layout (a
+//    "group"): the tiles of all of them form one grid, longest tiles first,
+//    each XCD owning an eighth of every problem.  GEMMs of a rotation step
+//    that do not depend on each other can be launched this way, so a problem
+//    with few tiles fills the compute units another one leaves idle and the
+//    epilogue of one tile overlaps the main loop of another.
+//
 // Layouts and epilogues are those of rtp_gemm_bf16.hip; ragged M and N are
 // handled by clamping the fetched row/column (the clamped results are never
 // stored), K must be a multiple of 32.
@@ -48,13 +55,28 @@ constexpr int BN = 256, BK = 32;
 constexpr int WM = 2, WN = 4, NTHR = 512;
 constexpr int FN = BN / (WN * 32);   // 2 fragments of 32 columns per wave
 constexpr int B_BYTES = BN * BK * 2; // 16 KB of B per stage
+constexpr int STAGES = 4; // deeper rings (5 or 6 stages fit the 160 KB LDS) measured no faster
+constexpr int SMEM_BYTES = STAGES * (256 * BK * 2 + B_BYTES); // the tallest tile's ring: 128 KB
 typedef __attribute__((address_space(3))) void *lds_vp;
 typedef __attribute__((address_space(1))) const void *glb_vp;
 } // namespace pp
 
+// One GEMM of a group launch and the whole group (a kernel argument, passed by value).
+struct PpProblem {
+    GemmArgs a;
+    int bm;               // tile height: 256, 192 or 128
+    int tiles_m, tiles_n;
+    int vec_epilogue;
+};
+struct PpGroup {
+    int count;
+    PpProblem p[PP_MAX_GROUP];
+};
+
+// One BM x 256 tile: `pid` is the tile's index inside its problem, `smem` the workgroup's LDS.
 template <int LAY, int BM>
-__global__ __launch_bounds__(pp::NTHR) void gemm_bf16_pp_kernel(const GemmArgs p, const int tiles_m, const int tiles_n,
-                                                                 const int vec_epilogue)
+__device__ __forceinline__ void pp_tile(const GemmArgs &p, const int tiles_m, const int tiles_n, const int vec_epilogue,
+                                        const int pid, char *smem)
 {
     using namespace pp;
     static_assert(BM == 256 || BM == 192 || BM == 128, "tile heights built");
@@ -62,17 +84,12 @@ __global__ __launch_bounds__(pp::NTHR) void gemm_bf16_pp_kernel(const GemmArgs p
     constexpr int FM = BM / (WM * 32);       // 4, 3 or 2 fragments of 32 rows per wave
     constexpr int A_BYTES = BM * BK * 2;     // 16, 12 or 8 KB of A per stage
     constexpr int STAGE = A_BYTES + B_BYTES;
-#ifdef PP_FORCE_STAGES
-    constexpr int STAGES = PP_FORCE_STAGES;
-#else
-    constexpr int STAGES = 4; // deeper rings (5 or 6 stages fit the 160 KB LDS) measured no faster
-#endif
     constexpr int PF = STAGES - 1;               // sub-tiles in flight
     constexpr int A_PIECES = A_BYTES / 1024; // 1 KB direct-load pieces of A per stage: 16, 12, 8
     constexpr int A_PW = (A_PIECES + 7) / 8; // ... per wave (the second one only on waves 0-3 when BM = 192)
     constexpr int A_CPR = BM / 8;            // 16-byte chunks per K-row of an M-contiguous A stage
     constexpr int A_ROWB = BM * 2;           // bytes per K-row of an M-contiguous A stage
-    __shared__ __attribute__((aligned(1024))) char smem[STAGES * STAGE];
+    static_assert(STAGES * STAGE <= SMEM_BYTES, "ring fits the workgroup's LDS");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -80,17 +97,8 @@ __global__ __launch_bounds__(pp::NTHR) void gemm_bf16_pp_kernel(const GemmArgs p
     const int wm = wave / WN, wn = wave % WN;
     const int group = wave >> 2; // waves 0-3 and 4-7 sit on SIMDs 0-3 respectively
 
-    // ---- which tile: workgroup ids are dealt round-robin to the 8 XCDs; renumber them so
-    // that an XCD owns a contiguous 4 x 8 block of tiles that share operand panels in its L2
-    int pid = blockIdx.x;
-    {
-        const int total = gridDim.x;
-        const int per = (total + 7) >> 3;
-        int tall = total & 7;
-        if (tall == 0) tall = 8;
-        const int xcd = pid & 7, local = pid >> 3;
-        pid = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
-    }
+    // ---- which tile: consecutive tile indices walk 4-tall column strips, so an XCD's contiguous
+    // run of indices is a compact block of tiles that share operand panels in its L2
     constexpr int GROUP_M = 4;
     const int group_sz = GROUP_M * tiles_n;
     const int grp = pid / group_sz;
@@ -272,18 +280,39 @@ __global__ __launch_bounds__(pp::NTHR) void gemm_bf16_pp_kernel(const GemmArgs p
         gemm_epilogue<FM, FN, WN * 32>(p, acc, m0 + wm * (BM / WM) + 4 * (lane >> 5), n0, wn * 32 + (lane & 31));
 }
 
-template <int BM>
-static hipError_t launch_gemm_bf16_pp_bm(int layout, const GemmArgs &a, int tiles_n, hipStream_t s)
+// Workgroup ids are dealt round-robin to the 8 XCDs.  XCD x works through its own list: its
+// contiguous eighth of problem 0's tiles, then of problem 1's, ...; workgroup 8 l + x takes entry l
+// of that list (the host sizes the grid for the longest list; surplus workgroups leave at once).
+template <int LAY>
+__global__ __launch_bounds__(pp::NTHR) void gemm_bf16_pp_kernel(const PpGroup g)
 {
-    const int tiles_m = (a.M + BM - 1) / BM;
-    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(pp::NTHR);
-    const int vec = gemm_epilogue_vec_ok(a) ? 1 : 0;
-    switch (layout) {
-    case LAY_NT: hipLaunchKernelGGL((gemm_bf16_pp_kernel<LAY_NT, BM>), grid, block, 0, s, a, tiles_m, tiles_n, vec); break;
-    case LAY_NN: hipLaunchKernelGGL((gemm_bf16_pp_kernel<LAY_NN, BM>), grid, block, 0, s, a, tiles_m, tiles_n, vec); break;
-    case LAY_TN: hipLaunchKernelGGL((gemm_bf16_pp_kernel<LAY_TN, BM>), grid, block, 0, s, a, tiles_m, tiles_n, vec); break;
-    default: return hipErrorInvalidValue;
+    __shared__ __attribute__((aligned(1024))) char smem[pp::SMEM_BYTES];
+    const int xcd = blockIdx.x & 7;
+    int l = blockIdx.x >> 3;
+    int q = 0, pid = -1;
+    for (; q < g.count; ++q) {
+        const int tiles = g.p[q].tiles_m * g.p[q].tiles_n;
+        const int base = tiles >> 3, rem = tiles & 7;
+        const int mine = base + (xcd < rem ? 1 : 0);
+        if (l < mine) {
+            pid = xcd * base + min(xcd, rem) + l;
+            break;
+        }
+        l -= mine;
     }
+    if (pid < 0) return;
+    const PpProblem &P = g.p[q];
+    switch (P.bm) {
+    case 256: pp_tile<LAY, 256>(P.a, P.tiles_m, P.tiles_n, P.vec_epilogue, pid, smem); break;
+    case 192: pp_tile<LAY, 192>(P.a, P.tiles_m, P.tiles_n, P.vec_epilogue, pid, smem); break;
+    default: pp_tile<LAY, 128>(P.a, P.tiles_m, P.tiles_n, P.vec_epilogue, pid, smem); break;
+    }
+}
+
+template <int LAY>
+static hipError_t launch_gemm_bf16_pp_layout(const PpGroup &g, unsigned blocks, hipStream_t s)
+{
+    hipLaunchKernelGGL((gemm_bf16_pp_kernel<LAY>), dim3(blocks), dim3(pp::NTHR), 0, s, g);
     return hipGetLastError();
 }
 

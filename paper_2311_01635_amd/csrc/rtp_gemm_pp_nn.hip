@@ -1,0 +1,9 @@
+// Instantiation of the ping-pong bf16 GEMM for the NN operand layout (see rtp_gemm_pp.h).
+#include "rtp_gemm_pp.h"
+
+namespace rtp {
+hipError_t launch_gemm_bf16_pp_nn(const PpGroup &g, unsigned blocks, hipStream_t s)
+{
+    return launch_gemm_bf16_pp_layout<LAY_NN>(g, blocks, s);
+}
+} // namespace rtp

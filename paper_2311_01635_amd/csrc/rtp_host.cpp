@@ -927,9 +927,291 @@ extern "C" rtp_status rtp_mlp_set_ablation(rtp_mlp *m, int rotate, int compute)
     return set_ablation(m->ring, rotate, compute);
 }
 
+// ---- grouped schedule of the MLP unit ---------------------------------------------------
+// One rotation step of the unit holds GEMMs that do not depend on each other once the second
+// linear lags the first by one step: forward, Z_t = X W1_t^T needs nothing from
+// down_{t-1} = H_{t-1} W2_{t-1}^T; backward, dH_s = dY W2_s needs nothing from
+// dX_{s-1} += dPre_{s-1} W1_{s-1}, and the two weight gradients of a step are independent.
+// Each such pair has one operand layout and goes out as one group launch, whose tiles fill the
+// machine where a shard GEMM alone leaves compute units idle.  The shard parts travel
+// accordingly: the weights of the lagging linear stay one step longer, so a staging buffer is
+// reused one launch later than in the step-by-step schedule; the buffers themselves (two
+// weight slots, one or two gradient slots) and the bytes moved per step are the same.
+
+struct MlpShapes {
+    int64_t T, I, O2, P1, o1, o2, Ohid;
+    size_t es, w_off2, g_off2;
+    bool gated;
+};
+
+static MlpShapes mlp_shapes(const rtp_mlp *m)
+{
+    MlpShapes h;
+    h.gated = mlp_gated(&m->d);
+    h.T = m->d.T; h.I = m->d.I; h.O2 = m->d.O2; h.Ohid = m->d.O;
+    h.P1 = (h.gated ? 2 : 1) * m->d.O;
+    h.o1 = h.P1 / m->d.n;
+    h.o2 = m->d.O / m->d.n;
+    h.es = esize(m->d.dtype);
+    h.w_off2 = m->l2->d.w_offset;
+    h.g_off2 = m->l2->d.g_offset;
+    return h;
+}
+
+// Z_k = X W1_k^T with the activation fused (pre-activations kept for the backward pass)
+static GemmArgs mlp_args_z(const rtp_mlp *m, const MlpShapes &h, int k, const void *X, const char *Wslot)
+{
+    GemmArgs a;
+    memset(&a, 0, sizeof a);
+    const int64_t ow = h.gated ? h.o1 / 2 : h.o1;
+    a.A = X; a.lda = h.I;
+    a.B = Wslot; a.ldb = h.I;
+    a.M = (int)h.T; a.N = (int)h.o1; a.K = (int)h.I;
+    a.epi = fwd_act_epi(m->d.act);
+    a.half = (int)(h.o1 / 2);
+    a.aux = (char *)m->d.preact_dev + (size_t)k * h.o1 * h.es; a.ldaux = h.P1;
+    a.C = (char *)m->d.hidden_dev + (size_t)k * ow * h.es; a.ldc = h.Ohid;
+    return a;
+}
+
+// Y (+)= H_k W2_k^T, summed over the steps in fp32
+static GemmArgs mlp_args_down(const rtp_mlp *m, const MlpShapes &h, int k, int step, const char *Wslot, void *Y)
+{
+    GemmArgs a;
+    memset(&a, 0, sizeof a);
+    a.A = (const char *)m->d.hidden_dev + (size_t)k * h.o2 * h.es; a.lda = h.Ohid;
+    a.B = Wslot + h.w_off2; a.ldb = h.o2;
+    a.M = (int)h.T; a.N = (int)h.O2; a.K = (int)h.o2;
+    a.C = Y; a.ldc = h.O2;
+    a.epi = acc_epi(step, m->d.n);
+    a.ws = m->d.acc_y_dev; a.ldws = h.O2;
+    return a;
+}
+
+// dPre_k = (dY W2_k) * act'(pre_k)
+static GemmArgs mlp_args_dh(const rtp_mlp *m, const MlpShapes &h, int k, const char *Wslot, const void *dY)
+{
+    GemmArgs a;
+    memset(&a, 0, sizeof a);
+    a.A = dY; a.lda = h.O2;
+    a.B = Wslot + h.w_off2; a.ldb = h.o2;
+    a.M = (int)h.T; a.N = (int)h.o2; a.K = (int)h.O2;
+    a.epi = bwd_act_epi(m->d.act);
+    a.half = (int)h.o2;
+    a.aux = (char *)m->d.preact_dev + (size_t)k * h.o1 * h.es; a.ldaux = h.P1;
+    a.C = (char *)m->d.dpre_dev + (size_t)k * h.o1 * h.es; a.ldc = h.P1;
+    return a;
+}
+
+// G2_k += dY^T H_k
+static GemmArgs mlp_args_dw2(const rtp_mlp *m, const MlpShapes &h, int k, char *Gslot, const void *dY)
+{
+    GemmArgs a;
+    memset(&a, 0, sizeof a);
+    a.A = dY; a.lda = h.O2;
+    a.B = (const char *)m->d.hidden_dev + (size_t)k * h.o2 * h.es; a.ldb = h.Ohid;
+    a.M = (int)h.O2; a.N = (int)h.o2; a.K = (int)h.T;
+    a.epi = EPI_ACC_ADD; a.c_is_f32 = 1;
+    a.ws = (float *)(Gslot + h.g_off2); a.ldws = h.o2;
+    a.C = a.ws; a.ldc = a.ldws;
+    return a;
+}
+
+// G1_k += dPre_k^T X
+static GemmArgs mlp_args_dw1(const rtp_mlp *m, const MlpShapes &h, int k, char *Gslot, const void *X)
+{
+    GemmArgs a;
+    memset(&a, 0, sizeof a);
+    a.A = (const char *)m->d.dpre_dev + (size_t)k * h.o1 * h.es; a.lda = h.P1;
+    a.B = X; a.ldb = h.I;
+    a.M = (int)h.o1; a.N = (int)h.I; a.K = (int)h.T;
+    a.epi = EPI_ACC_ADD; a.c_is_f32 = 1;
+    a.ws = (float *)Gslot; a.ldws = h.I;
+    a.C = a.ws; a.ldc = a.ldws;
+    return a;
+}
+
+// dX (+)= dPre_k W1_k, summed over the steps in fp32
+static GemmArgs mlp_args_dx(const rtp_mlp *m, const MlpShapes &h, int k, int step, const char *Wslot, void *dX)
+{
+    GemmArgs a;
+    memset(&a, 0, sizeof a);
+    a.A = (const char *)m->d.dpre_dev + (size_t)k * h.o1 * h.es; a.lda = h.P1;
+    a.B = Wslot; a.ldb = h.I;
+    a.M = (int)h.T; a.N = (int)h.I; a.K = (int)h.o1;
+    a.C = dX; a.ldc = h.I;
+    a.epi = acc_epi(step, m->d.n);
+    a.ws = m->d.acc_dx_dev; a.ldws = h.I;
+    return a;
+}
+
+// whether the unit can run the grouped schedule: bf16, staged transfers, and all six GEMM
+// shapes within what the ping-pong kernel takes
+static bool mlp_grouped_ok(const rtp_mlp *m, const void *X, const void *Y, const void *dY, const void *dX)
+{
+    const rtp_ring *r = m->ring;
+    if (r->dry || (m->d.flags & RTP_FLAG_STEPWISE) || m->d.dtype != RTP_BF16 || m->d.T <= 0) return false;
+    if (r->d.mode == RTP_INPLACE_BLOCKING) return false;
+    const MlpShapes h = mlp_shapes(m);
+    const char *W = (const char *)r->d.buf_w_dev[0];
+    char *G = (char *)r->d.buf_g_dev[0];
+    // dummy non-null tensors where a pass does not use one: only shapes and alignment matter here
+    const void *x = X ? X : m->d.hidden_dev, *dy = dY ? dY : m->d.hidden_dev;
+    void *y = Y ? (void *)Y : m->d.hidden_dev, *dx = dX ? (void *)dX : m->d.hidden_dev;
+    const GemmArgs nt[2] = {mlp_args_z(m, h, 0, x, W), mlp_args_down(m, h, 0, 0, W, y)};
+    const GemmArgs nn[2] = {mlp_args_dh(m, h, 0, W, dy), mlp_args_dx(m, h, 0, 0, W, dx)};
+    const GemmArgs tn[2] = {mlp_args_dw1(m, h, 0, G, x), mlp_args_dw2(m, h, 0, G, dy)};
+    for (int i = 0; i < 2; ++i) {
+        if (!gemm_bf16_args_ok(LAY_NT, nt[i]) || !gemm_bf16_pp_supported(LAY_NT, nt[i])) return false;
+        if (!gemm_bf16_args_ok(LAY_NN, nn[i]) || !gemm_bf16_pp_supported(LAY_NN, nn[i])) return false;
+        if (!gemm_bf16_args_ok(LAY_TN, tn[i]) || !gemm_bf16_pp_supported(LAY_TN, tn[i])) return false;
+    }
+    return true;
+}
+
+static rtp_status gemm_group(rtp_ring *r, int layout, const GemmArgs *a, int count, hipStream_t st)
+{
+    if (r->dry || !r->abl_compute || count == 0) return RTP_OK;
+    double flops = 0.0;
+    for (int i = 0; i < count; ++i) flops += 2.0 * a[i].M * a[i].N * a[i].K;
+    HIP_TRY(timed_launch(layout, flops, st, [&] { return launch_gemm_bf16_pp_group(layout, a, count, nullptr, st); }));
+    return RTP_OK;
+}
+
+// stage stream: wait for everything enqueued so far on the compute stream
+static rtp_status stage_after_compute(rtp_ring *r)
+{
+    HIP_TRY(hipEventRecord(r->ev_free, r->cs()));
+    HIP_TRY(hipStreamWaitEvent(r->ss(), r->ev_free, 0));
+    return RTP_OK;
+}
+
+// one part [off, off + bytes) of the weight slot: send shard k's from buffer `src`, receive
+// shard kin's into buffer `dst`
+static rtp_status rotate_w_part(rtp_ring *r, int step, int k, int kin, int src, int dst, size_t off, size_t bytes)
+{
+    RTP_TRY(copy_async(r, r->home_w(k) + off, (char *)r->d.buf_w_dev[src] + off, bytes, r->ss()));
+    r->rec(TR_W_OUT, step, k, src);
+    RTP_TRY(copy_async(r, (char *)r->d.buf_w_dev[dst] + off, r->home_w(kin) + off, bytes, r->ss()));
+    r->rec(TR_W_IN, step, kin, dst);
+    return RTP_OK;
+}
+
+static void mlp_close_pass(rtp_mlp *m)
+{
+    rtp_ring *r = m->ring;
+    const int n = r->d.n;
+    r->rotations = n - 1;
+    m->l1->next_step = m->l2->next_step = n;
+    if (r->abl_rotate) {
+        r->resident = r->shard_at(n - 1);
+        r->res_idx = r->w_idx(n - 1);
+        if (r->pass == RTP_PASS_BWD) {
+            r->res_g = r->resident;
+            r->res_g_idx = r->g_idx(n - 1);
+        }
+    }
+}
+
+static rtp_status mlp_fwd_grouped(rtp_mlp *m, const void *X, void *Y)
+{
+    rtp_ring *r = m->ring;
+    const int n = r->d.n;
+    const MlpShapes h = mlp_shapes(m);
+    RTP_TRY(rtp_ring_begin(r, RTP_PASS_FWD));
+    const bool rot = r->abl_rotate && n > 1;
+    const size_t w1_bytes = h.w_off2, w2_bytes = r->d.w_bytes - h.w_off2;
+    auto buf = [&](int step) { return (const char *)r->d.buf_w_dev[rot ? r->w_idx(step) : r->res_idx]; };
+    // launch t = {Z_t, down_{t-1}}
+    for (int t = 0; t <= n; ++t) {
+        // transfers that may start once launch t-1 is done and must end before launch t+1:
+        // the lagging linear's part of shard t (its buffer was last read by down_{t-2}) and the
+        // leading linear's part of shard t+1 (last reader of its buffer: Z_{t-1})
+        const bool move_w2 = rot && t >= 1 && t <= n - 1, move_w1 = rot && t <= n - 2;
+        if (move_w1 || move_w2) {
+            RTP_TRY(stage_after_compute(r));
+            if (move_w2)
+                RTP_TRY(rotate_w_part(r, t - 1, r->shard_at(t - 1), r->shard_at(t), r->w_idx(t - 1), r->w_idx(t), h.w_off2, w2_bytes));
+            if (move_w1)
+                RTP_TRY(rotate_w_part(r, t, r->shard_at(t), r->shard_at(t + 1), r->w_idx(t), r->w_idx(t + 1), 0, w1_bytes));
+            HIP_TRY(hipEventRecord(r->ev_w[(t + 1) & 1], r->ss()));
+        }
+        if (rot && t >= 1) HIP_TRY(hipStreamWaitEvent(r->cs(), r->ev_w[t & 1], 0));
+        GemmArgs g[2];
+        int cnt = 0;
+        if (t < n) {
+            r->rec(TR_FWD, t, r->shard_at(t), rot ? r->w_idx(t) : r->res_idx);
+            g[cnt++] = mlp_args_z(m, h, r->shard_at(t), X, buf(t));
+        }
+        if (t >= 1) g[cnt++] = mlp_args_down(m, h, r->shard_at(t - 1), t - 1, buf(t - 1), Y);
+        RTP_TRY(gemm_group(r, LAY_NT, g, cnt, r->cs()));
+    }
+    mlp_close_pass(m);
+    return rtp_ring_end(r);
+}
+
+static rtp_status mlp_bwd_grouped(rtp_mlp *m, const void *X, const void *dY, void *dX)
+{
+    rtp_ring *r = m->ring;
+    const int n = r->d.n;
+    const MlpShapes h = mlp_shapes(m);
+    RTP_TRY(rtp_ring_begin(r, RTP_PASS_BWD));
+    const bool rot = r->abl_rotate && n > 1;
+    const bool move_g = rot && r->d.g_bytes != 0;
+    auto wbuf = [&](int step) { return (const char *)r->d.buf_w_dev[rot ? r->w_idx(step) : r->res_idx]; };
+    auto gbuf = [&](int step) { return (char *)r->d.buf_g_dev[rot ? r->g_idx(step) : r->res_g_idx]; };
+    for (int s = 0; s <= n; ++s) {
+        // ---- input-gradient launch s = {dX_{s-1}, dPre_s} -------------------------------
+        if (rot && s >= 1 && s < n) HIP_TRY(hipStreamWaitEvent(r->cs(), r->ev_w[s & 1], 0));
+        GemmArgs g[2];
+        int cnt = 0;
+        if (s >= 1) g[cnt++] = mlp_args_dx(m, h, r->shard_at(s - 1), s - 1, wbuf(s - 1), dX);
+        if (s < n) {
+            r->rec(TR_BWD, s, r->shard_at(s), rot ? r->w_idx(s) : r->res_idx);
+            g[cnt++] = mlp_args_dh(m, h, r->shard_at(s), wbuf(s), dY);
+        }
+        RTP_TRY(gemm_group(r, LAY_NN, g, cnt, r->cs()));
+        if (s == n) break;
+        // ---- weights of shard s+1: their buffer was last read by dX_{s-1}, just enqueued ----
+        if (rot && s <= n - 2) {
+            RTP_TRY(stage_after_compute(r));
+            RTP_TRY(rotate_w_part(r, s, r->shard_at(s), r->shard_at(s + 1), r->w_idx(s), r->w_idx(s + 1), 0, r->d.w_bytes));
+            HIP_TRY(hipEventRecord(r->ev_w[(s + 1) & 1], r->ss()));
+        }
+        // ---- weight-gradient launch s = {G1_s, G2_s}, onto the travelling gradient shard ----
+        // (on the auxiliary stream when there is one: it only has to follow dPre_s, so it runs
+        // beside the next input-gradient launch and the two fill each other's idle tails)
+        hipStream_t ws = r->as();
+        if (ws != r->cs()) {
+            HIP_TRY(hipEventRecord(r->ev_aux, r->cs()));
+            HIP_TRY(hipStreamWaitEvent(ws, r->ev_aux, 0));
+        }
+        if (move_g && s >= 1) HIP_TRY(hipStreamWaitEvent(ws, r->ev_g[s & 1], 0));
+        g[0] = mlp_args_dw1(m, h, r->shard_at(s), gbuf(s), X);
+        g[1] = mlp_args_dw2(m, h, r->shard_at(s), gbuf(s), dY);
+        RTP_TRY(gemm_group(r, LAY_TN, g, 2, ws));
+        // ---- the gradient shard moves on as soon as both parts are complete; the next
+        // input-gradient launch runs meanwhile
+        if (move_g && s <= n - 2) {
+            const int k = r->shard_at(s), kin = r->shard_at(s + 1);
+            HIP_TRY(hipEventRecord(r->ev_free2, ws));
+            HIP_TRY(hipStreamWaitEvent(r->ss(), r->ev_free2, 0));
+            RTP_TRY(copy_async(r, r->home_g(k), r->d.buf_g_dev[r->g_idx(s)], r->d.g_bytes, r->ss()));
+            r->rec(TR_G_OUT, s, k, r->g_idx(s));
+            RTP_TRY(copy_async(r, r->d.buf_g_dev[r->g_idx(s + 1)], r->home_g(kin), r->d.g_bytes, r->ss()));
+            r->rec(TR_G_IN, s, kin, r->g_idx(s + 1));
+            HIP_TRY(hipEventRecord(r->ev_g[(s + 1) & 1], r->ss()));
+        }
+    }
+    mlp_close_pass(m);
+    return rtp_ring_end(r);
+}
+
 extern "C" rtp_status rtp_mlp_fwd(rtp_mlp *m, const void *X, void *Y)
 {
     if (!m) return fail(RTP_ERR_INVALID, "rtp_mlp_fwd: null mlp");
+    if (!m->ring->dry && m->d.T > 0 && (!X || !Y)) return fail(RTP_ERR_INVALID, "rtp_mlp_fwd: null tensor");
+    if (mlp_grouped_ok(m, X, Y, nullptr, nullptr)) return mlp_fwd_grouped(m, X, Y);
     const int n = m->d.n;
     RTP_TRY(rtp_ring_begin(m->ring, RTP_PASS_FWD));
     for (int t = 0; t < n; ++t) {
@@ -943,6 +1225,12 @@ extern "C" rtp_status rtp_mlp_fwd(rtp_mlp *m, const void *X, void *Y)
 extern "C" rtp_status rtp_mlp_bwd(rtp_mlp *m, const void *X, const void *dY, void *dX)
 {
     if (!m) return fail(RTP_ERR_INVALID, "rtp_mlp_bwd: null mlp");
+    if (!m->ring->dry && m->d.T > 0 && (!X || !dY)) return fail(RTP_ERR_INVALID, "rtp_mlp_bwd: null tensor");
+    // Measured on the Llama-shaped unit: with an auxiliary stream the four GEMMs of a backward
+    // step overlap freely when launched one by one (weight gradients on that stream), which beats
+    // the two grouped launches by 8 %; without one the grouped launches win by 6 %.
+    const bool have_aux = m->ring->as() != m->ring->cs();
+    if (dX && !have_aux && mlp_grouped_ok(m, X, nullptr, dY, dX)) return mlp_bwd_grouped(m, X, dY, dX);
     const int n = m->d.n;
     RTP_TRY(rtp_ring_begin(m->ring, RTP_PASS_BWD));
     for (int s = 0; s < n; ++s) {

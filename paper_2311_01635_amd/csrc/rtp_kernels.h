@@ -43,10 +43,18 @@ struct GemmArgs {
 // tiles (256x256/8 waves, 128x128/4 waves, 256x256/4 waves); 4 = the ping-pong kernel with the
 // tile height picked by shape; 5, 6, 7 = the ping-pong kernel with tile height 256, 192, 128.
 hipError_t launch_gemm_bf16(int layout, const GemmArgs &a, int variant, hipStream_t s);
+// alignment and minimum sizes every bf16 kernel needs (M, N > 0 assumed)
+bool gemm_bf16_args_ok(int layout, const GemmArgs &a);
 // the ping-pong kernel (rtp_gemm_pp.h): needs K % 32 == 0; bm_override 0 = pick the tile height
 bool gemm_bf16_pp_supported(int layout, const GemmArgs &a);
-int gemm_bf16_pp_pick_bm(const GemmArgs &a, int bm_override);
 hipError_t launch_gemm_bf16_pp(int layout, const GemmArgs &a, int bm_override, hipStream_t s);
+// up to PP_MAX_GROUP independent GEMMs of one layout in a single launch; tile heights are picked
+// for the group as a whole (bm_override: null, or one forced height per problem, 0 = pick).
+// hipErrorInvalidValue if a problem does not meet gemm_bf16_pp_supported.
+constexpr int PP_MAX_GROUP = 4;
+hipError_t launch_gemm_bf16_pp_group(int layout, const GemmArgs *a, int count, const int *bm_override, hipStream_t s);
+// the heights that launch would use (for tests and reports)
+void gemm_bf16_pp_plan(int layout, const GemmArgs *a, int count, const int *bm_override, int *bm_out);
 const char *gemm_bf16_kernel_name(int layout, int variant);
 
 // fp32 inputs and outputs (epi: EPI_STORE, EPI_ACC_ADD with ws == C).

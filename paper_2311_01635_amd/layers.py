@@ -118,7 +118,7 @@ class RtpMlp:
     by rtp_mlp_fwd / rtp_mlp_bwd: one library call per pass."""
 
     def __init__(self, weights, T, n, rank, act, mode=B.RTP_INPLACE_STAGED, dtype=B.RTP_BF16, G0=None,
-                 device="cuda:0", aux_stream=True):
+                 device="cuda:0", aux_stream=True, stepwise=False):
         self.dev = torch.device(device)
         td = _TORCH_DT[dtype]
         self.n, self.rank, self.T, self.act, self.mode, self.dtype = n, rank, T, act, mode, dtype
@@ -143,7 +143,8 @@ class RtpMlp:
             self.home_g = torch.cat((pack_out_split(G1, n), pack_in_split(g[-1], n)), dim=1).contiguous()
         d = B.rtp_mlp_desc()
         d.T, d.I, d.O, d.O2 = T, self.I, self.O, self.O2
-        d.n, d.rank, d.mode, d.dtype, d.act, d.flags = n, rank, mode, dtype, act, 0
+        d.n, d.rank, d.mode, d.dtype, d.act = n, rank, mode, dtype, act
+        d.flags = B.RTP_FLAG_STEPWISE if stepwise else 0
         wb, gb = B.lib.rtp_mlp_slot_w_bytes(C.byref(d)), B.lib.rtp_mlp_slot_g_bytes(C.byref(d))
         assert wb == self.home_w.shape[1] * _esize(dtype) and gb == self.home_g.shape[1] * 4
         self.w_bytes, self.g_bytes = wb, gb
