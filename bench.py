@@ -83,7 +83,7 @@ def measured_traffic(workload, layout):
 def cpu_baseline(w, inp, tokens):
     """The oracle as it stands, one worker's full rotated fwd+bwd over a token
     sample (the first `tokens` rows), timed on this host's cores.  tokens = 0:
-    a 16-token probe sizes the sample for roughly 15 s of CPU work."""
+    two short probes (16 and 64 tokens) size the sample for roughly 15 s of CPU work."""
     import numpy as np
     import oracle as orc
     f64 = lambda a: np.ascontiguousarray(a, dtype=np.float64)
@@ -100,8 +100,10 @@ def cpu_baseline(w, inp, tokens):
         return time.perf_counter() - t0
 
     if tokens <= 0:
-        probe = run(16)
-        tokens = int(min(w.T, max(16, 15.0 / (probe / 16.0)))) // 16 * 16
+        t16, t64 = run(16), run(64)
+        per_token = max((t64 - t16) / 48.0, 1e-6)
+        fixed = max(t16 - 16 * per_token, 0.0)
+        tokens = int(min(w.T, max(64, (15.0 - fixed) / per_token))) // 16 * 16
     dt = run(tokens)
     flops = 6.0 * tokens * ((2 if gated else 1) * w.I * w.O + w.O * w.O2)
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
@@ -134,6 +136,18 @@ def main():
     ms = timed(torch, mlp, X, Y, dY, dX, a.steps)
     ms_step = ms / a.steps
     tflops = w.flops / (ms_step * 1e-3) / 1e12
+
+    # ---- the shader clock the chip sustains under this load (the MFMA peak scales with it) ----
+    probe_out = torch.zeros(2, dtype=torch.int64, device=dev)
+    probe_stream = torch.cuda.Stream(dev)
+    torch.cuda.synchronize()
+    mlp.forward(X, Y)                       # the probe starts once the load is on
+    mlp.backward(X, dY, dX)
+    khz = B.rtp_clock_probe(probe_stream, probe_out, int(ms_step * 1e3 * 3))
+    timed(torch, mlp, X, Y, dY, dX, 5)
+    torch.cuda.synchronize()
+    wall, cyc = probe_out.tolist()
+    clock_ghz = cyc / max(wall, 1) * khz / 1e6
 
     # ---- dominant kernel, instrumented repeat of the same steps --------------------
     B.rtp_prof_begin()
@@ -182,6 +196,8 @@ def main():
                    "worker_param_bytes": mlp.worker_bytes(),
                    "table1_rtp_worker_bytes": B.rtp_table1_worker_bytes(False, mlp.w_bytes, mlp.g_bytes)},
         "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
+        "sustained_clock_ghz": clock_ghz, "nominal_clock_ghz": 2.4,
+        "frac_of_peak_at_sustained_clock": tflops / (PEAK_BF16_TFLOPS * clock_ghz / 2.4) if clock_ghz > 0 else None,
         "roofline": roofline, "overlap": overlap, "cpu_baseline": cpu,
     }
     mlp.close()

@@ -312,6 +312,17 @@ typedef struct { int64_t launches; double total_ms; double total_flops; } rtp_pr
 rtp_status rtp_prof_begin(void);
 rtp_status rtp_prof_end(rtp_prof_result out[3]);
 
+/* ---- sustained shader clock ------------------------------------------------ */
+
+/* Enqueues a one-wave kernel on `stream` that spins for `wall_us` microseconds
+ * of the constant-rate wall clock and then writes two int64 to `out_dev`
+ * (device memory, 16 bytes): the wall-clock ticks and the shader-clock cycles
+ * it saw.  Launched on a stream of its own beside the GEMMs it reports the
+ * clock the chip sustains under that load (the figure the MFMA peak scales
+ * with).  *wall_khz receives the wall clock's rate.  wall_us is capped at one
+ * second. */
+rtp_status rtp_clock_probe(void *stream, void *out_dev, int64_t wall_us, int *wall_khz);
+
 #ifdef __cplusplus
 }
 #endif

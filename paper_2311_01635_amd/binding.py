@@ -68,6 +68,7 @@ SYMBOLS = {
     "rtp_worker_bytes": (C.c_size_t, [C.c_int, C.c_size_t, C.c_size_t]),
     "rtp_table1_worker_bytes": (C.c_size_t, [C.c_int, C.c_size_t, C.c_size_t]),
     "rtp_status_str": (C.c_char_p, [C.c_int]),
+    "rtp_clock_probe": (C.c_int, [_P, _P, C.c_int64, C.POINTER(C.c_int)]),
     "rtp_last_error": (C.c_char_p, []),
     "rtp_ring_create": (C.c_int, [C.POINTER(_P), C.POINTER(rtp_ring_desc)]),
     "rtp_ring_destroy": (C.c_int, [_P]),
@@ -104,7 +105,7 @@ SYMBOLS = {
 def load_library(path: str = LIB_PATH):
     if not os.path.exists(path):
         raise RuntimeError(
-            f"{path} is missing: build it with `python -m paper_2311_01635_amd.build` "
+            f"{path} is missing: build it with `python paper_2311_01635_amd/build.py` "
             "(or __graft_entry__.build()); there is no fallback path")
     lib = C.CDLL(path)
     for name, (res, args) in SYMBOLS.items():
@@ -265,3 +266,11 @@ def rtp_prof_end():
     out = (rtp_prof_result * 3)()
     check(lib.rtp_prof_end(out), "rtp_prof_end")
     return {name: (out[i].launches, out[i].total_ms, out[i].total_flops) for i, name in enumerate(("nt", "nn", "tn"))}
+
+
+def rtp_clock_probe(stream, out, wall_us):
+    """Enqueue the clock probe on `stream`; `out` is an int64[2] device tensor.  Returns the wall
+    clock's rate in kHz; after the stream has drained, out[1] / out[0] * kHz is the shader clock."""
+    khz = C.c_int(0)
+    check(lib.rtp_clock_probe(_stream(stream), _ptr(out), int(wall_us), C.byref(khz)), "rtp_clock_probe")
+    return khz.value

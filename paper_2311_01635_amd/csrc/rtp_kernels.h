@@ -69,4 +69,7 @@ hipError_t launch_act_f32(int kind, const float *pre, int64_t ldpre, const float
 hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
 hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s);
 
+// out[0] = wall-clock ticks, out[1] = shader cycles over a spin of wall_ticks
+hipError_t launch_clock_probe(long long *out, long long wall_ticks, hipStream_t s);
+
 } // namespace rtp

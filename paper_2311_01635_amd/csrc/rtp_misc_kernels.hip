@@ -200,4 +200,25 @@ hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s)
     return hipGetLastError();
 }
 
+// ---- shader-clock probe -------------------------------------------------------------------
+// Spins on the constant-rate wall clock for a bounded time and reports how many shader cycles
+// went by.  One wave, a handful of registers: it fits beside any kernel.
+__global__ void clock_probe_kernel(long long *out, long long wall_ticks)
+{
+    const long long w0 = wall_clock64(), c0 = clock64();
+    long long w1 = w0;
+    while (w1 - w0 < wall_ticks) w1 = wall_clock64();
+    const long long c1 = clock64();
+    if (threadIdx.x == 0) {
+        out[0] = w1 - w0;
+        out[1] = c1 - c0;
+    }
+}
+
+hipError_t launch_clock_probe(long long *out, long long wall_ticks, hipStream_t s)
+{
+    hipLaunchKernelGGL(clock_probe_kernel, dim3(1), dim3(64), 0, s, out, wall_ticks);
+    return hipGetLastError();
+}
+
 } // namespace rtp

@@ -212,3 +212,17 @@ def test_mlp_slot_sizes():
     # the large config's footprint against the table's per-worker bound
     assert B.rtp_worker_bytes(B.RTP_INPLACE_STAGED, w, g) == 234881024
     assert B.rtp_table1_worker_bytes(False, w, g) == orc.worker_param_bytes("rtp", 939524096, 1879048192, 16)
+
+
+def test_build_script_loads_without_the_library():
+    """build() must work on a tree that holds no built library yet: the build script is loaded by
+    path (the package itself refuses to import without librtp.so) and names sources that exist."""
+    import os
+
+    import __graft_entry__ as entry
+    root = os.path.dirname(os.path.abspath(entry.__file__))
+    mod = entry._load_by_path("_rtp_lib_build_test", os.path.join(root, "paper_2311_01635_amd", "build.py"))
+    for src in mod.SOURCES:
+        assert os.path.exists(os.path.join(mod.CSRC, src)), src
+    assert "paper_2311_01635_amd" not in open(entry.__file__).read().split("def build()")[1].split("lib_build.build")[0].replace(
+        '"paper_2311_01635_amd"', ""), "build() imports the package before building it"
