@@ -7,6 +7,11 @@ loudly when the shared library has not been built: there is no fallback.
 import ctypes as C
 import os
 
+# torch first: librtp.so must bind to the HIP runtime torch has loaded.  Loaded the other way round,
+# the library pulls in the system's copy and torch's tensors then live in a different runtime
+# (every HIP call of the library fails with "no ROCm-capable device").
+import torch  # noqa: F401
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "librtp.so")
 

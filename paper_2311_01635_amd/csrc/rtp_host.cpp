@@ -772,25 +772,32 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
     }
     a.C = a.ws; a.ldc = a.ldws;
     a.cu_share = split ? 2 : 1;
+    // The send of the gradient part is fused into the kernel that completes it: when the shard
+    // moves on after this step, the sum (arriving content + this worker's contribution) is written
+    // straight to where it travels to, instead of back into the buffer and copied from there.
+    const bool moves_on = rotating && r->d.g_bytes && r->d.mode != RTP_INPLACE_BLOCKING;
+    const bool fused_send = moves_on && !f32 && !r->dry && r->abl_compute && d.T > 0;
+    if (fused_send) {
+        a.epi = EPI_ACC_LAST;
+        a.C = r->home_g(k) + d.g_offset;
+    }
     if (d.T > 0) RTP_TRY(gemm(l, LAY_TN, a, ws));
 
     // ---- hand the gradient part to the stage stream ---------------------------
-    if (rotating && r->d.g_bytes && r->d.mode != RTP_INPLACE_BLOCKING) {
+    if (moves_on) {
         const int kin = rtp_bwd_shard(r->d.rank, step + 1, n);
         if (!r->dry) {
             HIP_TRY(hipEventRecord(l->ev_dw, ws));
             HIP_TRY(hipStreamWaitEvent(r->ss(), l->ev_dw, 0));
         }
         char *part = (char *)r->d.buf_g_dev[gi] + d.g_offset;
+        if (!fused_send) RTP_TRY(copy_async(r, r->home_g(k) + d.g_offset, part, l->g_shard_bytes, r->ss()));
+        r->rec(TR_G_OUT, step, k, gi);
         if (staged_g) {
-            // in place: this linear's part goes out and the next shard's comes in, in one pass
-            RTP_TRY(rotate_async(r, r->home_g(k) + d.g_offset, part, part, r->home_g(kin) + d.g_offset, l->g_shard_bytes, r->ss()));
-            r->rec(TR_G_OUT, step, k, gi);
+            // in place: the next shard's part comes into the buffer the kernel has just finished with
+            RTP_TRY(copy_async(r, part, r->home_g(kin) + d.g_offset, l->g_shard_bytes, r->ss()));
             r->rec(TR_G_IN, step, kin, gi);
             if (!r->dry) HIP_TRY(hipEventRecord(l->ev_g_in, r->ss()));
-        } else {
-            RTP_TRY(copy_async(r, r->home_g(k) + d.g_offset, part, l->g_shard_bytes, r->ss()));
-            r->rec(TR_G_OUT, step, k, gi);
         }
     }
 
@@ -1204,6 +1211,14 @@ static rtp_status mlp_bwd_grouped(rtp_mlp *m, const void *X, const void *dY, voi
         if (move_g && s >= 1) HIP_TRY(hipStreamWaitEvent(ws, r->ev_g[s & 1], 0));
         g[0] = mlp_args_dw1(m, h, r->shard_at(s), gbuf(s), X);
         g[1] = mlp_args_dw2(m, h, r->shard_at(s), gbuf(s), dY);
+        // the send of the finished gradient shard is fused into the kernels (as in rtp_linear_bwd)
+        const bool fused_send = move_g && s <= n - 2 && r->abl_compute;
+        if (fused_send) {
+            char *home = r->home_g(r->shard_at(s));
+            g[0].epi = g[1].epi = EPI_ACC_LAST;
+            g[0].C = home;
+            g[1].C = home + h.g_off2;
+        }
         RTP_TRY(gemm_group(r, LAY_TN, g, 2, ws));
         // ---- the gradient shard moves on as soon as both parts are complete; the next
         // input-gradient launch runs meanwhile
@@ -1211,9 +1226,9 @@ static rtp_status mlp_bwd_grouped(rtp_mlp *m, const void *X, const void *dY, voi
             const int k = r->shard_at(s), kin = r->shard_at(s + 1);
             HIP_TRY(hipEventRecord(r->ev_free2, ws));
             HIP_TRY(hipStreamWaitEvent(r->ss(), r->ev_free2, 0));
-            RTP_TRY(rotate_async(r, r->home_g(k), r->d.buf_g_dev[r->g_idx(s)], r->d.buf_g_dev[r->g_idx(s + 1)], r->home_g(kin),
-                                 r->d.g_bytes, r->ss()));
+            if (!fused_send) RTP_TRY(copy_async(r, r->home_g(k), r->d.buf_g_dev[r->g_idx(s)], r->d.g_bytes, r->ss()));
             r->rec(TR_G_OUT, s, k, r->g_idx(s));
+            RTP_TRY(copy_async(r, r->d.buf_g_dev[r->g_idx(s + 1)], r->home_g(kin), r->d.g_bytes, r->ss()));
             r->rec(TR_G_IN, s, kin, r->g_idx(s + 1));
             HIP_TRY(hipEventRecord(r->ev_g[(s + 1) & 1], r->ss()));
         }
