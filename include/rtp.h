@@ -210,9 +210,11 @@ typedef struct {
  * [k*o/2, (k+1)*o/2) followed by the same rows of up; the forward output is
  * [T, O/2].  With SPLIT_IN and SWIGLU the backward output is [T, 2 I] in the
  * same shard-stacked column order.
- * Errors: RTP_ERR_SHAPE (n does not divide the partitioned dimension; bf16:
- * I, o not multiples of 8; shard does not fit the slot), RTP_ERR_INVALID,
- * RTP_ERR_UNSUPPORTED (RTP_F16; grad dtype other than F32 or dtype). */
+ * Errors: RTP_ERR_SHAPE (n does not divide the partitioned dimension; bf16 or
+ * fp16: I, o not multiples of 8; shard does not fit the slot),
+ * RTP_ERR_INVALID, RTP_ERR_UNSUPPORTED (gradient dtype other than F32; fp16
+ * with T, o or the unpartitioned dimension not a multiple of 32: fp16 inputs
+ * run on the tiled kernel only, which needs such contraction lengths). */
 rtp_status rtp_linear_create(rtp_linear **out, rtp_ring *ring, const rtp_linear_desc *desc);
 rtp_status rtp_linear_destroy(rtp_linear *lin);
 
@@ -243,7 +245,7 @@ typedef struct {
     int64_t T, I, O, O2;  /* X[T, I]; W1 (or gate, up) [O, I]; W2 (down) [O2, O]   */
     int n, rank;
     rtp_mode mode;
-    rtp_dtype dtype;      /* RTP_BF16 or RTP_F32                                  */
+    rtp_dtype dtype;      /* RTP_BF16, RTP_F16 or RTP_F32                         */
     rtp_act act;          /* GELU_* (one matrix) or SWIGLU (gate + up)            */
     unsigned flags;
     /* slot = [W1_k | W2_k] or [gate_k | up_k | down_k]; gradients fp32         */

@@ -8,6 +8,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librtp.so")
 SOURCES = ["rtp_gemm_bf16.hip", "rtp_gemm_pp.hip", "rtp_gemm_pp_nt.hip", "rtp_gemm_pp_nn.hip", "rtp_gemm_pp_tn.hip",
+           "rtp_gemm_pp_nt_f16.hip", "rtp_gemm_pp_nn_f16.hip", "rtp_gemm_pp_tn_f16.hip",
            "rtp_misc_kernels.hip", "rtp_host.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -packed-fp32-ops off: the compiler must not form packed fp32 arithmetic from scalar code
@@ -33,7 +34,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
             subprocess.run(cmd, check=True)
         return o
 
-    with ThreadPoolExecutor(max_workers=7) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     if force or not _newer(LIB, objs):
         subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs, check=True)

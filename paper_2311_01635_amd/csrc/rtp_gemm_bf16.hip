@@ -282,7 +282,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(const GemmArgs p
     }
 
     // ---- epilogue -------------------------------------------------------------------
-    gemm_epilogue<C::FM, C::FN, WN * 32>(p, acc, m0 + wm * (BM / WM) + 4 * (lane >> 5), n0, wn * 32 + (lane & 31));
+    gemm_epilogue<__bf16, C::FM, C::FN, WN * 32>(p, acc, m0 + wm * (BM / WM) + 4 * (lane >> 5), n0, wn * 32 + (lane & 31));
 }
 
 // ---- host side ------------------------------------------------------------------------
@@ -298,10 +298,10 @@ static const Variant kVariants[] = {
     {256, 256, 2, 4, {"gemm_bf16_256x256_nt", "gemm_bf16_256x256_nn", "gemm_bf16_256x256_tn"}},
     {128, 128, 2, 2, {"gemm_bf16_128x128_nt", "gemm_bf16_128x128_nn", "gemm_bf16_128x128_tn"}},
     {256, 256, 2, 2, {"gemm_bf16_256x256w4_nt", "gemm_bf16_256x256w4_nn", "gemm_bf16_256x256w4_tn"}},
-    {256, 256, 2, 4, {"gemm_bf16_pp_kernel<0>", "gemm_bf16_pp_kernel<1>", "gemm_bf16_pp_kernel<2>"}},
-    {256, 256, 2, 4, {"gemm_bf16_pp_kernel<0>", "gemm_bf16_pp_kernel<1>", "gemm_bf16_pp_kernel<2>"}},
-    {192, 256, 2, 4, {"gemm_bf16_pp_kernel<0>", "gemm_bf16_pp_kernel<1>", "gemm_bf16_pp_kernel<2>"}},
-    {128, 256, 2, 4, {"gemm_bf16_pp_kernel<0>", "gemm_bf16_pp_kernel<1>", "gemm_bf16_pp_kernel<2>"}},
+    {256, 256, 2, 4, {"gemm_pp_kernel<0, __bf16>", "gemm_pp_kernel<1, __bf16>", "gemm_pp_kernel<2, __bf16>"}},
+    {256, 256, 2, 4, {"gemm_pp_kernel<0, __bf16>", "gemm_pp_kernel<1, __bf16>", "gemm_pp_kernel<2, __bf16>"}},
+    {192, 256, 2, 4, {"gemm_pp_kernel<0, __bf16>", "gemm_pp_kernel<1, __bf16>", "gemm_pp_kernel<2, __bf16>"}},
+    {128, 256, 2, 4, {"gemm_pp_kernel<0, __bf16>", "gemm_pp_kernel<1, __bf16>", "gemm_pp_kernel<2, __bf16>"}},
 };
 constexpr int kNumVariants = 7;
 
@@ -313,6 +313,7 @@ const char *gemm_bf16_kernel_name(int layout, int variant)
 
 static int pick_variant(int layout, const GemmArgs &a)
 {
+    if (a.elem != ELEM_BF16) return 4; // fp16 inputs: only the tiled kernel is built
     // the ping-pong kernel whenever its shape rules hold and there is at least a tile's worth of work
     if (gemm_bf16_pp_supported(layout, a) && a.M >= 64 && a.N >= 64) return 4;
     // the large tile when it yields at least ~one workgroup per CU, else the small one
@@ -364,6 +365,7 @@ hipError_t launch_gemm_bf16(int layout, const GemmArgs &a, int variant, hipStrea
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
     if (!gemm_bf16_args_ok(layout, a)) return hipErrorInvalidValue;
     if (variant == 0) variant = pick_variant(layout, a);
+    if (a.elem != ELEM_BF16 && (variant < 4 || variant > 7)) return hipErrorInvalidValue; // fp16: tiled kernel only
     if (variant >= 4 && variant <= 7) {
         if (!gemm_bf16_pp_supported(layout, a)) return hipErrorInvalidValue;
         const int bm[4] = {0, 256, 192, 128};

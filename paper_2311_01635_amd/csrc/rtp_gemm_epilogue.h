@@ -6,7 +6,26 @@
 namespace rtp {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+// E is the 16-bit input/output element type of a kernel: __bf16 or _Float16
+template <typename E> struct ElemVec;
+template <> struct ElemVec<__bf16> {
+    typedef __attribute__((ext_vector_type(4))) __bf16 v4;
+    typedef bf16x8 v8;
+};
+template <> struct ElemVec<_Float16> {
+    typedef __attribute__((ext_vector_type(4))) _Float16 v4;
+    typedef f16x8 v8;
+};
+__device__ __forceinline__ f32x16 mfma_32x32x16(bf16x8 a, bf16x8 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16 mfma_32x32x16(f16x8 a, f16x8 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
@@ -38,7 +57,7 @@ __device__ __forceinline__ float silu_grad(float x)
     return s * (1.0f + x * (1.0f - s));
 }
 
-__device__ __forceinline__ float bf2f(__bf16 v) { return (float)v; }
+template <typename E> __device__ __forceinline__ float bf2f(E v) { return (float)v; }
 
 
 // Writes a wave's FM x FN grid of 32x32 accumulator fragments.
@@ -48,14 +67,14 @@ __device__ __forceinline__ float bf2f(__bf16 v) { return (float)v; }
 // The N fragments of a wave are NSTRIDE columns apart so that, for the gated
 // (gate, up) form, fragment j and fragment j + FN/2 of the same wave hold the
 // two halves of a pair in the same lanes.
-template <int FM, int FN, int NSTRIDE>
+template <typename E, int FM, int FN, int NSTRIDE>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, f32x16 (&acc)[FM][FN], int rbase, int n0, int cl)
 {
     const int M = p.M, N = p.N;
-    __bf16 *Cb = (__bf16 *)p.C;
+    E *Cb = (E *)p.C;
     float *Cf = (float *)p.C;
-    const __bf16 *auxr = (const __bf16 *)p.aux;
-    __bf16 *auxw = (__bf16 *)p.aux;
+    const E *auxr = (const E *)p.aux;
+    E *auxw = (E *)p.aux;
     const int64_t ldc = p.ldc, ldws = p.ldws, ldaux = p.ldaux;
     float *ws = p.ws;
 
@@ -72,9 +91,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, f32x16 (&acc)[F
                     const int row = rbase + i * 32 + 8 * (v >> 2) + (v & 3);
                     if (row >= M) continue;
                     const float a = acc[i][j][v], b = acc[i][j + FN / 2][v];
-                    auxw[(int64_t)row * ldaux + col] = (__bf16)a;
-                    auxw[(int64_t)row * ldaux + half + col] = (__bf16)b;
-                    Cb[(int64_t)row * ldc + col] = (__bf16)(silu(a) * b);
+                    auxw[(int64_t)row * ldaux + col] = (E)a;
+                    auxw[(int64_t)row * ldaux + half + col] = (E)b;
+                    Cb[(int64_t)row * ldc + col] = (E)(silu(a) * b);
                 }
             }
         return;
@@ -101,7 +120,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, f32x16 (&acc)[F
         if (p.c_is_f32)
             each([&](int row, int col, float x) { Cf[(int64_t)row * ldc + col] = x; });
         else
-            each([&](int row, int col, float x) { Cb[(int64_t)row * ldc + col] = (__bf16)x; });
+            each([&](int row, int col, float x) { Cb[(int64_t)row * ldc + col] = (E)x; });
         break;
     case EPI_ACC_FIRST:
         each([&](int row, int col, float x) { ws[(int64_t)row * ldws + col] = x; });
@@ -114,29 +133,29 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, f32x16 (&acc)[F
             each([&](int row, int col, float x) { Cf[(int64_t)row * ldc + col] = ws[(int64_t)row * ldws + col] + x; });
         else
             each([&](int row, int col, float x) {
-                Cb[(int64_t)row * ldc + col] = (__bf16)(ws[(int64_t)row * ldws + col] + x);
+                Cb[(int64_t)row * ldc + col] = (E)(ws[(int64_t)row * ldws + col] + x);
             });
         break;
     case EPI_GELU_ERF_FWD:
         each([&](int row, int col, float x) {
-            auxw[(int64_t)row * ldaux + col] = (__bf16)x;
-            Cb[(int64_t)row * ldc + col] = (__bf16)gelu_erf(x);
+            auxw[(int64_t)row * ldaux + col] = (E)x;
+            Cb[(int64_t)row * ldc + col] = (E)gelu_erf(x);
         });
         break;
     case EPI_GELU_TANH_FWD:
         each([&](int row, int col, float x) {
-            auxw[(int64_t)row * ldaux + col] = (__bf16)x;
-            Cb[(int64_t)row * ldc + col] = (__bf16)gelu_tanh(x);
+            auxw[(int64_t)row * ldaux + col] = (E)x;
+            Cb[(int64_t)row * ldc + col] = (E)gelu_tanh(x);
         });
         break;
     case EPI_GELU_ERF_BWD:
         each([&](int row, int col, float x) {
-            Cb[(int64_t)row * ldc + col] = (__bf16)(x * gelu_erf_grad(bf2f(auxr[(int64_t)row * ldaux + col])));
+            Cb[(int64_t)row * ldc + col] = (E)(x * gelu_erf_grad(bf2f(auxr[(int64_t)row * ldaux + col])));
         });
         break;
     case EPI_GELU_TANH_BWD:
         each([&](int row, int col, float x) {
-            Cb[(int64_t)row * ldc + col] = (__bf16)(x * gelu_tanh_grad(bf2f(auxr[(int64_t)row * ldaux + col])));
+            Cb[(int64_t)row * ldc + col] = (E)(x * gelu_tanh_grad(bf2f(auxr[(int64_t)row * ldaux + col])));
         });
         break;
     case EPI_SWIGLU_BWD: {
@@ -144,8 +163,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, f32x16 (&acc)[F
         each([&](int row, int col, float x) {
             const float a = bf2f(auxr[(int64_t)row * ldaux + col]);
             const float b = bf2f(auxr[(int64_t)row * ldaux + half + col]);
-            Cb[(int64_t)row * ldc + col] = (__bf16)(x * b * silu_grad(a));
-            Cb[(int64_t)row * ldc + half + col] = (__bf16)(x * silu(a));
+            Cb[(int64_t)row * ldc + col] = (E)(x * b * silu_grad(a));
+            Cb[(int64_t)row * ldc + half + col] = (E)(x * silu(a));
         });
         break;
     }
@@ -169,15 +188,16 @@ constexpr int EPI_LDS_PITCH = 72;                       // floats per staged row
 constexpr int EPI_LDS_BYTES_PER_WAVE = 32 * EPI_LDS_PITCH * 4;
 
 typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 
-__device__ __forceinline__ bf16x4 to_bf16x4(f32x4 x)
+template <typename E>
+__device__ __forceinline__ typename ElemVec<E>::v4 to_elem4(f32x4 x)
 {
-    bf16x4 r;
-    r.x = (__bf16)x.x; r.y = (__bf16)x.y; r.z = (__bf16)x.z; r.w = (__bf16)x.w;
+    typename ElemVec<E>::v4 r;
+    r.x = (E)x.x; r.y = (E)x.y; r.z = (E)x.z; r.w = (E)x.w;
     return r;
 }
-__device__ __forceinline__ f32x4 from_bf16x4(bf16x4 x)
+template <typename E>
+__device__ __forceinline__ f32x4 from_elem4(typename ElemVec<E>::v4 x)
 {
     f32x4 r;
     r.x = (float)x.x; r.y = (float)x.y; r.z = (float)x.z; r.w = (float)x.w;
@@ -200,17 +220,18 @@ __host__ __device__ inline bool gemm_epilogue_vec_ok(const GemmArgs &p)
     return ok && (p.N & 3) == 0;
 }
 
-template <int FM, int FN, int NSTRIDE>
+template <typename E, int FM, int FN, int NSTRIDE>
 __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (&acc)[FM][FN], float *wlds,
                                                      int rbase_wave, int n0, int wn32, int lane)
 {
+    typedef typename ElemVec<E>::v4 out4; // four consecutive elements of the 16-bit output type
     static_assert(FN == 2, "staging layout is written for two 32-column fragments per wave");
     const int M = p.M, N = p.N;
     const int64_t ldc = p.ldc, ldws = p.ldws, ldaux = p.ldaux;
     const int half = p.half;
-    __bf16 *Cb = (__bf16 *)p.C;
+    E *Cb = (E *)p.C;
     float *Cf = (float *)p.C;
-    __bf16 *aux = (__bf16 *)p.aux;
+    E *aux = (E *)p.aux;
     float *ws = p.ws;
     const int wrow = 4 * (lane >> 5), wcol = lane & 31;
 
@@ -237,11 +258,11 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
                 const f32x4 b = *(const f32x4 *)(wlds + row * EPI_LDS_PITCH + 32 + c);
                 const int grow = rbase_wave + i * 32 + row, col = n0 + wn32 + c;
                 if (grow < M && col < half) {
-                    *(bf16x4 *)(aux + (int64_t)grow * ldaux + col) = to_bf16x4(a);
-                    *(bf16x4 *)(aux + (int64_t)grow * ldaux + half + col) = to_bf16x4(b);
+                    *(out4 *)(aux + (int64_t)grow * ldaux + col) = to_elem4<E>(a);
+                    *(out4 *)(aux + (int64_t)grow * ldaux + half + col) = to_elem4<E>(b);
                     f32x4 h;
                     h.x = silu(a.x) * b.x; h.y = silu(a.y) * b.y; h.z = silu(a.z) * b.z; h.w = silu(a.w) * b.w;
-                    *(bf16x4 *)(Cb + (int64_t)grow * ldc + col) = to_bf16x4(h);
+                    *(out4 *)(Cb + (int64_t)grow * ldc + col) = to_elem4<E>(h);
                 }
             }
             __builtin_amdgcn_wave_barrier();
@@ -270,7 +291,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
         if (p.c_is_f32)
             each([&](int r, int c, f32x4 x) { *(f32x4 *)(Cf + (int64_t)r * ldc + c) = x; });
         else
-            each([&](int r, int c, f32x4 x) { *(bf16x4 *)(Cb + (int64_t)r * ldc + c) = to_bf16x4(x); });
+            each([&](int r, int c, f32x4 x) { *(out4 *)(Cb + (int64_t)r * ldc + c) = to_elem4<E>(x); });
         break;
     case EPI_ACC_FIRST:
         each([&](int r, int c, f32x4 x) { *(f32x4 *)(ws + (int64_t)r * ldws + c) = x; });
@@ -288,39 +309,39 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
             });
         else
             each([&](int r, int c, f32x4 x) {
-                *(bf16x4 *)(Cb + (int64_t)r * ldc + c) = to_bf16x4(*(const f32x4 *)(ws + (int64_t)r * ldws + c) + x);
+                *(out4 *)(Cb + (int64_t)r * ldc + c) = to_elem4<E>(*(const f32x4 *)(ws + (int64_t)r * ldws + c) + x);
             });
         break;
     case EPI_GELU_ERF_FWD:
         each([&](int r, int c, f32x4 x) {
-            *(bf16x4 *)(aux + (int64_t)r * ldaux + c) = to_bf16x4(x);
-            *(bf16x4 *)(Cb + (int64_t)r * ldc + c) = to_bf16x4(map4(x, [](float t) { return gelu_erf(t); }));
+            *(out4 *)(aux + (int64_t)r * ldaux + c) = to_elem4<E>(x);
+            *(out4 *)(Cb + (int64_t)r * ldc + c) = to_elem4<E>(map4(x, [](float t) { return gelu_erf(t); }));
         });
         break;
     case EPI_GELU_TANH_FWD:
         each([&](int r, int c, f32x4 x) {
-            *(bf16x4 *)(aux + (int64_t)r * ldaux + c) = to_bf16x4(x);
-            *(bf16x4 *)(Cb + (int64_t)r * ldc + c) = to_bf16x4(map4(x, [](float t) { return gelu_tanh(t); }));
+            *(out4 *)(aux + (int64_t)r * ldaux + c) = to_elem4<E>(x);
+            *(out4 *)(Cb + (int64_t)r * ldc + c) = to_elem4<E>(map4(x, [](float t) { return gelu_tanh(t); }));
         });
         break;
     case EPI_GELU_ERF_BWD:
         each([&](int r, int c, f32x4 x) {
-            const f32x4 z = from_bf16x4(*(const bf16x4 *)(aux + (int64_t)r * ldaux + c));
-            *(bf16x4 *)(Cb + (int64_t)r * ldc + c) = to_bf16x4(x * map4(z, [](float t) { return gelu_erf_grad(t); }));
+            const f32x4 z = from_elem4<E>(*(const out4 *)(aux + (int64_t)r * ldaux + c));
+            *(out4 *)(Cb + (int64_t)r * ldc + c) = to_elem4<E>(x * map4(z, [](float t) { return gelu_erf_grad(t); }));
         });
         break;
     case EPI_GELU_TANH_BWD:
         each([&](int r, int c, f32x4 x) {
-            const f32x4 z = from_bf16x4(*(const bf16x4 *)(aux + (int64_t)r * ldaux + c));
-            *(bf16x4 *)(Cb + (int64_t)r * ldc + c) = to_bf16x4(x * map4(z, [](float t) { return gelu_tanh_grad(t); }));
+            const f32x4 z = from_elem4<E>(*(const out4 *)(aux + (int64_t)r * ldaux + c));
+            *(out4 *)(Cb + (int64_t)r * ldc + c) = to_elem4<E>(x * map4(z, [](float t) { return gelu_tanh_grad(t); }));
         });
         break;
     case EPI_SWIGLU_BWD:
         each([&](int r, int c, f32x4 x) {
-            const f32x4 a = from_bf16x4(*(const bf16x4 *)(aux + (int64_t)r * ldaux + c));
-            const f32x4 b = from_bf16x4(*(const bf16x4 *)(aux + (int64_t)r * ldaux + half + c));
-            *(bf16x4 *)(Cb + (int64_t)r * ldc + c) = to_bf16x4(x * b * map4(a, [](float t) { return silu_grad(t); }));
-            *(bf16x4 *)(Cb + (int64_t)r * ldc + half + c) = to_bf16x4(x * map4(a, [](float t) { return silu(t); }));
+            const f32x4 a = from_elem4<E>(*(const out4 *)(aux + (int64_t)r * ldaux + c));
+            const f32x4 b = from_elem4<E>(*(const out4 *)(aux + (int64_t)r * ldaux + half + c));
+            *(out4 *)(Cb + (int64_t)r * ldc + c) = to_elem4<E>(x * b * map4(a, [](float t) { return silu_grad(t); }));
+            *(out4 *)(Cb + (int64_t)r * ldc + half + c) = to_elem4<E>(x * map4(a, [](float t) { return silu(t); }));
         });
         break;
     default:

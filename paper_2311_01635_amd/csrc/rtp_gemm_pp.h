@@ -1,4 +1,4 @@
-// bf16 partition GEMM for gfx950, "ping-pong" form: the kernel the rotated
+// bf16 / fp16 partition GEMM for gfx950, "ping-pong" form: the kernel the rotated
 // linear layer uses whenever the contraction length is a multiple of 32.
 // (Template; instantiated per operand layout in rtp_gemm_pp_<layout>.hip.)
 //
@@ -74,11 +74,12 @@ struct PpGroup {
 };
 
 // One BM x 256 tile: `pid` is the tile's index inside its problem, `smem` the workgroup's LDS.
-template <int LAY, int BM>
+template <int LAY, int BM, typename E>
 __device__ __forceinline__ void pp_tile(const GemmArgs &p, const int tiles_m, const int tiles_n, const int vec_epilogue,
                                         const int pid, char *smem)
 {
     using namespace pp;
+    typedef typename ElemVec<E>::v8 frag8; // eight K-consecutive elements of an operand: one lane's share of an MFMA input
     static_assert(BM == 256 || BM == 192 || BM == 128, "tile heights built");
     constexpr bool A_KC = (LAY != LAY_TN), B_KC = (LAY == LAY_NT);
     constexpr int FM = BM / (WM * 32);       // 4, 3 or 2 fragments of 32 rows per wave
@@ -208,7 +209,7 @@ __device__ __forceinline__ void pp_tile(const GemmArgs &p, const int tiles_m, co
         }
     }
     // 8 consecutive k of one row (K-contiguous stage) ...
-    auto frag_kc = [](const char *opnd, int off, int ks) { return *(const bf16x8 *)(opnd + (off ^ (ks << 5))); };
+    auto frag_kc = [](const char *opnd, int off, int ks) { return *(const frag8 *)(opnd + (off ^ (ks << 5))); };
     // ... or the same 8 k of one column through two transposing reads of 4 K-rows x 16 columns
     // (K-rows 16*ks + 8*(lane/32) + 0..3 and + 4..7: the row index changes by multiples of 4, so
     // the chunk permutation of the lane's row stays the one a_off / b_off were built with)
@@ -217,7 +218,7 @@ __device__ __forceinline__ void pp_tile(const GemmArgs &p, const int tiles_m, co
         const char *q = opnd + off + ks * 16 * rowb;
         union {
             s16x4 h[2];
-            bf16x8 v;
+            frag8 v;
         } u;
         u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(q));
         u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(q + 4 * rowb));
@@ -239,7 +240,7 @@ __device__ __forceinline__ void pp_tile(const GemmArgs &p, const int tiles_m, co
     end_slot_after_loads();
     if (group == 1) asm volatile("s_barrier" ::: "memory"); // start one slot late
 
-    bf16x8 af[2][FM], bf[2][FN];
+    frag8 af[2][FM], bf[2][FN];
     for (int kt = 0; kt < KT; ++kt) {
         // ---- memory slot ------------------------------------------------------------------
         const char *sa = smem + (kt % STAGES) * STAGE;
@@ -263,7 +264,7 @@ __device__ __forceinline__ void pp_tile(const GemmArgs &p, const int tiles_m, co
             for (int i = 0; i < FM; ++i)
 #pragma unroll
                 for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][i], bf[ks][j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = mfma_32x32x16(af[ks][i], bf[ks][j], acc[i][j]);
         __builtin_amdgcn_s_setprio(0);
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("s_barrier" ::: "memory");
@@ -274,17 +275,17 @@ __device__ __forceinline__ void pp_tile(const GemmArgs &p, const int tiles_m, co
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
 
     if (vec_epilogue)
-        gemm_epilogue_staged<FM, FN, WN * 32>(p, acc, (float *)(smem + wave * EPI_LDS_BYTES_PER_WAVE),
+        gemm_epilogue_staged<E, FM, FN, WN * 32>(p, acc, (float *)(smem + wave * EPI_LDS_BYTES_PER_WAVE),
                                               m0 + wm * (BM / WM), n0, wn * 32, lane);
     else
-        gemm_epilogue<FM, FN, WN * 32>(p, acc, m0 + wm * (BM / WM) + 4 * (lane >> 5), n0, wn * 32 + (lane & 31));
+        gemm_epilogue<E, FM, FN, WN * 32>(p, acc, m0 + wm * (BM / WM) + 4 * (lane >> 5), n0, wn * 32 + (lane & 31));
 }
 
 // Workgroup ids are dealt round-robin to the 8 XCDs.  XCD x works through its own list: its
 // contiguous eighth of problem 0's tiles, then of problem 1's, ...; workgroup 8 l + x takes entry l
 // of that list (the host sizes the grid for the longest list; surplus workgroups leave at once).
-template <int LAY>
-__global__ __launch_bounds__(pp::NTHR) void gemm_bf16_pp_kernel(const PpGroup g)
+template <int LAY, typename E>
+__global__ __launch_bounds__(pp::NTHR) void gemm_pp_kernel(const PpGroup g)
 {
     __shared__ __attribute__((aligned(1024))) char smem[pp::SMEM_BYTES];
     const int xcd = blockIdx.x & 7;
@@ -303,16 +304,16 @@ __global__ __launch_bounds__(pp::NTHR) void gemm_bf16_pp_kernel(const PpGroup g)
     if (pid < 0) return;
     const PpProblem &P = g.p[q];
     switch (P.bm) {
-    case 256: pp_tile<LAY, 256>(P.a, P.tiles_m, P.tiles_n, P.vec_epilogue, pid, smem); break;
-    case 192: pp_tile<LAY, 192>(P.a, P.tiles_m, P.tiles_n, P.vec_epilogue, pid, smem); break;
-    default: pp_tile<LAY, 128>(P.a, P.tiles_m, P.tiles_n, P.vec_epilogue, pid, smem); break;
+    case 256: pp_tile<LAY, 256, E>(P.a, P.tiles_m, P.tiles_n, P.vec_epilogue, pid, smem); break;
+    case 192: pp_tile<LAY, 192, E>(P.a, P.tiles_m, P.tiles_n, P.vec_epilogue, pid, smem); break;
+    default: pp_tile<LAY, 128, E>(P.a, P.tiles_m, P.tiles_n, P.vec_epilogue, pid, smem); break;
     }
 }
 
-template <int LAY>
-static hipError_t launch_gemm_bf16_pp_layout(const PpGroup &g, unsigned blocks, hipStream_t s)
+template <int LAY, typename E>
+static hipError_t launch_gemm_pp_layout(const PpGroup &g, unsigned blocks, hipStream_t s)
 {
-    hipLaunchKernelGGL((gemm_bf16_pp_kernel<LAY>), dim3(blocks), dim3(pp::NTHR), 0, s, g);
+    hipLaunchKernelGGL((gemm_pp_kernel<LAY, E>), dim3(blocks), dim3(pp::NTHR), 0, s, g);
     return hipGetLastError();
 }
 

@@ -11,9 +11,12 @@
 
 namespace rtp {
 
-hipError_t launch_gemm_bf16_pp_nt(const PpGroup &g, unsigned blocks, hipStream_t s);
-hipError_t launch_gemm_bf16_pp_nn(const PpGroup &g, unsigned blocks, hipStream_t s);
-hipError_t launch_gemm_bf16_pp_tn(const PpGroup &g, unsigned blocks, hipStream_t s);
+hipError_t launch_gemm_pp_nt_bf16(const PpGroup &g, unsigned blocks, hipStream_t s);
+hipError_t launch_gemm_pp_nn_bf16(const PpGroup &g, unsigned blocks, hipStream_t s);
+hipError_t launch_gemm_pp_tn_bf16(const PpGroup &g, unsigned blocks, hipStream_t s);
+hipError_t launch_gemm_pp_nt_f16(const PpGroup &g, unsigned blocks, hipStream_t s);
+hipError_t launch_gemm_pp_nn_f16(const PpGroup &g, unsigned blocks, hipStream_t s);
+hipError_t launch_gemm_pp_tn_f16(const PpGroup &g, unsigned blocks, hipStream_t s);
 
 bool gemm_bf16_pp_supported(int layout, const GemmArgs &a)
 {
@@ -142,6 +145,7 @@ hipError_t launch_gemm_bf16_pp_group(int layout, const GemmArgs *a_in, int count
     for (int q = 0; q < count_in; ++q) {
         if (a_in[q].M <= 0 || a_in[q].N <= 0) continue; // nothing to compute
         if (!gemm_bf16_args_ok(layout, a_in[q]) || !gemm_bf16_pp_supported(layout, a_in[q])) return hipErrorInvalidValue;
+        if (count > 0 && a_in[q].elem != a[0].elem) return hipErrorInvalidValue; // one element type per launch
         forced[count] = bm_override ? bm_override[q] : 0;
         a[count++] = a_in[q];
     }
@@ -164,10 +168,11 @@ hipError_t launch_gemm_bf16_pp_group(int layout, const GemmArgs *a_in, int count
         per_xcd += (unsigned)(((long)p.tiles_m * p.tiles_n + 7) / 8);
     }
     const unsigned blocks = per_xcd * 8;
+    const bool f16 = a[0].elem == ELEM_F16;
     switch (layout) {
-    case LAY_NT: return launch_gemm_bf16_pp_nt(g, blocks, s);
-    case LAY_NN: return launch_gemm_bf16_pp_nn(g, blocks, s);
-    case LAY_TN: return launch_gemm_bf16_pp_tn(g, blocks, s);
+    case LAY_NT: return f16 ? launch_gemm_pp_nt_f16(g, blocks, s) : launch_gemm_pp_nt_bf16(g, blocks, s);
+    case LAY_NN: return f16 ? launch_gemm_pp_nn_f16(g, blocks, s) : launch_gemm_pp_nn_bf16(g, blocks, s);
+    case LAY_TN: return f16 ? launch_gemm_pp_tn_f16(g, blocks, s) : launch_gemm_pp_tn_bf16(g, blocks, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -1,9 +1,9 @@
-// Instantiation of the ping-pong bf16 GEMM for the NT operand layout (see rtp_gemm_pp.h).
+// Instantiation of the ping-pong GEMM for bf16 inputs, NT operand layout (see rtp_gemm_pp.h).
 #include "rtp_gemm_pp.h"
 
 namespace rtp {
-hipError_t launch_gemm_bf16_pp_nt(const PpGroup &g, unsigned blocks, hipStream_t s)
+hipError_t launch_gemm_pp_nt_bf16(const PpGroup &g, unsigned blocks, hipStream_t s)
 {
-    return launch_gemm_bf16_pp_layout<LAY_NT>(g, blocks, s);
+    return launch_gemm_pp_layout<LAY_NT, __bf16>(g, blocks, s);
 }
 } // namespace rtp

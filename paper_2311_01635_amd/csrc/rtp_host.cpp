@@ -558,8 +558,7 @@ extern "C" rtp_status rtp_linear_create(rtp_linear **out, rtp_ring *ring, const 
     if (d->T > 0x7fffffff || d->I > 0x7fffffff || d->O > 0x7fffffff)
         return fail(RTP_ERR_SHAPE, "rtp_linear_create: a dimension exceeds 2^31-1");
     if (d->split != RTP_SPLIT_OUT && d->split != RTP_SPLIT_IN) return fail(RTP_ERR_INVALID, "bad split");
-    if (d->dtype == RTP_F16) return fail(RTP_ERR_UNSUPPORTED, "rtp_linear_create: fp16 inputs are not built");
-    if (d->dtype != RTP_F32 && d->dtype != RTP_BF16) return fail(RTP_ERR_INVALID, "bad dtype");
+    if (d->dtype != RTP_F32 && d->dtype != RTP_BF16 && d->dtype != RTP_F16) return fail(RTP_ERR_INVALID, "bad dtype");
     if (d->grad_dtype != RTP_F32)
         return fail(RTP_ERR_UNSUPPORTED, "rtp_linear_create: gradient shards are kept in fp32");
     if (d->act < RTP_ACT_NONE || d->act > RTP_ACT_SWIGLU) return fail(RTP_ERR_INVALID, "bad activation");
@@ -571,10 +570,18 @@ extern "C" rtp_status rtp_linear_create(rtp_linear **out, rtp_ring *ring, const 
     const int64_t o = part / n;
     if (d->act == RTP_ACT_SWIGLU && d->split == RTP_SPLIT_OUT && (o & 1))
         return fail(RTP_ERR_SHAPE, "rtp_linear_create: a (gate, up) shard needs an even width");
-    if (d->dtype == RTP_BF16) {
+    if (d->dtype != RTP_F32) {
         const int64_t half = (d->act == RTP_ACT_SWIGLU && d->split == RTP_SPLIT_OUT) ? o / 2 : o;
         if ((d->I & 7) || (d->O & 7) || (o & 7) || (half & 7))
-            return fail(RTP_ERR_SHAPE, "rtp_linear_create: bf16 kernels need I, O and the shard width to be multiples of 8");
+            return fail(RTP_ERR_SHAPE, "rtp_linear_create: 16-bit kernels need I, O and the shard width to be multiples of 8");
+    }
+    if (d->dtype == RTP_F16) {
+        // fp16 runs on the tiled kernel only: every contraction length (the batch, the shard width and
+        // the dimension that is not partitioned) must be a multiple of 32
+        const int64_t other = d->split == RTP_SPLIT_OUT ? d->I : d->O;
+        if ((d->T & 31) || (o & 31) || (other & 31))
+            return fail(RTP_ERR_UNSUPPORTED, "rtp_linear_create: fp16 inputs need T, the shard width and the other "
+                                             "matrix dimension to be multiples of 32");
     }
     const size_t wsz = (size_t)d->O * (size_t)d->I / (size_t)n * esize(d->dtype);
     const size_t gsz = (size_t)d->O * (size_t)d->I / (size_t)n * esize(d->grad_dtype);
@@ -634,10 +641,12 @@ static rtp_status gemm(rtp_linear *l, int layout, GemmArgs &a, hipStream_t st)
 {
     rtp_ring *r = l->ring;
     if (r->dry || !r->abl_compute) return RTP_OK;
-    if (l->d.dtype == RTP_BF16)
+    if (l->d.dtype != RTP_F32) {
+        a.elem = l->d.dtype == RTP_F16 ? ELEM_F16 : ELEM_BF16;
         HIP_TRY(timed_launch(layout, 2.0 * a.M * a.N * a.K, st, [&] { return launch_gemm_bf16(layout, a, 0, st); }));
-    else
+    } else {
         HIP_TRY(launch_gemm_f32(layout, a, st));
+    }
     return RTP_OK;
 }
 
@@ -985,6 +994,7 @@ static GemmArgs mlp_args_z(const rtp_mlp *m, const MlpShapes &h, int k, const vo
 {
     GemmArgs a;
     memset(&a, 0, sizeof a);
+    a.elem = m->d.dtype == RTP_F16 ? ELEM_F16 : ELEM_BF16;
     const int64_t ow = h.gated ? h.o1 / 2 : h.o1;
     a.A = X; a.lda = h.I;
     a.B = Wslot; a.ldb = h.I;
@@ -1001,6 +1011,7 @@ static GemmArgs mlp_args_down(const rtp_mlp *m, const MlpShapes &h, int k, int s
 {
     GemmArgs a;
     memset(&a, 0, sizeof a);
+    a.elem = m->d.dtype == RTP_F16 ? ELEM_F16 : ELEM_BF16;
     a.A = (const char *)m->d.hidden_dev + (size_t)k * h.o2 * h.es; a.lda = h.Ohid;
     a.B = Wslot + h.w_off2; a.ldb = h.o2;
     a.M = (int)h.T; a.N = (int)h.O2; a.K = (int)h.o2;
@@ -1015,6 +1026,7 @@ static GemmArgs mlp_args_dh(const rtp_mlp *m, const MlpShapes &h, int k, const c
 {
     GemmArgs a;
     memset(&a, 0, sizeof a);
+    a.elem = m->d.dtype == RTP_F16 ? ELEM_F16 : ELEM_BF16;
     a.A = dY; a.lda = h.O2;
     a.B = Wslot + h.w_off2; a.ldb = h.o2;
     a.M = (int)h.T; a.N = (int)h.o2; a.K = (int)h.O2;
@@ -1030,6 +1042,7 @@ static GemmArgs mlp_args_dw2(const rtp_mlp *m, const MlpShapes &h, int k, char *
 {
     GemmArgs a;
     memset(&a, 0, sizeof a);
+    a.elem = m->d.dtype == RTP_F16 ? ELEM_F16 : ELEM_BF16;
     a.A = dY; a.lda = h.O2;
     a.B = (const char *)m->d.hidden_dev + (size_t)k * h.o2 * h.es; a.ldb = h.Ohid;
     a.M = (int)h.O2; a.N = (int)h.o2; a.K = (int)h.T;
@@ -1044,6 +1057,7 @@ static GemmArgs mlp_args_dw1(const rtp_mlp *m, const MlpShapes &h, int k, char *
 {
     GemmArgs a;
     memset(&a, 0, sizeof a);
+    a.elem = m->d.dtype == RTP_F16 ? ELEM_F16 : ELEM_BF16;
     a.A = (const char *)m->d.dpre_dev + (size_t)k * h.o1 * h.es; a.lda = h.P1;
     a.B = X; a.ldb = h.I;
     a.M = (int)h.o1; a.N = (int)h.I; a.K = (int)h.T;
@@ -1058,6 +1072,7 @@ static GemmArgs mlp_args_dx(const rtp_mlp *m, const MlpShapes &h, int k, int ste
 {
     GemmArgs a;
     memset(&a, 0, sizeof a);
+    a.elem = m->d.dtype == RTP_F16 ? ELEM_F16 : ELEM_BF16;
     a.A = (const char *)m->d.dpre_dev + (size_t)k * h.o1 * h.es; a.lda = h.P1;
     a.B = Wslot; a.ldb = h.I;
     a.M = (int)h.T; a.N = (int)h.I; a.K = (int)h.o1;
@@ -1072,7 +1087,7 @@ static GemmArgs mlp_args_dx(const rtp_mlp *m, const MlpShapes &h, int k, int ste
 static bool mlp_grouped_ok(const rtp_mlp *m, const void *X, const void *Y, const void *dY, const void *dX)
 {
     const rtp_ring *r = m->ring;
-    if (r->dry || (m->d.flags & RTP_FLAG_STEPWISE) || m->d.dtype != RTP_BF16 || m->d.T <= 0) return false;
+    if (r->dry || (m->d.flags & RTP_FLAG_STEPWISE) || m->d.dtype == RTP_F32 || m->d.T <= 0) return false;
     if (r->d.mode == RTP_INPLACE_BLOCKING) return false;
     const MlpShapes h = mlp_shapes(m);
     const char *W = (const char *)r->d.buf_w_dev[0];
@@ -1293,8 +1308,9 @@ extern "C" rtp_status rtp_gemm(int layout, rtp_dtype in_dtype, rtp_dtype out_dty
     a.C = C; a.ldc = ldc; a.ws = (float *)C; a.ldws = ldc;
     a.epi = accumulate ? EPI_ACC_ADD : EPI_STORE;
     a.c_is_f32 = out_dtype == RTP_F32;
-    if (in_dtype == RTP_BF16) {
-        if (out_dtype != RTP_F32 && out_dtype != RTP_BF16) return fail(RTP_ERR_UNSUPPORTED, "rtp_gemm: bad output type");
+    if (in_dtype == RTP_BF16 || in_dtype == RTP_F16) {
+        if (out_dtype != RTP_F32 && out_dtype != in_dtype) return fail(RTP_ERR_UNSUPPORTED, "rtp_gemm: bad output type");
+        a.elem = in_dtype == RTP_F16 ? ELEM_F16 : ELEM_BF16;
         hipError_t e = timed_launch(layout, 2.0 * a.M * a.N * a.K, (hipStream_t)stream,
                                     [&] { return launch_gemm_bf16(layout, a, variant, (hipStream_t)stream); });
         if (e == hipErrorInvalidValue) return fail(RTP_ERR_SHAPE, "rtp_gemm: sizes/alignment the bf16 kernels need are not met");

@@ -6,6 +6,7 @@
 namespace rtp {
 
 enum : int { LAY_NT = 0, LAY_NN = 1, LAY_TN = 2 };
+enum : int { ELEM_BF16 = 0, ELEM_F16 = 1 }; // 16-bit element type of a GEMM's inputs and non-fp32 outputs
 
 // What happens to the fp32 accumulator tile when the K loop is done.
 enum : int {
@@ -35,6 +36,7 @@ struct GemmArgs {
     int64_t ldaux;
     int half;           // EPI_SWIGLU_FWD: N/2 ; EPI_SWIGLU_BWD: N
     int c_is_f32;       // EPI_STORE / EPI_ACC_LAST write fp32 instead of the input dtype
+    int elem;           // ELEM_BF16 or ELEM_F16 (the ping-pong kernel only; the register-staged one is bf16)
     int cu_share;       // > 1: this launch runs beside cu_share - 1 others of similar size, so the
                         // tile height is picked for 1/cu_share of the compute units (0, 1: all)
 };

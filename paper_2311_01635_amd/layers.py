@@ -7,7 +7,7 @@ import torch
 
 from . import binding as B
 
-_TORCH_DT = {B.RTP_F32: torch.float32, B.RTP_BF16: torch.bfloat16}
+_TORCH_DT = {B.RTP_F32: torch.float32, B.RTP_BF16: torch.bfloat16, B.RTP_F16: torch.float16}
 
 
 def _esize(dtype):

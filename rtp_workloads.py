@@ -23,7 +23,7 @@ class Workload:
     I: int               # in-features
     O: int               # out-features of the (first) partitioned matrix
     n: int               # partition factor N (virtual shards)
-    dtype: str           # "f32" | "bf16"
+    dtype: str           # "f32" | "bf16" | "f16"
     mode: str            # "double_buffer" | "inplace_staged"
     O2: int = 0          # out-features of the second (input-partitioned) matrix
     w_dist: tuple = ("normal", 0.02)
@@ -74,6 +74,8 @@ def round_to_bf16(x):
 
 def _store(x, dtype):
     x = np.ascontiguousarray(x, dtype=np.float32)
+    if dtype == "f16":
+        return x.astype(np.float16).astype(np.float32)   # nearest fp16 value, ties to even
     return round_to_bf16(x) if dtype == "bf16" else x
 
 

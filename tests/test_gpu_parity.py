@@ -47,22 +47,26 @@ def f64(x):
     return np.ascontiguousarray(x, dtype=np.float64)
 
 
+_TD = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
+_BD = {"f32": B.RTP_F32, "bf16": B.RTP_BF16, "f16": B.RTP_F16}
+TOL_F16 = 5e-3   # fp16 keeps 11 significant bits: stored intermediates round 8 times finer than bf16
+
 # ------------------------------------------------------------ single GEMMs --
 
-def _gemm_case(layout, M, N, K, variant, accumulate, out_f32, seed):
+def _gemm_case(layout, M, N, K, variant, accumulate, out_f32, seed, dtype="bf16"):
     rng = np.random.default_rng(seed)
     shapes = {B.LAYOUT_NT: ((M, K), (N, K)), B.LAYOUT_NN: ((M, K), (K, N)), B.LAYOUT_TN: ((K, M), (K, N))}[layout]
-    A = wl.round_to_bf16(rng.standard_normal(shapes[0], dtype=np.float32))
-    Bm = wl.round_to_bf16(rng.standard_normal(shapes[1], dtype=np.float32))
+    A = wl._store(rng.standard_normal(shapes[0], dtype=np.float32), dtype)
+    Bm = wl._store(rng.standard_normal(shapes[1], dtype=np.float32), dtype)
     C0 = rng.standard_normal((M, N), dtype=np.float32)
     ref = np.zeros((M, N))
     {B.LAYOUT_NT: orc.gemm_nt, B.LAYOUT_NN: orc.gemm_nn, B.LAYOUT_TN: orc.gemm_tn}[layout](f64(A), f64(Bm), ref)
     if accumulate:
         ref = ref + f64(C0)
-    dA, dB = dev(A, torch.bfloat16), dev(Bm, torch.bfloat16)
-    dC = dev(C0, torch.float32 if out_f32 else torch.bfloat16)
+    dA, dB = dev(A, _TD[dtype]), dev(Bm, _TD[dtype])
+    dC = dev(C0, torch.float32 if out_f32 else _TD[dtype])
     torch.cuda.synchronize()
-    B.rtp_gemm(layout, B.RTP_BF16, B.RTP_F32 if out_f32 else B.RTP_BF16, accumulate, dA, shapes[0][1], dB,
+    B.rtp_gemm(layout, _BD[dtype], B.RTP_F32 if out_f32 else _BD[dtype], accumulate, dA, shapes[0][1], dB,
                shapes[1][1], dC, N, M, N, K, variant)
     torch.cuda.synchronize()
     return relerr(host(dC), ref)
@@ -95,6 +99,30 @@ def test_gemm_bf16_layouts_and_tails(layout, variant):
             assert err <= (TOL_F32 if out_f32 else TOL_BF16), (layout, variant, M, N, K, accumulate, out_f32, err)
 
 
+@pytest.mark.parametrize("variant", [4, 5, 6, 7])
+@pytest.mark.parametrize("layout", [B.LAYOUT_NT, B.LAYOUT_NN, B.LAYOUT_TN])
+def test_gemm_fp16_layouts_and_tails(layout, variant):
+    """fp16 inputs run on the tiled kernel (K a multiple of 32); same shapes, same oracle."""
+    for i, (M, N, K) in enumerate(GEMM_SHAPES + GEMM_ODD[layout]):
+        if K % 32:
+            continue
+        for accumulate, out_f32 in ((False, True), (True, True), (False, False)):
+            say(f"fp16 gemm layout={layout} variant={variant} M={M} N={N} K={K} acc={accumulate} f32out={out_f32}")
+            err = _gemm_case(layout, M, N, K, variant, accumulate, out_f32, seed=300 * layout + i, dtype="f16")
+            assert err <= (TOL_F32 if out_f32 else TOL_F16), (layout, variant, M, N, K, accumulate, out_f32, err)
+
+
+def test_gemm_fp16_needs_the_tiled_kernel():
+    a = torch.zeros(64, 72, device=DEV, dtype=torch.float16)
+    c = torch.zeros(64, 64, device=DEV, dtype=torch.float32)
+    with pytest.raises(B.RtpError) as e:
+        B.rtp_gemm(B.LAYOUT_NT, B.RTP_F16, B.RTP_F32, False, a, 72, a, 72, c, 64, 64, 64, 72)    # K = 72: not a multiple of 32
+    assert e.value.status == B.RTP_ERR_SHAPE
+    with pytest.raises(B.RtpError) as e:
+        B.rtp_gemm(B.LAYOUT_NT, B.RTP_F16, B.RTP_F32, False, a, 72, a, 72, c, 64, 64, 64, 64, 1)  # register-staged variant
+    assert e.value.status == B.RTP_ERR_SHAPE
+
+
 def test_gemm_rejects_misaligned_shapes():
     a = torch.zeros(64, 64, device=DEV, dtype=torch.bfloat16)
     c = torch.zeros(64, 64, device=DEV, dtype=torch.float32)
@@ -111,8 +139,7 @@ def test_gemm_rejects_misaligned_shapes():
 # ------------------------------------------------------ rotated linear layer --
 
 def _linear_case(w: wl.Workload, rank, mode, split, seed=0, grad0=True, integer=False):
-    td = torch.float32 if w.dtype == "f32" else torch.bfloat16
-    bd = B.RTP_F32 if w.dtype == "f32" else B.RTP_BF16
+    td, bd = _TD[w.dtype], _BD[w.dtype]
     inp = wl.make_integer_inputs(w, seed) if integer else wl.make_inputs(w, seed, grad0=grad0)
     X, W, dY = inp["X"], inp["W"], inp["dY"]
     G0 = inp.get("G0_W")
@@ -201,6 +228,20 @@ def test_bf16_linear_integer_inputs_bit_exact(split):
     _check_linear(out, ref, 0.0, exact=True)
 
 
+@pytest.mark.parametrize("mode", [B.RTP_DOUBLE_BUFFER, B.RTP_INPLACE_STAGED, B.RTP_INPLACE_BLOCKING])
+@pytest.mark.parametrize("split", [B.RTP_SPLIT_OUT, B.RTP_SPLIT_IN])
+def test_fp16_linear_multi_tile(mode, split):
+    """fp16 inputs (contraction lengths multiples of 32): several tiles and ragged tails in the free dimensions."""
+    if split == B.RTP_SPLIT_OUT:
+        w = wl.Workload("f16_out", "linear", T=320, I=544, O=5 * 288, n=5, dtype="f16", mode="x", w_dist=("normal", 0.05))
+    else:
+        w = wl.Workload("f16_in", "linear", T=320, I=5 * 288, O=544, n=5, dtype="f16", mode="x", w_dist=("normal", 0.05))
+    for rank in (0, 3):
+        say(f"fp16 linear split={split} mode={mode} rank={rank}")
+        out, ref = _linear_case(w, rank, mode, split)
+        _check_linear(out, ref, TOL_F16)
+
+
 def test_degenerate_partitions():
     # n = 1 is the plain linear; one token; n equal to the number of 8-wide column groups
     for (T, I, O, n) in ((40, 64, 72, 1), (1, 64, 64, 2), (33, 16, 64, 8)):
@@ -231,8 +272,7 @@ def test_empty_batch_is_a_no_op():
 # -------------------------------------------------------------------- MLP unit --
 
 def _mlp_case(w: wl.Workload, rank, mode, seed=0, grad0=True, stepwise=False, aux_stream=True):
-    td = torch.float32 if w.dtype == "f32" else torch.bfloat16
-    bd = B.RTP_F32 if w.dtype == "f32" else B.RTP_BF16
+    td, bd = _TD[w.dtype], _BD[w.dtype]
     inp = wl.make_inputs(w, seed, grad0=grad0)
     X, dY = inp["X"], inp["dY"]
     if w.kind == "swiglu":
@@ -298,6 +338,19 @@ def test_mlp_unit_grouped_launches(kind, n, mode, schedule):
         for key in ("H", "Y", "dX") + tuple(gkeys):
             assert np.isfinite(out[key]).all(), key
             assert relerr(out[key], ref[key]) <= TOL_BF16, (key, relerr(out[key], ref[key]))
+
+
+@pytest.mark.parametrize("schedule", ["default", "grouped_one_stream", "stepwise"])
+@pytest.mark.parametrize("kind", ["mlp_gelu", "swiglu"])
+def test_mlp_unit_fp16(kind, schedule):
+    stepwise, aux = schedule.startswith("stepwise"), not schedule.endswith("one_stream")
+    w = wl.Workload("mlp_f16", kind, T=288, I=160, O=4 * 128, O2=96, n=4, dtype="f16", mode="x", w_dist=("normal", 0.08))
+    say(f"fp16 mlp kind={kind} schedule={schedule}")
+    out, ref, gkeys = _mlp_case(w, 2, B.RTP_INPLACE_STAGED, stepwise=stepwise, aux_stream=aux)
+    assert out["W_same"]
+    for key in ("H", "Y", "dX") + tuple(gkeys):
+        assert np.isfinite(out[key]).all(), key
+        assert relerr(out[key], ref[key]) <= TOL_F16, (key, relerr(out[key], ref[key]))
 
 
 def test_mlp_grouped_and_stepwise_agree_bitwise_on_integers():

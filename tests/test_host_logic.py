@@ -191,7 +191,9 @@ def test_create_rejects_bad_descriptions():
     assert lin_status(O=48) == B.RTP_ERR_SHAPE                 # shard width 12 is not a multiple of 8
     assert lin_status(I=60) == B.RTP_ERR_SHAPE
     assert lin_status(I=0) == B.RTP_ERR_SHAPE
-    assert lin_status(dtype=B.RTP_F16) == B.RTP_ERR_UNSUPPORTED
+    assert lin_status(dtype=B.RTP_F16) == B.RTP_ERR_UNSUPPORTED        # fp16: shard width 16 is not a multiple of 32
+    assert lin_status(dtype=B.RTP_F16, T=32, I=64, O=128) == B.RTP_OK
+    assert lin_status(dtype=B.RTP_F16, T=40, I=64, O=128) == B.RTP_ERR_UNSUPPORTED
     assert lin_status(grad_dtype=B.RTP_BF16) == B.RTP_ERR_UNSUPPORTED
     assert lin_status(O=4096) == B.RTP_ERR_SHAPE               # shard larger than the slot
     assert lin_status(w_offset=8) == B.RTP_ERR_SHAPE
