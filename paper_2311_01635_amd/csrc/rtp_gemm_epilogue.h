@@ -128,6 +128,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, f32x16 (&acc)[F
     case EPI_ACC_ADD:
         each([&](int row, int col, float x) { ws[(int64_t)row * ldws + col] += x; });
         break;
+    case EPI_ACC_ATOMIC:
+        each([&](int row, int col, float x) { unsafeAtomicAdd(ws + (int64_t)row * ldws + col, x); });
+        break;
     case EPI_ACC_LAST:
         if (p.c_is_f32)
             each([&](int row, int col, float x) { Cf[(int64_t)row * ldc + col] = ws[(int64_t)row * ldws + col] + x; });
@@ -215,8 +218,8 @@ __host__ __device__ inline bool gemm_epilogue_vec_ok(const GemmArgs &p)
 {
     auto al = [](const void *q, int a) { return ((uintptr_t)q & (uintptr_t)(a - 1)) == 0; };
     bool ok = (p.ldc & 3) == 0 && al(p.C, 16);
-    if (p.epi == EPI_ACC_FIRST || p.epi == EPI_ACC_ADD || p.epi == EPI_ACC_LAST) ok = ok && (p.ldws & 3) == 0 && al(p.ws, 16);
-    if (p.epi >= EPI_GELU_ERF_FWD) ok = ok && (p.ldaux & 3) == 0 && al(p.aux, 8) && (p.half & 3) == 0;
+    if (p.epi == EPI_ACC_FIRST || p.epi == EPI_ACC_ADD || p.epi == EPI_ACC_LAST || p.epi == EPI_ACC_ATOMIC) ok = ok && (p.ldws & 3) == 0 && al(p.ws, 16);
+    if (p.epi >= EPI_GELU_ERF_FWD && p.epi <= EPI_SWIGLU_BWD) ok = ok && (p.ldaux & 3) == 0 && al(p.aux, 8) && (p.half & 3) == 0;
     return ok && (p.N & 3) == 0;
 }
 
@@ -300,6 +303,15 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
         each([&](int r, int c, f32x4 x) {
             f32x4 *q = (f32x4 *)(ws + (int64_t)r * ldws + c);
             *q = *q + x;
+        });
+        break;
+    case EPI_ACC_ATOMIC:
+        each([&](int r, int c, f32x4 x) {
+            float *q = ws + (int64_t)r * ldws + c;
+            unsafeAtomicAdd(q, x.x);
+            unsafeAtomicAdd(q + 1, x.y);
+            unsafeAtomicAdd(q + 2, x.z);
+            unsafeAtomicAdd(q + 3, x.w);
         });
         break;
     case EPI_ACC_LAST:

@@ -67,16 +67,19 @@ struct PpProblem {
     int bm;               // tile height: 256, 192 or 128
     int tiles_m, tiles_n;
     int vec_epilogue;
+    int ksplit;           // > 1: the K loop is cut into this many chunks, one workgroup each, whose partial
+                          // sums meet in the fp32 accumulator through atomic adds (a.epi == EPI_ACC_ATOMIC)
 };
 struct PpGroup {
     int count;
     PpProblem p[PP_MAX_GROUP];
 };
 
-// One BM x 256 tile: `pid` is the tile's index inside its problem, `smem` the workgroup's LDS.
+// One BM x 256 tile over the K sub-tiles [kt_begin, kt_begin + kt_count): `pid` is the tile's index inside its
+// problem, `smem` the workgroup's LDS.
 template <int LAY, int BM, typename E>
 __device__ __forceinline__ void pp_tile(const GemmArgs &p, const int tiles_m, const int tiles_n, const int vec_epilogue,
-                                        const int pid, char *smem)
+                                        const int pid, const int kt_begin, const int kt_count, char *smem)
 {
     using namespace pp;
     typedef typename ElemVec<E>::v8 frag8; // eight K-consecutive elements of an operand: one lane's share of an MFMA input
@@ -157,7 +160,11 @@ __device__ __forceinline__ void pp_tile(const GemmArgs &p, const int tiles_m, co
     }
     const int64_t stepA = A_KC ? (int64_t)BK * 2 : (int64_t)BK * p.lda * 2;
     const int64_t stepB = B_KC ? (int64_t)BK * 2 : (int64_t)BK * p.ldb * 2;
-    const int KT = K / BK;
+    const int KT = kt_count;
+#pragma unroll
+    for (int i = 0; i < A_PW; ++i) ga[i] += kt_begin * stepA;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) gb[i] += kt_begin * stepB;
 
     auto issue = [&](int kt) {
         const int kk = min(kt, KT - 1); // past the end: refetch the last sub-tile into a stage nobody reads
@@ -292,7 +299,7 @@ __global__ __launch_bounds__(pp::NTHR) void gemm_pp_kernel(const PpGroup g)
     int l = blockIdx.x >> 3;
     int q = 0, pid = -1;
     for (; q < g.count; ++q) {
-        const int tiles = g.p[q].tiles_m * g.p[q].tiles_n;
+        const int tiles = g.p[q].tiles_m * g.p[q].tiles_n * g.p[q].ksplit;
         const int base = tiles >> 3, rem = tiles & 7;
         const int mine = base + (xcd < rem ? 1 : 0);
         if (l < mine) {
@@ -303,10 +310,19 @@ __global__ __launch_bounds__(pp::NTHR) void gemm_pp_kernel(const PpGroup g)
     }
     if (pid < 0) return;
     const PpProblem &P = g.p[q];
+    // K chunk of this workgroup: consecutive ids are different tiles of the same chunk, so they share panels
+    const int per_chunk = P.tiles_m * P.tiles_n;
+    const int chunk = pid / per_chunk;
+    pid -= chunk * per_chunk;
+    const int kt_total = P.a.K / pp::BK;
+    const int kt_each = (kt_total + P.ksplit - 1) / P.ksplit;
+    const int kt_begin = chunk * kt_each;
+    const int kt_count = min(kt_each, kt_total - kt_begin);
+    if (kt_count <= 0) return;
     switch (P.bm) {
-    case 256: pp_tile<LAY, 256, E>(P.a, P.tiles_m, P.tiles_n, P.vec_epilogue, pid, smem); break;
-    case 192: pp_tile<LAY, 192, E>(P.a, P.tiles_m, P.tiles_n, P.vec_epilogue, pid, smem); break;
-    default: pp_tile<LAY, 128, E>(P.a, P.tiles_m, P.tiles_n, P.vec_epilogue, pid, smem); break;
+    case 256: pp_tile<LAY, 256, E>(P.a, P.tiles_m, P.tiles_n, P.vec_epilogue, pid, kt_begin, kt_count, smem); break;
+    case 192: pp_tile<LAY, 192, E>(P.a, P.tiles_m, P.tiles_n, P.vec_epilogue, pid, kt_begin, kt_count, smem); break;
+    default: pp_tile<LAY, 128, E>(P.a, P.tiles_m, P.tiles_n, P.vec_epilogue, pid, kt_begin, kt_count, smem); break;
     }
 }
 

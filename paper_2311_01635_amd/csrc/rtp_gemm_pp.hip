@@ -6,6 +6,8 @@
 
 #include <algorithm>
 #include <functional>
+#include <map>
+#include <mutex>
 #include <queue>
 #include <vector>
 
@@ -56,6 +58,7 @@ static double epilogue_steps(int epi, int c_is_f32)
 {
     switch (epi) {
     case EPI_ACC_ADD: return 30.0;
+    case EPI_ACC_ATOMIC: return 40.0;
     case EPI_ACC_FIRST: return 16.0;
     case EPI_ACC_LAST: return 22.0;
     case EPI_SWIGLU_FWD: return 14.0;
@@ -68,24 +71,34 @@ static double epilogue_steps(int epi, int c_is_f32)
     }
 }
 
-static double tile_cost(const GemmArgs &a, int bm)
+static double tile_cost(const GemmArgs &a, int bm, int ksplit)
 {
     const double handicap = bm == 256 ? 1.0 : bm == 192 ? 1.04 : 1.12;
-    return handicap * (bm / 256.0) * (a.K / 32 + epilogue_steps(a.epi, a.c_is_f32));
+    const int kt = a.K / 32, each = (kt + ksplit - 1) / ksplit;
+    return handicap * (bm / 256.0) * (each + epilogue_steps(ksplit > 1 ? EPI_ACC_ATOMIC : a.epi, a.c_is_f32));
+}
+
+// A problem may have its K loop cut into chunks when its result is an fp32 sum onto an accumulator
+// (the chunks' partial sums are added atomically) and it is short of tiles: the weight-gradient
+// GEMM of a narrow shard contracts over all T tokens into an output of a few tiles.
+static bool may_split_k(const GemmArgs &a)
+{
+    return a.epi == EPI_ACC_ADD && a.c_is_f32 && a.C == (void *)a.ws && a.ldc == a.ldws;
 }
 
 // Greedy list schedule of one XCD's share (an eighth of each problem, rounded up) over its
 // compute units, problems in the order given: the finishing time of the last tile.
-static double makespan(const GemmArgs *a, const int *bm, const int *order, int count, int cus_per_xcd)
+static double makespan(const GemmArgs *a, const int *bm, const int *ks, const int *order, int count, int cus_per_xcd)
 {
     std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
     for (int i = 0; i < cus_per_xcd; ++i) free_at.push(0.0);
     double end = 0.0;
     for (int i = 0; i < count; ++i) {
         const int q = order[i];
-        const long tiles = (long)((a[q].M + bm[q] - 1) / bm[q]) * tiles_n_of(a[q]);
+        const int kt = a[q].K / 32, each = (kt + ks[q] - 1) / ks[q], chunks = (kt + each - 1) / each;
+        const long tiles = (long)((a[q].M + bm[q] - 1) / bm[q]) * tiles_n_of(a[q]) * chunks;
         const long mine = (tiles + 7) / 8;
-        const double c = tile_cost(a[q], bm[q]);
+        const double c = tile_cost(a[q], bm[q], ks[q]);
         for (long t = 0; t < mine; ++t) {
             const double start = free_at.top();
             free_at.pop();
@@ -96,44 +109,95 @@ static double makespan(const GemmArgs *a, const int *bm, const int *order, int c
     return end;
 }
 
-// Heights and launch order (longest tiles first) of a group.  Every combination of heights
-// is tried (at most 3^4); the estimate above picks.
-static void plan_group(const GemmArgs *a, int count, const int *bm_override, int cu_share, int *bm_out, int *order_out)
+// Heights, K splits and launch order (longest tiles first) of a group.  Every combination is tried
+// (3 heights, and up to 6 split factors for a problem that may be split and is short of tiles);
+// the estimate above picks.  Plans are remembered per shape.
+struct PlanKey {
+    int layout, count, cu_share;
+    int dims[PP_MAX_GROUP][6]; // M, N, K, epi, forced height, may split
+    bool operator<(const PlanKey &o) const { return memcmp(this, &o, sizeof *this) < 0; }
+};
+struct Plan {
+    int bm[PP_MAX_GROUP], ks[PP_MAX_GROUP], order[PP_MAX_GROUP];
+};
+
+static Plan plan_group(int layout, const GemmArgs *a, int count, const int *bm_override, int cu_share)
 {
+    static std::map<PlanKey, Plan> cache;
+    static std::mutex lock;
+    PlanKey key;
+    memset(&key, 0, sizeof key);
+    key.layout = layout; key.count = count; key.cu_share = cu_share;
+    for (int q = 0; q < count; ++q) {
+        const int forced = bm_override ? bm_override[q] : 0;
+        const int d[6] = {a[q].M, a[q].N, a[q].K, a[q].epi, forced, may_split_k(a[q]) ? 1 : 0};
+        memcpy(key.dims[q], d, sizeof d);
+    }
+    {
+        std::lock_guard<std::mutex> g(lock);
+        auto it = cache.find(key);
+        if (it != cache.end()) return it->second;
+    }
     const int heights[3] = {256, 192, 128};
-    const int cus_per_xcd = std::max(1, compute_units() / std::max(1, cu_share) / 8);
-    int combos = 1;
-    for (int q = 0; q < count; ++q) combos *= 3;
-    double best = 1e300;
-    int bm[PP_MAX_GROUP], order[PP_MAX_GROUP];
-    for (int c = 0; c < combos; ++c) {
-        int x = c;
-        bool ok = true;
-        for (int q = 0; q < count; ++q, x /= 3) {
-            bm[q] = heights[x % 3];
-            const int forced = bm_override ? bm_override[q] : 0;
-            if ((forced == 256 || forced == 192 || forced == 128) && forced != bm[q]) ok = false;
-        }
-        if (!ok) continue;
-        for (int q = 0; q < count; ++q) order[q] = q;
-        std::stable_sort(order, order + count, [&](int i, int j) { return tile_cost(a[i], bm[i]) > tile_cost(a[j], bm[j]); });
-        const double t = makespan(a, bm, order, count, cus_per_xcd);
-        if (t < best - 1e-9) {
-            best = t;
-            for (int q = 0; q < count; ++q) {
-                bm_out[q] = bm[q];
-                order_out[q] = order[q];
+    const int splits[6] = {1, 2, 4, 8, 16, 32};
+    const int cus = std::max(8, compute_units() / std::max(1, cu_share));
+    const int cus_per_xcd = std::max(1, cus / 8);
+    // options per problem
+    int nopt[PP_MAX_GROUP], obm[PP_MAX_GROUP][18], oks[PP_MAX_GROUP][18];
+    for (int q = 0; q < count; ++q) {
+        nopt[q] = 0;
+        const int forced = bm_override ? bm_override[q] : 0;
+        const long tiles128 = (long)((a[q].M + 127) / 128) * tiles_n_of(a[q]);
+        const bool split_ok = may_split_k(a[q]) && tiles128 < cus;
+        for (int h = 0; h < 3; ++h) {
+            if ((forced == 256 || forced == 192 || forced == 128) && forced != heights[h]) continue;
+            for (int k = 0; k < (split_ok ? 6 : 1); ++k) {
+                if (splits[k] > 1 && a[q].K / 32 / splits[k] < 4) break; // keep at least four sub-tiles per chunk
+                obm[q][nopt[q]] = heights[h];
+                oks[q][nopt[q]] = splits[k];
+                ++nopt[q];
             }
         }
     }
+    Plan best_plan;
+    memset(&best_plan, 0, sizeof best_plan);
+    double best = 1e300;
+    int idx[PP_MAX_GROUP] = {0, 0, 0, 0};
+    for (;;) {
+        int bm[PP_MAX_GROUP], ks[PP_MAX_GROUP], order[PP_MAX_GROUP];
+        for (int q = 0; q < count; ++q) {
+            bm[q] = obm[q][idx[q]];
+            ks[q] = oks[q][idx[q]];
+            order[q] = q;
+        }
+        std::stable_sort(order, order + count,
+                         [&](int i, int j) { return tile_cost(a[i], bm[i], ks[i]) > tile_cost(a[j], bm[j], ks[j]); });
+        const double t = makespan(a, bm, ks, order, count, cus_per_xcd);
+        if (t < best - 1e-9) {
+            best = t;
+            for (int q = 0; q < count; ++q) {
+                best_plan.bm[q] = bm[q];
+                best_plan.ks[q] = ks[q];
+                best_plan.order[q] = order[q];
+            }
+        }
+        int q = 0;
+        while (q < count && ++idx[q] == nopt[q]) idx[q++] = 0;
+        if (q == count) break;
+    }
+    std::lock_guard<std::mutex> g(lock);
+    cache[key] = best_plan;
+    return best_plan;
 }
 
-void gemm_bf16_pp_plan(int layout, const GemmArgs *a, int count, const int *bm_override, int *bm_out)
+void gemm_bf16_pp_plan(int layout, const GemmArgs *a, int count, const int *bm_override, int *bm_out, int *ksplit_out)
 {
-    (void)layout;
-    int order[PP_MAX_GROUP];
     if (count < 1 || count > PP_MAX_GROUP) return;
-    plan_group(a, count, bm_override, count == 1 ? a[0].cu_share : 1, bm_out, order);
+    const Plan pl = plan_group(layout, a, count, bm_override, count == 1 ? a[0].cu_share : 1);
+    for (int q = 0; q < count; ++q) {
+        if (bm_out) bm_out[q] = pl.bm[q];
+        if (ksplit_out) ksplit_out[q] = pl.ks[q];
+    }
 }
 
 hipError_t launch_gemm_bf16_pp_group(int layout, const GemmArgs *a_in, int count_in, const int *bm_override, hipStream_t s)
@@ -150,8 +214,8 @@ hipError_t launch_gemm_bf16_pp_group(int layout, const GemmArgs *a_in, int count
         a[count++] = a_in[q];
     }
     if (count == 0) return hipSuccess;
-    int bm[PP_MAX_GROUP], order[PP_MAX_GROUP];
-    plan_group(a, count, forced, count == 1 ? a[0].cu_share : 1, bm, order);
+    const Plan pl = plan_group(layout, a, count, forced, count == 1 ? a[0].cu_share : 1);
+    const int *bm = pl.bm, *order = pl.order;
 
     PpGroup g;
     memset(&g, 0, sizeof g);
@@ -165,7 +229,11 @@ hipError_t launch_gemm_bf16_pp_group(int layout, const GemmArgs *a_in, int count
         p.tiles_m = (a[q].M + bm[q] - 1) / bm[q];
         p.tiles_n = tiles_n_of(a[q]);
         p.vec_epilogue = gemm_epilogue_vec_ok(a[q]) ? 1 : 0;
-        per_xcd += (unsigned)(((long)p.tiles_m * p.tiles_n + 7) / 8);
+        // as many chunks as are not empty
+        const int kt = a[q].K / 32, each = (kt + pl.ks[q] - 1) / pl.ks[q];
+        p.ksplit = (kt + each - 1) / each;
+        if (p.ksplit > 1) p.a.epi = EPI_ACC_ATOMIC;
+        per_xcd += (unsigned)(((long)p.tiles_m * p.tiles_n * p.ksplit + 7) / 8);
     }
     const unsigned blocks = per_xcd * 8;
     const bool f16 = a[0].elem == ELEM_F16;

@@ -785,7 +785,14 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
     // moves on after this step, the sum (arriving content + this worker's contribution) is written
     // straight to where it travels to, instead of back into the buffer and copied from there.
     const bool moves_on = rotating && r->d.g_bytes && r->d.mode != RTP_INPLACE_BLOCKING;
-    const bool fused_send = moves_on && !f32 && !r->dry && r->abl_compute && d.T > 0;
+    bool fused_send = moves_on && !f32 && !r->dry && r->abl_compute && d.T > 0;
+    if (fused_send && gemm_bf16_pp_supported(LAY_TN, a)) {
+        // not when the launcher would cut this GEMM's K loop into chunks (few output tiles, long
+        // contraction): their partial sums need the plain `+=` form
+        int ks = 1;
+        gemm_bf16_pp_plan(LAY_TN, &a, 1, nullptr, nullptr, &ks);
+        if (ks > 1) fused_send = false;
+    }
     if (fused_send) {
         a.epi = EPI_ACC_LAST;
         a.C = r->home_g(k) + d.g_offset;
@@ -1227,7 +1234,12 @@ static rtp_status mlp_bwd_grouped(rtp_mlp *m, const void *X, const void *dY, voi
         g[0] = mlp_args_dw1(m, h, r->shard_at(s), gbuf(s), X);
         g[1] = mlp_args_dw2(m, h, r->shard_at(s), gbuf(s), dY);
         // the send of the finished gradient shard is fused into the kernels (as in rtp_linear_bwd)
-        const bool fused_send = move_g && s <= n - 2 && r->abl_compute;
+        bool fused_send = move_g && s <= n - 2 && r->abl_compute;
+        if (fused_send) {
+            int ks[2] = {1, 1};
+            gemm_bf16_pp_plan(LAY_TN, g, 2, nullptr, nullptr, ks);
+            if (ks[0] > 1 || ks[1] > 1) fused_send = false; // K-split partial sums need the plain `+=` form
+        }
         if (fused_send) {
             char *home = r->home_g(r->shard_at(s));
             g[0].epi = g[1].epi = EPI_ACC_LAST;

@@ -19,7 +19,8 @@ enum : int {
     EPI_SWIGLU_FWD = 6,   // B is [gate rows | up rows]; aux = (a | b); C = silu(a) * b
     EPI_GELU_ERF_BWD = 7, // C = acc * gelu'(aux)
     EPI_GELU_TANH_BWD = 8,
-    EPI_SWIGLU_BWD = 9    // C[:, n] = acc * b * silu'(a) ; C[:, half + n] = acc * silu(a)
+    EPI_SWIGLU_BWD = 9,   // C[:, n] = acc * b * silu'(a) ; C[:, half + n] = acc * silu(a)
+    EPI_ACC_ATOMIC = 10   // ws += acc with fp32 atomic adds (set by the launcher when it splits K; not for callers)
 };
 
 struct GemmArgs {
@@ -50,13 +51,14 @@ bool gemm_bf16_args_ok(int layout, const GemmArgs &a);
 // the ping-pong kernel (rtp_gemm_pp.h): needs K % 32 == 0; bm_override 0 = pick the tile height
 bool gemm_bf16_pp_supported(int layout, const GemmArgs &a);
 hipError_t launch_gemm_bf16_pp(int layout, const GemmArgs &a, int bm_override, hipStream_t s);
-// up to PP_MAX_GROUP independent GEMMs of one layout in a single launch; tile heights are picked
-// for the group as a whole (bm_override: null, or one forced height per problem, 0 = pick).
+// up to PP_MAX_GROUP independent GEMMs of one layout in a single launch; tile heights, and for an
+// fp32 `ws += ...` problem short of tiles a split of its K loop (partial sums meet through atomic
+// adds, so the order of that sum is not fixed), are picked for the group as a whole (bm_override: null, or one forced height per problem, 0 = pick).
 // hipErrorInvalidValue if a problem does not meet gemm_bf16_pp_supported.
 constexpr int PP_MAX_GROUP = 4;
 hipError_t launch_gemm_bf16_pp_group(int layout, const GemmArgs *a, int count, const int *bm_override, hipStream_t s);
-// the heights that launch would use (for tests and reports)
-void gemm_bf16_pp_plan(int layout, const GemmArgs *a, int count, const int *bm_override, int *bm_out);
+// the tile heights and K splits that launch would use (either output may be null)
+void gemm_bf16_pp_plan(int layout, const GemmArgs *a, int count, const int *bm_override, int *bm_out, int *ksplit_out);
 const char *gemm_bf16_kernel_name(int layout, int variant);
 
 // fp32 inputs and outputs (epi: EPI_STORE, EPI_ACC_ADD with ws == C).

@@ -112,6 +112,32 @@ def test_gemm_fp16_layouts_and_tails(layout, variant):
             assert err <= (TOL_F32 if out_f32 else TOL_F16), (layout, variant, M, N, K, accumulate, out_f32, err)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("layout", [B.LAYOUT_NT, B.LAYOUT_NN, B.LAYOUT_TN])
+def test_gemm_split_k_accumulate(layout, dtype):
+    """Few output tiles, long contraction, fp32 `C += A B`: the launcher cuts the K loop into chunks whose
+    partial sums meet through atomic adds (the weight-gradient GEMM of a narrow shard).  Random inputs to the
+    fp32 bar; integer inputs bit-exactly, whatever order the chunks arrive in."""
+    for i, (M, N, K) in enumerate([(384, 768, 8192), (128, 264, 4096), (768, 384, 2048 + 96)]):
+        for variant in (4, 7):
+            say(f"split-K gemm layout={layout} dtype={dtype} M={M} N={N} K={K} variant={variant}")
+            err = _gemm_case(layout, M, N, K, variant, True, True, seed=500 + 10 * layout + i, dtype=dtype)
+            assert err <= TOL_F32, (layout, M, N, K, variant, err)
+    M, N, K = 384, 520, 8192
+    rng = np.random.default_rng(77)
+    shapes = {B.LAYOUT_NT: ((M, K), (N, K)), B.LAYOUT_NN: ((M, K), (K, N)), B.LAYOUT_TN: ((K, M), (K, N))}[layout]
+    A = rng.integers(-2, 3, size=shapes[0]).astype(np.float32)
+    Bm = rng.integers(-2, 3, size=shapes[1]).astype(np.float32)
+    C0 = rng.integers(-8, 9, size=(M, N)).astype(np.float32)
+    Ad, Bd = torch.from_numpy(A).double(), torch.from_numpy(Bm).double()
+    prod = {B.LAYOUT_NT: lambda: Ad @ Bd.T, B.LAYOUT_NN: lambda: Ad @ Bd, B.LAYOUT_TN: lambda: Ad.T @ Bd}[layout]()
+    ref = (prod + torch.from_numpy(C0).double()).float()
+    dA, dB, dC = dev(A, _TD[dtype]), dev(Bm, _TD[dtype]), dev(C0, torch.float32)
+    B.rtp_gemm(layout, _BD[dtype], B.RTP_F32, True, dA, shapes[0][1], dB, shapes[1][1], dC, N, M, N, K, 4)
+    torch.cuda.synchronize()
+    assert torch.equal(dC.cpu(), ref)
+
+
 def test_gemm_fp16_needs_the_tiled_kernel():
     a = torch.zeros(64, 72, device=DEV, dtype=torch.float16)
     c = torch.zeros(64, 64, device=DEV, dtype=torch.float32)
