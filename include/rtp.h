@@ -97,6 +97,14 @@ int rtp_bwd_shard(int rank, int step, int n);
  * ways; -1 if n does not divide dim or k is outside [0, n). */
 int64_t rtp_shard_begin(int k, int64_t dim, int n);
 
+/* Width of the n equal shards of a dimension of size `dim` (FlatParameter
+ * section: the flat parameter is padded so that it divides evenly).  dim / n
+ * when n divides dim; otherwise the smallest width that covers dim and is a
+ * multiple of 8 (bf16), 32 (fp16) or 1 (fp32) elements: shard k then holds
+ * elements [k w, min((k + 1) w, dim)), its tail is padding (zeros, never read
+ * as data, never written).  -1 if that would leave the last shard empty. */
+int64_t rtp_shard_width(int64_t dim, int n, rtp_dtype dtype);
+
 /* Parameter bytes one worker holds for a unit whose slot has w_bytes of
  * weights and g_bytes of gradients, per mode; 0 on a bad mode.
  *   DOUBLE_BUFFER 2(w+g), INPLACE_STAGED 2w+g, INPLACE_BLOCKING w+g.
@@ -210,8 +218,12 @@ typedef struct {
  * [k*o/2, (k+1)*o/2) followed by the same rows of up; the forward output is
  * [T, O/2].  With SPLIT_IN and SWIGLU the backward output is [T, 2 I] in the
  * same shard-stacked column order.
- * Errors: RTP_ERR_SHAPE (n does not divide the partitioned dimension; bf16 or
- * fp16: I, o not multiples of 8; shard does not fit the slot),
+ * A layer without an activation may have a partitioned dimension n does not
+ * divide: its shards are padded to rtp_shard_width() and stored at that width
+ * ([w, I] rows for SPLIT_OUT, [O, w] columns for SPLIT_IN, padding zero).
+ * Errors: RTP_ERR_SHAPE (n does not divide the partitioned dimension of a
+ * layer with an activation, or padding would leave a shard empty; bf16 or
+ * fp16: I, O, o not multiples of 8; shard does not fit the slot),
  * RTP_ERR_INVALID, RTP_ERR_UNSUPPORTED (gradient dtype other than F32; fp16
  * with T, o or the unpartitioned dimension not a multiple of 32: fp16 inputs
  * run on the tiled kernel only, which needs such contraction lengths). */

@@ -70,6 +70,7 @@ SYMBOLS = {
     "rtp_fwd_shard": (C.c_int, [C.c_int, C.c_int, C.c_int]),
     "rtp_bwd_shard": (C.c_int, [C.c_int, C.c_int, C.c_int]),
     "rtp_shard_begin": (C.c_int64, [C.c_int, C.c_int64, C.c_int]),
+    "rtp_shard_width": (C.c_int64, [C.c_int64, C.c_int, C.c_int]),
     "rtp_worker_bytes": (C.c_size_t, [C.c_int, C.c_size_t, C.c_size_t]),
     "rtp_table1_worker_bytes": (C.c_size_t, [C.c_int, C.c_size_t, C.c_size_t]),
     "rtp_status_str": (C.c_char_p, [C.c_int]),

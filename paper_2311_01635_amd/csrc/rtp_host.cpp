@@ -143,6 +143,20 @@ extern "C" int64_t rtp_shard_begin(int k, int64_t dim, int n)
     return (int64_t)k * (dim / n);
 }
 
+static int64_t width_align(rtp_dtype t) { return t == RTP_F32 ? 1 : t == RTP_F16 ? 32 : 8; }
+
+extern "C" int64_t rtp_shard_width(int64_t dim, int n, rtp_dtype dtype)
+{
+    if (n <= 0 || dim <= 0) return -1;
+    if (dim % n == 0) return dim / n;
+    // FlatParameter-style padding: equal shards of the smallest aligned width that covers dim;
+    // the last one is only partly filled, and must not be empty
+    const int64_t al = width_align(dtype);
+    const int64_t o = ((dim + n - 1) / n + al - 1) / al * al;
+    if ((int64_t)(n - 1) * o >= dim) return -1;
+    return o;
+}
+
 extern "C" size_t rtp_worker_bytes(rtp_mode mode, size_t w, size_t g)
 {
     switch (mode) {
@@ -564,10 +578,13 @@ extern "C" rtp_status rtp_linear_create(rtp_linear **out, rtp_ring *ring, const 
     if (d->act < RTP_ACT_NONE || d->act > RTP_ACT_SWIGLU) return fail(RTP_ERR_INVALID, "bad activation");
     const int n = ring->d.n;
     const int64_t part = d->split == RTP_SPLIT_OUT ? d->O : d->I;
-    if (part % n != 0)
-        return fail(RTP_ERR_SHAPE, "rtp_linear_create: n=%d does not divide the partitioned dimension %lld", n,
-                    (long long)part);
-    const int64_t o = part / n;
+    if (part % n != 0 && d->act != RTP_ACT_NONE)
+        return fail(RTP_ERR_SHAPE, "rtp_linear_create: n=%d does not divide the partitioned dimension %lld "
+                                   "(padded shards are built for layers without an activation)", n, (long long)part);
+    const int64_t o = rtp_shard_width(part, n, d->dtype);
+    if (o <= 0)
+        return fail(RTP_ERR_SHAPE, "rtp_linear_create: dimension %lld cannot be split into n=%d non-empty aligned shards",
+                    (long long)part, n);
     if (d->act == RTP_ACT_SWIGLU && d->split == RTP_SPLIT_OUT && (o & 1))
         return fail(RTP_ERR_SHAPE, "rtp_linear_create: a (gate, up) shard needs an even width");
     if (d->dtype != RTP_F32) {
@@ -579,12 +596,13 @@ extern "C" rtp_status rtp_linear_create(rtp_linear **out, rtp_ring *ring, const 
         // fp16 runs on the tiled kernel only: every contraction length (the batch, the shard width and
         // the dimension that is not partitioned) must be a multiple of 32
         const int64_t other = d->split == RTP_SPLIT_OUT ? d->I : d->O;
-        if ((d->T & 31) || (o & 31) || (other & 31))
+        if ((d->T & 31) || (o & 31) || (other & 31) || (part & 31))
             return fail(RTP_ERR_UNSUPPORTED, "rtp_linear_create: fp16 inputs need T, the shard width and the other "
                                              "matrix dimension to be multiples of 32");
     }
-    const size_t wsz = (size_t)d->O * (size_t)d->I / (size_t)n * esize(d->dtype);
-    const size_t gsz = (size_t)d->O * (size_t)d->I / (size_t)n * esize(d->grad_dtype);
+    const size_t other_dim = (size_t)(d->split == RTP_SPLIT_OUT ? d->I : d->O);
+    const size_t wsz = (size_t)o * other_dim * esize(d->dtype);     // a padded shard is stored at its full width
+    const size_t gsz = (size_t)o * other_dim * esize(d->grad_dtype);
     if ((d->w_offset & 15) || (d->g_offset & 15)) return fail(RTP_ERR_SHAPE, "rtp_linear_create: offsets must be multiples of 16");
     if (d->w_offset + wsz > ring->d.w_bytes || d->g_offset + gsz > ring->d.g_bytes)
         return fail(RTP_ERR_SHAPE, "rtp_linear_create: the shard does not fit the ring's slot");
@@ -662,6 +680,8 @@ extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, voi
     const size_t es = esize(d.dtype);
     const char *Wk = (const char *)r->d.buf_w_dev[r->res_idx] + d.w_offset;
     const int64_t o = l->o;
+    // columns of this shard that exist (the last shard of a padded partition is narrower)
+    const int64_t ov = std::min<int64_t>(o, (d.split == RTP_SPLIT_OUT ? d.O : d.I) - (int64_t)k * o);
     const bool f32 = d.dtype == RTP_F32;
     r->rec(TR_FWD, step, k, r->res_idx);
     GemmArgs a;
@@ -675,6 +695,7 @@ extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, voi
         a.B = Wk; a.ldb = d.I;
         a.M = (int)d.T; a.N = (int)o; a.K = (int)d.I;
         if (d.act == RTP_ACT_NONE) {
+            a.N = (int)ov;
             a.epi = EPI_STORE;
             a.C = (char *)Y + (size_t)k * o * es; a.ldc = d.O;
             RTP_TRY(gemm(l, LAY_NT, a, r->cs()));
@@ -701,7 +722,7 @@ extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, voi
     } else {
         a.A = (const char *)X + (size_t)k * o * es; a.lda = d.I;
         a.B = Wk; a.ldb = o;
-        a.M = (int)d.T; a.N = (int)d.O; a.K = (int)o;
+        a.M = (int)d.T; a.N = (int)d.O; a.K = (int)ov;
         a.C = Y; a.ldc = d.O;
         if (f32) {
             a.epi = step == 0 ? EPI_STORE : EPI_ACC_ADD;
@@ -737,6 +758,7 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
     const int k = r->abl_rotate ? r->resident : rtp_bwd_shard(r->d.rank, step, n);
     const size_t es = esize(d.dtype);
     const int64_t o = l->o;
+    const int64_t ov = std::min<int64_t>(o, (d.split == RTP_SPLIT_OUT ? d.O : d.I) - (int64_t)k * o);
     const bool f32 = d.dtype == RTP_F32;
     const bool rotating = r->abl_rotate && step < n - 1;
     const bool staged_g = r->d.mode == RTP_INPLACE_STAGED;
@@ -771,12 +793,12 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
     if (d.split == RTP_SPLIT_OUT) {
         a.A = (const char *)dY + (size_t)k * o * es; a.lda = d.O;
         a.B = X; a.ldb = d.I;
-        a.M = (int)o; a.N = (int)d.I;
+        a.M = (int)ov; a.N = (int)d.I;
         a.ws = Gk; a.ldws = d.I;
     } else {
         a.A = dY; a.lda = d.O;
         a.B = (const char *)X + (size_t)k * o * es; a.ldb = d.I;
-        a.M = (int)d.O; a.N = (int)o;
+        a.M = (int)d.O; a.N = (int)ov;
         a.ws = Gk; a.ldws = o;
     }
     a.C = a.ws; a.ldc = a.ldws;
@@ -825,7 +847,7 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
         if (d.split == RTP_SPLIT_OUT) {
             a.A = (const char *)dY + (size_t)k * o * es; a.lda = d.O;
             a.B = Wk; a.ldb = d.I;
-            a.M = (int)d.T; a.N = (int)d.I; a.K = (int)o;
+            a.M = (int)d.T; a.N = (int)d.I; a.K = (int)ov;
             a.C = dX; a.ldc = d.I;
             if (f32) {
                 a.epi = step == 0 ? EPI_STORE : EPI_ACC_ADD;
@@ -839,6 +861,7 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
             a.B = Wk; a.ldb = o;
             a.M = (int)d.T; a.N = (int)o; a.K = (int)d.O;
             if (d.act == RTP_ACT_NONE) {
+                a.N = (int)ov;
                 a.epi = EPI_STORE;
                 a.C = (char *)dX + (size_t)k * o * es; a.ldc = d.I;
                 RTP_TRY(gemm(l, LAY_NN, a, r->cs()));

@@ -14,26 +14,31 @@ def _esize(dtype):
     return 4 if dtype == B.RTP_F32 else 2
 
 
-def pack_out_split(W, n):
-    """[O, I] -> [n, o*I]: shard k is rows [k o, (k+1) o)."""
+def pack_out_split(W, n, o=None):
+    """[O, I] -> [n, o*I]: shard k is rows [k o, (k+1) o); rows past O (padded partition) are zero."""
     O, I = W.shape
-    return W.reshape(n, (O // n) * I)
+    o = O // n if o is None else o
+    if n * o != O:
+        W = torch.cat((W, W.new_zeros(n * o - O, I)), dim=0)
+    return W.reshape(n, o * I)
 
 
-def pack_in_split(W, n):
-    """[O, I] -> [n, O*o]: shard k is columns [k o, (k+1) o), stored [O, o]."""
+def pack_in_split(W, n, o=None):
+    """[O, I] -> [n, O*o]: shard k is columns [k o, (k+1) o), stored [O, o]; columns past I are zero."""
     O, I = W.shape
-    o = I // n
+    o = I // n if o is None else o
+    if n * o != I:
+        W = torch.cat((W, W.new_zeros(O, n * o - I)), dim=1)
     return W.reshape(O, n, o).permute(1, 0, 2).contiguous().reshape(n, O * o)
 
 
 def unpack_out_split(P, n, O, I):
-    return P.reshape(O, I)
+    return P.reshape(-1, I)[:O].contiguous()
 
 
 def unpack_in_split(P, n, O, I):
-    o = I // n
-    return P.reshape(n, O, o).permute(1, 0, 2).contiguous().reshape(O, I)
+    o = P.shape[1] // O
+    return P.reshape(n, O, o).permute(1, 0, 2).reshape(O, n * o)[:, :I].contiguous()
 
 
 def stack_gate_up(Wg, Wu, n):
@@ -62,10 +67,13 @@ class RtpLinear:
         W = W.to(self.dev, td).contiguous()
         self.O, self.I = W.shape
         pack = pack_out_split if split == B.RTP_SPLIT_OUT else pack_in_split
-        self.home_w = pack(W, n).contiguous()
+        o = B.lib.rtp_shard_width(self.O if split == B.RTP_SPLIT_OUT else self.I, n, dtype)
+        if o <= 0:
+            raise ValueError("the partitioned dimension cannot be split into n non-empty aligned shards")
+        self.home_w = pack(W, n, o).contiguous()
         G0 = torch.zeros(self.O, self.I, device=self.dev, dtype=torch.float32) if G0 is None else \
             G0.to(self.dev, torch.float32)
-        self.home_g = pack(G0, n).contiguous()
+        self.home_g = pack(G0, n, o).contiguous()
         wb = self.home_w.shape[1] * _esize(dtype)
         gb = self.home_g.shape[1] * 4
         self.buf_w = [torch.empty(wb, dtype=torch.uint8, device=self.dev) for _ in range(2)]

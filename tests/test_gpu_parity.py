@@ -268,6 +268,41 @@ def test_fp16_linear_multi_tile(mode, split):
         _check_linear(out, ref, TOL_F16)
 
 
+@pytest.mark.parametrize("mode", [B.RTP_DOUBLE_BUFFER, B.RTP_INPLACE_STAGED, B.RTP_INPLACE_BLOCKING])
+@pytest.mark.parametrize("split", [B.RTP_SPLIT_OUT, B.RTP_SPLIT_IN])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_padded_partition(dtype, split, mode):
+    """n does not divide the partitioned dimension: shards are padded to equal width and the last one
+    is partly filled.  The result must still be the plain unsharded linear layer (forward, both
+    gradients, arriving gradient content added), so the reference is the plain definition."""
+    part, n = (50, 3) if dtype == "f32" else (520, 3)
+    other = 36 if dtype == "f32" else 264
+    O, I = (part, other) if split == B.RTP_SPLIT_OUT else (other, part)
+    w = wl.Workload("padded", "linear", T=70 if dtype == "f32" else 300, I=I, O=O, n=n, dtype=dtype, mode="x",
+                    w_dist=("uniform", 0.1))
+    inp = wl.make_inputs(w, seed=9, grad0=True)
+    X, W, dY, G0 = (f64(inp[k]) for k in ("X", "W", "dY", "G0_W"))
+    dX_ref, dW_ref = orc.plain_linear_bwd(X, W, dY)
+    ref = dict(Y=orc.plain_linear_fwd(X, W), dX=dX_ref, dW=dW_ref + G0)
+    for rank in (0, n - 1):
+        say(f"padded partition dtype={dtype} split={split} mode={mode} rank={rank}")
+        layer = RtpLinear(dev(inp["W"], _TD[dtype]), w.T, n, rank, split, mode, _BD[dtype], G0=dev(inp["G0_W"], torch.float32))
+        Xd, dYd = dev(inp["X"], _TD[dtype]), dev(inp["dY"], _TD[dtype])
+        Y = torch.full((w.T, O), float("nan"), device=DEV, dtype=_TD[dtype])
+        dX = torch.full((w.T, I), float("nan"), device=DEV, dtype=_TD[dtype])
+        torch.cuda.synchronize()
+        layer.forward(Xd, Y)
+        layer.backward(Xd, dYd, dX)
+        layer.sync()
+        Wb, G = layer.gathered()
+        assert torch.equal(Wb, dev(inp["W"], _TD[dtype]))
+        tol = TOL_F32 if dtype == "f32" else TOL_BF16
+        for key, got in (("Y", Y), ("dX", dX), ("dW", G)):
+            assert torch.isfinite(got.float()).all(), key
+            assert relerr(host(got), ref[key]) <= tol, (key, relerr(host(got), ref[key]))
+        layer.close()
+
+
 def test_degenerate_partitions():
     # n = 1 is the plain linear; one token; n equal to the number of 8-wide column groups
     for (T, I, O, n) in ((40, 64, 72, 1), (1, 64, 64, 2), (33, 16, 64, 8)):

@@ -228,3 +228,32 @@ def test_build_script_loads_without_the_library():
         assert os.path.exists(os.path.join(mod.CSRC, src)), src
     assert "paper_2311_01635_amd" not in open(entry.__file__).read().split("def build()")[1].split("lib_build.build")[0].replace(
         '"paper_2311_01635_amd"', ""), "build() imports the package before building it"
+
+
+def test_shard_width_with_padding():
+    """Equal shards; when n does not divide the dimension the width is rounded up to the element
+    alignment of the dtype and the last shard is partly filled, never empty."""
+    w = B.lib.rtp_shard_width
+    assert w(512, 4, B.RTP_BF16) == 128 and w(512, 4, B.RTP_F32) == 128
+    assert w(520, 3, B.RTP_BF16) == 176            # ceil(520/3) = 174 -> 176; shards 176, 176, 168
+    assert w(50, 3, B.RTP_F32) == 17               # 17, 17, 16
+    assert w(1056, 5, B.RTP_F16) == 224            # ceil = 212 -> 224; last shard 1056 - 896 = 160
+    assert w(42, 4, B.RTP_BF16) == -1              # width 16: shards 16, 16, 10, 0 -- the last would be empty
+    assert w(40, 4, B.RTP_BF16) == 10              # n divides: no padding (a bf16 layer then fails on alignment)
+    assert w(0, 4, B.RTP_BF16) == -1 and w(64, 0, B.RTP_BF16) == -1
+    for dim, n, dt, al in ((520, 3, B.RTP_BF16, 8), (1000, 7, B.RTP_F32, 1), (4000, 6, B.RTP_BF16, 8)):
+        o = w(dim, n, dt)
+        assert o % al == 0 and (n - 1) * o < dim <= n * o and o - al < -(-dim // n) <= o
+
+
+def test_padded_linear_descriptions():
+    ring = _dry_ring(3, 0, B.RTP_DOUBLE_BUFFER, w=176 * 64 * 2, g=176 * 64 * 4)
+    ok = B.Linear(ring, T=8, I=64, O=520, split=B.RTP_SPLIT_OUT, dtype=B.RTP_BF16)      # shards of 176 rows, padded
+    ok.close()
+    with pytest.raises(B.RtpError) as e:                                                  # an activation needs n | O
+        B.Linear(ring, T=8, I=64, O=520, split=B.RTP_SPLIT_OUT, dtype=B.RTP_BF16, act=B.RTP_ACT_GELU_ERF)
+    assert e.value.status == B.RTP_ERR_SHAPE
+    with pytest.raises(B.RtpError) as e:                                                  # padded shard larger than the slot
+        B.Linear(ring, T=8, I=64, O=536, split=B.RTP_SPLIT_OUT, dtype=B.RTP_BF16)
+    assert e.value.status == B.RTP_ERR_SHAPE
+    ring.close()
