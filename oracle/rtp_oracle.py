@@ -156,10 +156,15 @@ def shard_rows(k, O, n):
 # plain (unsharded) definitions
 # --------------------------------------------------------------------------
 
-def plain_linear_fwd(X, W):
+def plain_linear_fwd(X, W, b=None):
+    """Y = X W^T (+ b on every row)."""
     T, _ = X.shape
     O, _ = W.shape
-    return gemm_nt(X, W, np.empty((T, O)))
+    Y = gemm_nt(X, W, np.empty((T, O)))
+    if b is not None:
+        for t in range(T):
+            Y[t, :] += b
+    return Y
 
 
 def plain_linear_bwd(X, W, dY):
@@ -169,6 +174,15 @@ def plain_linear_bwd(X, W, dY):
     dX = gemm_nn(dY, W, np.empty((T, I)))
     dW = gemm_tn(dY, X, np.empty((O, I)))
     return dX, dW
+
+
+def plain_bias_grad(dY):
+    """db[j] = sum over tokens of dY[t, j]."""
+    T, O = dY.shape
+    db = np.zeros(O)
+    for t in range(T):
+        db += dY[t, :]
+    return db
 
 
 def plain_mlp(X, W1, W2, dY, kind=GELU_ERF):
@@ -304,6 +318,27 @@ def rtp_linear_out(X, W, dY, n, rank, G0=None):
                 fwd_log=fwd_log, bwd_log=bwd_log, resident_after_fwd=res_after_fwd,
                 resident_after_bwd=ring.res_id, fwd_rotations=n_fwd_rot,
                 bwd_rotations=len(ring.sent) - n_fwd_rot, sent=ring.sent, received=ring.received)
+
+
+def rtp_linear_out_bias(X, W, b, dY, n, rank, G0=None, gb0=None):
+    """Output-partitioned linear with a bias that rides in the same shard as its rows of W (the flat
+    parameter of the FlatParameter section holds every parameter of the unit).  Row j of the shard is
+    (W[j, :], b[j]); the step's product with (X, 1) gives X W_k^T + b_k, and the travelling gradient
+    shard collects (dY_k^T X, dY_k^T 1) in the same layout.  Returns the dict of rtp_linear_out with
+    G split into G (matrix part) and gb (bias part)."""
+    T, I = X.shape
+    O = W.shape[0]
+    Wa = np.concatenate((W, np.asarray(b, dtype=np.float64).reshape(O, 1)), axis=1)
+    Xa = np.concatenate((X, np.ones((T, 1))), axis=1)
+    Ga = np.concatenate((np.zeros((O, I)) if G0 is None else G0,
+                         (np.zeros(O) if gb0 is None else np.asarray(gb0, dtype=np.float64)).reshape(O, 1)), axis=1)
+    out = rtp_linear_out(np.ascontiguousarray(Xa), np.ascontiguousarray(Wa), dY, n, rank, np.ascontiguousarray(Ga))
+    out["dX"] = np.ascontiguousarray(out["dX"][:, :I])      # the constant 1 has no gradient
+    out["gb"] = np.ascontiguousarray(out["G"][:, I])
+    out["G"] = np.ascontiguousarray(out["G"][:, :I])
+    out["b_after"] = np.ascontiguousarray(out["W_after"][:, I])
+    out["W_after"] = np.ascontiguousarray(out["W_after"][:, :I])
+    return out
 
 
 def rtp_linear_in(Xin, W, dY, n, rank, G0=None):

@@ -358,3 +358,53 @@ def test_table1_large_config_numbers():
     assert orc.worker_param_bytes("rtp", W, G, N) == 293_601_280
     assert orc.worker_param_bytes("rtp_inplace", W, G, N) == 176_160_768
     assert orc.worker_param_bytes("rtp", W, W, N) == 176_160_768     # bf16 gradient shards
+
+
+# ------------------------------------------------------------------ bias in the flat parameter --
+
+def test_bias_plain_vs_brute_force():
+    """Y[t, j] = sum_i X[t, i] W[j, i] + b[j] and db[j] = sum_t dY[t, j], written out element by element
+    in extended precision."""
+    T, I, O = 5, 4, 6
+    X, W, dY = rng_mats(91, T, I, O)
+    b = np.random.default_rng(92).standard_normal(O)
+    Yb = np.zeros((T, O), dtype=np.longdouble)
+    db = np.zeros(O, dtype=np.longdouble)
+    for t in range(T):
+        for j in range(O):
+            acc = np.longdouble(b[j])
+            for i in range(I):
+                acc += np.longdouble(X[t, i]) * np.longdouble(W[j, i])
+            Yb[t, j] = acc
+            db[j] += np.longdouble(dY[t, j])
+    np.testing.assert_allclose(orc.plain_linear_fwd(X, W, b), Yb.astype(np.float64), rtol=0, atol=1e-13)
+    np.testing.assert_allclose(orc.plain_bias_grad(dY), db.astype(np.float64), rtol=0, atol=1e-13)
+    np.testing.assert_allclose(orc.plain_bias_grad(dY), dY.sum(axis=0), rtol=0, atol=1e-12)   # library routine
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 6])
+def test_bias_rides_with_its_rows(n):
+    """The rotated layer with the bias carried in the shard gives the plain layer with bias, the bias
+    gradient adds onto what arrives with the shard, and weights and bias come back unchanged."""
+    T, I, O = 7, 5, 12
+    X, W, dY = rng_mats(93 + n, T, I, O)
+    rng = np.random.default_rng(94)
+    b, gb0, G0 = rng.standard_normal(O), rng.standard_normal(O), rng.standard_normal((O, I))
+    for rank in range(n):
+        res = orc.rtp_linear_out_bias(X, W, b, dY, n, rank, G0, gb0)
+        np.testing.assert_allclose(res["Y"], orc.plain_linear_fwd(X, W, b), rtol=0, atol=1e-12)
+        dX, dW = orc.plain_linear_bwd(X, W, dY)
+        np.testing.assert_allclose(res["dX"], dX, rtol=0, atol=1e-12)
+        np.testing.assert_allclose(res["G"], G0 + dW, rtol=0, atol=1e-12)
+        np.testing.assert_allclose(res["gb"], gb0 + orc.plain_bias_grad(dY), rtol=0, atol=1e-12)
+        assert np.array_equal(res["W_after"], W) and np.array_equal(res["b_after"], b)
+        assert res["resident_after_bwd"] == rank
+
+
+def test_bias_gradient_by_finite_differences():
+    """L = sum(Y * dY) with Y = X W^T + b  =>  dL/db = column sums of dY (and dL/dX, dL/dW unchanged)."""
+    X, W, dY = rng_mats(95, 4, 5, 6)
+    b = np.random.default_rng(96).standard_normal(6)
+    res = orc.rtp_linear_out_bias(X, W, b, dY, 3, 2)
+    _fd_check(lambda: float(np.sum(orc.plain_linear_fwd(X, W, b) * dY)), {"X": X, "W": W, "b": b},
+              {"X": res["dX"], "W": res["G"], "b": res["gb"]})
