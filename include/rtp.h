@@ -211,7 +211,18 @@ typedef struct {
     float *acc_ws_dev;    /* fp32 [T, I] (SPLIT_OUT, dX) or [T, O] (SPLIT_IN, Y):
                              cross-step accumulator; needed when dtype != F32
                              and n > 1                                            */
+    int has_bias;         /* RTP_SPLIT_OUT only: the layer is Y = X W^T + b.  The
+                             bias rides in the flat parameter: shard k's w entries
+                             of b follow its rows of W in the slot (at w_offset +
+                             w * I * sizeof(dtype)), and the fp32 bias gradient
+                             follows the matrix gradient the same way             */
 } rtp_linear_desc;
+
+/* Bytes one shard of the layer takes in the weight part / the gradient part
+ * of a slot (matrix shard, bias shard if any, rounded up to 16); 0 on a bad
+ * description. */
+size_t rtp_linear_shard_w_bytes(const rtp_linear_desc *desc, int n);
+size_t rtp_linear_shard_g_bytes(const rtp_linear_desc *desc, int n);
 
 /* With act == RTP_ACT_SWIGLU and SPLIT_OUT, W is the stack of the gate and up
  * matrices arranged so that shard k (o = O/n rows, o even) is gate rows
@@ -224,7 +235,8 @@ typedef struct {
  * Errors: RTP_ERR_SHAPE (n does not divide the partitioned dimension of a
  * layer with an activation, or padding would leave a shard empty; bf16 or
  * fp16: I, O, o not multiples of 8; shard does not fit the slot),
- * RTP_ERR_INVALID, RTP_ERR_UNSUPPORTED (gradient dtype other than F32; fp16
+ * RTP_ERR_INVALID, RTP_ERR_UNSUPPORTED (gradient dtype other than F32; a bias
+ * on an input-partitioned layer; fp16
  * with T, o or the unpartitioned dimension not a multiple of 32: fp16 inputs
  * run on the tiled kernel only, which needs such contraction lengths). */
 rtp_status rtp_linear_create(rtp_linear **out, rtp_ring *ring, const rtp_linear_desc *desc);

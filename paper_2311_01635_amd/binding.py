@@ -42,7 +42,7 @@ class rtp_linear_desc(C.Structure):
     _fields_ = [("T", C.c_int64), ("I", C.c_int64), ("O", C.c_int64),
                 ("split", C.c_int), ("dtype", C.c_int), ("grad_dtype", C.c_int), ("act", C.c_int),
                 ("w_offset", C.c_size_t), ("g_offset", C.c_size_t),
-                ("preact_dev", C.c_void_p), ("acc_ws_dev", C.c_void_p)]
+                ("preact_dev", C.c_void_p), ("acc_ws_dev", C.c_void_p), ("has_bias", C.c_int)]
 
 
 class rtp_mlp_desc(C.Structure):
@@ -71,6 +71,8 @@ SYMBOLS = {
     "rtp_bwd_shard": (C.c_int, [C.c_int, C.c_int, C.c_int]),
     "rtp_shard_begin": (C.c_int64, [C.c_int, C.c_int64, C.c_int]),
     "rtp_shard_width": (C.c_int64, [C.c_int64, C.c_int, C.c_int]),
+    "rtp_linear_shard_w_bytes": (C.c_size_t, [C.POINTER(rtp_linear_desc), C.c_int]),
+    "rtp_linear_shard_g_bytes": (C.c_size_t, [C.POINTER(rtp_linear_desc), C.c_int]),
     "rtp_worker_bytes": (C.c_size_t, [C.c_int, C.c_size_t, C.c_size_t]),
     "rtp_table1_worker_bytes": (C.c_size_t, [C.c_int, C.c_size_t, C.c_size_t]),
     "rtp_status_str": (C.c_char_p, [C.c_int]),
@@ -229,12 +231,13 @@ class Ring:
 
 class Linear:
     def __init__(self, ring, T, I, O, split, dtype, act=RTP_ACT_NONE, w_offset=0, g_offset=0, preact=None,
-                 acc_ws=None, grad_dtype=RTP_F32):
+                 acc_ws=None, grad_dtype=RTP_F32, has_bias=False):
         d = rtp_linear_desc()
         d.T, d.I, d.O = T, I, O
         d.split, d.dtype, d.grad_dtype, d.act = split, dtype, grad_dtype, act
         d.w_offset, d.g_offset = w_offset, g_offset
         d.preact_dev, d.acc_ws_dev = _ptr(preact), _ptr(acc_ws)
+        d.has_bias = int(bool(has_bias))
         self._keep = (preact, acc_ws)
         self.ring = ring
         self.handle = C.c_void_p()

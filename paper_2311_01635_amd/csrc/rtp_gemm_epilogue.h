@@ -77,6 +77,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, f32x16 (&acc)[F
     E *auxw = (E *)p.aux;
     const int64_t ldc = p.ldc, ldws = p.ldws, ldaux = p.ldaux;
     float *ws = p.ws;
+    const E *bias = (const E *)p.bias;
 
     if (p.epi == EPI_SWIGLU_FWD) {
         const int half = p.half;
@@ -90,7 +91,11 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, f32x16 (&acc)[F
                 for (int v = 0; v < 16; ++v) {
                     const int row = rbase + i * 32 + 8 * (v >> 2) + (v & 3);
                     if (row >= M) continue;
-                    const float a = acc[i][j][v], b = acc[i][j + FN / 2][v];
+                    float a = acc[i][j][v], b = acc[i][j + FN / 2][v];
+                    if (bias) {
+                        a += (float)bias[col];
+                        b += (float)bias[half + col];
+                    }
                     auxw[(int64_t)row * ldaux + col] = (E)a;
                     auxw[(int64_t)row * ldaux + half + col] = (E)b;
                     Cb[(int64_t)row * ldc + col] = (E)(silu(a) * b);
@@ -115,6 +120,18 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, f32x16 (&acc)[F
                 }
             }
     };
+    // the bias joins the product before a store or a forward activation sees it
+    if (bias && (p.epi == EPI_STORE || p.epi == EPI_GELU_ERF_FWD || p.epi == EPI_GELU_TANH_FWD)) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            const int col = n0 + j * NSTRIDE + cl;
+            const float bj = col < N ? (float)bias[col] : 0.0f;
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] += bj;
+        }
+    }
     switch (p.epi) {
     case EPI_STORE:
         if (p.c_is_f32)
@@ -220,6 +237,7 @@ __host__ __device__ inline bool gemm_epilogue_vec_ok(const GemmArgs &p)
     bool ok = (p.ldc & 3) == 0 && al(p.C, 16);
     if (p.epi == EPI_ACC_FIRST || p.epi == EPI_ACC_ADD || p.epi == EPI_ACC_LAST || p.epi == EPI_ACC_ATOMIC) ok = ok && (p.ldws & 3) == 0 && al(p.ws, 16);
     if (p.epi >= EPI_GELU_ERF_FWD && p.epi <= EPI_SWIGLU_BWD) ok = ok && (p.ldaux & 3) == 0 && al(p.aux, 8) && (p.half & 3) == 0;
+    if (p.bias) ok = ok && al(p.bias, 8) && (p.epi != EPI_SWIGLU_FWD || (p.half & 3) == 0);
     return ok && (p.N & 3) == 0;
 }
 
@@ -236,6 +254,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
     float *Cf = (float *)p.C;
     E *aux = (E *)p.aux;
     float *ws = p.ws;
+    const E *bias = (const E *)p.bias;
     const int wrow = 4 * (lane >> 5), wcol = lane & 31;
 
     // park fragment row i: rows 8*(v/4) + 4*(lane/32) + v%4, columns j*32 + lane%32
@@ -257,10 +276,14 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int row = 8 * r + (lane >> 3), c = (lane & 7) * 4;
-                const f32x4 a = *(const f32x4 *)(wlds + row * EPI_LDS_PITCH + c);
-                const f32x4 b = *(const f32x4 *)(wlds + row * EPI_LDS_PITCH + 32 + c);
+                f32x4 a = *(const f32x4 *)(wlds + row * EPI_LDS_PITCH + c);
+                f32x4 b = *(const f32x4 *)(wlds + row * EPI_LDS_PITCH + 32 + c);
                 const int grow = rbase_wave + i * 32 + row, col = n0 + wn32 + c;
                 if (grow < M && col < half) {
+                    if (bias) {
+                        a = a + from_elem4<E>(*(const out4 *)(bias + col));
+                        b = b + from_elem4<E>(*(const out4 *)(bias + half + col));
+                    }
                     *(out4 *)(aux + (int64_t)grow * ldaux + col) = to_elem4<E>(a);
                     *(out4 *)(aux + (int64_t)grow * ldaux + half + col) = to_elem4<E>(b);
                     f32x4 h;
@@ -273,6 +296,8 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
         return;
     }
 
+    // the bias joins the product before a store or a forward activation sees it
+    const bool with_bias = bias && (p.epi == EPI_STORE || p.epi == EPI_GELU_ERF_FWD || p.epi == EPI_GELU_TANH_FWD);
     // every valid group of 4 consecutive columns; the branch on the kind stays outside the loops
     auto each = [&](auto op) {
 #pragma unroll
@@ -281,10 +306,13 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
                 const int row = 4 * r + (lane >> 4), c4 = lane & 15;
-                const f32x4 x = *(const f32x4 *)(wlds + row * EPI_LDS_PITCH + c4 * 4);
+                f32x4 x = *(const f32x4 *)(wlds + row * EPI_LDS_PITCH + c4 * 4);
                 const int grow = rbase_wave + i * 32 + row;
                 const int col = n0 + (c4 >> 3) * NSTRIDE + wn32 + (c4 & 7) * 4;
-                if (grow < M && col < N) op(grow, col, x);
+                if (grow < M && col < N) {
+                    if (with_bias) x = x + from_elem4<E>(*(const out4 *)(bias + col));
+                    op(grow, col, x);
+                }
             }
             __builtin_amdgcn_wave_barrier();
         }

@@ -563,6 +563,19 @@ extern "C" rtp_status rtp_ring_sync(rtp_ring *r)
 // ---------------------------------------------------------------------------
 static size_t esize(rtp_dtype t) { return t == RTP_F32 ? 4 : 2; }
 
+static size_t shard_bytes(const rtp_linear_desc *d, int n, size_t es)
+{
+    if (!d || n <= 0 || d->I <= 0 || d->O <= 0) return 0;
+    const int64_t o = rtp_shard_width(d->split == RTP_SPLIT_OUT ? d->O : d->I, n, d->dtype);
+    if (o <= 0) return 0;
+    const size_t other = (size_t)(d->split == RTP_SPLIT_OUT ? d->I : d->O);
+    const size_t elems = (size_t)o * other + (d->has_bias ? (size_t)o : 0);
+    return (elems * es + 15) & ~(size_t)15;
+}
+
+extern "C" size_t rtp_linear_shard_w_bytes(const rtp_linear_desc *d, int n) { return d ? shard_bytes(d, n, esize(d->dtype)) : 0; }
+extern "C" size_t rtp_linear_shard_g_bytes(const rtp_linear_desc *d, int n) { return d ? shard_bytes(d, n, 4) : 0; }
+
 extern "C" rtp_status rtp_linear_create(rtp_linear **out, rtp_ring *ring, const rtp_linear_desc *d)
 {
     if (!out || !ring || !d) return fail(RTP_ERR_INVALID, "rtp_linear_create: null argument");
@@ -600,9 +613,10 @@ extern "C" rtp_status rtp_linear_create(rtp_linear **out, rtp_ring *ring, const 
             return fail(RTP_ERR_UNSUPPORTED, "rtp_linear_create: fp16 inputs need T, the shard width and the other "
                                              "matrix dimension to be multiples of 32");
     }
-    const size_t other_dim = (size_t)(d->split == RTP_SPLIT_OUT ? d->I : d->O);
-    const size_t wsz = (size_t)o * other_dim * esize(d->dtype);     // a padded shard is stored at its full width
-    const size_t gsz = (size_t)o * other_dim * esize(d->grad_dtype);
+    if (d->has_bias && d->split != RTP_SPLIT_OUT)
+        return fail(RTP_ERR_UNSUPPORTED, "rtp_linear_create: a bias is built for output-partitioned layers only");
+    const size_t wsz = rtp_linear_shard_w_bytes(d, n);   // a padded shard is stored at its full width
+    const size_t gsz = rtp_linear_shard_g_bytes(d, n);
     if ((d->w_offset & 15) || (d->g_offset & 15)) return fail(RTP_ERR_SHAPE, "rtp_linear_create: offsets must be multiples of 16");
     if (d->w_offset + wsz > ring->d.w_bytes || d->g_offset + gsz > ring->d.g_bytes)
         return fail(RTP_ERR_SHAPE, "rtp_linear_create: the shard does not fit the ring's slot");
@@ -694,6 +708,7 @@ extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, voi
         a.A = X; a.lda = d.I;
         a.B = Wk; a.ldb = d.I;
         a.M = (int)d.T; a.N = (int)o; a.K = (int)d.I;
+        if (d.has_bias) a.bias = Wk + (size_t)o * d.I * es; // the shard's bias entries follow its rows
         if (d.act == RTP_ACT_NONE) {
             a.N = (int)ov;
             a.epi = EPI_STORE;
@@ -820,6 +835,17 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
         a.C = r->home_g(k) + d.g_offset;
     }
     if (d.T > 0) RTP_TRY(gemm(l, LAY_TN, a, ws));
+    if (d.has_bias && !r->dry && r->abl_compute) {
+        // bias gradient: column sums of this shard's slice of dY, onto the entries that follow the
+        // matrix gradient in the travelling shard (and out to where it travels, like the matrix part)
+        const size_t boff = (size_t)o * d.I * 4;
+        const float *gb_in = (const float *)((const char *)Gk + boff);
+        float *gb_out = fused_send ? (float *)(r->home_g(k) + d.g_offset + boff) : (float *)((char *)Gk + boff);
+        const int elem = f32 ? -1 : d.dtype == RTP_F16 ? ELEM_F16 : ELEM_BF16;
+        HIP_TRY(launch_colsum(elem, (const char *)dY + (size_t)k * o * es, d.O, (int)d.T, (int)ov, gb_in, gb_out, ws));
+        // (padding entries of a partly filled shard are zero in the buffer and in the slot alike, and nobody
+        // writes them)
+    }
 
     // ---- hand the gradient part to the stage stream ---------------------------
     if (moves_on) {

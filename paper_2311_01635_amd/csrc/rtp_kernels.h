@@ -35,6 +35,8 @@ struct GemmArgs {
     int64_t ldws;
     void *aux;          // pre-activations, in the input dtype
     int64_t ldaux;
+    const void *bias;   // optional, input dtype, one per column of B's rows (N of them, the (gate | up) order for
+                        // EPI_SWIGLU_FWD): added to the product before EPI_STORE / EPI_*_FWD act on it
     int half;           // EPI_SWIGLU_FWD: N/2 ; EPI_SWIGLU_BWD: N
     int c_is_f32;       // EPI_STORE / EPI_ACC_LAST write fp32 instead of the input dtype
     int elem;           // ELEM_BF16 or ELEM_F16 (the ping-pong kernel only; the register-staged one is bf16)
@@ -72,6 +74,9 @@ hipError_t launch_act_f32(int kind, const float *pre, int64_t ldpre, const float
 // device-to-device staging copy with a bounded number of workgroups
 hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
 hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s);
+// bias gradient: out[c] = in[c] + sum over rows of Y[r, c], c < cols (fp32 in/out, which may be the same);
+// elem: -1 fp32, ELEM_BF16, ELEM_F16
+hipError_t launch_colsum(int elem, const void *Y, int64_t ld, int rows, int cols, const float *in, float *out, hipStream_t s);
 
 // out[0] = wall-clock ticks, out[1] = shader cycles over a spin of wall_ticks
 hipError_t launch_clock_probe(long long *out, long long wall_ticks, hipStream_t s);

@@ -60,6 +60,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs p)
         __syncthreads();
     }
     float *C = (float *)p.C;
+    const float *bias = (const float *)p.bias;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int row = m0 + ty * 4 + i;
@@ -71,7 +72,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs p)
             if (p.epi == EPI_ACC_ADD)
                 C[(int64_t)row * p.ldc + col] += acc[i][j];
             else
-                C[(int64_t)row * p.ldc + col] = acc[i][j];
+                C[(int64_t)row * p.ldc + col] = acc[i][j] + (bias ? bias[col] : 0.0f);
         }
     }
 }
@@ -197,6 +198,37 @@ hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s)
     const int64_t n16 = (int64_t)(bytes >> 4);
     const int blocks = (int)((n16 + 255) / 256 > 4096 ? 4096 : (n16 + 255) / 256);
     hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, (u32x4 *)dst, n16);
+    return hipGetLastError();
+}
+
+// ---- bias gradient: column sums --------------------------------------------------------------
+// One workgroup per 64 columns: 4 row groups of 64 lanes walk the rows (coalesced 128- or 256-byte
+// row segments), the four partial sums meet in LDS.  Deterministic order; the matrices this runs
+// on ([tokens, shard width]) are small next to the GEMMs of the same step.
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(const T *Y, int64_t ld, int rows, int cols, const float *in, float *out)
+{
+    __shared__ float part[4][64];
+    const int c = blockIdx.x * 64 + (threadIdx.x & 63), g = threadIdx.x >> 6;
+    float s = 0.0f;
+    if (c < cols)
+        for (int r = g; r < rows; r += 4) s += (float)Y[(int64_t)r * ld + c];
+    part[g][threadIdx.x & 63] = s;
+    __syncthreads();
+    if (g == 0 && c < cols) out[c] = in[c] + ((part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]));
+}
+
+hipError_t launch_colsum(int elem, const void *Y, int64_t ld, int rows, int cols, const float *in, float *out, hipStream_t s)
+{
+    if (cols <= 0) return hipSuccess;
+    if (rows < 0 || !in || !out || (rows > 0 && !Y)) return hipErrorInvalidValue;
+    const dim3 grid((cols + 63) / 64), block(256);
+    if (elem == ELEM_BF16)
+        hipLaunchKernelGGL(colsum_kernel<__bf16>, grid, block, 0, s, (const __bf16 *)Y, ld, rows, cols, in, out);
+    else if (elem == ELEM_F16)
+        hipLaunchKernelGGL(colsum_kernel<_Float16>, grid, block, 0, s, (const _Float16 *)Y, ld, rows, cols, in, out);
+    else
+        hipLaunchKernelGGL(colsum_kernel<float>, grid, block, 0, s, (const float *)Y, ld, rows, cols, in, out);
     return hipGetLastError();
 }
 

@@ -60,7 +60,7 @@ class RtpLinear:
     rtp_rotate_step / rtp_linear_fwd / rtp_linear_bwd."""
 
     def __init__(self, W, T, n, rank, split=B.RTP_SPLIT_OUT, mode=B.RTP_DOUBLE_BUFFER, dtype=B.RTP_BF16,
-                 act=B.RTP_ACT_NONE, G0=None, preact=None, device="cuda:0", aux_stream=True):
+                 act=B.RTP_ACT_NONE, G0=None, preact=None, device="cuda:0", aux_stream=True, bias=None, gb0=None):
         self.dev = torch.device(device)
         self.n, self.rank, self.T, self.split, self.mode, self.dtype, self.act = n, rank, T, split, mode, dtype, act
         td = _TORCH_DT[dtype]
@@ -70,10 +70,26 @@ class RtpLinear:
         o = B.lib.rtp_shard_width(self.O if split == B.RTP_SPLIT_OUT else self.I, n, dtype)
         if o <= 0:
             raise ValueError("the partitioned dimension cannot be split into n non-empty aligned shards")
+        self.o, self.has_bias = o, bias is not None
         self.home_w = pack(W, n, o).contiguous()
         G0 = torch.zeros(self.O, self.I, device=self.dev, dtype=torch.float32) if G0 is None else \
             G0.to(self.dev, torch.float32)
         self.home_g = pack(G0, n, o).contiguous()
+        self.n_mat = self.home_w.shape[1]                  # elements of a matrix shard
+        if self.has_bias:
+            # shard k of the flat parameter = its rows of W, then its entries of b, padded to 16 bytes
+            d = B.rtp_linear_desc()
+            d.T, d.I, d.O, d.split, d.dtype, d.grad_dtype, d.has_bias = T, self.I, self.O, split, dtype, B.RTP_F32, 1
+            wbytes, gbytes = B.lib.rtp_linear_shard_w_bytes(C.byref(d), n), B.lib.rtp_linear_shard_g_bytes(C.byref(d), n)
+            def with_bias(mat, vec, total):
+                vec = torch.cat((vec, vec.new_zeros(n * o - vec.numel()))).reshape(n, o)
+                out = mat.new_zeros(n, total)
+                out[:, :self.n_mat] = mat
+                out[:, self.n_mat:self.n_mat + o] = vec
+                return out.contiguous()
+            gb0 = torch.zeros(self.O, device=self.dev) if gb0 is None else gb0
+            self.home_w = with_bias(self.home_w, bias.to(self.dev, td), wbytes // _esize(dtype))
+            self.home_g = with_bias(self.home_g, gb0.to(self.dev, torch.float32), gbytes // 4)
         wb = self.home_w.shape[1] * _esize(dtype)
         gb = self.home_g.shape[1] * 4
         self.buf_w = [torch.empty(wb, dtype=torch.uint8, device=self.dev) for _ in range(2)]
@@ -86,7 +102,8 @@ class RtpLinear:
         acc_cols = self.I if split == B.RTP_SPLIT_OUT else self.O
         self.acc_ws = torch.empty(T, acc_cols, dtype=torch.float32, device=self.dev)
         self.preact = preact
-        self.lin = B.Linear(self.ring, T, self.I, self.O, split, dtype, act, 0, 0, preact, self.acc_ws)
+        self.lin = B.Linear(self.ring, T, self.I, self.O, split, dtype, act, 0, 0, preact, self.acc_ws,
+                            has_bias=self.has_bias)
         torch.cuda.synchronize(self.dev)
 
     def forward(self, X, Y):
@@ -115,7 +132,13 @@ class RtpLinear:
         self.ring.flush()
         self.ring.sync()
         un = unpack_out_split if self.split == B.RTP_SPLIT_OUT else unpack_in_split
-        return un(self.home_w, self.n, self.O, self.I), un(self.home_g, self.n, self.O, self.I)
+        return (un(self.home_w[:, :self.n_mat].contiguous(), self.n, self.O, self.I),
+                un(self.home_g[:, :self.n_mat].contiguous(), self.n, self.O, self.I))
+
+    def gathered_bias(self):
+        """(b, gradient of b) read back from the home store (call gathered() first: it flushes)."""
+        sl = slice(self.n_mat, self.n_mat + self.o)
+        return self.home_w[:, sl].reshape(-1)[:self.O].contiguous(), self.home_g[:, sl].reshape(-1)[:self.O].contiguous()
 
     def close(self):
         self.ring.close()

@@ -303,6 +303,59 @@ def test_padded_partition(dtype, split, mode):
         layer.close()
 
 
+@pytest.mark.parametrize("mode", [B.RTP_DOUBLE_BUFFER, B.RTP_INPLACE_STAGED, B.RTP_INPLACE_BLOCKING])
+@pytest.mark.parametrize("dtype,act", [("f32", B.RTP_ACT_NONE), ("bf16", B.RTP_ACT_NONE), ("f16", B.RTP_ACT_NONE),
+                                       ("bf16", B.RTP_ACT_GELU_ERF), ("f32", B.RTP_ACT_GELU_ERF)])
+def test_linear_with_bias(dtype, act, mode):
+    """Y = act(X W^T + b) with the bias riding in the flat parameter: forward, input gradient, weight
+    gradient and bias gradient (column sums of dY onto what arrives with the shard) against the oracle's
+    rotated layer with bias; weights and bias come back unchanged.  One case has a padded last shard."""
+    if dtype == "f32":
+        T, I, O, n = 70, 36, 50, 3           # padded: shards of 17, 17, 16 rows
+    elif dtype == "bf16" and act == B.RTP_ACT_NONE:
+        T, I, O, n = 300, 264, 520, 3        # padded: 176, 176, 168
+    else:
+        T, I, O, n = 320, 288, 4 * 160, 4
+    if act != B.RTP_ACT_NONE and O % n:
+        O = 48 if dtype == "f32" else O      # an activation needs n | O
+    w = wl.Workload("bias", "linear", T=T, I=I, O=O, n=n, dtype=dtype, mode="x", w_dist=("uniform", 0.1))
+    inp = wl.make_inputs(w, seed=21, grad0=True)
+    rng = np.random.default_rng(22)
+    b = wl._store(rng.standard_normal(O).astype(np.float32) * 0.5, dtype)
+    gb0 = rng.standard_normal(O).astype(np.float32)
+    X, W, dY, G0 = (f64(inp[k]) for k in ("X", "W", "dY", "G0_W"))
+    td, bd = _TD[dtype], _BD[dtype]
+    tol = {"f32": TOL_F32, "bf16": TOL_BF16, "f16": TOL_F16}[dtype]
+    Z = orc.plain_linear_fwd(X, W, f64(b))
+    dX_ref, dW_ref = orc.plain_linear_bwd(X, W, dY)
+    ref = dict(Y=Z if act == B.RTP_ACT_NONE else orc.act(Z, orc.GELU_ERF), dX=dX_ref, dW=dW_ref + G0,
+               gb=f64(gb0) + orc.plain_bias_grad(dY))
+    for rank in (0, n - 1):
+        say(f"linear with bias dtype={dtype} act={act} mode={mode} rank={rank}")
+        if O % n == 0:   # the rotated oracle (equal shards) must agree with the plain definitions used above
+            rot = orc.rtp_linear_out_bias(X, W, f64(b), dY, n, rank, G0, f64(gb0))
+            assert relerr(rot["gb"], ref["gb"]) < 1e-12 and relerr(rot["G"], ref["dW"]) < 1e-12
+        preact = torch.empty(T, O, device=DEV, dtype=td) if act != B.RTP_ACT_NONE else None
+        layer = RtpLinear(dev(inp["W"], td), T, n, rank, B.RTP_SPLIT_OUT, mode, bd, act=act, preact=preact,
+                          G0=dev(inp["G0_W"], torch.float32), bias=dev(b, td), gb0=dev(gb0, torch.float32))
+        Xd, dYd = dev(inp["X"], td), dev(inp["dY"], td)
+        Y = torch.full((T, O), float("nan"), device=DEV, dtype=td)
+        dX = torch.full((T, I), float("nan"), device=DEV, dtype=td)
+        torch.cuda.synchronize()
+        layer.forward(Xd, Y)
+        layer.backward(Xd, dYd, dX)      # dY is the gradient at the pre-activation, as the layer's backward takes it
+        layer.sync()
+        Wb, G = layer.gathered()
+        bb, gb = layer.gathered_bias()
+        assert torch.equal(Wb, dev(inp["W"], td)) and torch.equal(bb, dev(b, td))
+        if preact is not None:
+            assert relerr(host(preact), Z) <= tol
+        for key, got in (("Y", Y), ("dX", dX), ("dW", G), ("gb", gb)):
+            assert torch.isfinite(got.float()).all(), key
+            assert relerr(host(got), ref[key]) <= tol, (key, relerr(host(got), ref[key]))
+        layer.close()
+
+
 def test_degenerate_partitions():
     # n = 1 is the plain linear; one token; n equal to the number of 8-wide column groups
     for (T, I, O, n) in ((40, 64, 72, 1), (1, 64, 64, 2), (33, 16, 64, 8)):

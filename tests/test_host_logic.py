@@ -198,6 +198,10 @@ def test_create_rejects_bad_descriptions():
     assert lin_status(O=4096) == B.RTP_ERR_SHAPE               # shard larger than the slot
     assert lin_status(w_offset=8) == B.RTP_ERR_SHAPE
     assert lin_status(split=5) == B.RTP_ERR_INVALID
+    assert lin_status(has_bias=True) == B.RTP_OK
+    assert lin_status(has_bias=True, split=B.RTP_SPLIT_IN) == B.RTP_ERR_UNSUPPORTED   # bias: output-partitioned only
+    assert lin_status(O=512) == B.RTP_OK                                               # 128 x 64 rows fill the slot exactly
+    assert lin_status(has_bias=True, O=512) == B.RTP_ERR_SHAPE                         # ... so the bias entries do not fit
     assert lin_status(dtype=B.RTP_F32, O=12, I=3) == B.RTP_OK  # fp32 has no alignment rule
     ring.close()
     assert B.lib.rtp_status_str(B.RTP_ERR_STATE) == b"RTP_ERR_STATE"
