@@ -29,9 +29,17 @@ def build(force: bool = True, verbose: bool = False) -> str:
         o = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
         if force or not _newer(o, [s] + headers):
             cmd = [HIPCC] + FLAGS + ["-c", s, "-o", o]
+            tiled = src.startswith("rtp_gemm_pp_")
+            if tiled:
+                cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
             if verbose:
                 print(" ".join(cmd), flush=True)
-            subprocess.run(cmd, check=True)
+            res = subprocess.run(cmd, check=True, stderr=subprocess.PIPE, text=True)
+            if tiled:
+                # the tiled GEMM must keep its accumulators in registers: a build that spills is a broken build
+                spills = [ln for ln in res.stderr.splitlines() if "ScratchSize" in ln and not ln.rstrip().endswith(": 0 [-Rpass-analysis=kernel-resource-usage]")]
+                if spills:
+                    raise RuntimeError(f"{src}: the tiled GEMM kernel spills registers to scratch memory:\n" + "\n".join(spills))
         return o
 
     with ThreadPoolExecutor(max_workers=8) as ex:

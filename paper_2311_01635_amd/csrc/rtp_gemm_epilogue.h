@@ -60,6 +60,34 @@ __device__ __forceinline__ float silu_grad(float x)
 template <typename E> __device__ __forceinline__ float bf2f(E v) { return (float)v; }
 
 
+// The bias joins the product before a store or a forward activation sees it.  A lane's accumulators of
+// fragment column j all belong to one output column (col0 + j * NSTRIDE), so it needs one value per j
+// (zero when there is no bias or the epilogue takes none), added where the accumulators are read;
+// for the gated form fragment j < FN/2 is a gate column and fragment j + FN/2 the up column with the
+// same index, whose bias entries sit `half` further on.
+template <typename E, int FN, int NSTRIDE>
+__device__ __forceinline__ void gemm_epilogue_bias(const GemmArgs &p, int col0, float (&bj)[FN])
+{
+    const E *bias = (const E *)p.bias;
+    const bool gated = p.epi == EPI_SWIGLU_FWD;
+    const bool on = bias && (gated || p.epi == EPI_STORE || p.epi == EPI_GELU_ERF_FWD || p.epi == EPI_GELU_TANH_FWD);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+        int idx;
+        bool lim;
+        if (gated) {
+            const int col = col0 + (j % (FN / 2)) * NSTRIDE;
+            lim = col < p.half;
+            idx = col + (j >= FN / 2 ? p.half : 0);
+        } else {
+            idx = col0 + j * NSTRIDE;
+            lim = idx < p.N;
+        }
+        bj[j] = 0.0f;
+        if (on && lim) bj[j] = (float)bias[idx];
+    }
+}
+
 // Writes a wave's FM x FN grid of 32x32 accumulator fragments.
 // acc[i][j][v] is C[row, col] with
 //   row = rbase + i*32 + 8*(v/4) + v%4        (rbase already holds 4*(lane/32))
@@ -77,7 +105,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, f32x16 (&acc)[F
     E *auxw = (E *)p.aux;
     const int64_t ldc = p.ldc, ldws = p.ldws, ldaux = p.ldaux;
     float *ws = p.ws;
-    const E *bias = (const E *)p.bias;
+    float bj[FN];
+    gemm_epilogue_bias<E, FN, NSTRIDE>(p, n0 + cl, bj);
 
     if (p.epi == EPI_SWIGLU_FWD) {
         const int half = p.half;
@@ -91,11 +120,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, f32x16 (&acc)[F
                 for (int v = 0; v < 16; ++v) {
                     const int row = rbase + i * 32 + 8 * (v >> 2) + (v & 3);
                     if (row >= M) continue;
-                    float a = acc[i][j][v], b = acc[i][j + FN / 2][v];
-                    if (bias) {
-                        a += (float)bias[col];
-                        b += (float)bias[half + col];
-                    }
+                    const float a = acc[i][j][v] + bj[j], b = acc[i][j + FN / 2][v] + bj[j + FN / 2];
                     auxw[(int64_t)row * ldaux + col] = (E)a;
                     auxw[(int64_t)row * ldaux + half + col] = (E)b;
                     Cb[(int64_t)row * ldc + col] = (E)(silu(a) * b);
@@ -116,22 +141,10 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, f32x16 (&acc)[F
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int row = rbase + i * 32 + 8 * (v >> 2) + (v & 3);
-                    if (row < M) fn(row, col, acc[i][j][v]);
+                    if (row < M) fn(row, col, acc[i][j][v] + bj[j]);
                 }
             }
     };
-    // the bias joins the product before a store or a forward activation sees it
-    if (bias && (p.epi == EPI_STORE || p.epi == EPI_GELU_ERF_FWD || p.epi == EPI_GELU_TANH_FWD)) {
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            const int col = n0 + j * NSTRIDE + cl;
-            const float bj = col < N ? (float)bias[col] : 0.0f;
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] += bj;
-        }
-    }
     switch (p.epi) {
     case EPI_STORE:
         if (p.c_is_f32)
@@ -237,7 +250,6 @@ __host__ __device__ inline bool gemm_epilogue_vec_ok(const GemmArgs &p)
     bool ok = (p.ldc & 3) == 0 && al(p.C, 16);
     if (p.epi == EPI_ACC_FIRST || p.epi == EPI_ACC_ADD || p.epi == EPI_ACC_LAST || p.epi == EPI_ACC_ATOMIC) ok = ok && (p.ldws & 3) == 0 && al(p.ws, 16);
     if (p.epi >= EPI_GELU_ERF_FWD && p.epi <= EPI_SWIGLU_BWD) ok = ok && (p.ldaux & 3) == 0 && al(p.aux, 8) && (p.half & 3) == 0;
-    if (p.bias) ok = ok && al(p.bias, 8) && (p.epi != EPI_SWIGLU_FWD || (p.half & 3) == 0);
     return ok && (p.N & 3) == 0;
 }
 
@@ -254,8 +266,9 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
     float *Cf = (float *)p.C;
     E *aux = (E *)p.aux;
     float *ws = p.ws;
-    const E *bias = (const E *)p.bias;
     const int wrow = 4 * (lane >> 5), wcol = lane & 31;
+    float bj[FN];
+    gemm_epilogue_bias<E, FN, NSTRIDE>(p, n0 + wn32 + wcol, bj);
 
     // park fragment row i: rows 8*(v/4) + 4*(lane/32) + v%4, columns j*32 + lane%32
     auto park = [&](int i) {
@@ -263,7 +276,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
         for (int j = 0; j < FN; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v)
-                wlds[(8 * (v >> 2) + wrow + (v & 3)) * EPI_LDS_PITCH + j * 32 + wcol] = acc[i][j][v];
+                wlds[(8 * (v >> 2) + wrow + (v & 3)) * EPI_LDS_PITCH + j * 32 + wcol] = acc[i][j][v] + bj[j];
         __builtin_amdgcn_s_waitcnt(0xc07f); // lgkmcnt(0): the wave's own writes have landed
         __builtin_amdgcn_wave_barrier();
     };
@@ -276,14 +289,10 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int row = 8 * r + (lane >> 3), c = (lane & 7) * 4;
-                f32x4 a = *(const f32x4 *)(wlds + row * EPI_LDS_PITCH + c);
-                f32x4 b = *(const f32x4 *)(wlds + row * EPI_LDS_PITCH + 32 + c);
+                const f32x4 a = *(const f32x4 *)(wlds + row * EPI_LDS_PITCH + c);
+                const f32x4 b = *(const f32x4 *)(wlds + row * EPI_LDS_PITCH + 32 + c);
                 const int grow = rbase_wave + i * 32 + row, col = n0 + wn32 + c;
                 if (grow < M && col < half) {
-                    if (bias) {
-                        a = a + from_elem4<E>(*(const out4 *)(bias + col));
-                        b = b + from_elem4<E>(*(const out4 *)(bias + half + col));
-                    }
                     *(out4 *)(aux + (int64_t)grow * ldaux + col) = to_elem4<E>(a);
                     *(out4 *)(aux + (int64_t)grow * ldaux + half + col) = to_elem4<E>(b);
                     f32x4 h;
@@ -296,8 +305,6 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
         return;
     }
 
-    // the bias joins the product before a store or a forward activation sees it
-    const bool with_bias = bias && (p.epi == EPI_STORE || p.epi == EPI_GELU_ERF_FWD || p.epi == EPI_GELU_TANH_FWD);
     // every valid group of 4 consecutive columns; the branch on the kind stays outside the loops
     auto each = [&](auto op) {
 #pragma unroll
@@ -306,13 +313,10 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
                 const int row = 4 * r + (lane >> 4), c4 = lane & 15;
-                f32x4 x = *(const f32x4 *)(wlds + row * EPI_LDS_PITCH + c4 * 4);
+                const f32x4 x = *(const f32x4 *)(wlds + row * EPI_LDS_PITCH + c4 * 4);
                 const int grow = rbase_wave + i * 32 + row;
                 const int col = n0 + (c4 >> 3) * NSTRIDE + wn32 + (c4 & 7) * 4;
-                if (grow < M && col < N) {
-                    if (with_bias) x = x + from_elem4<E>(*(const out4 *)(bias + col));
-                    op(grow, col, x);
-                }
+                if (grow < M && col < N) op(grow, col, x);
             }
             __builtin_amdgcn_wave_barrier();
         }
