@@ -149,7 +149,10 @@ rtp_status rtp_ring_destroy(rtp_ring *ring);
  * buffer (weights) -- the worker's own shard.  RTP_PASS_BWD: must follow a
  * completed forward pass (the worker holds shard (rank+1) mod n) or, with
  * n == 1 or after rtp_ring_seek(), any idle state; loads that shard's
- * gradient part.  RTP_ERR_STATE if a pass is in progress. */
+ * gradient part, after writing the gradient shard an earlier backward pass
+ * left in the buffer (the worker's own) back to its slot: gradients
+ * accumulate over any number of passes.  RTP_ERR_STATE if a pass is in
+ * progress. */
 rtp_status rtp_ring_begin(rtp_ring *ring, rtp_pass pass);
 
 /* Makes shard (rank+1) mod n resident without a forward pass (tests and

@@ -370,6 +370,12 @@ extern "C" rtp_status rtp_ring_begin(rtp_ring *r, rtp_pass pass)
     } else {
         // gradient shards come into being where the weights ended the forward pass
         r->base_idx = r->res_idx;
+        if (r->d.g_bytes && r->res_g >= 0) {
+            // the gradient shard the previous backward pass ended on (the worker's own) is still in the
+            // buffer: it goes back to its slot before the buffer takes the shard this pass starts with
+            RTP_TRY(copy_async(r, r->home_g(r->res_g), r->d.buf_g_dev[r->res_g_idx], r->d.g_bytes, r->cs()));
+            r->rec(TR_G_OUT, -1, r->res_g, r->res_g_idx);
+        }
         r->res_g_idx = 0;
         r->res_g = r->resident;
         if (r->d.g_bytes) {

@@ -356,6 +356,31 @@ def test_linear_with_bias(dtype, act, mode):
         layer.close()
 
 
+@pytest.mark.parametrize("n", [1, 8])
+@pytest.mark.parametrize("mode", [B.RTP_DOUBLE_BUFFER, B.RTP_INPLACE_STAGED, B.RTP_INPLACE_BLOCKING])
+def test_gradients_accumulate_over_passes(mode, n):
+    """Two forward + backward passes without reading the store in between: every gradient shard, the
+    one the worker ends a pass on included, holds arriving content + twice the pass's contribution
+    (integer inputs: bit-exact), and the weights are unchanged."""
+    T, I, O = 512, 1024, 2048
+    g = torch.Generator(device="cpu").manual_seed(4)
+    ri = lambda lo, hi, shape: torch.randint(lo, hi, shape, generator=g).float()
+    W, X, dY, G0 = ri(-2, 3, (O, I)), ri(-2, 3, (T, I)), ri(-2, 3, (T, O)), ri(-4, 5, (O, I))
+    layer = RtpLinear(W.to(DEV, torch.bfloat16), T, n, n // 2, B.RTP_SPLIT_OUT, mode, B.RTP_BF16, G0=G0.to(DEV))
+    Xd, dYd = X.to(DEV, torch.bfloat16), dY.to(DEV, torch.bfloat16)
+    Y = torch.empty(T, O, device=DEV, dtype=torch.bfloat16)
+    dX = torch.empty(T, I, device=DEV, dtype=torch.bfloat16)
+    for _ in range(2):
+        layer.forward(Xd, Y)
+        layer.backward(Xd, dYd, dX)
+    layer.sync()
+    Wb, G = layer.gathered()
+    assert torch.equal(Wb.cpu().float(), W)
+    assert torch.equal(G.cpu(), G0 + 2 * (dY.double().T @ X.double()).float())
+    assert torch.equal(Y.cpu(), (X.double() @ W.double().T).to(torch.bfloat16))
+    layer.close()
+
+
 def test_degenerate_partitions():
     # n = 1 is the plain linear; one token; n equal to the number of 8-wide column groups
     for (T, I, O, n) in ((40, 64, 72, 1), (1, 64, 64, 2), (33, 16, 64, 8)):
