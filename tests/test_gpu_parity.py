@@ -522,6 +522,33 @@ def test_mlp_grouped_and_stepwise_agree_bitwise_on_integers():
             assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("schedule", ["default", "grouped_one_stream", "stepwise"])
+def test_mlp_gradients_accumulate_over_passes(schedule):
+    """Two passes of the unit without reading the store in between add the pass's weight gradients twice
+    onto what arrived (all shards, the one the worker ends on included)."""
+    stepwise, aux = schedule.startswith("stepwise"), not schedule.endswith("one_stream")
+    w = wl.Workload("mlp_twice", "swiglu", T=288, I=160, O=4 * 128, O2=96, n=4, dtype="bf16", mode="x", w_dist=("normal", 0.08))
+    inp = wl.make_inputs(w, seed=12, grad0=True)
+    names = ("Wg", "Wu", "Wd")
+    res = []
+    for passes in (1, 2):
+        mlp = RtpMlp([dev(inp[k], torch.bfloat16) for k in names], w.T, w.n, 1, B.RTP_ACT_SWIGLU, B.RTP_INPLACE_STAGED,
+                     B.RTP_BF16, G0=[dev(inp["G0_" + k], torch.float32) for k in names], stepwise=stepwise, aux_stream=aux)
+        X, dY = dev(inp["X"], torch.bfloat16), dev(inp["dY"], torch.bfloat16)
+        Y = torch.empty(w.T, w.O2, device=DEV, dtype=torch.bfloat16)
+        dX = torch.empty(w.T, w.I, device=DEV, dtype=torch.bfloat16)
+        for _ in range(passes):
+            mlp.forward(X, Y)
+            mlp.backward(X, dY, dX)
+        mlp.sync()
+        _, Gs = mlp.gathered()
+        res.append([host(g) for g in Gs])
+        mlp.close()
+    for k, g1, g2 in zip(names, *res):
+        g0 = f64(inp["G0_" + k])
+        assert relerr(g2 - g0, 2.0 * (g1 - g0)) <= 1e-5, (k, relerr(g2 - g0, 2.0 * (g1 - g0)))
+
+
 def test_mlp_gelu_tanh_variant():
     w = wl.Workload("mlp_tanh", "mlp_gelu", T=64, I=64, O=128, O2=64, n=2, dtype="bf16", mode="x",
                     w_dist=("normal", 0.1), extra={"act": B.RTP_ACT_GELU_TANH})
