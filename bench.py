@@ -166,6 +166,15 @@ def main():
                 "per_kernel": {k: {"launches_per_step": v[0] / a.steps, "avg_us": v[1] * 1e3 / max(v[0], 1),
                                    "tflops": v[2] / max(v[1], 1e-9) / 1e9} for k, v in prof.items()}}
 
+    # the same launches, each with the device to itself (drained before and after): what the kernel does when no
+    # other GEMM and no staging copy shares the compute units and HBM with it
+    k_alone = max(2, min(a.steps, 5))
+    B.rtp_prof_begin(alone=True)
+    timed(torch, mlp, X, Y, dY, dX, k_alone)
+    prof_alone = B.rtp_prof_end()
+    roofline["alone"] = {k: {"avg_us": v[1] * 1e3 / max(v[0], 1), "tflops": v[2] / max(v[1], 1e-9) / 1e9,
+                             "frac": v[2] / max(v[1], 1e-9) / 1e9 / PEAK_BF16_TFLOPS} for k, v in prof_alone.items()}
+
     # ---- how much of the shard staging hides under compute -------------------------
     overlap = None
     if not a.no_overlap and w.n > 1:

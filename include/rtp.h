@@ -339,6 +339,10 @@ const char *rtp_gemm_kernel_name(int layout, int variant);
  * not thread-safe; meant for benchmarks. */
 typedef struct { int64_t launches; double total_ms; double total_flops; } rtp_prof_result;
 rtp_status rtp_prof_begin(void);
+/* The same with alone != 0: the host drains the device before and after every
+ * timed launch, so each duration is that of the kernel running by itself (no
+ * other GEMM, no staging copy beside it).  Slow; for reports only. */
+rtp_status rtp_prof_begin_alone(int alone);
 rtp_status rtp_prof_end(rtp_prof_result out[3]);
 
 /* ---- sustained shader clock ------------------------------------------------ */

@@ -76,6 +76,7 @@ SYMBOLS = {
     "rtp_worker_bytes": (C.c_size_t, [C.c_int, C.c_size_t, C.c_size_t]),
     "rtp_table1_worker_bytes": (C.c_size_t, [C.c_int, C.c_size_t, C.c_size_t]),
     "rtp_status_str": (C.c_char_p, [C.c_int]),
+    "rtp_prof_begin_alone": (C.c_int, [C.c_int]),
     "rtp_clock_probe": (C.c_int, [_P, _P, C.c_int64, C.POINTER(C.c_int)]),
     "rtp_last_error": (C.c_char_p, []),
     "rtp_ring_create": (C.c_int, [C.POINTER(_P), C.POINTER(rtp_ring_desc)]),
@@ -266,8 +267,8 @@ def rtp_gemm_kernel_name(layout, variant):
     return lib.rtp_gemm_kernel_name(layout, variant).decode()
 
 
-def rtp_prof_begin():
-    check(lib.rtp_prof_begin(), "rtp_prof_begin")
+def rtp_prof_begin(alone=False):
+    check(lib.rtp_prof_begin_alone(int(alone)), "rtp_prof_begin")
 
 
 def rtp_prof_end():

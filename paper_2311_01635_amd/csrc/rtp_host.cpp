@@ -66,16 +66,19 @@ struct ProfRec {
     double flops;
     hipEvent_t start, stop;
 };
-static bool g_prof_on = false;
+static bool g_prof_on = false, g_prof_alone = false;
 static std::vector<ProfRec> g_prof;
 
-extern "C" rtp_status rtp_prof_begin(void)
+extern "C" rtp_status rtp_prof_begin_alone(int alone)
 {
     if (g_prof_on) return fail(RTP_ERR_STATE, "rtp_prof_begin: already collecting");
     g_prof.clear();
     g_prof_on = true;
+    g_prof_alone = alone != 0;
     return RTP_OK;
 }
+
+extern "C" rtp_status rtp_prof_begin(void) { return rtp_prof_begin_alone(0); }
 
 extern "C" rtp_status rtp_prof_end(rtp_prof_result out[3])
 {
@@ -110,12 +113,16 @@ static hipError_t timed_launch(int layout, double flops, hipStream_t s, F launch
     if (e != hipSuccess) return e;
     e = hipEventCreate(&r.stop);
     if (e != hipSuccess) return e;
+    // "alone": the device is idle when the launch starts and nothing else is enqueued until it has
+    // ended, so its duration is that of the kernel with the machine to itself
+    if (g_prof_alone && (e = hipDeviceSynchronize()) != hipSuccess) return e;
     e = hipEventRecord(r.start, s);
     if (e != hipSuccess) return e;
     e = launch();
     if (e != hipSuccess) return e;
     e = hipEventRecord(r.stop, s);
     if (e != hipSuccess) return e;
+    if (g_prof_alone && (e = hipDeviceSynchronize()) != hipSuccess) return e;
     g_prof.push_back(r);
     return hipSuccess;
 }
