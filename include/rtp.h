@@ -177,8 +177,18 @@ rtp_status rtp_rotate_step(rtp_ring *ring, int direction, int step);
 rtp_status rtp_ring_end(rtp_ring *ring);
 
 /* Copies the resident (W, G) to their home slot so that a reader of the home
- * store sees every shard (tests, checkpoints).  Idle state only. */
+ * store sees every shard (tests, checkpoints, an optimizer).  Idle state only.
+ * Between a backward pass and the flush the home slot of the worker's own
+ * gradient shard is stale: write to the gradient store only after a flush (or
+ * through rtp_ring_zero_grads), else the next backward pass writes the
+ * worker's copy back over it. */
 rtp_status rtp_ring_flush(rtp_ring *ring);
+
+/* Clears every gradient slot of the home store (a fill kernel on the compute
+ * stream, ordered after everything enqueued so far) and drops the gradient
+ * shard the worker still holds, so that the next backward pass accumulates
+ * from zero.  Idle state only. */
+rtp_status rtp_ring_zero_grads(rtp_ring *ring);
 
 /* Joins both streams; returns RTP_ERR_HIP if anything asynchronous failed. */
 rtp_status rtp_ring_sync(rtp_ring *ring);

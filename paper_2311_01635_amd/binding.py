@@ -86,6 +86,7 @@ SYMBOLS = {
     "rtp_rotate_step": (C.c_int, [_P, C.c_int, C.c_int]),
     "rtp_ring_end": (C.c_int, [_P]),
     "rtp_ring_flush": (C.c_int, [_P]),
+    "rtp_ring_zero_grads": (C.c_int, [_P]),
     "rtp_ring_sync": (C.c_int, [_P]),
     "rtp_ring_resident": (C.c_int, [_P]),
     "rtp_ring_trace": (C.c_int64, [_P, C.POINTER(rtp_trace_rec), C.c_int64, C.c_int]),
@@ -209,6 +210,9 @@ class Ring:
 
     def flush(self):
         check(lib.rtp_ring_flush(self.handle), "rtp_ring_flush")
+
+    def zero_grads(self):
+        check(lib.rtp_ring_zero_grads(self.handle), "rtp_ring_zero_grads")
 
     def sync(self):
         check(lib.rtp_ring_sync(self.handle), "rtp_ring_sync")

@@ -556,7 +556,19 @@ extern "C" rtp_status rtp_ring_flush(rtp_ring *r)
     if (r->d.g_bytes && r->res_g >= 0) {
         RTP_TRY(copy_async(r, r->home_g(r->res_g), r->d.buf_g_dev[r->res_g_idx], r->d.g_bytes, r->cs()));
         r->rec(TR_G_OUT, -1, r->res_g, r->res_g_idx);
+        r->res_g = -1; // the slot is current: the next backward pass has nothing to write back
     }
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_ring_zero_grads(rtp_ring *r)
+{
+    if (!r) return fail(RTP_ERR_INVALID, "rtp_ring_zero_grads: null ring");
+    if (r->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_ring_zero_grads: a pass is open");
+    RTP_TRY(ensure_events(r));
+    RTP_TRY(cross_join(r));
+    if (!r->dry && r->d.g_bytes) HIP_TRY(launch_fill_zero(r->d.home_g_dev, (size_t)r->d.n * r->d.g_bytes, r->cs()));
+    r->res_g = -1; // the copy in the worker's buffer is dropped with the rest
     return RTP_OK;
 }
 

@@ -127,6 +127,9 @@ class RtpLinear:
     def sync(self):
         self.ring.sync()
 
+    def zero_grads(self):
+        self.ring.zero_grads()
+
     def gathered(self):
         """(W, G) as full matrices, read back from the home store."""
         self.ring.flush()
@@ -215,7 +218,7 @@ class RtpMlp:
         B.check(B.lib.rtp_mlp_sync(self.handle), "rtp_mlp_sync")
 
     def zero_grads(self):
-        self.home_g.zero_()
+        B.check(B.lib.rtp_ring_zero_grads(B.lib.rtp_mlp_ring(self.handle)), "rtp_ring_zero_grads")
 
     def worker_bytes(self):
         return B.rtp_worker_bytes(self.mode, self.w_bytes, self.g_bytes)

@@ -381,6 +381,37 @@ def test_gradients_accumulate_over_passes(mode, n):
     layer.close()
 
 
+@pytest.mark.parametrize("how", ["zero_grads", "flush_then_clear"])
+@pytest.mark.parametrize("mode", [B.RTP_DOUBLE_BUFFER, B.RTP_INPLACE_STAGED, B.RTP_INPLACE_BLOCKING])
+def test_cleared_gradients_start_from_zero(mode, how):
+    """An optimizer step between passes: after the store is cleared (by the library's call, or by the
+    caller after a flush) the next pass's gradients hold that pass alone: the copy of its own
+    shard the worker kept from the previous pass does not come back (integer inputs: bit-exact)."""
+    T, I, O, n = 256, 512, 1024, 4
+    g = torch.Generator(device="cpu").manual_seed(5)
+    ri = lambda lo, hi, shape: torch.randint(lo, hi, shape, generator=g).float()
+    W, X, dY, G0 = ri(-2, 3, (O, I)), ri(-2, 3, (T, I)), ri(-2, 3, (T, O)), ri(-4, 5, (O, I))
+    layer = RtpLinear(W.to(DEV, torch.bfloat16), T, n, 1, B.RTP_SPLIT_OUT, mode, B.RTP_BF16, G0=G0.to(DEV))
+    Xd, dYd = X.to(DEV, torch.bfloat16), dY.to(DEV, torch.bfloat16)
+    Y = torch.empty(T, O, device=DEV, dtype=torch.bfloat16)
+    dX = torch.empty(T, I, device=DEV, dtype=torch.bfloat16)
+    layer.forward(Xd, Y)
+    layer.backward(Xd, dYd, dX)
+    if how == "zero_grads":
+        layer.zero_grads()
+    else:
+        layer.ring.flush()
+        layer.sync()
+        layer.home_g.zero_()
+        torch.cuda.synchronize()
+    layer.forward(Xd, Y)
+    layer.backward(Xd, (2 * dY).to(DEV, torch.bfloat16), dX)
+    layer.sync()
+    _, G = layer.gathered()
+    assert torch.equal(G.cpu(), 2 * (dY.double().T @ X.double()).float())
+    layer.close()
+
+
 def test_degenerate_partitions():
     # n = 1 is the plain linear; one token; n equal to the number of 8-wide column groups
     for (T, I, O, n) in ((40, 64, 72, 1), (1, 64, 64, 2), (33, 16, 64, 8)):

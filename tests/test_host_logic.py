@@ -119,6 +119,45 @@ def test_dry_run_trace_matches_oracle_schedule(n, mode):
                     assert b != comp[(p, s)] and b == comp[(p, s + 1)]
 
 
+@pytest.mark.parametrize("between", ["nothing", "flush", "zero_grads"])
+def test_gradient_shard_left_in_the_buffer_goes_home_once(between):
+    """A second backward pass first sends the worker's own gradient shard, still in its buffer from
+    the first pass, to its slot; not when a flush already did, nor after the gradients were cleared."""
+    n, rank = 4, 2
+    ring = _dry_ring(n, rank, B.RTP_INPLACE_STAGED, w=16 * 8 * n * 4, g=16 * 8 * n * 4)
+    lin = B.Linear(ring, 4, 8, 8 * n, B.RTP_SPLIT_OUT, B.RTP_F32)
+
+    def one_pass():
+        ring.begin(B.RTP_PASS_FWD)
+        for t in range(n):
+            if t < n - 1:
+                ring.rotate_step(B.RTP_CW, t)
+            lin.fwd(t, None, None)
+        ring.end()
+        ring.begin(B.RTP_PASS_BWD)
+        for s in range(n):
+            if s < n - 1:
+                ring.rotate_step(B.RTP_CCW, s)
+            lin.bwd(s, None, None, None)
+        ring.end()
+
+    one_pass()
+    assert [r for r in ring.trace(clear=True) if r[0] == "g_out" and r[2] < 0] == [], "first pass: nothing to write back"
+    if between == "flush":
+        ring.flush()
+        assert [r[3] for r in ring.trace(clear=True) if r[0] == "g_out"] == [rank]
+    elif between == "zero_grads":
+        ring.zero_grads()
+    one_pass()
+    early = [r[3] for r in ring.trace(clear=True) if r[0] == "g_out" and r[2] < 0]
+    assert early == ([rank] if between == "nothing" else [])
+    lin.close()
+    ring.begin(B.RTP_PASS_FWD)
+    with pytest.raises(B.RtpError):
+        ring.zero_grads()
+    ring.close()
+
+
 def test_state_machine_rejects_out_of_sequence_calls():
     n = 4
     ring = _dry_ring(n, 1, B.RTP_DOUBLE_BUFFER, w=16 * 32, g=16 * 32)
