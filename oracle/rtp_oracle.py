@@ -489,6 +489,145 @@ def rtp_swiglu(X, Wg, Wu, Wd, dY, n, rank, Gg0=None, Gu0=None, Gd0=None):
 
 
 # --------------------------------------------------------------------------
+# expert partition (Partition Strategies section, last item; RTP Transformers
+# section, MoE block item)
+# --------------------------------------------------------------------------
+# Worker r starts with expert r; the experts rotate like any other shard, and
+# at each step the worker runs the expert it holds on those of its own tokens
+# that are routed to it; the outputs of the N steps, put back in token order
+# ("concatenation"), are the layer's output.  No token leaves the worker.
+# The paper defines no router: the routing (one expert per token) is an input.
+
+def moe_dispatch(route, n, align=1):
+    """Groups token indices by expert, token order kept inside a group
+    (a stable grouping), each group starting at a multiple of `align` rows.
+    Returns (counts[n], begin[n+1], perm) with perm[p] = the token held by
+    grouped row p, or -1 for a padding row; begin[n] = len(perm)."""
+    route = [int(e) for e in route]
+    counts = [0] * n
+    for e in route:
+        assert 0 <= e < n, "route holds expert ids"
+        counts[e] += 1
+    begin = [0]
+    for e in range(n):
+        begin.append(begin[-1] + (counts[e] + align - 1) // align * align)
+    perm = [-1] * begin[n]
+    fill = list(begin[:n])
+    for t, e in enumerate(route):
+        perm[fill[e]] = t
+        fill[e] += 1
+    return counts, begin, perm
+
+
+def _expert_fwd(X, W, kind, gated):
+    """One expert on the rows of X: returns (pre-activations, hidden, output)."""
+    if gated:
+        Wg, Wu, Wd = W
+        A, Bm = plain_linear_fwd(X, Wg), plain_linear_fwd(X, Wu)
+        H = act(A, SILU) * Bm
+        return (A, Bm), H, plain_linear_fwd(H, Wd)
+    W1, W2 = W
+    Z = plain_linear_fwd(X, W1)
+    H = act(Z, kind)
+    return (Z,), H, plain_linear_fwd(H, W2)
+
+
+def _expert_bwd(X, W, pre, H, dY, G, kind, gated):
+    """Chain rule through one expert: adds the weight gradients onto the
+    arrays of G and returns the gradient of the expert's input rows."""
+    Tm, I = X.shape
+    if gated:
+        Wg, Wu, Wd = W
+        A, Bm = pre
+        gemm_tn(dY, H, G[2], accumulate=True)
+        dH = gemm_nn(dY, Wd, np.empty_like(H))
+        dA = dH * Bm * act_grad(A, SILU)
+        dB = dH * act(A, SILU)
+        gemm_tn(dA, X, G[0], accumulate=True)
+        gemm_tn(dB, X, G[1], accumulate=True)
+        dX = gemm_nn(dA, Wg, np.empty((Tm, I)))
+        return gemm_nn(dB, Wu, dX, accumulate=True)
+    W1, W2 = W
+    (Z,) = pre
+    gemm_tn(dY, H, G[1], accumulate=True)
+    dH = gemm_nn(dY, W2, np.empty_like(H))
+    dZ = dH * act_grad(Z, kind)
+    gemm_tn(dZ, X, G[0], accumulate=True)
+    return gemm_nn(dZ, W1, np.empty((Tm, I)))
+
+
+def plain_moe(X, route, experts, dY, kind=GELU_ERF, G0=None):
+    """The definition, token by token: token t goes through expert route[t]
+    and nothing else.  `experts[e]` is (W1, W2) or (Wg, Wu, Wd); G0 the
+    gradients to accumulate onto (same structure).  Returns Y, dX and the
+    per-expert weight gradients."""
+    T, I = X.shape
+    gated = len(experts[0]) == 3
+    O2 = experts[0][-1].shape[0]
+    G = [[np.zeros_like(w) for w in ex] for ex in experts] if G0 is None else [[g.copy() for g in ex] for ex in G0]
+    Y = np.full((T, O2), np.nan)
+    dX = np.full((T, I), np.nan)
+    for t in range(T):
+        e = int(route[t])
+        x = np.ascontiguousarray(X[t:t + 1])
+        pre, H, y = _expert_fwd(x, experts[e], kind, gated)
+        Y[t] = y[0]
+        dX[t] = _expert_bwd(x, experts[e], pre, H, np.ascontiguousarray(dY[t:t + 1]), G[e], kind, gated)[0]
+    return dict(Y=Y, dX=dX, G=G)
+
+
+def rtp_moe(X, route, experts, dY, n, rank, kind=GELU_ERF, G0=None):
+    """Expert rotation on one worker: N steps forward (clockwise), N steps
+    backward (counter-clockwise, each expert's gradients travelling with it).
+    The shard of the ring is one whole expert."""
+    T, I = X.shape
+    assert len(experts) == n
+    gated = len(experts[0]) == 3
+    O2 = experts[0][-1].shape[0]
+    G0 = [[np.zeros_like(w) for w in ex] for ex in experts] if G0 is None else G0
+    nm = len(experts[0])
+    rings = [_Ring([experts[e][j] for e in range(n)], [G0[e][j] for e in range(n)], rank) for j in range(nm)]
+    counts, begin, perm = moe_dispatch(route, n)
+    Y = np.full((T, O2), np.nan)
+    saved = {}
+    fwd_log, bwd_log = [], []
+    for t in range(n):
+        e = rings[0].res_id
+        assert e == fwd_shard(rank, t, n)
+        rows = perm[begin[e]:begin[e + 1]]
+        fwd_log.append((t, e, len(rows)))
+        if rows:                                   # an expert without tokens only passes through
+            Xe = np.ascontiguousarray(X[rows]).reshape(len(rows), I)
+            pre, H, Ye = _expert_fwd(Xe, [r_.res_w for r_ in rings], kind, gated)
+            Y[rows] = Ye
+            saved[e] = (Xe, pre, H)
+        if t < n - 1:
+            for r_ in rings:
+                r_.rotate((e - 1) % n, with_grad=False)
+    dX = np.full((T, I), np.nan)
+    for r_ in rings:
+        r_.begin_backward()
+    for s in range(n):
+        e = rings[0].res_id
+        assert e == bwd_shard(rank, s, n)
+        rows = perm[begin[e]:begin[e + 1]]
+        bwd_log.append((s, e, len(rows)))
+        if rows:
+            Xe, pre, H = saved[e]
+            dYe = np.ascontiguousarray(dY[rows]).reshape(len(rows), O2)
+            dX[rows] = _expert_bwd(Xe, [r_.res_w for r_ in rings], pre, H, dYe, [r_.res_g for r_ in rings], kind,
+                                   gated)
+        if s < n - 1:
+            for r_ in rings:
+                r_.rotate((e + 1) % n, with_grad=True)
+    G = []
+    for e in range(n):
+        G.append([(r_.res_g if r_.res_id == e else r_.home_g[e]).copy() for r_ in rings])
+    return dict(Y=Y, dX=dX, G=G, counts=counts, begin=begin, perm=perm, fwd_log=fwd_log, bwd_log=bwd_log,
+                resident_after_bwd=rings[0].res_id)
+
+
+# --------------------------------------------------------------------------
 # the whole ring of N workers (tiny shapes only)
 # --------------------------------------------------------------------------
 

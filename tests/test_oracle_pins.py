@@ -408,3 +408,128 @@ def test_bias_gradient_by_finite_differences():
     res = orc.rtp_linear_out_bias(X, W, b, dY, 3, 2)
     _fd_check(lambda: float(np.sum(orc.plain_linear_fwd(X, W, b) * dY)), {"X": X, "W": W, "b": b},
               {"X": res["dX"], "W": res["G"], "b": res["gb"]})
+
+
+# ------------------------------------------------------ expert partition --
+
+def _experts(rng, n, I, O, O2, gated, scale=0.5):
+    k = 3 if gated else 2
+    shapes = [(O, I), (O, I), (O2, O)] if gated else [(O, I), (O2, O)]
+    return [tuple(scale * rng.standard_normal(shapes[j]) for j in range(k)) for _ in range(n)]
+
+
+def _numpy_expert(x, ex, gated):
+    """Independent of the oracle's C routines: numpy matmul, scipy erf."""
+    from scipy.special import erf
+    if gated:
+        Wg, Wu, Wd = ex
+        a, b = Wg @ x, Wu @ x
+        return Wd @ (a / (1.0 + np.exp(-a)) * b)
+    W1, W2 = ex
+    z = W1 @ x
+    return W2 @ (0.5 * z * (1.0 + erf(z / np.sqrt(2.0))))
+
+
+@pytest.mark.parametrize("align", [1, 4, 32])
+def test_moe_dispatch_against_a_stable_sort(align):
+    rng = np.random.default_rng(11)
+    for n, T in ((1, 5), (4, 0), (4, 37), (7, 200), (16, 64)):
+        route = rng.integers(0, n, T)
+        if T > 10:
+            route[route == n - 1] = 0                # an expert nobody is routed to
+        counts, begin, perm = orc.moe_dispatch(route, n, align)
+        assert counts == [int((route == e).sum()) for e in range(n)]
+        order = np.argsort(route, kind="stable")     # library routine: tokens by expert, order kept
+        got = [p for p in perm if p >= 0]
+        assert got == list(order)
+        assert len(perm) == begin[n] and all(b % align == 0 for b in begin)
+        for e in range(n):
+            seg = perm[begin[e]:begin[e + 1]]
+            assert len(seg) < counts[e] + align
+            assert all(p >= 0 for p in seg[:counts[e]]) and all(p == -1 for p in seg[counts[e]:])
+            assert all(route[p] == e for p in seg[:counts[e]])
+
+
+@pytest.mark.parametrize("gated", [False, True])
+@pytest.mark.parametrize("n", [1, 2, 5])
+def test_moe_rotated_matches_the_token_by_token_definition(n, gated):
+    """Expert rotation reaches what the definition gives: every token through its own expert, every
+    expert's gradient summed over its tokens onto what arrived, whatever worker does it; the
+    forward output also against plain numpy."""
+    rng = np.random.default_rng(100 + n)
+    T, I, O, O2 = 23, 6, 5, 4
+    X, dY = rng.standard_normal((T, I)), rng.standard_normal((T, O2))
+    ex = _experts(rng, n, I, O, O2, gated)
+    G0 = [tuple(rng.standard_normal(w.shape) for w in e) for e in ex]
+    route = rng.integers(0, n, T)
+    ref = orc.plain_moe(X, route, ex, dY, G0=G0)
+    for t in range(T):
+        np.testing.assert_allclose(ref["Y"][t], _numpy_expert(X[t], ex[route[t]], gated), rtol=1e-12, atol=1e-12)
+    for rank in range(n):
+        out = orc.rtp_moe(X, route, ex, dY, n, rank, G0=G0)
+        np.testing.assert_allclose(out["Y"], ref["Y"], rtol=1e-13, atol=1e-13)
+        np.testing.assert_allclose(out["dX"], ref["dX"], rtol=1e-13, atol=1e-13)
+        for e in range(n):
+            for j in range(len(ex[e])):
+                np.testing.assert_allclose(out["G"][e][j], ref["G"][e][j], rtol=1e-12, atol=1e-12)
+        assert [e for (_, e, _) in out["fwd_log"]] == [orc.fwd_shard(rank, t, n) for t in range(n)]
+        assert [e for (_, e, _) in out["bwd_log"]] == [orc.bwd_shard(rank, s, n) for s in range(n)]
+        assert out["resident_after_bwd"] == rank
+        assert sum(c for (_, _, c) in out["fwd_log"]) == T, "every token is computed exactly once"
+
+
+def test_moe_special_cases():
+    """All tokens on one expert: that expert's plain MLP, the other experts' gradients pass through
+    untouched.  Reordering the tokens reorders the outputs and leaves the weight gradients alone."""
+    rng = np.random.default_rng(7)
+    n, T, I, O, O2 = 4, 17, 5, 6, 3
+    X, dY = rng.standard_normal((T, I)), rng.standard_normal((T, O2))
+    ex = _experts(rng, n, I, O, O2, False)
+    G0 = [tuple(rng.standard_normal(w.shape) for w in e) for e in ex]
+    out = orc.rtp_moe(X, np.full(T, 2), ex, dY, n, 1, G0=G0)
+    ref = orc.plain_mlp(X, ex[2][0], ex[2][1], dY)
+    np.testing.assert_allclose(out["Y"], ref["Y"], rtol=1e-13)
+    np.testing.assert_allclose(out["dX"], ref["dX"], rtol=1e-13)
+    np.testing.assert_allclose(out["G"][2][0], G0[2][0] + ref["dW1"], rtol=1e-12)
+    np.testing.assert_allclose(out["G"][2][1], G0[2][1] + ref["dW2"], rtol=1e-12)
+    for e in (0, 1, 3):
+        for j in range(2):
+            assert np.array_equal(out["G"][e][j], G0[e][j])
+    route = rng.integers(0, n, T)
+    a = orc.rtp_moe(X, route, ex, dY, n, 0)
+    sh = rng.permutation(T)
+    b = orc.rtp_moe(X[sh], route[sh], ex, dY[sh], n, 0)
+    np.testing.assert_allclose(b["Y"], a["Y"][sh], rtol=1e-13)
+    np.testing.assert_allclose(b["dX"], a["dX"][sh], rtol=1e-13)
+    for e in range(n):
+        for j in range(2):
+            np.testing.assert_allclose(b["G"][e][j], a["G"][e][j], rtol=1e-11, atol=1e-12)
+
+
+@pytest.mark.parametrize("gated", [False, True])
+def test_moe_gradients_by_finite_differences(gated):
+    """d/dθ of L = sum(Y * dY), with the forward taken from plain numpy, against the oracle's backward."""
+    rng = np.random.default_rng(21)
+    n, T, I, O, O2 = 3, 9, 4, 5, 3
+    X, dY = rng.standard_normal((T, I)), rng.standard_normal((T, O2))
+    ex = _experts(rng, n, I, O, O2, gated)
+    route = rng.integers(0, n, T)
+    out = orc.rtp_moe(X, route, ex, dY, n, 2)
+
+    def loss(Xv, exv):
+        return sum(float(_numpy_expert(Xv[t], exv[route[t]], gated) @ dY[t]) for t in range(T))
+
+    h = 1e-6
+    for (t, i) in ((0, 0), (4, 3), (8, 1)):
+        Xp, Xm = X.copy(), X.copy()
+        Xp[t, i] += h
+        Xm[t, i] -= h
+        assert abs((loss(Xp, ex) - loss(Xm, ex)) / (2 * h) - out["dX"][t, i]) < 1e-6
+    for e in range(n):
+        for j in range(len(ex[e])):
+            r, c = rng.integers(0, ex[e][j].shape[0]), rng.integers(0, ex[e][j].shape[1])
+            exp_, exm = [list(map(np.copy, x)) for x in ex], [list(map(np.copy, x)) for x in ex]
+            exp_[e][j][r, c] += h
+            exm[e][j][r, c] -= h
+            fd = (loss(X, exp_) - loss(X, exm)) / (2 * h)
+            assert abs(fd - out["G"][e][j][r, c]) < 1e-6, (e, j)
