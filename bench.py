@@ -52,6 +52,70 @@ def build_inputs(w, torch, dev):
     return inp, weights, to(inp["X"]), to(inp["dY"])
 
 
+class MoeUnit:
+    """The expert-partitioned layer behind the same forward / backward calls as the MLP unit."""
+
+    def __init__(self, moe, route):
+        self.moe, self.route, self.compute_stream = moe, route, moe.compute_stream
+        self.w_bytes, self.g_bytes = moe.w_bytes, moe.g_bytes
+
+    def forward(self, X, Y):
+        self.moe.forward(X, self.route, Y)
+
+    def backward(self, X, dY, dX):
+        self.moe.backward(dY, dX)
+
+    def set_ablation(self, rotate=True, compute=True):
+        self.moe.set_ablation(rotate, compute)
+
+    def sync(self):
+        self.moe.sync()
+
+    def worker_bytes(self):
+        return self.moe.worker_bytes()
+
+    def close(self):
+        self.moe.close()
+
+
+def build_moe(w, torch, dev, aux_stream):
+    import numpy as np
+    import rtp_workloads as wl
+    from paper_2311_01635_amd import binding as B
+    from paper_2311_01635_amd.layers import RtpMoe
+    inp = wl.make_moe_inputs(w.T, w.I, w.O, w.O2, w.n, dtype="bf16", gated=True, seed=0, skew=w.extra["skew"],
+                             w_scale=0.02, grad0=False)
+    to = lambda a, t=torch.bfloat16: torch.from_numpy(np.ascontiguousarray(a)).to(dev, t)
+    moe = RtpMoe([tuple(to(m) for m in ex) for ex in inp["experts"]], w.T, 0, B.RTP_ACT_SWIGLU, B.RTP_INPLACE_STAGED,
+                 B.RTP_BF16, aux_stream=aux_stream)
+    return inp, MoeUnit(moe, to(inp["route"], torch.int32)), to(inp["X"]), to(inp["dY"])
+
+
+def cpu_baseline_moe(w, inp, tokens):
+    """The oracle's expert rotation over the first `tokens` tokens (their own routing), all experts."""
+    import numpy as np
+    import oracle as orc
+    f64 = lambda a: np.ascontiguousarray(a, dtype=np.float64)
+    ex = [tuple(f64(m) for m in e) for e in inp["experts"]]
+
+    def run(nt):
+        X, dY = f64(inp["X"][:nt]), f64(inp["dY"][:nt])
+        t0 = time.perf_counter()
+        orc.rtp_moe(X, inp["route"][:nt], ex, dY, w.n, 0)
+        return time.perf_counter() - t0
+
+    if tokens <= 0:
+        t16, t64 = run(16), run(64)
+        per_token = max((t64 - t16) / 48.0, 1e-6)
+        fixed = max(t16 - 16 * per_token, 0.0)
+        tokens = int(min(w.T, max(64, (15.0 - fixed) / per_token))) // 16 * 16
+    dt = run(tokens)
+    flops = 6.0 * tokens * (2 * w.I * w.O + w.O * w.O2)
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"first {tokens} of {w.T} tokens with their routing, all {w.n} experts rotating fwd+bwd, "
+                      f"{dt:.1f} s, fp64 triple loops"}
+
+
 def timed(torch, mlp, X, Y, dY, dX, steps, fwd=True, bwd=True):
     """ms for `steps` fwd+bwd passes, HIP events on the compute stream."""
     s = mlp.compute_stream
@@ -123,11 +187,15 @@ def main():
     from paper_2311_01635_amd.layers import RtpMlp
 
     dev = torch.device("cuda:0")
-    w = wl.CONFIGS[a.workload]
-    inp, weights, X, dY = build_inputs(w, torch, dev)
-    act = B.RTP_ACT_SWIGLU if w.kind == "swiglu" else B.RTP_ACT_GELU_ERF
-    mode = {"double_buffer": B.RTP_DOUBLE_BUFFER, "inplace_staged": B.RTP_INPLACE_STAGED}[w.mode]
-    mlp = RtpMlp(weights, w.T, w.n, 0, act, mode, B.RTP_BF16, stepwise=a.stepwise, aux_stream=not a.no_aux_stream)
+    is_moe = a.workload in wl.MOE_CONFIGS
+    w = wl.MOE_CONFIGS[a.workload] if is_moe else wl.CONFIGS[a.workload]
+    if is_moe:
+        inp, mlp, X, dY = build_moe(w, torch, dev, not a.no_aux_stream)
+    else:
+        inp, weights, X, dY = build_inputs(w, torch, dev)
+        act = B.RTP_ACT_SWIGLU if w.kind == "swiglu" else B.RTP_ACT_GELU_ERF
+        mode = {"double_buffer": B.RTP_DOUBLE_BUFFER, "inplace_staged": B.RTP_INPLACE_STAGED}[w.mode]
+        mlp = RtpMlp(weights, w.T, w.n, 0, act, mode, B.RTP_BF16, stepwise=a.stepwise, aux_stream=not a.no_aux_stream)
     Y = torch.empty(w.T, w.O2, device=dev, dtype=torch.bfloat16)
     dX = torch.empty(w.T, w.I, device=dev, dtype=torch.bfloat16)
     torch.cuda.synchronize()
@@ -193,7 +261,7 @@ def main():
 
     cpu = None
     if not a.no_cpu_baseline:
-        cpu = cpu_baseline(w, inp, a.cpu_tokens)
+        cpu = cpu_baseline_moe(w, inp, a.cpu_tokens) if is_moe else cpu_baseline(w, inp, a.cpu_tokens)
 
     out = {
         "metric": "TFLOP/s rotated-shard linear fwd+bwd per GPU", "value": tflops, "unit": "TFLOP/s",
@@ -201,7 +269,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "T": w.T, "I": w.I, "O": w.O, "O2": w.O2, "n_shards": w.n, "mode": w.mode,
                    "grad_dtype": "f32", "flops_per_step": w.flops,
-                   "schedule": "stepwise" if a.stepwise else "grouped", "aux_stream": not a.no_aux_stream,
+                   "schedule": "expert rotation" if is_moe else "stepwise" if a.stepwise else "grouped",
+                   "aux_stream": not a.no_aux_stream,
                    "worker_param_bytes": mlp.worker_bytes(),
                    "table1_rtp_worker_bytes": B.rtp_table1_worker_bytes(False, mlp.w_bytes, mlp.g_bytes)},
         "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,

@@ -84,6 +84,7 @@ typedef enum { RTP_PASS_IDLE = 0, RTP_PASS_FWD = 1, RTP_PASS_BWD = 2 } rtp_pass;
 typedef struct rtp_ring rtp_ring;
 typedef struct rtp_linear rtp_linear;
 typedef struct rtp_mlp rtp_mlp;
+typedef struct rtp_moe rtp_moe;
 
 /* ---- pure host integer helpers (no GPU needed) ------------------------- */
 
@@ -322,6 +323,75 @@ rtp_status rtp_mlp_set_ablation(rtp_mlp *mlp, int rotate, int compute);
 rtp_status rtp_mlp_flush(rtp_mlp *mlp);
 rtp_status rtp_mlp_sync(rtp_mlp *mlp);
 rtp_ring *rtp_mlp_ring(rtp_mlp *mlp);
+
+/* ---- expert partition: the ring's shard is one whole expert -------------- */
+
+/* Expert partition (Partition Strategies section, last item; MoE block item
+ * of the RTP Transformers section): n experts of one shape, worker `rank`
+ * starts with expert `rank`, the experts rotate like any other shard and at
+ * each step the worker runs the expert it holds on those of its own tokens
+ * that are routed to it; the outputs of the n steps, back in token order, are
+ * the layer's output (no token leaves the worker).  The paper gives no
+ * router: the routing, one expert id per token, is an input.
+ *
+ * Slot e of the ring = [W1_e | W2_e], W1_e [O, I] (for RTP_ACT_SWIGLU
+ * [gate_e ; up_e], 2*O rows), W2_e [O2, O]; gradients fp32 in the same order.
+ * Inputs 16-bit (RTP_BF16: I, O, O2 multiples of 8; RTP_F16: of 32).
+ * Workspace (device, caller-owned, Tp = rtp_moe_padded_rows(T, n) rows):
+ * tokens grouped by expert, each group padded with zero rows to a multiple of
+ * 32 rows. */
+typedef struct {
+    int64_t T, I, O, O2;
+    int n, rank;
+    rtp_mode mode;
+    rtp_dtype dtype;
+    rtp_act act;          /* GELU_* or SWIGLU                                      */
+    unsigned flags;       /* RTP_FLAG_DRY_RUN is not available here                */
+    void *home_w_dev, *home_g_dev;
+    void *buf_w_dev[2], *buf_g_dev[2];
+    void *xp_dev;         /* [Tp, I]    grouped tokens                             */
+    void *preact_dev;     /* [Tp, P*O]  P = 2 for SWIGLU                           */
+    void *hidden_dev;     /* [Tp, O]                                               */
+    void *yp_dev;         /* [Tp, O2]   grouped outputs; grouped dY in backward    */
+    void *dpre_dev;       /* [Tp, P*O]                                             */
+    void *dxp_dev;        /* [Tp, I]                                               */
+    int32_t *perm_dev;    /* [Tp]       token of each grouped row, -1 = padding    */
+    int32_t *counts_dev;  /* [n + 1]    tokens per expert; [n] = ids out of range  */
+    void *compute_stream, *stage_stream;
+    void *aux_stream;     /* optional, as in rtp_ring_desc                         */
+} rtp_moe_desc;
+
+/* Rows of the grouped workspace: 32 * (T / 32 + n), an upper bound of the sum
+ * of the padded group sizes for any routing.  -1 for bad arguments. */
+int64_t rtp_moe_padded_rows(int64_t T, int n);
+size_t rtp_moe_slot_w_bytes(const rtp_moe_desc *d);
+size_t rtp_moe_slot_g_bytes(const rtp_moe_desc *d);
+
+rtp_status rtp_moe_create(rtp_moe **out, const rtp_moe_desc *desc);
+rtp_status rtp_moe_destroy(rtp_moe *moe);
+
+/* Forward: groups the tokens by route_dev[t] (int32 in [0, n), device; a
+ * stable grouping computed on the device), then n x (rotate, expert on its
+ * group), then Y[t] = output of token t.  X [T, I], Y [T, O2] device.
+ * The group sizes shape the GEMMs, so this call waits once for the grouping
+ * kernel on the compute stream (it cannot be captured into a graph).
+ * RTP_ERR_INVALID if an id is out of range (nothing else has run then). */
+rtp_status rtp_moe_fwd(rtp_moe *moe, const void *X_dev, const int32_t *route_dev, void *Y_dev);
+
+/* Backward of the last forward (its routing and saved activations):
+ * per step G_e += its expert's weight gradients over the group (travelling
+ * with the expert), dX[t] = gradient of token t.  dY [T, O2], dX [T, I].
+ * RTP_ERR_STATE without a preceding forward. */
+rtp_status rtp_moe_bwd(rtp_moe *moe, const void *dY_dev, void *dX_dev);
+
+/* Group sizes (counts_out[n]) and first grouped row of each expert
+ * (begin_out[n + 1]) of the last forward; either may be NULL.  Host arrays. */
+rtp_status rtp_moe_routing(const rtp_moe *moe, int32_t *counts_out, int64_t *begin_out);
+/* As rtp_mlp_set_ablation: timing of compute alone / of the staging traffic alone. */
+rtp_status rtp_moe_set_ablation(rtp_moe *moe, int rotate, int compute);
+rtp_status rtp_moe_flush(rtp_moe *moe);
+rtp_status rtp_moe_sync(rtp_moe *moe);
+rtp_ring *rtp_moe_ring(rtp_moe *moe);
 
 /* ---- single GEMM launch (kernel tests and roofline timing) -------------- */
 

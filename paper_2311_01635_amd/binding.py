@@ -56,6 +56,18 @@ class rtp_mlp_desc(C.Structure):
                 ("compute_stream", C.c_void_p), ("stage_stream", C.c_void_p), ("aux_stream", C.c_void_p)]
 
 
+class rtp_moe_desc(C.Structure):
+    _fields_ = [("T", C.c_int64), ("I", C.c_int64), ("O", C.c_int64), ("O2", C.c_int64),
+                ("n", C.c_int), ("rank", C.c_int), ("mode", C.c_int), ("dtype", C.c_int),
+                ("act", C.c_int), ("flags", C.c_uint),
+                ("home_w_dev", C.c_void_p), ("home_g_dev", C.c_void_p),
+                ("buf_w_dev", C.c_void_p * 2), ("buf_g_dev", C.c_void_p * 2),
+                ("xp_dev", C.c_void_p), ("preact_dev", C.c_void_p), ("hidden_dev", C.c_void_p),
+                ("yp_dev", C.c_void_p), ("dpre_dev", C.c_void_p), ("dxp_dev", C.c_void_p),
+                ("perm_dev", C.c_void_p), ("counts_dev", C.c_void_p),
+                ("compute_stream", C.c_void_p), ("stage_stream", C.c_void_p), ("aux_stream", C.c_void_p)]
+
+
 class rtp_prof_result(C.Structure):
     _fields_ = [("launches", C.c_int64), ("total_ms", C.c_double), ("total_flops", C.c_double)]
 
@@ -104,6 +116,18 @@ SYMBOLS = {
     "rtp_mlp_flush": (C.c_int, [_P]),
     "rtp_mlp_sync": (C.c_int, [_P]),
     "rtp_mlp_ring": (_P, [_P]),
+    "rtp_moe_padded_rows": (C.c_int64, [C.c_int64, C.c_int]),
+    "rtp_moe_slot_w_bytes": (C.c_size_t, [C.POINTER(rtp_moe_desc)]),
+    "rtp_moe_slot_g_bytes": (C.c_size_t, [C.POINTER(rtp_moe_desc)]),
+    "rtp_moe_create": (C.c_int, [C.POINTER(_P), C.POINTER(rtp_moe_desc)]),
+    "rtp_moe_destroy": (C.c_int, [_P]),
+    "rtp_moe_fwd": (C.c_int, [_P, _P, _P, _P]),
+    "rtp_moe_bwd": (C.c_int, [_P, _P, _P]),
+    "rtp_moe_routing": (C.c_int, [_P, C.POINTER(C.c_int32), C.POINTER(C.c_int64)]),
+    "rtp_moe_flush": (C.c_int, [_P]),
+    "rtp_moe_set_ablation": (C.c_int, [_P, C.c_int, C.c_int]),
+    "rtp_moe_sync": (C.c_int, [_P]),
+    "rtp_moe_ring": (_P, [_P]),
     "rtp_gemm": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, _P, C.c_int64, _P, C.c_int64, _P, C.c_int64,
                            C.c_int64, C.c_int64, C.c_int64, C.c_int, _P]),
     "rtp_gemm_kernel_name": (C.c_char_p, [C.c_int, C.c_int]),

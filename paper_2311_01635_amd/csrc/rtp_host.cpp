@@ -476,12 +476,12 @@ extern "C" rtp_status rtp_rotate_step(rtp_ring *r, int direction, int step)
     return RTP_OK;
 }
 
-// Called by every linear before it enqueues kernels for `step`.
-static rtp_status enter_step(rtp_ring *r, rtp_linear *l, int step, rtp_pass pass, const char *who)
+// Called by every linear (or unit) before it enqueues kernels for `step`; next_step is the caller's own count.
+static rtp_status enter_step(rtp_ring *r, int next_step, int step, rtp_pass pass, const char *who)
 {
     if (r->pass != pass) return fail(RTP_ERR_STATE, "%s: the matching pass is not open", who);
-    if (step != l->next_step)
-        return fail(RTP_ERR_STATE, "%s: step %d out of order (next is %d)", who, step, l->next_step);
+    if (step != next_step)
+        return fail(RTP_ERR_STATE, "%s: step %d out of order (next is %d)", who, step, next_step);
     if (step >= r->d.n) return fail(RTP_ERR_STATE, "%s: step %d past the last (n=%d)", who, step, r->d.n);
     if (step > 0 && r->rotations < step)
         return fail(RTP_ERR_STATE, "%s: the shard of step %d has not been staged (rtp_rotate_step(%d) missing)", who,
@@ -712,7 +712,7 @@ extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, voi
     if (!l) return fail(RTP_ERR_INVALID, "rtp_linear_fwd: null linear");
     rtp_ring *r = l->ring;
     if (!r->dry && l->d.T > 0 && (!X || !Y)) return fail(RTP_ERR_INVALID, "rtp_linear_fwd: null tensor");
-    RTP_TRY(enter_step(r, l, step, RTP_PASS_FWD, "rtp_linear_fwd"));
+    RTP_TRY(enter_step(r, l->next_step, step, RTP_PASS_FWD, "rtp_linear_fwd"));
     const rtp_linear_desc &d = l->d;
     const int n = r->d.n;
     const int k = r->abl_rotate ? r->resident : rtp_fwd_shard(r->d.rank, step, n);
@@ -792,7 +792,7 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
     if (!l) return fail(RTP_ERR_INVALID, "rtp_linear_bwd: null linear");
     rtp_ring *r = l->ring;
     if (!r->dry && l->d.T > 0 && (!X || !dY)) return fail(RTP_ERR_INVALID, "rtp_linear_bwd: null tensor");
-    RTP_TRY(enter_step(r, l, step, RTP_PASS_BWD, "rtp_linear_bwd"));
+    RTP_TRY(enter_step(r, l->next_step, step, RTP_PASS_BWD, "rtp_linear_bwd"));
     const rtp_linear_desc &d = l->d;
     const int n = r->d.n;
     const int k = r->abl_rotate ? r->resident : rtp_bwd_shard(r->d.rank, step, n);
@@ -1374,6 +1374,328 @@ extern "C" rtp_status rtp_mlp_bwd(rtp_mlp *m, const void *X, const void *dY, voi
 
 extern "C" rtp_status rtp_mlp_flush(rtp_mlp *m) { return m ? rtp_ring_flush(m->ring) : fail(RTP_ERR_INVALID, "null mlp"); }
 extern "C" rtp_status rtp_mlp_sync(rtp_mlp *m) { return m ? rtp_ring_sync(m->ring) : fail(RTP_ERR_INVALID, "null mlp"); }
+
+// ---------------------------------------------------------------------------
+// expert partition: the ring's shard is one whole expert
+// ---------------------------------------------------------------------------
+// The worker's tokens are grouped by the expert they are routed to (a stable grouping, each group
+// padded with zero rows to a multiple of MOE_ROW_ALIGN so that the token count is a legal
+// contraction length for the tiled kernels); at rotation step t the worker runs the expert it
+// holds on that expert's group, and the outputs go back to token order at the end.  Padding rows
+// are zero through the whole unit (act(0) = 0 for every activation here), so they add nothing.
+constexpr int MOE_ROW_ALIGN = 32;
+
+struct rtp_moe {
+    rtp_moe_desc d;
+    rtp_ring *ring = nullptr;
+    int next_step = 0;
+    bool routed = false;                 // a forward pass has left a routing and saved activations
+    std::vector<int> counts;             // [n + 1], as the dispatch kernel wrote them
+    std::vector<int64_t> begin;          // [n + 1] first grouped row of each expert
+    hipEvent_t ev_dw = nullptr, ev_g_in = nullptr, ev_dpre = nullptr;
+};
+
+static bool moe_gated(const rtp_moe_desc *d) { return d->act == RTP_ACT_SWIGLU; }
+
+extern "C" int64_t rtp_moe_padded_rows(int64_t T, int n)
+{
+    if (T < 0 || n < 1) return -1;
+    return (int64_t)MOE_ROW_ALIGN * (T / MOE_ROW_ALIGN + n);
+}
+
+extern "C" size_t rtp_moe_slot_w_bytes(const rtp_moe_desc *d)
+{
+    if (!d || d->I <= 0 || d->O <= 0 || d->O2 <= 0) return 0;
+    const size_t p = moe_gated(d) ? 2 : 1;
+    return (p * (size_t)d->O * d->I + (size_t)d->O2 * d->O) * esize(d->dtype);
+}
+
+extern "C" size_t rtp_moe_slot_g_bytes(const rtp_moe_desc *d)
+{
+    if (!d || d->I <= 0 || d->O <= 0 || d->O2 <= 0) return 0;
+    const size_t p = moe_gated(d) ? 2 : 1;
+    return (p * (size_t)d->O * d->I + (size_t)d->O2 * d->O) * 4;
+}
+
+extern "C" rtp_status rtp_moe_create(rtp_moe **out, const rtp_moe_desc *d)
+{
+    if (!out || !d) return fail(RTP_ERR_INVALID, "rtp_moe_create: null argument");
+    *out = nullptr;
+    if (d->flags & RTP_FLAG_DRY_RUN) return fail(RTP_ERR_UNSUPPORTED, "rtp_moe_create: no dry run (the routing is read on the device)");
+    if (d->act <= RTP_ACT_NONE || d->act > RTP_ACT_SWIGLU) return fail(RTP_ERR_INVALID, "rtp_moe_create: an expert has an activation");
+    if (d->dtype != RTP_BF16 && d->dtype != RTP_F16) return fail(RTP_ERR_UNSUPPORTED, "rtp_moe_create: 16-bit inputs only");
+    if (d->n < 1 || d->n > MOE_MAX_EXPERTS) return fail(RTP_ERR_SHAPE, "rtp_moe_create: 1 to %d experts", MOE_MAX_EXPERTS);
+    if (d->T < 0 || d->I <= 0 || d->O <= 0 || d->O2 <= 0 || d->T > 0x3fffffff || d->I > 0x3fffffff || d->O > 0x3fffffff ||
+        d->O2 > 0x3fffffff)
+        return fail(RTP_ERR_SHAPE, "rtp_moe_create: bad sizes");
+    const int64_t mult = d->dtype == RTP_F16 ? 32 : 8;
+    if ((d->I % mult) || (d->O % mult) || (d->O2 % mult))
+        return fail(d->dtype == RTP_F16 ? RTP_ERR_UNSUPPORTED : RTP_ERR_SHAPE,
+                    "rtp_moe_create: I, O and O2 must be multiples of %d for this input type", (int)mult);
+    if (!d->xp_dev || !d->preact_dev || !d->hidden_dev || !d->yp_dev || !d->dpre_dev || !d->dxp_dev || !d->perm_dev ||
+        !d->counts_dev)
+        return fail(RTP_ERR_INVALID, "rtp_moe_create: a workspace buffer is missing");
+    rtp_ring_desc rd;
+    memset(&rd, 0, sizeof rd);
+    rd.n = d->n; rd.rank = d->rank; rd.mode = d->mode; rd.flags = d->flags;
+    rd.w_bytes = rtp_moe_slot_w_bytes(d);
+    rd.g_bytes = rtp_moe_slot_g_bytes(d);
+    rd.home_w_dev = d->home_w_dev; rd.home_g_dev = d->home_g_dev;
+    rd.buf_w_dev[0] = d->buf_w_dev[0]; rd.buf_w_dev[1] = d->buf_w_dev[1];
+    rd.buf_g_dev[0] = d->buf_g_dev[0]; rd.buf_g_dev[1] = d->buf_g_dev[1];
+    rd.compute_stream = d->compute_stream; rd.stage_stream = d->stage_stream; rd.aux_stream = d->aux_stream;
+    rtp_moe *m = new (std::nothrow) rtp_moe;
+    if (!m) return fail(RTP_ERR_INVALID, "out of host memory");
+    m->d = *d;
+    m->counts.assign((size_t)d->n + 1, 0);
+    m->begin.assign((size_t)d->n + 1, 0);
+    rtp_status s = rtp_ring_create(&m->ring, &rd);
+    if (s != RTP_OK) { delete m; return s; }
+    *out = m;
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_moe_destroy(rtp_moe *m)
+{
+    if (!m) return RTP_OK;
+    if (m->ring->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_moe_destroy: a pass is open");
+    for (hipEvent_t e : {m->ev_dw, m->ev_g_in, m->ev_dpre})
+        if (e) (void)hipEventDestroy(e);
+    RTP_TRY(rtp_ring_destroy(m->ring));
+    delete m;
+    return RTP_OK;
+}
+
+extern "C" rtp_ring *rtp_moe_ring(rtp_moe *m) { return m ? m->ring : nullptr; }
+extern "C" rtp_status rtp_moe_flush(rtp_moe *m) { return m ? rtp_ring_flush(m->ring) : fail(RTP_ERR_INVALID, "null moe"); }
+extern "C" rtp_status rtp_moe_sync(rtp_moe *m) { return m ? rtp_ring_sync(m->ring) : fail(RTP_ERR_INVALID, "null moe"); }
+
+extern "C" rtp_status rtp_moe_set_ablation(rtp_moe *m, int rotate, int compute)
+{
+    if (!m) return fail(RTP_ERR_INVALID, "null moe");
+    return set_ablation(m->ring, rotate, compute);
+}
+
+extern "C" rtp_status rtp_moe_routing(const rtp_moe *m, int32_t *counts_out, int64_t *begin_out)
+{
+    if (!m) return fail(RTP_ERR_INVALID, "null moe");
+    if (!m->routed) return fail(RTP_ERR_STATE, "rtp_moe_routing: no forward pass has run");
+    for (int e = 0; e < m->d.n; ++e)
+        if (counts_out) counts_out[e] = m->counts[(size_t)e];
+    for (int e = 0; e <= m->d.n; ++e)
+        if (begin_out) begin_out[e] = m->begin[(size_t)e];
+    return RTP_OK;
+}
+
+static rtp_status moe_gemm(rtp_moe *m, int layout, GemmArgs &a, hipStream_t st)
+{
+    rtp_ring *r = m->ring;
+    if (!r->abl_compute || a.M <= 0 || a.N <= 0 || a.K <= 0) return RTP_OK;
+    a.elem = m->d.dtype == RTP_F16 ? ELEM_F16 : ELEM_BF16;
+    HIP_TRY(timed_launch(layout, 2.0 * a.M * a.N * a.K, st, [&] { return launch_gemm_bf16(layout, a, 0, st); }));
+    return RTP_OK;
+}
+
+static rtp_status moe_events(rtp_moe *m)
+{
+    for (hipEvent_t *e : {&m->ev_dw, &m->ev_g_in, &m->ev_dpre})
+        if (!*e) HIP_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_moe_fwd(rtp_moe *m, const void *X, const int32_t *route, void *Y)
+{
+    if (!m) return fail(RTP_ERR_INVALID, "rtp_moe_fwd: null moe");
+    rtp_ring *r = m->ring;
+    const rtp_moe_desc &d = m->d;
+    if (d.T > 0 && (!X || !route || !Y)) return fail(RTP_ERR_INVALID, "rtp_moe_fwd: null tensor");
+    if (r->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_moe_fwd: a pass is open");
+    RTP_TRY(moe_events(m));
+    const int n = d.n;
+    const size_t es = esize(d.dtype);
+    const int64_t P = moe_gated(&d) ? 2 : 1, PO = P * d.O;
+    const int64_t cap = rtp_moe_padded_rows(d.T, n);
+    hipStream_t cs = r->cs();
+    m->routed = false;
+    // ---- group the tokens; the host needs the group sizes to shape the GEMMs: the one wait of the pass
+    HIP_TRY(launch_moe_dispatch(route, (int)d.T, n, MOE_ROW_ALIGN, (int)cap, d.counts_dev, d.perm_dev, cs));
+    HIP_TRY(hipMemcpyAsync(m->counts.data(), d.counts_dev, ((size_t)n + 1) * sizeof(int), hipMemcpyDeviceToHost, cs));
+    HIP_TRY(hipStreamSynchronize(cs));
+    if (m->counts[(size_t)n] != 0)
+        return fail(RTP_ERR_INVALID, "rtp_moe_fwd: %d tokens are routed to an expert outside [0, %d)", m->counts[(size_t)n], n);
+    m->begin[0] = 0;
+    for (int e = 0; e < n; ++e)
+        m->begin[(size_t)e + 1] = m->begin[(size_t)e] + (m->counts[(size_t)e] + MOE_ROW_ALIGN - 1) / MOE_ROW_ALIGN * MOE_ROW_ALIGN;
+    const int64_t rows = m->begin[(size_t)n];
+    if (rows > cap) return fail(RTP_ERR_STATE, "rtp_moe_fwd: grouped rows exceed the workspace");
+    HIP_TRY(launch_gather_rows(d.xp_dev, X, d.perm_dev, (int)rows, (size_t)d.I * es, cs));
+
+    RTP_TRY(rtp_ring_begin(r, RTP_PASS_FWD));
+    m->next_step = 0;
+    for (int t = 0; t < n; ++t) {
+        if (t < n - 1) RTP_TRY(rtp_rotate_step(r, RTP_CW, t));
+        RTP_TRY(enter_step(r, m->next_step, t, RTP_PASS_FWD, "rtp_moe_fwd"));
+        const int e = r->abl_rotate ? r->resident : rtp_fwd_shard(d.rank, t, n);
+        r->rec(TR_FWD, t, e, r->res_idx);
+        const int64_t b = m->begin[(size_t)e], rows_e = m->begin[(size_t)e + 1] - b;
+        const char *W1 = (const char *)r->d.buf_w_dev[r->res_idx];
+        const char *W2 = W1 + (size_t)PO * d.I * es;
+        GemmArgs a;
+        memset(&a, 0, sizeof a);
+        a.A = (const char *)d.xp_dev + (size_t)b * d.I * es; a.lda = d.I;
+        a.B = W1; a.ldb = d.I;
+        a.M = (int)rows_e; a.N = (int)PO; a.K = (int)d.I;
+        a.epi = fwd_act_epi(d.act);
+        a.half = (int)d.O;
+        a.aux = (char *)d.preact_dev + (size_t)b * PO * es; a.ldaux = PO;
+        a.C = (char *)d.hidden_dev + (size_t)b * d.O * es; a.ldc = d.O;
+        RTP_TRY(moe_gemm(m, LAY_NT, a, cs));
+        memset(&a, 0, sizeof a);
+        a.A = (const char *)d.hidden_dev + (size_t)b * d.O * es; a.lda = d.O;
+        a.B = W2; a.ldb = d.O;
+        a.M = (int)rows_e; a.N = (int)d.O2; a.K = (int)d.O;
+        a.epi = EPI_STORE;
+        a.C = (char *)d.yp_dev + (size_t)b * d.O2 * es; a.ldc = d.O2;
+        RTP_TRY(moe_gemm(m, LAY_NT, a, cs));
+        m->next_step = t + 1;
+    }
+    RTP_TRY(rtp_ring_end(r));
+    // "concatenation": the outputs of the N steps back in token order
+    if (r->abl_compute) HIP_TRY(launch_scatter_rows(Y, d.yp_dev, d.perm_dev, (int)rows, (size_t)d.O2 * es, cs));
+    m->routed = true;
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_moe_bwd(rtp_moe *m, const void *dY, void *dX)
+{
+    if (!m) return fail(RTP_ERR_INVALID, "rtp_moe_bwd: null moe");
+    rtp_ring *r = m->ring;
+    const rtp_moe_desc &d = m->d;
+    if (d.T > 0 && (!dY || !dX)) return fail(RTP_ERR_INVALID, "rtp_moe_bwd: null tensor");
+    if (r->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_moe_bwd: a pass is open");
+    if (!m->routed) return fail(RTP_ERR_STATE, "rtp_moe_bwd: needs the routing and activations of a forward pass");
+    const int n = d.n;
+    const size_t es = esize(d.dtype);
+    const int64_t P = moe_gated(&d) ? 2 : 1, PO = P * d.O;
+    const int64_t rows = m->begin[(size_t)n];
+    hipStream_t cs = r->cs(), ws = r->as();
+    const bool split = ws != cs;
+    // the gradient of the output, grouped like the tokens (into the buffer the expert outputs used)
+    HIP_TRY(launch_gather_rows(d.yp_dev, dY, d.perm_dev, (int)rows, (size_t)d.O2 * es, cs));
+
+    RTP_TRY(rtp_ring_begin(r, RTP_PASS_BWD));
+    m->next_step = 0;
+    for (int s = 0; s < n; ++s) {
+        if (s < n - 1) RTP_TRY(rtp_rotate_step(r, RTP_CCW, s));
+        RTP_TRY(enter_step(r, m->next_step, s, RTP_PASS_BWD, "rtp_moe_bwd"));
+        const int e = r->abl_rotate ? r->resident : rtp_bwd_shard(d.rank, s, n);
+        r->rec(TR_BWD, s, e, r->res_idx);
+        const int gi = r->res_g_idx;
+        const int64_t b = m->begin[(size_t)e], rows_e = m->begin[(size_t)e + 1] - b;
+        const char *W1 = (const char *)r->d.buf_w_dev[r->res_idx];
+        const char *W2 = W1 + (size_t)PO * d.I * es;
+        float *G1 = (float *)r->d.buf_g_dev[gi];
+        float *G2 = G1 + (size_t)PO * d.I;
+        const char *dYe = (const char *)d.yp_dev + (size_t)b * d.O2 * es;
+        const char *He = (const char *)d.hidden_dev + (size_t)b * d.O * es;
+        const char *Xe = (const char *)d.xp_dev + (size_t)b * d.I * es;
+        char *dPe = (char *)d.dpre_dev + (size_t)b * PO * es;
+        const bool rotating = r->abl_rotate && s < n - 1;
+        const bool staged_g = r->d.mode == RTP_INPLACE_STAGED;
+
+        // the weight-gradient kernels run on the auxiliary stream when there is one
+        if (split) {
+            HIP_TRY(hipEventRecord(r->ev_aux, cs));
+            HIP_TRY(hipStreamWaitEvent(ws, r->ev_aux, 0));
+        }
+        // the gradient shard this step adds onto must have arrived
+        if (r->abl_rotate && s > 0) {
+            if (r->d.mode == RTP_DOUBLE_BUFFER) HIP_TRY(hipStreamWaitEvent(ws, r->ev_g[s & 1], 0));
+            else if (staged_g) HIP_TRY(hipStreamWaitEvent(ws, m->ev_g_in, 0));
+        }
+        // When the expert moves on after this step, a weight-gradient kernel writes its sum (arriving
+        // content + this worker's contribution) straight to where the gradients travel to instead of
+        // back into the buffer; not for a group without tokens (no kernel runs) or when the launcher
+        // would cut the contraction into chunks (their partial sums need the plain `+=` form).
+        const bool moves_on = rotating && r->d.g_bytes && r->d.mode != RTP_INPLACE_BLOCKING;
+        auto send_fused = [&](GemmArgs &g, size_t g_off) {
+            if (!moves_on || !r->abl_compute || rows_e <= 0) return false;
+            if (gemm_bf16_pp_supported(LAY_TN, g)) {
+                int ks = 1;
+                gemm_bf16_pp_plan(LAY_TN, &g, 1, nullptr, nullptr, &ks);
+                if (ks > 1) return false;
+            }
+            g.epi = EPI_ACC_LAST;
+            g.C = r->home_g(e) + g_off;
+            return true;
+        };
+        const size_t g1_bytes = (size_t)PO * d.I * 4, g2_bytes = (size_t)d.O2 * d.O * 4;
+        GemmArgs a;
+        // G2_e += dY_e^T H_e
+        memset(&a, 0, sizeof a);
+        a.A = dYe; a.lda = d.O2;
+        a.B = He; a.ldb = d.O;
+        a.M = (int)d.O2; a.N = (int)d.O; a.K = (int)rows_e;
+        a.epi = EPI_ACC_ADD; a.c_is_f32 = 1;
+        a.ws = G2; a.ldws = d.O; a.C = G2; a.ldc = d.O;
+        a.cu_share = split ? 2 : 1;
+        const bool sent2 = send_fused(a, g1_bytes);
+        RTP_TRY(moe_gemm(m, LAY_TN, a, ws));
+        // dPre_e = (dY_e W2_e) * act'(pre_e)
+        memset(&a, 0, sizeof a);
+        a.A = dYe; a.lda = d.O2;
+        a.B = W2; a.ldb = d.O;
+        a.M = (int)rows_e; a.N = (int)d.O; a.K = (int)d.O2;
+        a.epi = bwd_act_epi(d.act);
+        a.half = (int)d.O;
+        a.aux = (char *)d.preact_dev + (size_t)b * PO * es; a.ldaux = PO;
+        a.C = dPe; a.ldc = PO;
+        a.cu_share = split ? 2 : 1;
+        RTP_TRY(moe_gemm(m, LAY_NN, a, cs));
+        if (split) {
+            HIP_TRY(hipEventRecord(m->ev_dpre, cs));
+            HIP_TRY(hipStreamWaitEvent(ws, m->ev_dpre, 0));
+        }
+        // G1_e += dPre_e^T X_e
+        memset(&a, 0, sizeof a);
+        a.A = dPe; a.lda = PO;
+        a.B = Xe; a.ldb = d.I;
+        a.M = (int)PO; a.N = (int)d.I; a.K = (int)rows_e;
+        a.epi = EPI_ACC_ADD; a.c_is_f32 = 1;
+        a.ws = G1; a.ldws = d.I; a.C = G1; a.ldc = d.I;
+        a.cu_share = split ? 2 : 1;
+        const bool sent1 = send_fused(a, 0);
+        RTP_TRY(moe_gemm(m, LAY_TN, a, ws));
+        // the expert's gradients move on with it: handed to the stage stream once both kernels are done
+        if (moves_on) {
+            const int ein = rtp_bwd_shard(d.rank, s + 1, n);
+            HIP_TRY(hipEventRecord(m->ev_dw, ws));
+            HIP_TRY(hipStreamWaitEvent(r->ss(), m->ev_dw, 0));
+            char *buf = (char *)r->d.buf_g_dev[gi];
+            if (!sent1) RTP_TRY(copy_async(r, r->home_g(e), buf, g1_bytes, r->ss()));
+            if (!sent2) RTP_TRY(copy_async(r, r->home_g(e) + g1_bytes, buf + g1_bytes, g2_bytes, r->ss()));
+            r->rec(TR_G_OUT, s, e, gi);
+            if (staged_g) {
+                RTP_TRY(copy_async(r, r->d.buf_g_dev[gi], r->home_g(ein), r->d.g_bytes, r->ss()));
+                r->rec(TR_G_IN, s, ein, gi);
+                HIP_TRY(hipEventRecord(m->ev_g_in, r->ss()));
+            }
+        }
+        // dX_e = dPre_e W1_e
+        memset(&a, 0, sizeof a);
+        a.A = dPe; a.lda = PO;
+        a.B = W1; a.ldb = d.I;
+        a.M = (int)rows_e; a.N = (int)d.I; a.K = (int)PO;
+        a.epi = EPI_STORE;
+        a.C = (char *)d.dxp_dev + (size_t)b * d.I * es; a.ldc = d.I;
+        a.cu_share = split ? 2 : 1;
+        RTP_TRY(moe_gemm(m, LAY_NN, a, cs));
+        m->next_step = s + 1;
+    }
+    RTP_TRY(rtp_ring_end(r));
+    if (r->abl_compute) HIP_TRY(launch_scatter_rows(dX, d.dxp_dev, d.perm_dev, (int)rows, (size_t)d.I * es, cs));
+    return RTP_OK;
+}
 
 // ---------------------------------------------------------------------------
 // single GEMM launch

@@ -78,6 +78,18 @@ hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s);
 // elem: -1 fp32, ELEM_BF16, ELEM_F16
 hipError_t launch_colsum(int elem, const void *Y, int64_t ld, int rows, int cols, const float *in, float *out, hipStream_t s);
 
+// ---- expert partition: tokens grouped by the expert they are routed to -----------------------
+// Stable grouping of T tokens by route[t] in [0, n): group e starts at a multiple of `align` rows,
+// perm[p] = the token in grouped row p or -1 (padding), p < cap.  counts[e] = tokens of expert e,
+// counts[n] = tokens whose id is out of range (they are left out).  One workgroup; n <= MOE_MAX_EXPERTS;
+// cap >= align * (T / align + n) is the caller's to guarantee.
+constexpr int MOE_MAX_EXPERTS = 64;
+hipError_t launch_moe_dispatch(const int *route, int T, int n, int align, int cap, int *counts, int *perm, hipStream_t s);
+// out[p, :] = in[perm[p], :], zero where perm[p] < 0 (rows of row_bytes, a multiple of 16)
+hipError_t launch_gather_rows(void *out, const void *in, const int *perm, int rows, size_t row_bytes, hipStream_t s);
+// out[perm[p], :] = in[p, :] where perm[p] >= 0
+hipError_t launch_scatter_rows(void *out, const void *in, const int *perm, int rows, size_t row_bytes, hipStream_t s);
+
 // out[0] = wall-clock ticks, out[1] = shader cycles over a spin of wall_ticks
 hipError_t launch_clock_probe(long long *out, long long wall_ticks, hipStream_t s);
 

@@ -201,6 +201,115 @@ hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s)
     return hipGetLastError();
 }
 
+// ---- expert partition: grouping tokens by expert, row gather and scatter ------------------------
+// One workgroup: thread i owns the i-th contiguous chunk of tokens.  Per-(expert, chunk) counts
+// in LDS, an exclusive scan over the chunks of each expert, the group starts from the counts,
+// then every thread places its tokens in order: the result is the stable grouping whatever the
+// number of threads.
+constexpr int DISPATCH_THREADS = 128;
+
+__global__ __launch_bounds__(DISPATCH_THREADS) void moe_dispatch_kernel(const int *__restrict__ route, int T, int n, int align,
+                                                                        int cap, int *__restrict__ counts, int *__restrict__ perm)
+{
+    extern __shared__ int dispatch_lds[];
+    int *hist = dispatch_lds;                     // [n][DISPATCH_THREADS]
+    int *seg = dispatch_lds + n * DISPATCH_THREADS; // [n + 1] group starts
+    __shared__ int bad;
+    const int tid = threadIdx.x;
+    const int chunk = (T + DISPATCH_THREADS - 1) / DISPATCH_THREADS;
+    const int lo = min(T, tid * chunk), hi = min(T, lo + chunk);
+    for (int e = 0; e < n; ++e) hist[e * DISPATCH_THREADS + tid] = 0;
+    if (tid == 0) bad = 0;
+    __syncthreads();
+    int my_bad = 0;
+    for (int t = lo; t < hi; ++t) {
+        const int e = route[t];
+        if ((unsigned)e < (unsigned)n) hist[e * DISPATCH_THREADS + tid]++;
+        else my_bad++;
+    }
+    if (my_bad) atomicAdd(&bad, my_bad);
+    __syncthreads();
+    for (int e = tid; e < n; e += DISPATCH_THREADS) {
+        int run = 0;
+        for (int i = 0; i < DISPATCH_THREADS; ++i) {
+            const int c = hist[e * DISPATCH_THREADS + i];
+            hist[e * DISPATCH_THREADS + i] = run;
+            run += c;
+        }
+        counts[e] = run;
+        seg[e + 1] = run;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        seg[0] = 0;
+        for (int e = 0; e < n; ++e) seg[e + 1] = seg[e] + (seg[e + 1] + align - 1) / align * align;
+        counts[n] = bad;
+    }
+    for (int p = tid; p < cap; p += DISPATCH_THREADS) perm[p] = -1;
+    __syncthreads();
+    for (int t = lo; t < hi; ++t) {
+        const int e = route[t];
+        if ((unsigned)e < (unsigned)n) {
+            const int p = seg[e] + hist[e * DISPATCH_THREADS + tid]++;
+            if (p < cap) perm[p] = t;
+        }
+    }
+}
+
+hipError_t launch_moe_dispatch(const int *route, int T, int n, int align, int cap, int *counts, int *perm, hipStream_t s)
+{
+    if (n < 1 || n > MOE_MAX_EXPERTS || T < 0 || align < 1 || cap < 0) return hipErrorInvalidValue;
+    if ((int64_t)cap < (int64_t)align * (T / align + n)) return hipErrorInvalidValue;
+    const size_t lds = (size_t)(n * DISPATCH_THREADS + n + 1) * sizeof(int);
+    hipLaunchKernelGGL(moe_dispatch_kernel, dim3(1), dim3(DISPATCH_THREADS), lds, s, route, T, n, align, cap, counts, perm);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void gather_rows_kernel(u32x4 *__restrict__ out, const u32x4 *__restrict__ in,
+                                                          const int *__restrict__ perm, int rows, int chunks)
+{
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (int r = blockIdx.x; r < rows; r += gridDim.x) {
+        const int src = perm[r];
+        for (int c = threadIdx.x; c < chunks; c += 256)
+            out[(int64_t)r * chunks + c] = src >= 0 ? in[(int64_t)src * chunks + c] : z;
+    }
+}
+
+__global__ __launch_bounds__(256) void scatter_rows_kernel(u32x4 *__restrict__ out, const u32x4 *__restrict__ in,
+                                                           const int *__restrict__ perm, int rows, int chunks)
+{
+    for (int r = blockIdx.x; r < rows; r += gridDim.x) {
+        const int dst = perm[r];
+        if (dst < 0) continue;
+        for (int c = threadIdx.x; c < chunks; c += 256) out[(int64_t)dst * chunks + c] = in[(int64_t)r * chunks + c];
+    }
+}
+
+static hipError_t launch_rows(bool gather, void *out, const void *in, const int *perm, int rows, size_t row_bytes, hipStream_t s)
+{
+    if (rows <= 0 || row_bytes == 0) return hipSuccess;
+    if ((row_bytes & 15) || ((uintptr_t)out & 15) || ((uintptr_t)in & 15) || (row_bytes >> 4) > 0x7fffffff)
+        return hipErrorInvalidValue;
+    const int chunks = (int)(row_bytes >> 4);
+    const int blocks = rows < 8192 ? rows : 8192;
+    if (gather)
+        hipLaunchKernelGGL(gather_rows_kernel, dim3(blocks), dim3(256), 0, s, (u32x4 *)out, (const u32x4 *)in, perm, rows, chunks);
+    else
+        hipLaunchKernelGGL(scatter_rows_kernel, dim3(blocks), dim3(256), 0, s, (u32x4 *)out, (const u32x4 *)in, perm, rows, chunks);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_rows(void *out, const void *in, const int *perm, int rows, size_t row_bytes, hipStream_t s)
+{
+    return launch_rows(true, out, in, perm, rows, row_bytes, s);
+}
+
+hipError_t launch_scatter_rows(void *out, const void *in, const int *perm, int rows, size_t row_bytes, hipStream_t s)
+{
+    return launch_rows(false, out, in, perm, rows, row_bytes, s);
+}
+
 // ---- bias gradient: column sums --------------------------------------------------------------
 // One workgroup per 64 columns: 4 row groups of 64 lanes walk the rows (coalesced 128- or 256-byte
 // row segments), the four partial sums meet in LDS.  Deterministic order; the matrices this runs

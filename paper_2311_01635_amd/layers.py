@@ -240,3 +240,105 @@ class RtpMlp:
         if self.handle:
             B.check(B.lib.rtp_mlp_destroy(self.handle), "rtp_mlp_destroy")
             self.handle = C.c_void_p()
+
+
+class RtpMoe:
+    """Expert-partitioned layer run by rtp_moe_fwd / rtp_moe_bwd: the ring's
+    shard is one whole expert.  `experts[e]` = (W1, W2) or (Wg, Wu, Wd)."""
+
+    def __init__(self, experts, T, rank, act, mode=B.RTP_INPLACE_STAGED, dtype=B.RTP_BF16, G0=None,
+                 device="cuda:0", aux_stream=True):
+        self.dev = torch.device(device)
+        td = _TORCH_DT[dtype]
+        n = len(experts)
+        self.n, self.rank, self.T, self.act, self.mode, self.dtype = n, rank, T, act, mode, dtype
+        self.gated = act == B.RTP_ACT_SWIGLU
+        self.shapes = [tuple(w.shape) for w in experts[0]]
+        self.O, self.I = self.shapes[0]
+        self.O2 = self.shapes[-1][0]
+        self.p = 2 if self.gated else 1
+
+        def slot(mats, t):
+            # [W1_e | W2_e], W1_e = [gate_e ; up_e] for a gated expert: every matrix flattened row-major
+            return torch.cat([m.to(self.dev, t).contiguous().reshape(-1) for m in mats])
+
+        self.home_w = torch.stack([slot(ex, td) for ex in experts]).contiguous()
+        if G0 is None:
+            self.home_g = torch.zeros(n, self.home_w.shape[1], dtype=torch.float32, device=self.dev)
+        else:
+            self.home_g = torch.stack([slot(g, torch.float32) for g in G0]).contiguous()
+        d = B.rtp_moe_desc()
+        d.T, d.I, d.O, d.O2 = T, self.I, self.O, self.O2
+        d.n, d.rank, d.mode, d.dtype, d.act, d.flags = n, rank, mode, dtype, act, 0
+        wb, gb = B.lib.rtp_moe_slot_w_bytes(C.byref(d)), B.lib.rtp_moe_slot_g_bytes(C.byref(d))
+        assert wb == self.home_w.shape[1] * _esize(dtype) and gb == self.home_g.shape[1] * 4
+        self.w_bytes, self.g_bytes = wb, gb
+        self.buf_w = [torch.empty(wb, dtype=torch.uint8, device=self.dev) for _ in range(2)]
+        ng = 2 if mode == B.RTP_DOUBLE_BUFFER else 1
+        self.buf_g = [torch.empty(gb, dtype=torch.uint8, device=self.dev) for _ in range(ng)] + [None] * (2 - ng)
+        Tp = self.Tp = B.lib.rtp_moe_padded_rows(T, n)
+        self.xp = torch.empty(Tp, self.I, dtype=td, device=self.dev)
+        self.preact = torch.empty(Tp, self.p * self.O, dtype=td, device=self.dev)
+        self.hidden = torch.empty(Tp, self.O, dtype=td, device=self.dev)
+        self.yp = torch.empty(Tp, self.O2, dtype=td, device=self.dev)
+        self.dpre = torch.empty(Tp, self.p * self.O, dtype=td, device=self.dev)
+        self.dxp = torch.empty(Tp, self.I, dtype=td, device=self.dev)
+        self.perm = torch.empty(Tp, dtype=torch.int32, device=self.dev)
+        self.counts = torch.empty(n + 1, dtype=torch.int32, device=self.dev)
+        self.compute_stream = torch.cuda.Stream(self.dev)
+        self.stage_stream = torch.cuda.Stream(self.dev)
+        self.aux_stream = torch.cuda.Stream(self.dev) if aux_stream else None
+        d.home_w_dev, d.home_g_dev = B._ptr(self.home_w), B._ptr(self.home_g)
+        d.buf_w_dev[0], d.buf_w_dev[1] = B._ptr(self.buf_w[0]), B._ptr(self.buf_w[1])
+        d.buf_g_dev[0], d.buf_g_dev[1] = B._ptr(self.buf_g[0]), B._ptr(self.buf_g[1])
+        d.xp_dev, d.preact_dev, d.hidden_dev = B._ptr(self.xp), B._ptr(self.preact), B._ptr(self.hidden)
+        d.yp_dev, d.dpre_dev, d.dxp_dev = B._ptr(self.yp), B._ptr(self.dpre), B._ptr(self.dxp)
+        d.perm_dev, d.counts_dev = B._ptr(self.perm), B._ptr(self.counts)
+        d.compute_stream, d.stage_stream = B._stream(self.compute_stream), B._stream(self.stage_stream)
+        d.aux_stream = B._stream(self.aux_stream) if aux_stream else None
+        self.desc = d
+        self.handle = C.c_void_p()
+        torch.cuda.synchronize(self.dev)
+        B.check(B.lib.rtp_moe_create(C.byref(self.handle), C.byref(d)), "rtp_moe_create")
+
+    def forward(self, X, route, Y):
+        B.check(B.lib.rtp_moe_fwd(self.handle, B._ptr(X), B._ptr(route), B._ptr(Y)), "rtp_moe_fwd")
+
+    def backward(self, dY, dX):
+        B.check(B.lib.rtp_moe_bwd(self.handle, B._ptr(dY), B._ptr(dX)), "rtp_moe_bwd")
+
+    def sync(self):
+        B.check(B.lib.rtp_moe_sync(self.handle), "rtp_moe_sync")
+
+    def set_ablation(self, rotate=True, compute=True):
+        B.check(B.lib.rtp_moe_set_ablation(self.handle, int(rotate), int(compute)), "rtp_moe_set_ablation")
+
+    def worker_bytes(self):
+        return B.rtp_worker_bytes(self.mode, self.w_bytes, self.g_bytes)
+
+    def routing(self):
+        """(tokens per expert, first grouped row of each expert) of the last forward."""
+        c, b = (C.c_int32 * self.n)(), (C.c_int64 * (self.n + 1))()
+        B.check(B.lib.rtp_moe_routing(self.handle, c, b), "rtp_moe_routing")
+        return list(c), list(b)
+
+    def gathered(self):
+        """(weights, gradients), each a list over experts of the expert's matrices, from the home store."""
+        B.check(B.lib.rtp_moe_flush(self.handle), "rtp_moe_flush")
+        self.sync()
+        out = []
+        for home in (self.home_w, self.home_g):
+            per = []
+            for e in range(self.n):
+                mats, off = [], 0
+                for (r, c) in self.shapes:
+                    mats.append(home[e, off:off + r * c].reshape(r, c).clone())
+                    off += r * c
+                per.append(tuple(mats))
+            out.append(per)
+        return out
+
+    def close(self):
+        if self.handle:
+            B.check(B.lib.rtp_moe_destroy(self.handle), "rtp_moe_destroy")
+            self.handle = C.c_void_p()

@@ -38,6 +38,8 @@ class Workload:
             return 6 * self.T * (self.I * self.O + self.O * self.O2)
         if self.kind == "swiglu":
             return 6 * self.T * (2 * self.I * self.O + self.O * self.O2)
+        if self.kind == "moe_swiglu":      # every token goes through one expert
+            return 6 * self.T * (2 * self.I * self.O + self.O * self.O2)
         if self.kind == "linears":
             return sum(6 * self.T * i * o for (_, o, i) in self.extra["matrices"])
         raise ValueError(self.kind)
@@ -57,6 +59,15 @@ CONFIGS = {
                                     n=8, dtype="bf16", mode="inplace_staged"),
     "cfg5_large_mlp": Workload("cfg5_large_mlp", "mlp_gelu", T=2048, I=8192, O=28672, O2=8192, n=16,
                                dtype="bf16", mode="inplace_staged", w_dist=("normal", 0.01)),
+}
+
+
+# Expert partition (the paper names the layer but gives no sizes): eight experts of the shape of a
+# widely used open mixture-of-experts model's feed-forward block, one expert per token, 8192 local
+# tokens, load skewed as (e + 1)^-1.  `make_moe_inputs` draws it.
+MOE_CONFIGS = {
+    "moe_8x_swiglu": Workload("moe_8x_swiglu", "moe_swiglu", T=8192, I=4096, O=14336, O2=4096, n=8, dtype="bf16",
+                              mode="inplace_staged", extra={"skew": 1.0}),
 }
 
 
@@ -147,6 +158,26 @@ def make_integer_inputs(wl: Workload, seed: int = 0, lo: int = -2, hi: int = 2):
         "W": rng.integers(lo, hi + 1, size=(wl.O, wl.I)).astype(np.float32),
         "dY": rng.integers(lo, hi + 1, size=(wl.T, wl.O)).astype(np.float32),
     }
+    return out
+
+
+def make_moe_inputs(T, I, O, O2, n, dtype="bf16", gated=False, seed=0, skew=1.0, w_scale=0.05, grad0=True):
+    """Inputs of an expert-partitioned layer: n experts of one shape, and one expert id per token.
+
+    The paper defines no router, so the routing is a drawn input: token t goes to expert e with
+    probability proportional to (e + 1)^-skew (skew 0: uniform load; 1: the few-busy-many-idle
+    load mixture-of-experts layers show), independently per token.  Draw order: X, the experts in
+    order (each matrix in order), dY, route, then the arriving gradients."""
+    rng = np.random.default_rng(seed)
+    shapes = [(O, I), (O, I), (O2, O)] if gated else [(O, I), (O2, O)]
+    out = {"X": _store(rng.standard_normal((T, I), dtype=np.float32), dtype)}
+    out["experts"] = [tuple(_store(_weight(rng, sh, ("normal", w_scale)), dtype) for sh in shapes) for _ in range(n)]
+    out["dY"] = _store(rng.standard_normal((T, O2), dtype=np.float32), dtype)
+    p = (np.arange(n) + 1.0) ** -float(skew)
+    out["route"] = rng.choice(n, size=T, p=p / p.sum()).astype(np.int32)
+    if grad0:
+        out["G0"] = [tuple(rng.standard_normal(sh, dtype=np.float32) * np.float32(0.5) for sh in shapes)
+                     for _ in range(n)]
     return out
 
 

@@ -15,7 +15,7 @@ import torch
 import oracle as orc
 import rtp_workloads as wl
 from paper_2311_01635_amd import binding as B
-from paper_2311_01635_amd.layers import RtpLinear, RtpMlp
+from paper_2311_01635_amd.layers import RtpLinear, RtpMlp, RtpMoe
 
 pytestmark = pytest.mark.gpu
 
@@ -31,6 +31,9 @@ def say(msg):
 
 def relerr(gpu, ref):
     gpu = np.asarray(gpu, dtype=np.float64)
+    assert gpu.shape == np.shape(ref)
+    if gpu.size == 0:
+        return 0.0
     den = np.abs(ref).max()
     return float(np.abs(gpu - ref).max() / (den if den > 0 else 1.0))
 
@@ -586,3 +589,123 @@ def test_mlp_gelu_tanh_variant():
     out, ref, gkeys = _mlp_case(w, 1, B.RTP_DOUBLE_BUFFER)
     for key in ("H", "Y", "dX") + tuple(gkeys):
         assert relerr(out[key], ref[key]) <= TOL_BF16, (key, relerr(out[key], ref[key]))
+
+
+# ------------------------------------------------------- expert partition --
+
+def _moe_case(T, I, O, O2, n, rank, mode, gated, dtype="bf16", seed=0, skew=1.0, route=None, aux_stream=True, passes=1):
+    td, bd = _TD[dtype], _BD[dtype]
+    inp = wl.make_moe_inputs(T, I, O, O2, n, dtype=dtype, gated=gated, seed=seed, skew=skew)
+    if route is not None:
+        inp["route"] = np.asarray(route, dtype=np.int32)
+    act = B.RTP_ACT_SWIGLU if gated else B.RTP_ACT_GELU_ERF
+    ex64 = [tuple(f64(w) for w in ex) for ex in inp["experts"]]
+    g64 = [tuple(f64(g) for g in ex) for ex in inp["G0"]]
+    ref = orc.rtp_moe(f64(inp["X"]), inp["route"], ex64, f64(inp["dY"]), n, rank, G0=g64)
+    moe = RtpMoe([tuple(dev(w, td) for w in ex) for ex in inp["experts"]], T, rank, act, mode, bd,
+                 G0=[tuple(dev(g, torch.float32) for g in ex) for ex in inp["G0"]], aux_stream=aux_stream)
+    Xd, dYd, rd = dev(inp["X"], td), dev(inp["dY"], td), dev(inp["route"], torch.int32)
+    Y = torch.full((T, O2), float("nan"), device=DEV, dtype=td)
+    dX = torch.full((T, I), float("nan"), device=DEV, dtype=td)
+    torch.cuda.synchronize()
+    for _ in range(passes):
+        moe.forward(Xd, rd, Y)
+        moe.backward(dYd, dX)
+    moe.sync()
+    counts, begin = moe.routing()
+    perm = moe.perm.cpu().tolist()
+    Ws, Gs = moe.gathered()
+    same = all(torch.equal(a, dev(b, td)) for exa, exb in zip(Ws, inp["experts"]) for a, b in zip(exa, exb))
+    out = dict(Y=host(Y), dX=host(dX), G=[[host(g) for g in ex] for ex in Gs], W_same=same, counts=counts, begin=begin,
+               perm=perm, Tp=moe.Tp)
+    moe.close()
+    return out, ref, inp
+
+
+def _check_moe(out, ref, inp, n, tol, passes=1):
+    # integer work, bit-exact: group sizes, group starts, the token of every grouped row, padding rows
+    c, b, perm = orc.moe_dispatch(inp["route"], n, 32)
+    assert out["counts"] == c == ref["counts"] and out["begin"] == b
+    assert out["perm"][:b[n]] == perm and all(p == -1 for p in out["perm"][b[n]:]) and len(out["perm"]) == out["Tp"]
+    assert out["W_same"], "the expert weights come back unchanged"
+    for key in ("Y", "dX"):
+        assert np.isfinite(out[key]).all(), key
+        assert relerr(out[key], ref[key]) <= tol, (key, relerr(out[key], ref[key]))
+    for e in range(n):
+        for j, g in enumerate(out["G"][e]):
+            g0 = f64(inp["G0"][e][j])
+            want = g0 + passes * (ref["G"][e][j] - g0)
+            assert relerr(g, want) <= tol, (e, j, relerr(g, want))
+            if c[e] == 0:
+                assert np.array_equal(g, g0), "an expert without tokens passes through untouched"
+
+
+@pytest.mark.parametrize("mode", [B.RTP_DOUBLE_BUFFER, B.RTP_INPLACE_STAGED, B.RTP_INPLACE_BLOCKING])
+@pytest.mark.parametrize("gated", [False, True])
+def test_moe_small(gated, mode):
+    """Ragged group sizes, an output width that sends one GEMM to the register-staged kernel."""
+    n = 4
+    for rank in (0, 3):
+        say(f"moe small gated={gated} mode={mode} rank={rank}")
+        out, ref, inp = _moe_case(300, 64, 96, 72, n, rank, mode, gated, seed=rank)
+        _check_moe(out, ref, inp, n, TOL_BF16)
+
+
+@pytest.mark.parametrize("aux", [True, False])
+@pytest.mark.parametrize("gated,skew", [(False, 0.0), (True, 1.0), (True, 2.5)])
+def test_moe_several_tiles(gated, skew, aux):
+    """Groups from a handful of rows to several row tiles; uniform to heavily skewed load."""
+    n = 8
+    say(f"moe tiles gated={gated} skew={skew} aux={aux}")
+    out, ref, inp = _moe_case(1500, 256, 384, 256, n, 5, B.RTP_INPLACE_STAGED, gated, seed=3, skew=skew, aux_stream=aux)
+    _check_moe(out, ref, inp, n, TOL_BF16)
+
+
+def test_moe_degenerate_routings():
+    n, T = 4, 200
+    for name, route in (("one expert takes all", np.full(T, 2)), ("two experts idle", np.arange(T) % 2 * 3),
+                        ("one token each", None)):
+        say(f"moe degenerate: {name}")
+        if route is None:
+            T_, route = n, np.arange(n)[::-1].copy()
+        else:
+            T_ = T
+        out, ref, inp = _moe_case(T_, 64, 64, 64, n, 1, B.RTP_DOUBLE_BUFFER, False, route=route)
+        _check_moe(out, ref, inp, n, TOL_BF16)
+    say("moe degenerate: a single expert, one worker")
+    out, ref, inp = _moe_case(100, 64, 64, 64, 1, 0, B.RTP_INPLACE_STAGED, True)
+    _check_moe(out, ref, inp, 1, TOL_BF16)
+    say("moe degenerate: no tokens")
+    out, ref, inp = _moe_case(0, 64, 64, 64, 4, 0, B.RTP_INPLACE_STAGED, False)
+    _check_moe(out, ref, inp, 4, TOL_BF16)
+
+
+def test_moe_fp16():
+    say("moe fp16")
+    out, ref, inp = _moe_case(500, 128, 256, 96, 4, 2, B.RTP_INPLACE_STAGED, True, dtype="f16", seed=2)
+    _check_moe(out, ref, inp, 4, TOL_F16)
+
+
+def test_moe_gradients_accumulate_over_passes():
+    say("moe two passes")
+    out, ref, inp = _moe_case(400, 64, 128, 64, 4, 1, B.RTP_INPLACE_STAGED, False, passes=2)
+    _check_moe(out, ref, inp, 4, TOL_BF16, passes=2)
+
+
+def test_moe_rejects_an_expert_id_out_of_range_and_goes_on():
+    n, T = 4, 64
+    inp = wl.make_moe_inputs(T, 64, 64, 64, n, seed=9)
+    moe = RtpMoe([tuple(dev(w, torch.bfloat16) for w in ex) for ex in inp["experts"]], T, 0, B.RTP_ACT_GELU_ERF)
+    Xd, Y = dev(inp["X"], torch.bfloat16), torch.empty(T, 64, device=DEV, dtype=torch.bfloat16)
+    bad = inp["route"].copy()
+    bad[5], bad[17] = n, -1
+    with pytest.raises(B.RtpError):
+        moe.forward(Xd, dev(bad, torch.int32), Y)
+    with pytest.raises(B.RtpError):
+        moe.backward(Xd, Y)                      # no forward has completed
+    moe.forward(Xd, dev(inp["route"], torch.int32), Y)
+    moe.sync()
+    ex64 = [tuple(f64(w) for w in ex) for ex in inp["experts"]]
+    ref = orc.plain_moe(f64(inp["X"]), inp["route"], ex64, f64(inp["dY"]))
+    assert relerr(host(Y), ref["Y"]) <= TOL_BF16
+    moe.close()

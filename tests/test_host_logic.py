@@ -300,3 +300,81 @@ def test_padded_linear_descriptions():
         B.Linear(ring, T=8, I=64, O=536, split=B.RTP_SPLIT_OUT, dtype=B.RTP_BF16)
     assert e.value.status == B.RTP_ERR_SHAPE
     ring.close()
+
+
+# ------------------------------------------------------ expert partition --
+
+def test_moe_padded_rows_bound_every_routing():
+    """The grouped workspace holds any routing: groups padded to 32 rows never exceed it, and the
+    bound is attained."""
+    import numpy as np
+    rng = np.random.default_rng(0)
+    assert B.lib.rtp_moe_padded_rows(-1, 4) == -1 and B.lib.rtp_moe_padded_rows(10, 0) == -1
+    for n in (1, 2, 5, 8, 64):
+        for T in (0, 1, 31, 32, 33, 200, 4096):
+            cap = B.lib.rtp_moe_padded_rows(T, n)
+            assert cap % 32 == 0
+            worst = 0
+            for trial in range(20):
+                route = rng.integers(0, n, T)
+                _, begin, _ = orc.moe_dispatch(route, n, 32)
+                worst = max(worst, begin[n])
+            # the adversarial routing: one token over a multiple of 32 on as many experts as possible
+            c = [0] * n
+            left = T
+            for e in range(n - 1):
+                if left >= 1:
+                    c[e] = 1
+                    left -= 1
+            c[n - 1] = left
+            worst = max(worst, sum((x + 31) // 32 * 32 for x in c))
+            assert worst <= cap
+    assert B.lib.rtp_moe_padded_rows(33, 2) == 96 and sum((x + 31) // 32 * 32 for x in (1, 32)) == 64
+
+
+def _moe_desc(**kw):
+    import ctypes as C
+    d = B.rtp_moe_desc()
+    d.T, d.I, d.O, d.O2, d.n, d.rank = 128, 64, 96, 64, 4, 0
+    d.mode, d.dtype, d.act, d.flags = B.RTP_INPLACE_STAGED, B.RTP_BF16, B.RTP_ACT_GELU_ERF, 0
+    fake = 0x1000
+    for name in ("home_w_dev", "home_g_dev", "xp_dev", "preact_dev", "hidden_dev", "yp_dev", "dpre_dev", "dxp_dev",
+                 "perm_dev", "counts_dev", "compute_stream", "stage_stream"):
+        fake += 0x1000
+        setattr(d, name, fake)
+    d.buf_w_dev[0], d.buf_w_dev[1], d.buf_g_dev[0] = 0x100000, 0x200000, 0x300000
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def test_moe_descriptions():
+    import ctypes as C
+    d = _moe_desc()
+    assert B.lib.rtp_moe_slot_w_bytes(C.byref(d)) == (96 * 64 + 64 * 96) * 2
+    assert B.lib.rtp_moe_slot_g_bytes(C.byref(d)) == (96 * 64 + 64 * 96) * 4
+    g = _moe_desc(act=B.RTP_ACT_SWIGLU)
+    assert B.lib.rtp_moe_slot_w_bytes(C.byref(g)) == (2 * 96 * 64 + 64 * 96) * 2, "a gated expert holds gate and up"
+    h = C.c_void_p()
+    assert B.lib.rtp_moe_create(C.byref(h), C.byref(d)) == B.RTP_OK      # validation and bookkeeping only: no GPU call
+    assert B.lib.rtp_moe_ring(h) is not None
+    assert B.lib.rtp_moe_bwd(h, 0x1000, 0x1000) == B.RTP_ERR_STATE, "backward needs a forward's routing"
+    assert B.lib.rtp_moe_routing(h, None, None) == B.RTP_ERR_STATE
+    assert B.lib.rtp_moe_destroy(h) == B.RTP_OK
+    bad = [
+        (dict(flags=B.RTP_FLAG_DRY_RUN), B.RTP_ERR_UNSUPPORTED),
+        (dict(act=B.RTP_ACT_NONE), B.RTP_ERR_INVALID),
+        (dict(dtype=B.RTP_F32), B.RTP_ERR_UNSUPPORTED),
+        (dict(n=65), B.RTP_ERR_SHAPE),
+        (dict(n=0), B.RTP_ERR_SHAPE),
+        (dict(I=60), B.RTP_ERR_SHAPE),
+        (dict(O2=0), B.RTP_ERR_SHAPE),
+        (dict(dtype=B.RTP_F16, O=72), B.RTP_ERR_UNSUPPORTED),
+        (dict(perm_dev=None), B.RTP_ERR_INVALID),
+        (dict(rank=4), B.RTP_ERR_SHAPE),
+        (dict(stage_stream=_moe_desc().compute_stream), B.RTP_ERR_INVALID),
+    ]
+    for kw, want in bad:
+        h = C.c_void_p()
+        assert B.lib.rtp_moe_create(C.byref(h), C.byref(_moe_desc(**kw))) == want, kw
+        assert not h.value
