@@ -21,7 +21,7 @@ import torch
 import oracle as orc
 import rtp_workloads as wl
 from paper_2311_01635_amd import binding as B
-from paper_2311_01635_amd.layers import RtpLinear, RtpMlp
+from paper_2311_01635_amd.layers import RtpLinear, RtpMlp, RtpMoe
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -205,3 +205,58 @@ def test_integer_inputs_bit_exact_at_real_shapes(split, T, I, O, n):
     assert torch.equal(G.cpu(), refG)
     assert torch.equal(Wb, dev(Wn))
     layer.close()
+
+
+def test_moe_8x_swiglu_fullsize():
+    """The expert-partition benchmark configuration at full size: grouping compared exactly; per
+    expert a sample of its tokens (first, last, random) for Y and dX, and a sample of hidden units
+    (rows of the gate/up gradients, columns of the down gradient) summed over all of its tokens."""
+    w = wl.MOE_CONFIGS["moe_8x_swiglu"]
+    rng = np.random.default_rng(99)
+    say("moe_8x_swiglu: drawing inputs")
+    inp = wl.make_moe_inputs(w.T, w.I, w.O, w.O2, w.n, dtype="bf16", gated=True, seed=0, skew=w.extra["skew"],
+                             w_scale=0.02, grad0=False)
+    moe = RtpMoe([tuple(dev(m) for m in ex) for ex in inp["experts"]], w.T, 0, B.RTP_ACT_SWIGLU, B.RTP_INPLACE_STAGED,
+                 B.RTP_BF16)
+    X, dY, route = dev(inp["X"]), dev(inp["dY"]), dev(inp["route"], torch.int32)
+    Y = torch.full((w.T, w.O2), float("nan"), device=DEV, dtype=torch.bfloat16)
+    dX = torch.full((w.T, w.I), float("nan"), device=DEV, dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    say("moe_8x_swiglu: GPU forward + backward")
+    moe.forward(X, route, Y)
+    moe.backward(dY, dX)
+    moe.sync()
+    counts, begin, perm = orc.moe_dispatch(inp["route"], w.n, 32)
+    got_counts, got_begin = moe.routing()
+    assert got_counts == counts and got_begin == begin
+    assert moe.perm.cpu().tolist()[:begin[w.n]] == perm
+    assert torch.isfinite(Y.float()).all() and torch.isfinite(dX.float()).all(), "an output element was never written"
+    assert moe.worker_bytes() <= B.rtp_table1_worker_bytes(False, moe.w_bytes, moe.g_bytes)
+    Ws, Gs = moe.gathered()
+    Yh, dXh = host(Y), host(dX)
+    worst = {}
+    for e in range(w.n):
+        toks = np.array([p for p in perm[begin[e]:begin[e + 1]] if p >= 0])
+        assert len(toks) == counts[e] and len(toks) > 0
+        Wg, Wu, Wd = (f64(m) for m in inp["experts"][e])
+        for a, b in zip(Ws[e], inp["experts"][e]):
+            assert torch.equal(a, dev(b)), "weight store changed by the round trip"
+        S = toks[sample_rows(len(toks), 4, rng)]
+        ref = orc.plain_swiglu(f64(inp["X"][S]), Wg, Wu, Wd, f64(inp["dY"][S]))
+        J = sample_rows(w.O, 3, rng)
+        Xe, dYe = f64(inp["X"][toks]), f64(inp["dY"][toks])
+        A = orc.gemm_nt(Xe, np.ascontiguousarray(Wg[J]), np.empty((len(toks), len(J))))
+        Bm = orc.gemm_nt(Xe, np.ascontiguousarray(Wu[J]), np.empty((len(toks), len(J))))
+        sA = orc.act(A, orc.SILU)
+        dH = orc.gemm_nn(dYe, np.ascontiguousarray(Wd[:, J]), np.empty((len(toks), len(J))))
+        refs = {"Y": ref["Y"], "dX": ref["dX"],
+                "dWg": orc.gemm_tn(dH * Bm * orc.act_grad(A, orc.SILU), Xe, np.empty((len(J), w.I))),
+                "dWu": orc.gemm_tn(dH * sA, Xe, np.empty((len(J), w.I))),
+                "dWd": orc.gemm_tn(dYe, sA * Bm, np.empty((w.O2, len(J))))}
+        got = {"Y": Yh[S], "dX": dXh[S], "dWg": host(Gs[e][0][J]), "dWu": host(Gs[e][1][J]), "dWd": host(Gs[e][2][:, J])}
+        for k in refs:
+            worst[k] = max(worst.get(k, 0.0), relerr(got[k], refs[k]))
+        say(f"moe_8x_swiglu: expert {e}, {len(toks)} tokens, worst so far {worst}")
+    moe.close()
+    for k, err in worst.items():
+        assert err <= TOL, (k, err)
