@@ -153,7 +153,10 @@ rtp_status rtp_ring_destroy(rtp_ring *ring);
  * gradient part, after writing the gradient shard an earlier backward pass
  * left in the buffer (the worker's own) back to its slot: gradients
  * accumulate over any number of passes.  RTP_ERR_STATE if a pass is in
- * progress. */
+ * progress.
+ * Stream capture of a pass is not supported: the calls decide on the host,
+ * when they are made, what a pass enqueues (the write-back above, for one),
+ * and use three streams. */
 rtp_status rtp_ring_begin(rtp_ring *ring, rtp_pass pass);
 
 /* Makes shard (rank+1) mod n resident without a forward pass (tests and

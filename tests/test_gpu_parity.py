@@ -591,6 +591,62 @@ def test_mlp_gelu_tanh_variant():
         assert relerr(out[key], ref[key]) <= TOL_BF16, (key, relerr(out[key], ref[key]))
 
 
+# ------------------------------------------------------------ HIP graphs --
+
+@pytest.mark.skip(reason="capturing a linear layer's pass (double-buffer mode, three streams) crashed the host inside the "
+                         "runtime's end-of-capture call; the cause is not established, so stream capture of a pass is "
+                         "documented as unsupported and this case stays off the GPU")
+@pytest.mark.parametrize("mode", [B.RTP_DOUBLE_BUFFER, B.RTP_INPLACE_STAGED])
+def test_captured_pass_replays_like_eager(mode):
+    """A forward + backward pass captured into a HIP graph (after one eager pass, so that the
+    capture holds the write-back of the gradient shard the previous pass ended on) and replayed
+    three times, with eager passes and synchronisations in between: every replay gives the eager
+    outputs, and the gradients count every pass, eager or replayed (integer inputs: bit-exact)."""
+    T, I, O, n = 256, 512, 1024, 4
+    g = torch.Generator(device="cpu").manual_seed(6)
+    ri = lambda lo, hi, shape: torch.randint(lo, hi, shape, generator=g).float()
+    W, X, dY, G0 = ri(-2, 3, (O, I)), ri(-2, 3, (T, I)), ri(-2, 3, (T, O)), ri(-4, 5, (O, I))
+    layer = RtpLinear(W.to(DEV, torch.bfloat16), T, n, 1, B.RTP_SPLIT_OUT, mode, B.RTP_BF16, G0=G0.to(DEV))
+    Xd, dYd = X.to(DEV, torch.bfloat16), dY.to(DEV, torch.bfloat16)
+    Y = torch.empty(T, O, device=DEV, dtype=torch.bfloat16)
+    dX = torch.empty(T, I, device=DEV, dtype=torch.bfloat16)
+    Y_ref = (X.double() @ W.double().T).to(torch.bfloat16)
+    dX_ref = (dY.double() @ W.double()).to(torch.bfloat16)
+    dW = (dY.double().T @ X.double()).float()
+    passes = 0
+
+    def eager():
+        nonlocal passes
+        layer.forward(Xd, Y)
+        layer.backward(Xd, dYd, dX)
+        layer.sync()
+        passes += 1
+
+    eager()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    say(f"capturing a pass, mode {mode}")
+    with torch.cuda.graph(graph, stream=layer.compute_stream, capture_error_mode="relaxed"):
+        layer.forward(Xd, Y)
+        layer.backward(Xd, dYd, dX)
+    torch.cuda.synchronize()             # capture enqueues nothing: the pass has not run
+    for i in range(3):
+        Y.fill_(float("nan"))
+        dX.fill_(float("nan"))
+        torch.cuda.synchronize()
+        say(f"replay {i}")
+        graph.replay()
+        torch.cuda.synchronize()
+        passes += 1
+        assert torch.equal(Y.cpu(), Y_ref) and torch.equal(dX.cpu(), dX_ref), f"replay {i}"
+        eager()
+        assert torch.equal(Y.cpu(), Y_ref) and torch.equal(dX.cpu(), dX_ref)
+    _, G = layer.gathered()
+    assert torch.equal(G.cpu(), G0 + passes * dW), "every pass, eager or replayed, adds its weight gradient once"
+    del graph
+    layer.close()
+
+
 # ------------------------------------------------------- expert partition --
 
 def _moe_case(T, I, O, O2, n, rank, mode, gated, dtype="bf16", seed=0, skew=1.0, route=None, aux_stream=True, passes=1):
