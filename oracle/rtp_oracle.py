@@ -185,16 +185,17 @@ def plain_bias_grad(dY):
     return db
 
 
-def plain_mlp(X, W1, W2, dY, kind=GELU_ERF):
+def plain_mlp(X, W1, W2, dY, kind=GELU_ERF, b1=None, b2=None):
     """MLP block: a GEMM, the nonlinearity, a second GEMM (RTP Transformers
-    section, linear-block item).  Returns a dict of every tensor."""
-    Z = plain_linear_fwd(X, W1)
+    section, linear-block item), each with an optional bias.  Returns a dict
+    of every tensor."""
+    Z = plain_linear_fwd(X, W1, b1)
     H = act(Z, kind)
-    Y = plain_linear_fwd(H, W2)
+    Y = plain_linear_fwd(H, W2, b2)
     dH, dW2 = plain_linear_bwd(H, W2, dY)
     dZ = dH * act_grad(Z, kind)
     dX, dW1 = plain_linear_bwd(X, W1, dZ)
-    return dict(Z=Z, H=H, Y=Y, dH=dH, dZ=dZ, dX=dX, dW1=dW1, dW2=dW2)
+    return dict(Z=Z, H=H, Y=Y, dH=dH, dZ=dZ, dX=dX, dW1=dW1, dW2=dW2, db1=plain_bias_grad(dZ), db2=plain_bias_grad(dY))
 
 
 def plain_swiglu(X, Wg, Wu, Wd, dY):
@@ -341,17 +342,50 @@ def rtp_linear_out_bias(X, W, b, dY, n, rank, G0=None, gb0=None):
     return out
 
 
-def rtp_linear_in(Xin, W, dY, n, rank, G0=None):
+def bias_pieces(O, n):
+    """The bias of an input-partitioned layer is not partitioned by the layer's
+    own split; the flat parameter spreads it evenly over the N shards
+    (FlatParameter paragraph): piece k = entries [k p, (k+1) p) of b with
+    p = ceil(O / N), the last pieces short or empty."""
+    p = -(-O // n)
+    return [(min(k * p, O), min((k + 1) * p, O)) for k in range(n)]
+
+
+def _padded_pieces(v, pieces):
+    """The pieces of a vector as equal-sized arrays, the short ones padded with zeros (the flat
+    parameter's padding): every shard of the ring has the same size."""
+    p = max(hi - lo for lo, hi in pieces)
+    out = []
+    for lo, hi in pieces:
+        a = np.zeros(p)
+        a[:hi - lo] = v[lo:hi]
+        out.append(a)
+    return out
+
+
+def _unpad_pieces(arrs, pieces):
+    return np.concatenate([a[:hi - lo] for a, (lo, hi) in zip(arrs, pieces)])
+
+
+def rtp_linear_in(Xin, W, dY, n, rank, G0=None, b=None, gb0=None):
     """Input-partitioned linear (the layer that follows a column-partitioned
     one: Partition Strategies section, second item).  Shard k is columns
     [k o, (k+1) o) of W[O, I]; forward sums the N partial products into Y,
     backward writes the matching column slice of dXin and adds dY^T Xin_k
-    onto the travelling gradient shard."""
+    onto the travelling gradient shard.  With a bias, shard k also carries
+    piece k of b (bias_pieces): its step adds the piece to its entries of every
+    output row, and in the backward pass the piece's gradient (column sums of
+    dY) is added onto the piece of the travelling gradient shard."""
     T, I = Xin.shape
     O = W.shape[0]
     if G0 is None:
         G0 = np.zeros((O, I))
     ring = _Ring(_split_cols(W, n), _split_cols(G0, n), rank)
+    pieces = bias_pieces(O, n)
+    if b is not None:
+        b = np.asarray(b, dtype=np.float64)
+        gb0 = np.zeros(O) if gb0 is None else np.asarray(gb0, dtype=np.float64)
+        bring = _Ring(_padded_pieces(b, pieces), _padded_pieces(gb0, pieces), rank)
     Y = np.zeros((T, O))
     fwd_log, bwd_log = [], []
     for t in range(n):
@@ -359,35 +393,60 @@ def rtp_linear_in(Xin, W, dY, n, rank, G0=None):
         assert k == fwd_shard(rank, t, n)
         lo, hi = shard_rows(k, I, n)
         gemm_nt(Xin[:, lo:hi], ring.res_w, Y, accumulate=True)
+        if b is not None:
+            assert bring.res_id == k
+            plo, phi = pieces[k]
+            for row in range(T):
+                Y[row, plo:phi] += bring.res_w[:phi - plo]
         fwd_log.append((t, k))
         if t < n - 1:
             ring.rotate((k - 1) % n, with_grad=False)
+            if b is not None:
+                bring.rotate((k - 1) % n, with_grad=False)
     res_after_fwd = ring.res_id
     dXin = np.full((T, I), np.nan)
     ring.begin_backward()
+    if b is not None:
+        bring.begin_backward()
     for s in range(n):
         k = ring.res_id
         assert k == bwd_shard(rank, s, n)
         lo, hi = shard_rows(k, I, n)
         gemm_tn(dY, Xin[:, lo:hi], ring.res_g, accumulate=True)
         gemm_nn(dY, ring.res_w, dXin[:, lo:hi])
+        if b is not None:
+            assert bring.res_id == k
+            plo, phi = pieces[k]
+            bring.res_g[:phi - plo] += plain_bias_grad(np.ascontiguousarray(dY[:, plo:phi]))
         bwd_log.append((s, k))
         if s < n - 1:
             ring.rotate((k + 1) % n, with_grad=True)
+            if b is not None:
+                bring.rotate((k + 1) % n, with_grad=True)
     G = [g.copy() for g in ring.home_g]
     G[ring.res_id] = ring.res_g.copy()
     Wback = [w.copy() for w in ring.home_w]
     Wback[ring.res_id] = ring.res_w.copy()
-    return dict(Y=Y, dX=dXin, G=np.concatenate(G, axis=1), W_after=np.concatenate(Wback, axis=1),
-                fwd_log=fwd_log, bwd_log=bwd_log, resident_after_fwd=res_after_fwd,
-                resident_after_bwd=ring.res_id)
+    out = dict(Y=Y, dX=dXin, G=np.concatenate(G, axis=1), W_after=np.concatenate(Wback, axis=1),
+               fwd_log=fwd_log, bwd_log=bwd_log, resident_after_fwd=res_after_fwd,
+               resident_after_bwd=ring.res_id)
+    if b is not None:
+        gb = [g.copy() for g in bring.home_g]
+        gb[bring.res_id] = bring.res_g.copy()
+        bb = [w.copy() for w in bring.home_w]
+        bb[bring.res_id] = bring.res_w.copy()
+        out["gb"] = _unpad_pieces(gb, pieces)
+        out["b_after"] = _unpad_pieces(bb, pieces)
+    return out
 
 
-def rtp_mlp(X, W1, W2, dY, n, rank, kind=GELU_ERF, G1_0=None, G2_0=None):
+def rtp_mlp(X, W1, W2, dY, n, rank, kind=GELU_ERF, G1_0=None, G2_0=None, b1=None, b2=None, gb1_0=None, gb2_0=None):
     """MLP block with W1 output-partitioned and W2 input-partitioned, so that
     unit k = (rows k of W1, columns k of W2) is self-contained and the two
     shards rotate as one message (the FlatParameter idea).  Step order is the
-    rotation schedule; inside a step the order is the chain rule's."""
+    rotation schedule; inside a step the order is the chain rule's.  Optional
+    biases (both or none): b1's entries ride with their rows of W1, b2 is
+    spread over the shards in pieces (bias_pieces)."""
     T, I = X.shape
     O1 = W1.shape[0]
     O2 = W2.shape[0]
@@ -395,41 +454,71 @@ def rtp_mlp(X, W1, W2, dY, n, rank, kind=GELU_ERF, G1_0=None, G2_0=None):
     G2_0 = np.zeros_like(W2) if G2_0 is None else G2_0
     r1 = _Ring(_split_rows(W1, n), _split_rows(G1_0, n), rank)
     r2 = _Ring(_split_cols(W2, n), _split_cols(G2_0, n), rank)
+    rings = [r1, r2]
+    biased = b1 is not None
+    assert biased == (b2 is not None)
+    if biased:
+        b1, b2 = np.asarray(b1, dtype=np.float64), np.asarray(b2, dtype=np.float64)
+        gb1_0 = np.zeros(O1) if gb1_0 is None else np.asarray(gb1_0, dtype=np.float64)
+        gb2_0 = np.zeros(O2) if gb2_0 is None else np.asarray(gb2_0, dtype=np.float64)
+        rows = [shard_rows(k, O1, n) for k in range(n)]
+        pieces = bias_pieces(O2, n)
+        rb1 = _Ring([b1[lo:hi].copy() for lo, hi in rows], [gb1_0[lo:hi].copy() for lo, hi in rows], rank)
+        rb2 = _Ring(_padded_pieces(b2, pieces), _padded_pieces(gb2_0, pieces), rank)
+        rings += [rb1, rb2]
     Z = np.full((T, O1), np.nan)
     H = np.full((T, O1), np.nan)
     Y = np.zeros((T, O2))
     for t in range(n):
         k = r1.res_id
-        assert k == r2.res_id == fwd_shard(rank, t, n)
+        assert all(r_.res_id == k for r_ in rings) and k == fwd_shard(rank, t, n)
         lo, hi = shard_rows(k, O1, n)
         gemm_nt(X, r1.res_w, Z[:, lo:hi])
+        if biased:
+            for row in range(T):
+                Z[row, lo:hi] += rb1.res_w
         H[:, lo:hi] = act(Z[:, lo:hi], kind)
         gemm_nt(np.ascontiguousarray(H[:, lo:hi]), r2.res_w, Y, accumulate=True)
+        if biased:
+            plo, phi = pieces[k]
+            for row in range(T):
+                Y[row, plo:phi] += rb2.res_w[:phi - plo]
         if t < n - 1:
-            r1.rotate((k - 1) % n, with_grad=False)
-            r2.rotate((k - 1) % n, with_grad=False)
+            for r_ in rings:
+                r_.rotate((k - 1) % n, with_grad=False)
     dX = np.zeros((T, I))
-    r1.begin_backward()
-    r2.begin_backward()
+    for r_ in rings:
+        r_.begin_backward()
     for s in range(n):
         k = r1.res_id
-        assert k == r2.res_id == bwd_shard(rank, s, n)
+        assert all(r_.res_id == k for r_ in rings) and k == bwd_shard(rank, s, n)
         lo, hi = shard_rows(k, O1, n)
         Hk = np.ascontiguousarray(H[:, lo:hi])
         gemm_tn(dY, Hk, r2.res_g, accumulate=True)
+        if biased:
+            plo, phi = pieces[k]
+            rb2.res_g[:phi - plo] += plain_bias_grad(np.ascontiguousarray(dY[:, plo:phi]))
         dHk = gemm_nn(dY, r2.res_w, np.empty((T, hi - lo)))
         dZk = dHk * act_grad(Z[:, lo:hi], kind)
         gemm_tn(dZk, X, r1.res_g, accumulate=True)
+        if biased:
+            rb1.res_g += plain_bias_grad(dZk)
         gemm_nn(dZk, r1.res_w, dX, accumulate=True)
         if s < n - 1:
-            r1.rotate((k + 1) % n, with_grad=True)
-            r2.rotate((k + 1) % n, with_grad=True)
-    G1 = [g.copy() for g in r1.home_g]
-    G1[r1.res_id] = r1.res_g.copy()
-    G2 = [g.copy() for g in r2.home_g]
-    G2[r2.res_id] = r2.res_g.copy()
-    return dict(Z=Z, H=H, Y=Y, dX=dX, dW1=np.concatenate(G1, axis=0), dW2=np.concatenate(G2, axis=1),
-                resident_after_bwd=r1.res_id)
+            for r_ in rings:
+                r_.rotate((k + 1) % n, with_grad=True)
+
+    def gather(ring, axis):
+        g = [x.copy() for x in ring.home_g]
+        g[ring.res_id] = ring.res_g.copy()
+        return np.concatenate(g, axis=axis)
+
+    out = dict(Z=Z, H=H, Y=Y, dX=dX, dW1=gather(r1, 0), dW2=gather(r2, 1), resident_after_bwd=r1.res_id)
+    if biased:
+        g2 = [x.copy() for x in rb2.home_g]
+        g2[rb2.res_id] = rb2.res_g.copy()
+        out["db1"], out["db2"] = gather(rb1, 0), _unpad_pieces(g2, pieces)
+    return out
 
 
 def rtp_swiglu(X, Wg, Wu, Wd, dY, n, rank, Gg0=None, Gu0=None, Gd0=None):

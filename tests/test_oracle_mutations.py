@@ -138,3 +138,11 @@ def test_wrong_memory_row_is_caught(monkeypatch):
     plant(monkeypatch, "param_bytes", lambda tech, W, G, n: real(tech, W, G, n) + (W // n if n > 1 else 1))
     assert some_pin_fails(lambda: pins.test_table1_closed_forms(1000, 2000, 4),
                           lambda: pins.test_table1_large_config_numbers())
+
+
+def test_bias_piece_added_at_every_step_is_caught(monkeypatch):
+    # every shard carrying the whole first piece: entries of b added N times or never
+    real = impl.bias_pieces
+    plant(monkeypatch, "bias_pieces", lambda O, n: [real(O, n)[0]] * n)
+    assert some_pin_fails(lambda: pins.test_input_partition_bias_spread_over_the_shards(3, 7))
+    assert some_pin_fails(lambda: pins.test_mlp_with_biases_rotated_matches_plain_numpy_and_fd(orc.GELU_ERF))

@@ -533,3 +533,60 @@ def test_moe_gradients_by_finite_differences(gated):
             exm[e][j][r, c] -= h
             fd = (loss(X, exp_) - loss(X, exm)) / (2 * h)
             assert abs(fd - out["G"][e][j][r, c]) < 1e-6, (e, j)
+
+
+# ------------------------------------ bias of the input-partitioned layer --
+
+@pytest.mark.parametrize("n,O", [(1, 7), (3, 7), (4, 8), (8, 5)])
+def test_input_partition_bias_spread_over_the_shards(n, O):
+    """Pieces of b ride with the shards (the last ones short or empty when N does not divide, or
+    exceeds, the output width): the sum over the steps is X W^T + b, the pieces' gradients are the
+    column sums of dY on top of what arrived, from every rank; numpy is the reference."""
+    rng = np.random.default_rng(40 + n)
+    T, I = 6, 4 * n
+    X, W, dY = rng.standard_normal((T, I)), rng.standard_normal((O, I)), rng.standard_normal((T, O))
+    b, gb0, G0 = rng.standard_normal(O), rng.standard_normal(O), rng.standard_normal((O, I))
+    pieces = orc.bias_pieces(O, n)
+    assert pieces[0][0] == 0 and pieces[-1][1] == O and all(a[1] == c[0] for a, c in zip(pieces, pieces[1:]))
+    sizes = [hi - lo for lo, hi in pieces]
+    assert sum(sizes) == O and max(sizes) == -(-O // n) and sizes == sorted(sizes, reverse=True)
+    for rank in range(n):
+        out = orc.rtp_linear_in(X, W, dY, n, rank, G0=G0, b=b, gb0=gb0)
+        np.testing.assert_allclose(out["Y"], X @ W.T + b[None, :], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(out["gb"], gb0 + dY.sum(axis=0), rtol=0, atol=1e-12)
+        np.testing.assert_allclose(out["G"], G0 + dY.T @ X, rtol=0, atol=1e-12)
+        np.testing.assert_allclose(out["dX"], dY @ W, rtol=0, atol=1e-12)
+        assert np.array_equal(out["b_after"], b) and np.array_equal(out["W_after"], W)
+    # W = 0: the output is the bias on every row
+    out = orc.rtp_linear_in(X, np.zeros_like(W), dY, n, 0, b=b)
+    assert np.array_equal(out["Y"], np.tile(b, (T, 1)))
+
+
+@pytest.mark.parametrize("kind", [orc.GELU_ERF, orc.GELU_TANH])
+def test_mlp_with_biases_rotated_matches_plain_numpy_and_fd(kind):
+    from scipy.special import erf
+    rng = np.random.default_rng(77)
+    n, T, I, O1, O2 = 4, 5, 6, 8, 7
+    X, dY = rng.standard_normal((T, I)), rng.standard_normal((T, O2))
+    W1, W2 = 0.5 * rng.standard_normal((O1, I)), 0.5 * rng.standard_normal((O2, O1))
+    b1, b2 = rng.standard_normal(O1), rng.standard_normal(O2)
+    gb1_0, gb2_0 = rng.standard_normal(O1), rng.standard_normal(O2)
+    ref = orc.plain_mlp(X, W1, W2, dY, kind, b1=b1, b2=b2)
+    if kind == orc.GELU_ERF:
+        z = X @ W1.T + b1
+        np.testing.assert_allclose(ref["Y"], (0.5 * z * (1 + erf(z / np.sqrt(2)))) @ W2.T + b2, rtol=1e-12, atol=1e-12)
+    for rank in (0, 3):
+        out = orc.rtp_mlp(X, W1, W2, dY, n, rank, kind, b1=b1, b2=b2, gb1_0=gb1_0, gb2_0=gb2_0)
+        for key in ("Y", "dX", "dW1", "dW2"):
+            np.testing.assert_allclose(out[key], ref[key], rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(out["db1"], gb1_0 + ref["db1"], rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(out["db2"], gb2_0 + ref["db2"], rtol=1e-12, atol=1e-12)
+    # finite differences of L = sum(Y * dY) in the two biases
+    out = orc.rtp_mlp(X, W1, W2, dY, n, 1, kind, b1=b1, b2=b2)
+    h = 1e-6
+    loss = lambda c1, c2: float((orc.plain_mlp(X, W1, W2, dY, kind, b1=c1, b2=c2)["Y"] * dY).sum())
+    for j in (0, 5):
+        e1, e2 = np.zeros(O1), np.zeros(O2)
+        e1[j], e2[j] = h, h
+        assert abs((loss(b1 + e1, b2) - loss(b1 - e1, b2)) / (2 * h) - out["db1"][j]) < 1e-6
+        assert abs((loss(b1, b2 + e2) - loss(b1, b2 - e2)) / (2 * h) - out["db2"][j]) < 1e-6
