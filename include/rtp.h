@@ -228,12 +228,22 @@ typedef struct {
     float *acc_ws_dev;    /* fp32 [T, I] (SPLIT_OUT, dX) or [T, O] (SPLIT_IN, Y):
                              cross-step accumulator; needed when dtype != F32
                              and n > 1                                            */
-    int has_bias;         /* RTP_SPLIT_OUT only: the layer is Y = X W^T + b.  The
-                             bias rides in the flat parameter: shard k's w entries
-                             of b follow its rows of W in the slot (at w_offset +
-                             w * I * sizeof(dtype)), and the fp32 bias gradient
-                             follows the matrix gradient the same way             */
+    int has_bias;         /* the layer is Y = X W^T + b.  The bias rides in the flat
+                             parameter (FlatParameter paragraph).  RTP_SPLIT_OUT:
+                             shard k's w entries of b follow its rows of W in the
+                             slot (at w_offset + w * I * sizeof(dtype)).
+                             RTP_SPLIT_IN: b is spread evenly over the shards, piece
+                             k = entries [k p, (k+1) p) with
+                             p = rtp_bias_piece_width(O, n, dtype) (zero padding
+                             past O), after shard k's [O, w] matrix; shard k's step
+                             adds its piece.  The fp32 bias gradient follows the
+                             matrix gradient the same way                          */
 } rtp_linear_desc;
+
+/* Entries of the bias piece an input-partitioned layer's shard carries:
+ * ceil(O / n) rounded up to a whole number of 16-byte units.  -1 for bad
+ * arguments. */
+int64_t rtp_bias_piece_width(int64_t O, int n, rtp_dtype dtype);
 
 /* Bytes one shard of the layer takes in the weight part / the gradient part
  * of a slot (matrix shard, bias shard if any, rounded up to 16); 0 on a bad
@@ -299,6 +309,10 @@ typedef struct {
     float *acc_dx_dev;    /* fp32 [T, I]                                           */
     void *compute_stream, *stage_stream;
     void *aux_stream;     /* optional, as in rtp_ring_desc                           */
+    int has_bias;         /* both linears carry a bias (GELU_* units only): slot =
+                             [W1_k | b1_k | W2_k | piece k of b2], each part padded to
+                             16 bytes as rtp_linear_shard_w_bytes gives it; such a
+                             unit runs step by step                                  */
 } rtp_mlp_desc;
 
 size_t rtp_mlp_slot_w_bytes(const rtp_mlp_desc *d);

@@ -53,7 +53,8 @@ class rtp_mlp_desc(C.Structure):
                 ("buf_w_dev", C.c_void_p * 2), ("buf_g_dev", C.c_void_p * 2),
                 ("preact_dev", C.c_void_p), ("hidden_dev", C.c_void_p), ("dpre_dev", C.c_void_p),
                 ("acc_y_dev", C.c_void_p), ("acc_dx_dev", C.c_void_p),
-                ("compute_stream", C.c_void_p), ("stage_stream", C.c_void_p), ("aux_stream", C.c_void_p)]
+                ("compute_stream", C.c_void_p), ("stage_stream", C.c_void_p), ("aux_stream", C.c_void_p),
+                ("has_bias", C.c_int)]
 
 
 class rtp_moe_desc(C.Structure):
@@ -83,6 +84,7 @@ SYMBOLS = {
     "rtp_bwd_shard": (C.c_int, [C.c_int, C.c_int, C.c_int]),
     "rtp_shard_begin": (C.c_int64, [C.c_int, C.c_int64, C.c_int]),
     "rtp_shard_width": (C.c_int64, [C.c_int64, C.c_int, C.c_int]),
+    "rtp_bias_piece_width": (C.c_int64, [C.c_int64, C.c_int, C.c_int]),
     "rtp_linear_shard_w_bytes": (C.c_size_t, [C.POINTER(rtp_linear_desc), C.c_int]),
     "rtp_linear_shard_g_bytes": (C.c_size_t, [C.POINTER(rtp_linear_desc), C.c_int]),
     "rtp_worker_bytes": (C.c_size_t, [C.c_int, C.c_size_t, C.c_size_t]),

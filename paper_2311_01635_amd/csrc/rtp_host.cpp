@@ -588,13 +588,23 @@ extern "C" rtp_status rtp_ring_sync(rtp_ring *r)
 // ---------------------------------------------------------------------------
 static size_t esize(rtp_dtype t) { return t == RTP_F32 ? 4 : 2; }
 
+// Entries of the bias piece an input-partitioned layer's shard carries: ceil(O / n), rounded up so
+// that the piece is a whole number of 16-byte units in the parameter's and the gradient's type.
+extern "C" int64_t rtp_bias_piece_width(int64_t O, int n, rtp_dtype dtype)
+{
+    if (O <= 0 || n < 1) return -1;
+    const int64_t p = (O + n - 1) / n, al = dtype == RTP_F32 ? 4 : 8;
+    return (p + al - 1) / al * al;
+}
+
 static size_t shard_bytes(const rtp_linear_desc *d, int n, size_t es)
 {
     if (!d || n <= 0 || d->I <= 0 || d->O <= 0) return 0;
     const int64_t o = rtp_shard_width(d->split == RTP_SPLIT_OUT ? d->O : d->I, n, d->dtype);
     if (o <= 0) return 0;
     const size_t other = (size_t)(d->split == RTP_SPLIT_OUT ? d->I : d->O);
-    const size_t elems = (size_t)o * other + (d->has_bias ? (size_t)o : 0);
+    const size_t bias = !d->has_bias ? 0 : d->split == RTP_SPLIT_OUT ? (size_t)o : (size_t)rtp_bias_piece_width(d->O, n, d->dtype);
+    const size_t elems = (size_t)o * other + bias;
     return (elems * es + 15) & ~(size_t)15;
 }
 
@@ -638,8 +648,6 @@ extern "C" rtp_status rtp_linear_create(rtp_linear **out, rtp_ring *ring, const 
             return fail(RTP_ERR_UNSUPPORTED, "rtp_linear_create: fp16 inputs need T, the shard width and the other "
                                              "matrix dimension to be multiples of 32");
     }
-    if (d->has_bias && d->split != RTP_SPLIT_OUT)
-        return fail(RTP_ERR_UNSUPPORTED, "rtp_linear_create: a bias is built for output-partitioned layers only");
     const size_t wsz = rtp_linear_shard_w_bytes(d, n);   // a padded shard is stored at its full width
     const size_t gsz = rtp_linear_shard_g_bytes(d, n);
     if ((d->w_offset & 15) || (d->g_offset & 15)) return fail(RTP_ERR_SHAPE, "rtp_linear_create: offsets must be multiples of 16");
@@ -781,7 +789,24 @@ extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, voi
             if (r->abl_rotate && step > 0 && r->d.mode != RTP_INPLACE_BLOCKING)
                 HIP_TRY(hipStreamWaitEvent(fs, r->ev_w[step & 1], 0));
         }
+        // The bias of this layer is spread over the shards in pieces; shard k's piece, which follows
+        // its matrix in the slot, is added to its entries of every output row at shard k's step:
+        // onto the fp32 sum (after the kernel that starts it, before the kernel that rounds it),
+        // or inside the kernel when there is only one step.
+        const int64_t pb = d.has_bias ? rtp_bias_piece_width(d.O, n, d.dtype) : 0;
+        const int64_t pv = d.has_bias ? std::max<int64_t>(0, std::min<int64_t>(pb, d.O - (int64_t)k * pb)) : 0;
+        const char *bk = Wk + (size_t)d.O * o * es;
+        const int belem = f32 ? -1 : d.dtype == RTP_F16 ? ELEM_F16 : ELEM_BF16;
+        const bool live = pv > 0 && !r->dry && r->abl_compute && d.T > 0;
+        float *bdst = (f32 ? (float *)Y : d.acc_ws_dev) + (size_t)k * pb;
+        bool after = false;
+        if (live) {
+            if (f32 || (n > 1 && step == 0)) after = true;
+            else if (n == 1) a.bias = bk;
+            else HIP_TRY(launch_bias_add(belem, bdst, d.O, (int)d.T, (int)pv, bk, fs));
+        }
         RTP_TRY(gemm(l, LAY_NT, a, fs));
+        if (after) HIP_TRY(launch_bias_add(belem, bdst, d.O, (int)d.T, (int)pv, bk, fs));
     }
     l->next_step = step + 1;
     return RTP_OK;
@@ -863,11 +888,15 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
     if (d.has_bias && !r->dry && r->abl_compute) {
         // bias gradient: column sums of this shard's slice of dY, onto the entries that follow the
         // matrix gradient in the travelling shard (and out to where it travels, like the matrix part)
-        const size_t boff = (size_t)o * d.I * 4;
+        // (input-partitioned layer: the shard carries a piece of the bias, the columns of dY that piece covers)
+        const bool out_split = d.split == RTP_SPLIT_OUT;
+        const int64_t pb = out_split ? o : rtp_bias_piece_width(d.O, n, d.dtype);
+        const int64_t pv = out_split ? ov : std::max<int64_t>(0, std::min<int64_t>(pb, d.O - (int64_t)k * pb));
+        const size_t boff = (out_split ? (size_t)o * d.I : (size_t)d.O * o) * 4;
         const float *gb_in = (const float *)((const char *)Gk + boff);
         float *gb_out = fused_send ? (float *)(r->home_g(k) + d.g_offset + boff) : (float *)((char *)Gk + boff);
         const int elem = f32 ? -1 : d.dtype == RTP_F16 ? ELEM_F16 : ELEM_BF16;
-        HIP_TRY(launch_colsum(elem, (const char *)dY + (size_t)k * o * es, d.O, (int)d.T, (int)ov, gb_in, gb_out, ws));
+        HIP_TRY(launch_colsum(elem, (const char *)dY + (size_t)k * pb * es, d.O, (int)d.T, (int)pv, gb_in, gb_out, ws));
         // (padding entries of a partly filled shard are zero in the buffer and in the slot alike, and nobody
         // writes them)
     }
@@ -956,18 +985,38 @@ struct rtp_mlp {
 
 static bool mlp_gated(const rtp_mlp_desc *d) { return d->act == RTP_ACT_SWIGLU; }
 
+// the unit's two linears: the first output-partitioned with the activation, the second input-partitioned
+static void mlp_linear_descs(const rtp_mlp_desc *d, rtp_linear_desc *l1, rtp_linear_desc *l2)
+{
+    const int64_t p = mlp_gated(d) ? 2 : 1;
+    memset(l1, 0, sizeof *l1);
+    l1->T = d->T; l1->I = d->I; l1->O = p * d->O;
+    l1->split = RTP_SPLIT_OUT; l1->dtype = d->dtype; l1->grad_dtype = RTP_F32; l1->act = d->act;
+    l1->preact_dev = d->preact_dev; l1->acc_ws_dev = d->acc_dx_dev;
+    l1->has_bias = d->has_bias;
+    memset(l2, 0, sizeof *l2);
+    l2->T = d->T; l2->I = d->O; l2->O = d->O2;
+    l2->split = RTP_SPLIT_IN; l2->dtype = d->dtype; l2->grad_dtype = RTP_F32; l2->act = d->act;
+    l2->preact_dev = d->preact_dev; l2->acc_ws_dev = d->acc_y_dev;
+    l2->has_bias = d->has_bias;
+    l2->w_offset = rtp_linear_shard_w_bytes(l1, d->n);
+    l2->g_offset = rtp_linear_shard_g_bytes(l1, d->n);
+}
+
 extern "C" size_t rtp_mlp_slot_w_bytes(const rtp_mlp_desc *d)
 {
-    if (!d || d->n < 1) return 0;
-    const size_t p = mlp_gated(d) ? 2 : 1;
-    return (p * (size_t)d->O * d->I + (size_t)d->O2 * d->O) / (size_t)d->n * esize(d->dtype);
+    if (!d || d->n < 1 || d->O <= 0 || d->I <= 0 || d->O2 <= 0 || d->O % d->n != 0) return 0;
+    rtp_linear_desc l1, l2;
+    mlp_linear_descs(d, &l1, &l2);
+    return l2.w_offset + rtp_linear_shard_w_bytes(&l2, d->n);
 }
 
 extern "C" size_t rtp_mlp_slot_g_bytes(const rtp_mlp_desc *d)
 {
-    if (!d || d->n < 1) return 0;
-    const size_t p = mlp_gated(d) ? 2 : 1;
-    return (p * (size_t)d->O * d->I + (size_t)d->O2 * d->O) / (size_t)d->n * 4;
+    if (!d || d->n < 1 || d->O <= 0 || d->I <= 0 || d->O2 <= 0 || d->O % d->n != 0) return 0;
+    rtp_linear_desc l1, l2;
+    mlp_linear_descs(d, &l1, &l2);
+    return l2.g_offset + rtp_linear_shard_g_bytes(&l2, d->n);
 }
 
 extern "C" rtp_status rtp_mlp_create(rtp_mlp **out, const rtp_mlp_desc *d)
@@ -977,8 +1026,8 @@ extern "C" rtp_status rtp_mlp_create(rtp_mlp **out, const rtp_mlp_desc *d)
     if (d->act == RTP_ACT_NONE) return fail(RTP_ERR_INVALID, "rtp_mlp_create: an MLP block has an activation");
     if (d->n < 1 || d->O <= 0 || d->I <= 0 || d->O2 <= 0 || d->O % d->n != 0)
         return fail(RTP_ERR_SHAPE, "rtp_mlp_create: n must divide the hidden width");
-    const bool gated = mlp_gated(d);
-    const size_t p = gated ? 2 : 1;
+    if (d->has_bias && mlp_gated(d))
+        return fail(RTP_ERR_UNSUPPORTED, "rtp_mlp_create: biases are built for the one-matrix activations");
     rtp_ring_desc rd;
     memset(&rd, 0, sizeof rd);
     rd.n = d->n; rd.rank = d->rank; rd.mode = d->mode; rd.flags = d->flags;
@@ -993,19 +1042,8 @@ extern "C" rtp_status rtp_mlp_create(rtp_mlp **out, const rtp_mlp_desc *d)
     m->d = *d;
     rtp_status s = rtp_ring_create(&m->ring, &rd);
     if (s != RTP_OK) { delete m; return s; }
-    const size_t w1 = p * (size_t)d->O * d->I / (size_t)d->n;
-    rtp_linear_desc l1;
-    memset(&l1, 0, sizeof l1);
-    l1.T = d->T; l1.I = d->I; l1.O = (int64_t)p * d->O;
-    l1.split = RTP_SPLIT_OUT; l1.dtype = d->dtype; l1.grad_dtype = RTP_F32; l1.act = d->act;
-    l1.w_offset = 0; l1.g_offset = 0;
-    l1.preact_dev = d->preact_dev; l1.acc_ws_dev = d->acc_dx_dev;
-    rtp_linear_desc l2;
-    memset(&l2, 0, sizeof l2);
-    l2.T = d->T; l2.I = d->O; l2.O = d->O2;
-    l2.split = RTP_SPLIT_IN; l2.dtype = d->dtype; l2.grad_dtype = RTP_F32; l2.act = d->act;
-    l2.w_offset = w1 * esize(d->dtype); l2.g_offset = w1 * 4;
-    l2.preact_dev = d->preact_dev; l2.acc_ws_dev = d->acc_y_dev;
+    rtp_linear_desc l1, l2;
+    mlp_linear_descs(d, &l1, &l2);
     s = rtp_linear_create(&m->l1, m->ring, &l1);
     if (s == RTP_OK) s = rtp_linear_create(&m->l2, m->ring, &l2);
     if (s == RTP_OK && !(d->flags & RTP_FLAG_DRY_RUN) && (!d->hidden_dev || !d->dpre_dev))
@@ -1169,6 +1207,7 @@ static bool mlp_grouped_ok(const rtp_mlp *m, const void *X, const void *Y, const
 {
     const rtp_ring *r = m->ring;
     if (r->dry || (m->d.flags & RTP_FLAG_STEPWISE) || m->d.dtype == RTP_F32 || m->d.T <= 0) return false;
+    if (m->d.has_bias) return false; // the grouped launches are built for units without biases
     if (r->d.mode == RTP_INPLACE_BLOCKING) return false;
     const MlpShapes h = mlp_shapes(m);
     const char *W = (const char *)r->d.buf_w_dev[0];

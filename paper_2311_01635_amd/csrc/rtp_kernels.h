@@ -90,6 +90,10 @@ hipError_t launch_gather_rows(void *out, const void *in, const int *perm, int ro
 // out[perm[p], :] = in[p, :] where perm[p] >= 0
 hipError_t launch_scatter_rows(void *out, const void *in, const int *perm, int rows, size_t row_bytes, hipStream_t s);
 
+// dst[r, c] += bias[c] for r < rows, c < cols (dst fp32 with leading dimension ld; bias in the
+// element type: -1 fp32, ELEM_BF16, ELEM_F16)
+hipError_t launch_bias_add(int elem, float *dst, int64_t ld, int rows, int cols, const void *bias, hipStream_t s);
+
 // out[0] = wall-clock ticks, out[1] = shader cycles over a spin of wall_ticks
 hipError_t launch_clock_probe(long long *out, long long wall_ticks, hipStream_t s);
 

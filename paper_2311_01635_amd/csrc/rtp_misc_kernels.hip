@@ -1,6 +1,7 @@
 // fp32 path of the partition GEMM (the small fp32 configuration), the
 // elementwise activation kernels that path uses, and the shard-staging copy.
 #include "rtp_kernels.h"
+#include <algorithm>
 
 namespace rtp {
 
@@ -198,6 +199,29 @@ hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s)
     const int64_t n16 = (int64_t)(bytes >> 4);
     const int blocks = (int)((n16 + 255) / 256 > 4096 ? 4096 : (n16 + 255) / 256);
     hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, (u32x4 *)dst, n16);
+    return hipGetLastError();
+}
+
+// ---- bias piece of an input-partitioned layer, added onto a slice of the fp32 accumulator ----------
+template <typename T>
+__global__ __launch_bounds__(256) void bias_add_kernel(float *dst, int64_t ld, int rows, int cols, const T *bias)
+{
+    const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+    if (c >= cols) return;
+    const float b = (float)bias[c];
+    for (int r = blockIdx.y * 4 + (threadIdx.x >> 6); r < rows; r += gridDim.y * 4) dst[(int64_t)r * ld + c] += b;
+}
+
+hipError_t launch_bias_add(int elem, float *dst, int64_t ld, int rows, int cols, const void *bias, hipStream_t s)
+{
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    const dim3 grid((unsigned)((cols + 63) / 64), (unsigned)std::min(1024, (rows + 3) / 4)), block(256);
+    if (elem == ELEM_BF16)
+        hipLaunchKernelGGL(bias_add_kernel<__bf16>, grid, block, 0, s, dst, ld, rows, cols, (const __bf16 *)bias);
+    else if (elem == ELEM_F16)
+        hipLaunchKernelGGL(bias_add_kernel<_Float16>, grid, block, 0, s, dst, ld, rows, cols, (const _Float16 *)bias);
+    else
+        hipLaunchKernelGGL(bias_add_kernel<float>, grid, block, 0, s, dst, ld, rows, cols, (const float *)bias);
     return hipGetLastError();
 }
 

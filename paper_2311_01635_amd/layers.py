@@ -81,11 +81,14 @@ class RtpLinear:
             d = B.rtp_linear_desc()
             d.T, d.I, d.O, d.split, d.dtype, d.grad_dtype, d.has_bias = T, self.I, self.O, split, dtype, B.RTP_F32, 1
             wbytes, gbytes = B.lib.rtp_linear_shard_w_bytes(C.byref(d), n), B.lib.rtp_linear_shard_g_bytes(C.byref(d), n)
+            # (an input-partitioned layer spreads b over the shards in pieces of rtp_bias_piece_width entries)
+            pw = self.pw = o if split == B.RTP_SPLIT_OUT else B.lib.rtp_bias_piece_width(self.O, n, dtype)
+
             def with_bias(mat, vec, total):
-                vec = torch.cat((vec, vec.new_zeros(n * o - vec.numel()))).reshape(n, o)
+                vec = torch.cat((vec, vec.new_zeros(n * pw - vec.numel()))).reshape(n, pw)
                 out = mat.new_zeros(n, total)
                 out[:, :self.n_mat] = mat
-                out[:, self.n_mat:self.n_mat + o] = vec
+                out[:, self.n_mat:self.n_mat + pw] = vec
                 return out.contiguous()
             gb0 = torch.zeros(self.O, device=self.dev) if gb0 is None else gb0
             self.home_w = with_bias(self.home_w, bias.to(self.dev, td), wbytes // _esize(dtype))
@@ -140,7 +143,7 @@ class RtpLinear:
 
     def gathered_bias(self):
         """(b, gradient of b) read back from the home store (call gathered() first: it flushes)."""
-        sl = slice(self.n_mat, self.n_mat + self.o)
+        sl = slice(self.n_mat, self.n_mat + self.pw)
         return self.home_w[:, sl].reshape(-1)[:self.O].contiguous(), self.home_g[:, sl].reshape(-1)[:self.O].contiguous()
 
     def close(self):
@@ -152,11 +155,12 @@ class RtpMlp:
     by rtp_mlp_fwd / rtp_mlp_bwd: one library call per pass."""
 
     def __init__(self, weights, T, n, rank, act, mode=B.RTP_INPLACE_STAGED, dtype=B.RTP_BF16, G0=None,
-                 device="cuda:0", aux_stream=True, stepwise=False):
+                 device="cuda:0", aux_stream=True, stepwise=False, biases=None, gb0=None):
         self.dev = torch.device(device)
         td = _TORCH_DT[dtype]
         self.n, self.rank, self.T, self.act, self.mode, self.dtype = n, rank, T, act, mode, dtype
         self.gated = act == B.RTP_ACT_SWIGLU
+        self.has_bias = biases is not None
         ws = [w.to(self.dev, td).contiguous() for w in weights]
         if self.gated:
             Wg, Wu, Wd = ws
@@ -166,20 +170,47 @@ class RtpMlp:
         self.O, self.I = (W1.shape[0] // 2 if self.gated else W1.shape[0]), W1.shape[1]
         self.O2 = Wd.shape[0]
         self.p = 2 if self.gated else 1
-        self.home_w = torch.cat((pack_out_split(W1, n), pack_in_split(Wd, n)), dim=1).contiguous()
         self.n1 = self.p * self.O * self.I // n           # elements of the first matrix's shard
         self.n2 = self.O2 * self.O // n
-        if G0 is None:
-            self.home_g = torch.zeros(n, self.n1 + self.n2, dtype=torch.float32, device=self.dev)
-        else:
-            g = [x.to(self.dev, torch.float32) for x in G0]
-            G1 = stack_gate_up(g[0], g[1], n) if self.gated else g[0]
-            self.home_g = torch.cat((pack_out_split(G1, n), pack_in_split(g[-1], n)), dim=1).contiguous()
         d = B.rtp_mlp_desc()
         d.T, d.I, d.O, d.O2 = T, self.I, self.O, self.O2
         d.n, d.rank, d.mode, d.dtype, d.act = n, rank, mode, dtype, act
         d.flags = B.RTP_FLAG_STEPWISE if stepwise else 0
+        d.has_bias = int(self.has_bias)
         wb, gb = B.lib.rtp_mlp_slot_w_bytes(C.byref(d)), B.lib.rtp_mlp_slot_g_bytes(C.byref(d))
+        g = None if G0 is None else [x.to(self.dev, torch.float32) for x in G0]
+        G1 = None if g is None else (stack_gate_up(g[0], g[1], n) if self.gated else g[0])
+        if not self.has_bias:
+            self.off2 = self.n1                           # where the second linear's part starts, in elements
+            self.home_w = torch.cat((pack_out_split(W1, n), pack_in_split(Wd, n)), dim=1).contiguous()
+            if G0 is None:
+                self.home_g = torch.zeros(n, self.n1 + self.n2, dtype=torch.float32, device=self.dev)
+            else:
+                self.home_g = torch.cat((pack_out_split(G1, n), pack_in_split(g[-1], n)), dim=1).contiguous()
+        else:
+            # slot = [W1_k | b1_k | W2_k | piece k of b2]; each linear's part is padded to 16 bytes in the
+            # weight type and in fp32 alike, so one element offset serves both stores
+            self.o1 = self.O // n
+            self.pw2 = B.lib.rtp_bias_piece_width(self.O2, n, dtype)
+            l1 = B.rtp_linear_desc()
+            l1.T, l1.I, l1.O, l1.split, l1.dtype, l1.grad_dtype, l1.has_bias = T, self.I, self.O, B.RTP_SPLIT_OUT, dtype, B.RTP_F32, 1
+            self.off2 = B.lib.rtp_linear_shard_w_bytes(C.byref(l1), n) // _esize(dtype)
+            assert self.off2 * 4 == B.lib.rtp_linear_shard_g_bytes(C.byref(l1), n)
+            gb0 = [torch.zeros(self.O), torch.zeros(self.O2)] if gb0 is None else gb0
+
+            def slot(M1, v1, M2, v2, t, total):
+                out = torch.zeros(n, total, dtype=t, device=self.dev)
+                out[:, :self.n1] = pack_out_split(M1.to(self.dev, t), n)
+                out[:, self.n1:self.n1 + self.o1] = v1.to(self.dev, t).reshape(n, self.o1)
+                out[:, self.off2:self.off2 + self.n2] = pack_in_split(M2.to(self.dev, t), n)
+                v2 = v2.to(self.dev, t)
+                v2 = torch.cat((v2, v2.new_zeros(n * self.pw2 - v2.numel()))).reshape(n, self.pw2)
+                out[:, self.off2 + self.n2:self.off2 + self.n2 + self.pw2] = v2
+                return out.contiguous()
+
+            self.home_w = slot(W1, biases[0], Wd, biases[1], td, wb // _esize(dtype))
+            Z1, Z2 = torch.zeros(self.O, self.I), torch.zeros(self.O2, self.O)
+            self.home_g = slot(Z1 if g is None else G1, gb0[0], Z2 if g is None else g[-1], gb0[1], torch.float32, gb // 4)
         assert wb == self.home_w.shape[1] * _esize(dtype) and gb == self.home_g.shape[1] * 4
         self.w_bytes, self.g_bytes = wb, gb
         self.buf_w = [torch.empty(wb, dtype=torch.uint8, device=self.dev) for _ in range(2)]
@@ -230,10 +261,20 @@ class RtpMlp:
         self.sync()
         out = []
         for home in (self.home_w, self.home_g):
-            P1, P2 = home[:, :self.n1].contiguous(), home[:, self.n1:].contiguous()
+            P1, P2 = home[:, :self.n1].contiguous(), home[:, self.off2:self.off2 + self.n2].contiguous()
             M1 = unpack_out_split(P1, self.n, self.p * self.O, self.I)
             M2 = unpack_in_split(P2, self.n, self.O2, self.O)
             out.append((*unstack_gate_up(M1, self.n), M2) if self.gated else (M1, M2))
+        return out
+
+    def gathered_biases(self):
+        """((b1, b2), (gradient of b1, gradient of b2)) from the home store (call gathered() first: it flushes)."""
+        out = []
+        for home in (self.home_w, self.home_g):
+            v1 = home[:, self.n1:self.n1 + self.o1].reshape(-1).contiguous()
+            s2 = self.off2 + self.n2
+            v2 = home[:, s2:s2 + self.pw2].reshape(-1)[:self.O2].contiguous()
+            out.append((v1, v2))
         return out
 
     def close(self):

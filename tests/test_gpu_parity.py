@@ -359,6 +359,42 @@ def test_linear_with_bias(dtype, act, mode):
         layer.close()
 
 
+@pytest.mark.parametrize("mode", [B.RTP_DOUBLE_BUFFER, B.RTP_INPLACE_STAGED, B.RTP_INPLACE_BLOCKING])
+@pytest.mark.parametrize("dtype,T,I,O,n", [("f32", 70, 48, 50, 3), ("bf16", 300, 512, 104, 8), ("bf16", 96, 64, 40, 1),
+                                           ("f16", 320, 256, 96, 4), ("bf16", 64, 128, 8, 4)])
+def test_input_partitioned_linear_with_bias(dtype, T, I, O, n, mode):
+    """Y = X W^T + b with b spread over the shards in pieces (widths that N does not divide, a piece
+    per shard narrower than 16 bytes' worth, more shards than pieces, a single shard): forward, both
+    gradients and the pieces' gradients (onto what arrives) against the oracle's rotated layer."""
+    w = wl.Workload("bias_in", "linear_in", T=T, I=I, O=O, n=n, dtype=dtype, mode="x", w_dist=("uniform", 0.1))
+    inp = wl.make_inputs(w, seed=31, grad0=True)
+    rng = np.random.default_rng(32)
+    b = wl._store(rng.standard_normal(O).astype(np.float32) * 0.5, dtype)
+    gb0 = rng.standard_normal(O).astype(np.float32)
+    td, bd = _TD[dtype], _BD[dtype]
+    tol = {"f32": TOL_F32, "bf16": TOL_BF16, "f16": TOL_F16}[dtype]
+    for rank in sorted({0, n - 1}):
+        say(f"input-partitioned linear with bias dtype={dtype} T={T} I={I} O={O} n={n} mode={mode} rank={rank}")
+        ref = orc.rtp_linear_in(f64(inp["X"]), f64(inp["W"]), f64(inp["dY"]), n, rank, G0=f64(inp["G0_W"]), b=f64(b),
+                                gb0=f64(gb0))
+        layer = RtpLinear(dev(inp["W"], td), T, n, rank, B.RTP_SPLIT_IN, mode, bd, G0=dev(inp["G0_W"], torch.float32),
+                          bias=dev(b, td), gb0=dev(gb0, torch.float32))
+        Xd, dYd = dev(inp["X"], td), dev(inp["dY"], td)
+        Y = torch.full((T, O), float("nan"), device=DEV, dtype=td)
+        dX = torch.full((T, I), float("nan"), device=DEV, dtype=td)
+        torch.cuda.synchronize()
+        layer.forward(Xd, Y)
+        layer.backward(Xd, dYd, dX)
+        layer.sync()
+        Wb, G = layer.gathered()
+        bb, gb = layer.gathered_bias()
+        assert torch.equal(Wb, dev(inp["W"], td)) and torch.equal(bb, dev(b, td))
+        for key, got in (("Y", Y), ("dX", dX), ("G", G), ("gb", gb)):
+            assert torch.isfinite(got.float()).all(), key
+            assert relerr(host(got), ref[key]) <= tol, (key, relerr(host(got), ref[key]))
+        layer.close()
+
+
 @pytest.mark.parametrize("n", [1, 8])
 @pytest.mark.parametrize("mode", [B.RTP_DOUBLE_BUFFER, B.RTP_INPLACE_STAGED, B.RTP_INPLACE_BLOCKING])
 def test_gradients_accumulate_over_passes(mode, n):
@@ -589,6 +625,45 @@ def test_mlp_gelu_tanh_variant():
     out, ref, gkeys = _mlp_case(w, 1, B.RTP_DOUBLE_BUFFER)
     for key in ("H", "Y", "dX") + tuple(gkeys):
         assert relerr(out[key], ref[key]) <= TOL_BF16, (key, relerr(out[key], ref[key]))
+
+
+@pytest.mark.parametrize("mode", [B.RTP_DOUBLE_BUFFER, B.RTP_INPLACE_STAGED, B.RTP_INPLACE_BLOCKING])
+@pytest.mark.parametrize("dtype,act", [("bf16", B.RTP_ACT_GELU_ERF), ("f32", B.RTP_ACT_GELU_ERF), ("f16", B.RTP_ACT_GELU_TANH)])
+def test_mlp_unit_with_biases(dtype, act, mode):
+    """The unit's flat parameter with both biases: [W1_k | b1_k | W2_k | piece k of b2]."""
+    T, I, O, O2, n = (288, 160, 512, 96, 4) if dtype != "f32" else (100, 40, 48, 20, 4)
+    w = wl.Workload("mlp_bias", "mlp_gelu", T=T, I=I, O=O, O2=O2, n=n, dtype=dtype, mode="x", w_dist=("normal", 0.08))
+    inp = wl.make_inputs(w, seed=41, grad0=True)
+    rng = np.random.default_rng(42)
+    b1 = wl._store(rng.standard_normal(O).astype(np.float32) * 0.3, dtype)
+    b2 = wl._store(rng.standard_normal(O2).astype(np.float32) * 0.3, dtype)
+    gb1, gb2 = rng.standard_normal(O).astype(np.float32), rng.standard_normal(O2).astype(np.float32)
+    td, bd = _TD[dtype], _BD[dtype]
+    tol = {"f32": TOL_F32, "bf16": TOL_BF16, "f16": TOL_F16}[dtype]
+    kind = orc.GELU_TANH if act == B.RTP_ACT_GELU_TANH else orc.GELU_ERF
+    for rank in (0, 2):
+        say(f"mlp with biases dtype={dtype} act={act} mode={mode} rank={rank}")
+        ref = orc.rtp_mlp(f64(inp["X"]), f64(inp["W1"]), f64(inp["W2"]), f64(inp["dY"]), n, rank, kind,
+                          f64(inp["G0_W1"]), f64(inp["G0_W2"]), b1=f64(b1), b2=f64(b2), gb1_0=f64(gb1), gb2_0=f64(gb2))
+        mlp = RtpMlp([dev(inp[k], td) for k in ("W1", "W2")], T, n, rank, act, mode, bd,
+                     G0=[dev(inp["G0_" + k], torch.float32) for k in ("W1", "W2")],
+                     biases=[dev(b1, td), dev(b2, td)], gb0=[dev(gb1, torch.float32), dev(gb2, torch.float32)])
+        Xd, dYd = dev(inp["X"], td), dev(inp["dY"], td)
+        Y = torch.full((T, O2), float("nan"), device=DEV, dtype=td)
+        dX = torch.full((T, I), float("nan"), device=DEV, dtype=td)
+        torch.cuda.synchronize()
+        mlp.forward(Xd, Y)
+        mlp.backward(Xd, dYd, dX)
+        mlp.sync()
+        Ws, Gs = mlp.gathered()
+        (bb1, bb2), (g1, g2) = mlp.gathered_biases()
+        assert all(torch.equal(a, dev(inp[k], td)) for a, k in zip(Ws, ("W1", "W2")))
+        assert torch.equal(bb1, dev(b1, td)) and torch.equal(bb2, dev(b2, td))
+        got = dict(Y=Y, dX=dX, H=mlp.hidden, dW1=Gs[0], dW2=Gs[1], db1=g1, db2=g2)
+        for key, val in got.items():
+            assert torch.isfinite(val.float()).all(), key
+            assert relerr(host(val), ref[key]) <= tol, (key, relerr(host(val), ref[key]))
+        mlp.close()
 
 
 # ------------------------------------------------------------ HIP graphs --

@@ -238,7 +238,7 @@ def test_create_rejects_bad_descriptions():
     assert lin_status(w_offset=8) == B.RTP_ERR_SHAPE
     assert lin_status(split=5) == B.RTP_ERR_INVALID
     assert lin_status(has_bias=True) == B.RTP_OK
-    assert lin_status(has_bias=True, split=B.RTP_SPLIT_IN) == B.RTP_ERR_UNSUPPORTED   # bias: output-partitioned only
+    assert lin_status(has_bias=True, split=B.RTP_SPLIT_IN) == B.RTP_OK                # bias spread over the shards in pieces
     assert lin_status(O=512) == B.RTP_OK                                               # 128 x 64 rows fill the slot exactly
     assert lin_status(has_bias=True, O=512) == B.RTP_ERR_SHAPE                         # ... so the bias entries do not fit
     assert lin_status(dtype=B.RTP_F32, O=12, I=3) == B.RTP_OK  # fp32 has no alignment rule
@@ -378,3 +378,29 @@ def test_moe_descriptions():
         h = C.c_void_p()
         assert B.lib.rtp_moe_create(C.byref(h), C.byref(_moe_desc(**kw))) == want, kw
         assert not h.value
+
+
+def test_bias_piece_width_and_slot_sizes():
+    """Piece of an input-partitioned layer's bias: ceil(O / n) rounded up to 16 bytes; the shard sizes
+    count it; an MLP unit with biases = the two linears' shards back to back."""
+    assert B.lib.rtp_bias_piece_width(768, 8, B.RTP_BF16) == 96
+    assert B.lib.rtp_bias_piece_width(100, 8, B.RTP_BF16) == 16        # ceil = 13 -> 16
+    assert B.lib.rtp_bias_piece_width(100, 8, B.RTP_F32) == 16         # 13 -> 16 (multiples of 4)
+    assert B.lib.rtp_bias_piece_width(10, 8, B.RTP_F32) == 4           # ceil = 2 -> 4
+    assert B.lib.rtp_bias_piece_width(0, 8, B.RTP_F32) == -1 and B.lib.rtp_bias_piece_width(8, 0, B.RTP_F32) == -1
+    for O in (8, 100, 768, 4096):
+        for n in (1, 3, 8, 16):
+            p = B.lib.rtp_bias_piece_width(O, n, B.RTP_BF16)
+            pieces = orc.bias_pieces(O, n)
+            assert p >= max(hi - lo for lo, hi in pieces) and n * p >= O and p % 8 == 0
+    d = B.rtp_linear_desc()
+    d.T, d.I, d.O, d.split, d.dtype, d.grad_dtype, d.has_bias = 64, 256, 100, B.RTP_SPLIT_IN, B.RTP_BF16, B.RTP_F32, 1
+    assert B.lib.rtp_linear_shard_w_bytes(C.byref(d), 8) == (100 * 32 + 16) * 2
+    assert B.lib.rtp_linear_shard_g_bytes(C.byref(d), 8) == (100 * 32 + 16) * 4
+    m = B.rtp_mlp_desc()
+    m.T, m.I, m.O, m.O2, m.n, m.dtype, m.act = 64, 128, 512, 100, 8, B.RTP_BF16, B.RTP_ACT_GELU_ERF
+    plain = B.lib.rtp_mlp_slot_w_bytes(C.byref(m))
+    assert plain == (512 * 128 + 100 * 512) // 8 * 2
+    m.has_bias = 1
+    assert B.lib.rtp_mlp_slot_w_bytes(C.byref(m)) == plain + (64 + 16) * 2
+    assert B.lib.rtp_mlp_slot_g_bytes(C.byref(m)) == 2 * (plain + (64 + 16) * 2)
