@@ -357,6 +357,9 @@ class RtpMoe:
     def worker_bytes(self):
         return B.rtp_worker_bytes(self.mode, self.w_bytes, self.g_bytes)
 
+    def zero_grads(self):
+        B.check(B.lib.rtp_ring_zero_grads(B.lib.rtp_moe_ring(self.handle)), "rtp_ring_zero_grads")
+
     def routing(self):
         """(tokens per expert, first grouped row of each expert) of the last forward."""
         c, b = (C.c_int32 * self.n)(), (C.c_int64 * (self.n + 1))()

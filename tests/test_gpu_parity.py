@@ -666,6 +666,53 @@ def test_mlp_unit_with_biases(dtype, act, mode):
         mlp.close()
 
 
+def test_units_cleared_gradients_start_from_zero():
+    """zero_grads between two passes of the MLP unit and of the expert-partitioned layer: the second
+    pass's gradients are those of one pass from zero (the shard the worker kept is dropped)."""
+    w = wl.Workload("mlp_zero", "swiglu", T=288, I=160, O=512, O2=96, n=4, dtype="bf16", mode="x", w_dist=("normal", 0.08))
+    inp = wl.make_inputs(w, seed=8, grad0=True)
+    names = ("Wg", "Wu", "Wd")
+    ref = orc.rtp_swiglu(f64(inp["X"]), *[f64(inp[k]) for k in names], f64(inp["dY"]), 4, 1)
+    mlp = RtpMlp([dev(inp[k], torch.bfloat16) for k in names], w.T, 4, 1, B.RTP_ACT_SWIGLU, B.RTP_INPLACE_STAGED, B.RTP_BF16,
+                 G0=[dev(inp["G0_" + k], torch.float32) for k in names])
+    Xd, dYd = dev(inp["X"], torch.bfloat16), dev(inp["dY"], torch.bfloat16)
+    Y = torch.empty(w.T, w.O2, device=DEV, dtype=torch.bfloat16)
+    dX = torch.empty(w.T, w.I, device=DEV, dtype=torch.bfloat16)
+    say("mlp: pass, zero_grads, pass")
+    mlp.forward(Xd, Y)
+    mlp.backward(Xd, dYd, dX)
+    mlp.zero_grads()
+    mlp.forward(Xd, Y)
+    mlp.backward(Xd, dYd, dX)
+    mlp.sync()
+    _, Gs = mlp.gathered()
+    for key, g in zip(("dWg", "dWu", "dWd"), Gs):
+        assert relerr(host(g), ref[key]) <= TOL_BF16, key
+    mlp.close()
+
+    n, T = 4, 300
+    mi = wl.make_moe_inputs(T, 64, 96, 64, n, seed=12)
+    ex64 = [tuple(f64(m) for m in ex) for ex in mi["experts"]]
+    mref = orc.rtp_moe(f64(mi["X"]), mi["route"], ex64, f64(mi["dY"]), n, 2)
+    moe = RtpMoe([tuple(dev(m, torch.bfloat16) for m in ex) for ex in mi["experts"]], T, 2, B.RTP_ACT_GELU_ERF,
+                 G0=[tuple(dev(g, torch.float32) for g in ex) for ex in mi["G0"]])
+    Xd, dYd, rd = dev(mi["X"], torch.bfloat16), dev(mi["dY"], torch.bfloat16), dev(mi["route"], torch.int32)
+    Y = torch.empty(T, 64, device=DEV, dtype=torch.bfloat16)
+    dX = torch.empty(T, 64, device=DEV, dtype=torch.bfloat16)
+    say("moe: pass, zero_grads, pass")
+    moe.forward(Xd, rd, Y)
+    moe.backward(dYd, dX)
+    moe.zero_grads()
+    moe.forward(Xd, rd, Y)
+    moe.backward(dYd, dX)
+    moe.sync()
+    _, Gs = moe.gathered()
+    for e in range(n):
+        for j in range(2):
+            assert relerr(host(Gs[e][j]), mref["G"][e][j]) <= TOL_BF16, (e, j)
+    moe.close()
+
+
 # ------------------------------------------------------------ HIP graphs --
 
 @pytest.mark.skip(reason="capturing a linear layer's pass (double-buffer mode, three streams) crashed the host inside the "
