@@ -404,3 +404,16 @@ def test_bias_piece_width_and_slot_sizes():
     m.has_bias = 1
     assert B.lib.rtp_mlp_slot_w_bytes(C.byref(m)) == plain + (64 + 16) * 2
     assert B.lib.rtp_mlp_slot_g_bytes(C.byref(m)) == 2 * (plain + (64 + 16) * 2)
+
+
+def test_header_is_plain_c():
+    """The boundary is a C ABI: the header compiles as C99 and as C++ with no torch or HIP type in sight."""
+    import shutil
+    import subprocess
+    hdr = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "rtp.h")
+    if shutil.which("gcc") is None:
+        pytest.skip("no host C compiler")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", hdr], check=True)
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", hdr], check=True)
+    text = open(hdr).read()
+    assert "torch" not in text.lower() and "hipStream_t " not in text.replace("/* hipStream_t", "")
