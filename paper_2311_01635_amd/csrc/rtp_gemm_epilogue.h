@@ -338,13 +338,21 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
         });
         break;
     case EPI_ACC_ATOMIC:
-        each([&](int r, int c, f32x4 x) {
-            float *q = ws + (int64_t)r * ldws + c;
-            unsafeAtomicAdd(q, x.x);
-            unsafeAtomicAdd(q + 1, x.y);
-            unsafeAtomicAdd(q + 2, x.z);
-            unsafeAtomicAdd(q + 3, x.w);
-        });
+        // one float per lane, 32 consecutive lanes on 32 consecutive columns: an atomic instruction
+        // then covers two whole 128-byte lines (one row of each fragment) instead of a quarter of eight
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            park(i);
+            const int j = lane >> 5, c = lane & 31;
+            const int col = n0 + j * NSTRIDE + wn32 + c;
+#pragma unroll 8
+            for (int row = 0; row < 32; ++row) {
+                const float x = wlds[row * EPI_LDS_PITCH + j * 32 + c];
+                const int grow = rbase_wave + i * 32 + row;
+                if (grow < M && col < N) unsafeAtomicAdd(ws + (int64_t)grow * ldws + col, x);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
         break;
     case EPI_ACC_LAST:
         if (p.c_is_f32)
