@@ -131,6 +131,24 @@ def timed(torch, mlp, X, Y, dY, dX, steps, fwd=True, bwd=True):
     return e0.elapsed_time(e1)
 
 
+def algorithmic_bytes(w, staging_bytes):
+    """HBM bytes one fwd+bwd pass of an MLP unit has to move if every operand of every step's GEMMs is read once and
+    every result written once (fp32 sums read and written each step but the first read and the last write), plus the
+    staging copies.  16-bit activations and weights, fp32 gradient shards and cross-step sums."""
+    gated = w.kind == "swiglu"
+    P, n, T, I, O, O2 = (2 if gated else 1), w.n, w.T, w.I, w.O, w.O2
+    o = O // n
+    a = 2
+    per_step_fwd = T * I * a + P * o * I * a + P * T * o * a + T * o * a      # X, W1_k -> pre-activations, hidden
+    per_step_fwd += T * o * a + O2 * o * a                                    # hidden, W2_k -> the sum over steps
+    per_step_bwd = (T * O2 * a + T * o * a + 2 * O2 * o * 4)                  # dW2: dY, hidden, G2 +=
+    per_step_bwd += (T * O2 * a + O2 * o * a + P * T * o * a + P * T * o * a)   # dPre: dY, W2_k, pre-activations -> dPre
+    per_step_bwd += (P * T * o * a + T * I * a + 2 * P * o * I * 4)           # dW1: dPre, X, G1 +=
+    per_step_bwd += (P * T * o * a + P * o * I * a)                           # dX: dPre, W1_k -> the sum over steps
+    sums = (2 * (n - 1)) * T * O2 * 4 + T * O2 * a + (2 * (n - 1)) * T * I * 4 + T * I * a
+    return n * (per_step_fwd + per_step_bwd) + sums + staging_bytes
+
+
 def measured_traffic(workload, layout):
     """HBM bytes per launch of a GEMM kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs whose
     summary is kept under profiles/ (counters cannot be read from inside this process); None if absent."""
@@ -263,6 +281,14 @@ def main():
     if not a.no_cpu_baseline:
         cpu = cpu_baseline_moe(w, inp, a.cpu_tokens) if is_moe else cpu_baseline(w, inp, a.cpu_tokens)
 
+    hbm = None
+    if not is_moe:
+        # staging: every copy reads and writes its bytes; per pass 2(n-1) weight rotations (out + in), one initial
+        # load, and per backward rotation the gradient shard in (its way out is a GEMM's store, counted above)
+        stg = 2 * (2 * (2 * (w.n - 1)) + 1) * mlp.w_bytes + 2 * (w.n - 1 + 1) * mlp.g_bytes
+        nbytes = algorithmic_bytes(w, stg)
+        hbm = {"algorithmic_bytes_per_step": nbytes, "achieved": nbytes / (ms_step * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+               "unit": "GB/s", "frac": nbytes / (ms_step * 1e-3) / 1e9 / PEAK_HBM_GBS}
     out = {
         "metric": "TFLOP/s rotated-shard linear fwd+bwd per GPU", "value": tflops, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step, "higher_is_better": True,
@@ -276,7 +302,7 @@ def main():
         "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
         "sustained_clock_ghz": clock_ghz, "nominal_clock_ghz": 2.4,
         "frac_of_peak_at_sustained_clock": tflops / (PEAK_BF16_TFLOPS * clock_ghz / 2.4) if clock_ghz > 0 else None,
-        "roofline": roofline, "overlap": overlap, "cpu_baseline": cpu,
+        "roofline": roofline, "hbm_algorithmic": hbm, "overlap": overlap, "cpu_baseline": cpu,
     }
     mlp.close()
     print(json.dumps(out))
