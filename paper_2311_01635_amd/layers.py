@@ -20,7 +20,7 @@ def pack_out_split(W, n, o=None):
     o = O // n if o is None else o
     if n * o != O:
         W = torch.cat((W, W.new_zeros(n * o - O, I)), dim=0)
-    return W.reshape(n, o * I)
+    return W.reshape(n, o * I).clone()       # a store of its own: the ring writes into it
 
 
 def pack_in_split(W, n, o=None):
@@ -29,7 +29,7 @@ def pack_in_split(W, n, o=None):
     o = I // n if o is None else o
     if n * o != I:
         W = torch.cat((W, W.new_zeros(O, n * o - I)), dim=1)
-    return W.reshape(O, n, o).permute(1, 0, 2).contiguous().reshape(n, O * o)
+    return W.reshape(O, n, o).permute(1, 0, 2).clone(memory_format=torch.contiguous_format).reshape(n, O * o)
 
 
 def unpack_out_split(P, n, O, I):
