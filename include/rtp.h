@@ -66,8 +66,9 @@ typedef enum { RTP_SPLIT_OUT = 0, RTP_SPLIT_IN = 1 } rtp_split;
 typedef enum { RTP_DOUBLE_BUFFER = 0, RTP_INPLACE_STAGED = 1, RTP_INPLACE_BLOCKING = 2 } rtp_mode;
 
 /* Activation fused after an output-partitioned GEMM (RTP Transformers
- * section: "a GEMM succeeded by a GeLU"); RTP_ACT_SWIGLU is the gated form
- * silu(a)*b over a (gate, up) pair. */
+ * section, linear-block item: the first GEMM of an MLP block is followed by
+ * its activation); RTP_ACT_SWIGLU is the gated form silu(a)*b over a
+ * (gate, up) pair. */
 typedef enum { RTP_ACT_NONE = 0, RTP_ACT_GELU_ERF = 1, RTP_ACT_GELU_TANH = 2, RTP_ACT_SWIGLU = 3 } rtp_act;
 
 typedef enum { RTP_PASS_IDLE = 0, RTP_PASS_FWD = 1, RTP_PASS_BWD = 2 } rtp_pass;
@@ -149,14 +150,16 @@ rtp_status rtp_ring_destroy(rtp_ring *ring);
 /* Starts a pass.  RTP_PASS_FWD: copies home slot `rank` into the resident
  * buffer (weights) -- the worker's own shard.  RTP_PASS_BWD: must follow a
  * completed forward pass (the worker holds shard (rank+1) mod n) or, with
- * n == 1 or after rtp_ring_seek(), any idle state; loads that shard's
+ * n == 1 or after rtp_ring_seek_bwd_start(), any idle state; loads that shard's
  * gradient part, after writing the gradient shard an earlier backward pass
  * left in the buffer (the worker's own) back to its slot: gradients
  * accumulate over any number of passes.  RTP_ERR_STATE if a pass is in
  * progress.
  * Stream capture of a pass is not supported: the calls decide on the host,
  * when they are made, what a pass enqueues (the write-back above, for one),
- * and use three streams. */
+ * and use three streams.  RTP_ERR_UNSUPPORTED, before anything is enqueued,
+ * if any of the ring's streams is capturing (so do rtp_ring_seek_bwd_start,
+ * rtp_ring_flush, rtp_ring_zero_grads and the rtp_mlp_* / rtp_moe_* passes). */
 rtp_status rtp_ring_begin(rtp_ring *ring, rtp_pass pass);
 
 /* Makes shard (rank+1) mod n resident without a forward pass (tests and
@@ -176,19 +179,35 @@ rtp_status rtp_ring_seek_bwd_start(rtp_ring *ring);
  * a step out of order or >= n-1, a linear lagging behind. */
 rtp_status rtp_rotate_step(rtp_ring *ring, int direction, int step);
 
-/* Ends a pass after step n-1.  After a backward pass writes nothing: the
- * worker holds its own (W_rank, G_rank).  RTP_ERR_STATE if steps remain. */
+/* Ends a pass after step n-1 (Design section, workflow paragraph: a forward
+ * pass ends on the next worker's shard, a backward pass on the worker's own).
+ * After a backward pass writes nothing: the worker holds its own
+ * (W_rank, G_rank).  The stage and auxiliary streams are joined into the
+ * compute stream.  RTP_ERR_STATE if steps remain. */
 rtp_status rtp_ring_end(rtp_ring *ring);
 
+/* Way out of a pass that failed half-way (any call of an open pass returned
+ * an error): joins the three streams, closes the pass and forgets what the
+ * worker holds, so that rtp_ring_begin(RTP_PASS_FWD), rtp_ring_zero_grads,
+ * rtp_ring_flush (a no-op then) and the destroy calls work again.  Outputs,
+ * saved activations and the gradient shard the worker held are undefined
+ * after it: clear the gradients and start over.  The rtp_mlp_* and rtp_moe_*
+ * passes call it themselves before they return an error.  No-op when idle. */
+rtp_status rtp_ring_abort(rtp_ring *ring);
+
 /* Copies the resident (W, G) to their home slot so that a reader of the home
- * store sees every shard (tests, checkpoints, an optimizer).  Idle state only.
+ * store sees every shard (tests, checkpoints, an optimizer): between passes
+ * the worker's copy is the only current one of the shard it holds (Memory
+ * Arrangement section: each parameter exists once in the system).  Idle state only.
  * Between a backward pass and the flush the home slot of the worker's own
  * gradient shard is stale: write to the gradient store only after a flush (or
  * through rtp_ring_zero_grads), else the next backward pass writes the
  * worker's copy back over it. */
 rtp_status rtp_ring_flush(rtp_ring *ring);
 
-/* Clears every gradient slot of the home store (a fill kernel on the compute
+/* The optimizer step's "zero the gradients" for a store whose shards travel
+ * (Design section: the gradient shard rides with its weight): clears
+ * every gradient slot of the home store (a fill kernel on the compute
  * stream, ordered after everything enqueued so far) and drops the gradient
  * shard the worker still holds, so that the next backward pass accumulates
  * from zero.  Idle state only. */
@@ -227,7 +246,8 @@ typedef struct {
                              (read by bwd), P = I (GELU) or 2 I (SWIGLU)          */
     float *acc_ws_dev;    /* fp32 [T, I] (SPLIT_OUT, dX) or [T, O] (SPLIT_IN, Y):
                              cross-step accumulator; needed when dtype != F32
-                             and n > 1                                            */
+                             and n > 1 (a call that needs it and finds NULL returns
+                             RTP_ERR_INVALID)                                      */
     int has_bias;         /* the layer is Y = X W^T + b.  The bias rides in the flat
                              parameter (FlatParameter paragraph).  RTP_SPLIT_OUT:
                              shard k's w entries of b follow its rows of W in the
@@ -262,8 +282,7 @@ size_t rtp_linear_shard_g_bytes(const rtp_linear_desc *desc, int n);
  * Errors: RTP_ERR_SHAPE (n does not divide the partitioned dimension of a
  * layer with an activation, or padding would leave a shard empty; bf16 or
  * fp16: I, O, o not multiples of 8; shard does not fit the slot),
- * RTP_ERR_INVALID, RTP_ERR_UNSUPPORTED (gradient dtype other than F32; a bias
- * on an input-partitioned layer; fp16
+ * RTP_ERR_INVALID, RTP_ERR_UNSUPPORTED (gradient dtype other than F32; fp16
  * with T, o or the unpartitioned dimension not a multiple of 32: fp16 inputs
  * run on the tiled kernel only, which needs such contraction lengths). */
 rtp_status rtp_linear_create(rtp_linear **out, rtp_ring *ring, const rtp_linear_desc *desc);

@@ -99,6 +99,7 @@ SYMBOLS = {
     "rtp_ring_seek_bwd_start": (C.c_int, [_P]),
     "rtp_rotate_step": (C.c_int, [_P, C.c_int, C.c_int]),
     "rtp_ring_end": (C.c_int, [_P]),
+    "rtp_ring_abort": (C.c_int, [_P]),
     "rtp_ring_flush": (C.c_int, [_P]),
     "rtp_ring_zero_grads": (C.c_int, [_P]),
     "rtp_ring_sync": (C.c_int, [_P]),
@@ -233,6 +234,9 @@ class Ring:
 
     def end(self):
         check(lib.rtp_ring_end(self.handle), "rtp_ring_end")
+
+    def abort(self):
+        check(lib.rtp_ring_abort(self.handle), "rtp_ring_abort")
 
     def flush(self):
         check(lib.rtp_ring_flush(self.handle), "rtp_ring_flush")

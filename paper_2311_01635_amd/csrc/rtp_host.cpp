@@ -5,12 +5,13 @@
 #include "../../include/rtp.h"
 #include "rtp_kernels.h"
 
-#include <hip/hip_runtime_api.h>
+#include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -112,17 +113,22 @@ static hipError_t timed_launch(int layout, double flops, hipStream_t s, F launch
     hipError_t e = hipEventCreate(&r.start);
     if (e != hipSuccess) return e;
     e = hipEventCreate(&r.stop);
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess) {
+        (void)hipEventDestroy(r.start);
+        return e;
+    }
     // "alone": the device is idle when the launch starts and nothing else is enqueued until it has
     // ended, so its duration is that of the kernel with the machine to itself
-    if (g_prof_alone && (e = hipDeviceSynchronize()) != hipSuccess) return e;
-    e = hipEventRecord(r.start, s);
-    if (e != hipSuccess) return e;
-    e = launch();
-    if (e != hipSuccess) return e;
-    e = hipEventRecord(r.stop, s);
-    if (e != hipSuccess) return e;
-    if (g_prof_alone && (e = hipDeviceSynchronize()) != hipSuccess) return e;
+    e = g_prof_alone ? hipDeviceSynchronize() : hipSuccess;
+    if (e == hipSuccess) e = hipEventRecord(r.start, s);
+    if (e == hipSuccess) e = launch();
+    if (e == hipSuccess) e = hipEventRecord(r.stop, s);
+    if (e == hipSuccess && g_prof_alone) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+        return e;
+    }
     g_prof.push_back(r);
     return hipSuccess;
 }
@@ -285,6 +291,23 @@ static rtp_status cross_join(rtp_ring *r)
     return RTP_OK;
 }
 
+// A pass cannot be recorded into a HIP graph (the calls decide on the host what they enqueue, on
+// three streams): refuse, before anything is enqueued, when one of the ring's streams is capturing.
+static rtp_status refuse_capture(const rtp_ring *r, const char *who)
+{
+    if (r->dry) return RTP_OK;
+    hipStream_t all[3] = {r->cs(), r->ss(), r->as()};
+    for (int i = 0; i < 3; ++i) {
+        if (i > 0 && all[i] == all[0]) continue;
+        hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+        HIP_TRY(hipStreamIsCapturing(all[i], &st));
+        if (st != hipStreamCaptureStatusNone)
+            return fail(RTP_ERR_UNSUPPORTED, "%s: a stream of the ring is being captured into a graph; "
+                                             "passes cannot be captured", who);
+    }
+    return RTP_OK;
+}
+
 extern "C" rtp_status rtp_ring_create(rtp_ring **out, const rtp_ring_desc *d)
 {
     if (!out || !d) return fail(RTP_ERR_INVALID, "rtp_ring_create: null argument");
@@ -361,6 +384,7 @@ extern "C" rtp_status rtp_ring_begin(rtp_ring *r, rtp_pass pass)
     if (pass == RTP_PASS_BWD && r->resident != (rank + 1) % n)
         return fail(RTP_ERR_STATE, "rtp_ring_begin: backward needs shard %d resident (forward pass first), have %d",
                     (rank + 1) % n, r->resident);
+    RTP_TRY(refuse_capture(r, "rtp_ring_begin"));
     RTP_TRY(ensure_events(r));
     RTP_TRY(cross_join(r));
     r->pass = pass;
@@ -397,6 +421,7 @@ extern "C" rtp_status rtp_ring_seek_bwd_start(rtp_ring *r)
 {
     if (!r) return fail(RTP_ERR_INVALID, "null ring");
     if (r->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_ring_seek_bwd_start: a pass is open");
+    RTP_TRY(refuse_capture(r, "rtp_ring_seek_bwd_start"));
     RTP_TRY(ensure_events(r));
     RTP_TRY(cross_join(r));
     const int k = (r->d.rank + 1) % r->d.n;
@@ -544,11 +569,38 @@ extern "C" rtp_status rtp_ring_end(rtp_ring *r)
     return RTP_OK;
 }
 
+extern "C" rtp_status rtp_ring_abort(rtp_ring *r)
+{
+    if (!r) return fail(RTP_ERR_INVALID, "rtp_ring_abort: null ring");
+    if (r->pass == RTP_PASS_IDLE) return RTP_OK;
+    // whatever the streams still hold runs to its end before anybody reuses the buffers
+    rtp_status st = (r->dry || !r->events_ready) ? RTP_OK : cross_join(r);
+    r->pass = RTP_PASS_IDLE;
+    r->resident = -1;
+    r->res_g = -1;
+    r->rotations = 0;
+    r->executed = 0;
+    for (rtp_linear *l : r->linears) l->next_step = 0;
+    return st;
+}
+
+// error path of the calls that run a whole pass: leave the ring usable, keep the first error's text
+static rtp_status close_failed_pass(rtp_ring *r, rtp_status s)
+{
+    if (s == RTP_OK || r->pass == RTP_PASS_IDLE) return s;
+    char keep[sizeof g_err];
+    memcpy(keep, g_err, sizeof keep);
+    (void)rtp_ring_abort(r);
+    memcpy(g_err, keep, sizeof keep);
+    return s;
+}
+
 extern "C" rtp_status rtp_ring_flush(rtp_ring *r)
 {
     if (!r) return fail(RTP_ERR_INVALID, "rtp_ring_flush: null ring");
     if (r->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_ring_flush: a pass is open");
     if (r->resident < 0) return RTP_OK;
+    RTP_TRY(refuse_capture(r, "rtp_ring_flush"));
     RTP_TRY(ensure_events(r));
     RTP_TRY(cross_join(r));
     RTP_TRY(copy_async(r, r->home_w(r->resident), r->d.buf_w_dev[r->res_idx], r->d.w_bytes, r->cs()));
@@ -565,6 +617,7 @@ extern "C" rtp_status rtp_ring_zero_grads(rtp_ring *r)
 {
     if (!r) return fail(RTP_ERR_INVALID, "rtp_ring_zero_grads: null ring");
     if (r->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_ring_zero_grads: a pass is open");
+    RTP_TRY(refuse_capture(r, "rtp_ring_zero_grads"));
     RTP_TRY(ensure_events(r));
     RTP_TRY(cross_join(r));
     if (!r->dry && r->d.g_bytes) HIP_TRY(launch_fill_zero(r->d.home_g_dev, (size_t)r->d.n * r->d.g_bytes, r->cs()));
@@ -656,8 +709,6 @@ extern "C" rtp_status rtp_linear_create(rtp_linear **out, rtp_ring *ring, const 
     if (!ring->dry && d->T > 0) {
         if (d->act != RTP_ACT_NONE && !d->preact_dev)
             return fail(RTP_ERR_INVALID, "rtp_linear_create: an activation needs the pre-activation buffer");
-        if (d->dtype != RTP_F32 && n > 1 && !d->acc_ws_dev)
-            return fail(RTP_ERR_INVALID, "rtp_linear_create: the fp32 cross-step accumulator is missing");
     }
     rtp_linear *l = new (std::nothrow) rtp_linear;
     if (!l) return fail(RTP_ERR_INVALID, "out of host memory");
@@ -715,12 +766,17 @@ static rtp_status gemm(rtp_linear *l, int layout, GemmArgs &a, hipStream_t st)
     return RTP_OK;
 }
 
-extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, void *Y)
+// whether the layer's steps meet in an fp32 accumulator (16-bit layer, more than one step)
+static bool needs_acc(const rtp_linear *l) { return l->d.dtype != RTP_F32 && l->ring->d.n > 1 && l->d.T > 0 && !l->ring->dry; }
+
+// `acc`: the fp32 cross-step accumulator of an input-partitioned layer (null where none is needed)
+static rtp_status linear_fwd_step(rtp_linear *l, int step, const void *X, void *Y, float *acc, const char *who)
 {
-    if (!l) return fail(RTP_ERR_INVALID, "rtp_linear_fwd: null linear");
     rtp_ring *r = l->ring;
-    if (!r->dry && l->d.T > 0 && (!X || !Y)) return fail(RTP_ERR_INVALID, "rtp_linear_fwd: null tensor");
-    RTP_TRY(enter_step(r, l->next_step, step, RTP_PASS_FWD, "rtp_linear_fwd"));
+    if (!r->dry && l->d.T > 0 && (!X || !Y)) return fail(RTP_ERR_INVALID, "%s: null tensor", who);
+    if (l->d.split == RTP_SPLIT_IN && needs_acc(l) && !acc)
+        return fail(RTP_ERR_INVALID, "%s: the layer was created without its fp32 cross-step accumulator", who);
+    RTP_TRY(enter_step(r, l->next_step, step, RTP_PASS_FWD, who));
     const rtp_linear_desc &d = l->d;
     const int n = r->d.n;
     const int k = r->abl_rotate ? r->resident : rtp_fwd_shard(r->d.rank, step, n);
@@ -776,7 +832,7 @@ extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, voi
             a.epi = step == 0 ? EPI_STORE : EPI_ACC_ADD;
         } else {
             a.epi = acc_epi(step, n);
-            a.ws = d.acc_ws_dev; a.ldws = d.O;
+            a.ws = acc; a.ldws = d.O;
         }
         // The partial products of the N steps only meet in the accumulator, so this GEMM can run
         // on the auxiliary stream beside the next step's output-partitioned GEMM.  It starts after
@@ -798,7 +854,7 @@ extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, voi
         const char *bk = Wk + (size_t)d.O * o * es;
         const int belem = f32 ? -1 : d.dtype == RTP_F16 ? ELEM_F16 : ELEM_BF16;
         const bool live = pv > 0 && !r->dry && r->abl_compute && d.T > 0;
-        float *bdst = (f32 ? (float *)Y : d.acc_ws_dev) + (size_t)k * pb;
+        float *bdst = (f32 ? (float *)Y : acc) + (size_t)k * pb;
         bool after = false;
         if (live) {
             if (f32 || (n > 1 && step == 0)) after = true;
@@ -812,11 +868,19 @@ extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, voi
     return RTP_OK;
 }
 
+extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, void *Y)
+{
+    if (!l) return fail(RTP_ERR_INVALID, "rtp_linear_fwd: null linear");
+    return linear_fwd_step(l, step, X, Y, l->d.acc_ws_dev, "rtp_linear_fwd");
+}
+
 extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, const void *dY, void *dX)
 {
     if (!l) return fail(RTP_ERR_INVALID, "rtp_linear_bwd: null linear");
     rtp_ring *r = l->ring;
     if (!r->dry && l->d.T > 0 && (!X || !dY)) return fail(RTP_ERR_INVALID, "rtp_linear_bwd: null tensor");
+    if (l->d.split == RTP_SPLIT_OUT && dX && needs_acc(l) && !l->d.acc_ws_dev)
+        return fail(RTP_ERR_INVALID, "rtp_linear_bwd: the layer was created without its fp32 cross-step accumulator");
     RTP_TRY(enter_step(r, l->next_step, step, RTP_PASS_BWD, "rtp_linear_bwd"));
     const rtp_linear_desc &d = l->d;
     const int n = r->d.n;
@@ -1377,10 +1441,8 @@ static rtp_status mlp_bwd_grouped(rtp_mlp *m, const void *X, const void *dY, voi
     return rtp_ring_end(r);
 }
 
-extern "C" rtp_status rtp_mlp_fwd(rtp_mlp *m, const void *X, void *Y)
+static rtp_status mlp_fwd_pass(rtp_mlp *m, const void *X, void *Y)
 {
-    if (!m) return fail(RTP_ERR_INVALID, "rtp_mlp_fwd: null mlp");
-    if (!m->ring->dry && m->d.T > 0 && (!X || !Y)) return fail(RTP_ERR_INVALID, "rtp_mlp_fwd: null tensor");
     if (mlp_grouped_ok(m, X, Y, nullptr, nullptr)) return mlp_fwd_grouped(m, X, Y);
     const int n = m->d.n;
     RTP_TRY(rtp_ring_begin(m->ring, RTP_PASS_FWD));
@@ -1392,10 +1454,8 @@ extern "C" rtp_status rtp_mlp_fwd(rtp_mlp *m, const void *X, void *Y)
     return rtp_ring_end(m->ring);
 }
 
-extern "C" rtp_status rtp_mlp_bwd(rtp_mlp *m, const void *X, const void *dY, void *dX)
+static rtp_status mlp_bwd_pass(rtp_mlp *m, const void *X, const void *dY, void *dX)
 {
-    if (!m) return fail(RTP_ERR_INVALID, "rtp_mlp_bwd: null mlp");
-    if (!m->ring->dry && m->d.T > 0 && (!X || !dY)) return fail(RTP_ERR_INVALID, "rtp_mlp_bwd: null tensor");
     // Measured on the Llama-shaped unit: with an auxiliary stream the four GEMMs of a backward
     // step overlap freely when launched one by one (weight gradients on that stream), which beats
     // the two grouped launches by 8 %; without one the grouped launches win by 6 %.
@@ -1409,6 +1469,23 @@ extern "C" rtp_status rtp_mlp_bwd(rtp_mlp *m, const void *X, const void *dY, voi
         RTP_TRY(rtp_linear_bwd(m->l1, s, X, m->d.dpre_dev, dX));
     }
     return rtp_ring_end(m->ring);
+}
+
+// A failure half-way through a pass leaves the ring idle again (rtp_ring_abort), not wedged.
+extern "C" rtp_status rtp_mlp_fwd(rtp_mlp *m, const void *X, void *Y)
+{
+    if (!m) return fail(RTP_ERR_INVALID, "rtp_mlp_fwd: null mlp");
+    if (!m->ring->dry && m->d.T > 0 && (!X || !Y)) return fail(RTP_ERR_INVALID, "rtp_mlp_fwd: null tensor");
+    if (m->ring->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_mlp_fwd: a pass is already open");
+    return close_failed_pass(m->ring, mlp_fwd_pass(m, X, Y));
+}
+
+extern "C" rtp_status rtp_mlp_bwd(rtp_mlp *m, const void *X, const void *dY, void *dX)
+{
+    if (!m) return fail(RTP_ERR_INVALID, "rtp_mlp_bwd: null mlp");
+    if (!m->ring->dry && m->d.T > 0 && (!X || !dY)) return fail(RTP_ERR_INVALID, "rtp_mlp_bwd: null tensor");
+    if (m->ring->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_mlp_bwd: a pass is already open");
+    return close_failed_pass(m->ring, mlp_bwd_pass(m, X, dY, dX));
 }
 
 extern "C" rtp_status rtp_mlp_flush(rtp_mlp *m) { return m ? rtp_ring_flush(m->ring) : fail(RTP_ERR_INVALID, "null mlp"); }
@@ -1542,13 +1619,13 @@ static rtp_status moe_events(rtp_moe *m)
     return RTP_OK;
 }
 
-extern "C" rtp_status rtp_moe_fwd(rtp_moe *m, const void *X, const int32_t *route, void *Y)
+static rtp_status moe_fwd_pass(rtp_moe *m, const void *X, const int32_t *route, void *Y)
 {
-    if (!m) return fail(RTP_ERR_INVALID, "rtp_moe_fwd: null moe");
     rtp_ring *r = m->ring;
     const rtp_moe_desc &d = m->d;
     if (d.T > 0 && (!X || !route || !Y)) return fail(RTP_ERR_INVALID, "rtp_moe_fwd: null tensor");
     if (r->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_moe_fwd: a pass is open");
+    RTP_TRY(refuse_capture(r, "rtp_moe_fwd"));
     RTP_TRY(moe_events(m));
     const int n = d.n;
     const size_t es = esize(d.dtype);
@@ -1605,14 +1682,21 @@ extern "C" rtp_status rtp_moe_fwd(rtp_moe *m, const void *X, const int32_t *rout
     return RTP_OK;
 }
 
-extern "C" rtp_status rtp_moe_bwd(rtp_moe *m, const void *dY, void *dX)
+extern "C" rtp_status rtp_moe_fwd(rtp_moe *m, const void *X, const int32_t *route, void *Y)
 {
-    if (!m) return fail(RTP_ERR_INVALID, "rtp_moe_bwd: null moe");
+    if (!m) return fail(RTP_ERR_INVALID, "rtp_moe_fwd: null moe");
+    if (m->ring->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_moe_fwd: a pass is open");
+    return close_failed_pass(m->ring, moe_fwd_pass(m, X, route, Y));
+}
+
+static rtp_status moe_bwd_pass(rtp_moe *m, const void *dY, void *dX)
+{
     rtp_ring *r = m->ring;
     const rtp_moe_desc &d = m->d;
     if (d.T > 0 && (!dY || !dX)) return fail(RTP_ERR_INVALID, "rtp_moe_bwd: null tensor");
     if (r->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_moe_bwd: a pass is open");
     if (!m->routed) return fail(RTP_ERR_STATE, "rtp_moe_bwd: needs the routing and activations of a forward pass");
+    RTP_TRY(refuse_capture(r, "rtp_moe_bwd"));
     const int n = d.n;
     const size_t es = esize(d.dtype);
     const int64_t P = moe_gated(&d) ? 2 : 1, PO = P * d.O;
@@ -1734,6 +1818,13 @@ extern "C" rtp_status rtp_moe_bwd(rtp_moe *m, const void *dY, void *dX)
     RTP_TRY(rtp_ring_end(r));
     if (r->abl_compute) HIP_TRY(launch_scatter_rows(dX, d.dxp_dev, d.perm_dev, (int)rows, (size_t)d.I * es, cs));
     return RTP_OK;
+}
+
+extern "C" rtp_status rtp_moe_bwd(rtp_moe *m, const void *dY, void *dX)
+{
+    if (!m) return fail(RTP_ERR_INVALID, "rtp_moe_bwd: null moe");
+    if (m->ring->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_moe_bwd: a pass is open");
+    return close_failed_pass(m->ring, moe_bwd_pass(m, dY, dX));
 }
 
 // ---------------------------------------------------------------------------

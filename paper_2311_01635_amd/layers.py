@@ -14,6 +14,19 @@ def _esize(dtype):
     return 4 if dtype == B.RTP_F32 else 2
 
 
+class _PassStreams:
+    """Orders a layer's private streams with the caller's: a pass starts after everything the
+    caller's current stream holds (X, dY or the routing may just have been produced there) and the
+    caller's stream continues after the pass (rtp_ring_end has joined the stage and auxiliary
+    streams into the compute stream)."""
+
+    def _enter(self):
+        self.compute_stream.wait_stream(torch.cuda.current_stream(self.dev))
+
+    def _leave(self):
+        torch.cuda.current_stream(self.dev).wait_stream(self.compute_stream)
+
+
 def pack_out_split(W, n, o=None):
     """[O, I] -> [n, o*I]: shard k is rows [k o, (k+1) o); rows past O (padded partition) are zero."""
     O, I = W.shape
@@ -55,7 +68,7 @@ def unstack_gate_up(Wgu, n):
     return v[:, 0].reshape(n * o, I).contiguous(), v[:, 1].reshape(n * o, I).contiguous()
 
 
-class RtpLinear:
+class RtpLinear(_PassStreams):
     """One rotated linear layer: the N-step loop issued call by call through
     rtp_rotate_step / rtp_linear_fwd / rtp_linear_bwd."""
 
@@ -111,21 +124,25 @@ class RtpLinear:
 
     def forward(self, X, Y):
         r, n = self.ring, self.n
+        self._enter()
         r.begin(B.RTP_PASS_FWD)
         for t in range(n):
             if t < n - 1:
                 r.rotate_step(B.RTP_CW, t)
             self.lin.fwd(t, X, Y)
         r.end()
+        self._leave()
 
     def backward(self, X, dY, dX):
         r, n = self.ring, self.n
+        self._enter()
         r.begin(B.RTP_PASS_BWD)
         for s in range(n):
             if s < n - 1:
                 r.rotate_step(B.RTP_CCW, s)
             self.lin.bwd(s, X, dY, dX)
         r.end()
+        self._leave()
 
     def sync(self):
         self.ring.sync()
@@ -150,7 +167,7 @@ class RtpLinear:
         self.ring.close()
 
 
-class RtpMlp:
+class RtpMlp(_PassStreams):
     """MLP unit (first GEMM output-partitioned, second input-partitioned) run
     by rtp_mlp_fwd / rtp_mlp_bwd: one library call per pass."""
 
@@ -237,10 +254,14 @@ class RtpMlp:
         torch.cuda.synchronize(self.dev)
 
     def forward(self, X, Y):
+        self._enter()
         B.check(B.lib.rtp_mlp_fwd(self.handle, B._ptr(X), B._ptr(Y)), "rtp_mlp_fwd")
+        self._leave()
 
     def backward(self, X, dY, dX):
+        self._enter()
         B.check(B.lib.rtp_mlp_bwd(self.handle, B._ptr(X), B._ptr(dY), B._ptr(dX)), "rtp_mlp_bwd")
+        self._leave()
 
     def set_ablation(self, rotate=True, compute=True):
         B.check(B.lib.rtp_mlp_set_ablation(self.handle, int(rotate), int(compute)), "rtp_mlp_set_ablation")
@@ -283,7 +304,7 @@ class RtpMlp:
             self.handle = C.c_void_p()
 
 
-class RtpMoe:
+class RtpMoe(_PassStreams):
     """Expert-partitioned layer run by rtp_moe_fwd / rtp_moe_bwd: the ring's
     shard is one whole expert.  `experts[e]` = (W1, W2) or (Wg, Wu, Wd)."""
 
@@ -343,10 +364,14 @@ class RtpMoe:
         B.check(B.lib.rtp_moe_create(C.byref(self.handle), C.byref(d)), "rtp_moe_create")
 
     def forward(self, X, route, Y):
+        self._enter()
         B.check(B.lib.rtp_moe_fwd(self.handle, B._ptr(X), B._ptr(route), B._ptr(Y)), "rtp_moe_fwd")
+        self._leave()
 
     def backward(self, dY, dX):
+        self._enter()
         B.check(B.lib.rtp_moe_bwd(self.handle, B._ptr(dY), B._ptr(dX)), "rtp_moe_bwd")
+        self._leave()
 
     def sync(self):
         B.check(B.lib.rtp_moe_sync(self.handle), "rtp_moe_sync")

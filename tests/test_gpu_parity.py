@@ -715,6 +715,35 @@ def test_units_cleared_gradients_start_from_zero():
 
 # ------------------------------------------------------------ HIP graphs --
 
+def test_a_capturing_stream_is_refused_before_anything_is_enqueued():
+    """Passes cannot be recorded into a HIP graph: with the compute stream capturing, every call that would open
+    a pass or enqueue on the ring's streams returns RTP_ERR_UNSUPPORTED and enqueues nothing (the capture stays
+    empty of the library's work and ends normally); afterwards the layer works as before."""
+    T, I, O, n = 64, 64, 128, 4
+    g = torch.Generator(device="cpu").manual_seed(9)
+    ri = lambda lo, hi, shape: torch.randint(lo, hi, shape, generator=g).float()
+    W, X = ri(-2, 3, (O, I)), ri(-2, 3, (T, I))
+    layer = RtpLinear(W.to(DEV, torch.bfloat16), T, n, 1, B.RTP_SPLIT_OUT, B.RTP_DOUBLE_BUFFER, B.RTP_BF16)
+    Xd = X.to(DEV, torch.bfloat16)
+    Y = torch.zeros(T, O, device=DEV, dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    seen = []
+    say("begin an (empty) capture on the compute stream")
+    with torch.cuda.graph(graph, stream=layer.compute_stream, capture_error_mode="relaxed"):
+        for call in (lambda: layer.ring.begin(B.RTP_PASS_FWD), layer.ring.seek_bwd_start, layer.ring.zero_grads):
+            with pytest.raises(B.RtpError) as e:
+                call()
+            seen.append(e.value.status)
+    say("capture ended")
+    torch.cuda.synchronize()
+    assert seen == [B.RTP_ERR_UNSUPPORTED] * 3
+    layer.forward(Xd, Y)
+    layer.sync()
+    assert torch.equal(Y.float().cpu(), (X.double() @ W.double().T).float())
+    layer.close()
+
+
 @pytest.mark.skip(reason="capturing a linear layer's pass (double-buffer mode, three streams) crashed the host inside the "
                          "runtime's end-of-capture call; the cause is not established, so stream capture of a pass is "
                          "documented as unsupported and this case stays off the GPU")

@@ -197,6 +197,40 @@ def test_state_machine_rejects_out_of_sequence_calls():
     ring.close()
 
 
+def test_abort_is_the_way_out_of_a_failed_pass():
+    """A pass that stops half-way (here: simply abandoned after two steps) leaves the ring open; rtp_ring_abort
+    closes it and forgets what the worker holds, after which a forward pass starts over and the destroy calls work."""
+    n = 4
+    ring = _dry_ring(n, 1, B.RTP_DOUBLE_BUFFER, w=16 * 32, g=16 * 32)
+    lin = B.Linear(ring, 4, 8, 32, B.RTP_SPLIT_OUT, B.RTP_F32)
+    ring.abort()                                                     # idle: nothing to do
+    ring.begin(B.RTP_PASS_FWD)
+    ring.rotate_step(B.RTP_CW, 0)
+    lin.fwd(0, None, None)
+    ring.rotate_step(B.RTP_CW, 1)
+    lin.fwd(1, None, None)
+    for call in (ring.flush, ring.zero_grads, lambda: ring.begin(B.RTP_PASS_FWD)):
+        with pytest.raises(B.RtpError) as e:
+            call()
+        assert e.value.status == B.RTP_ERR_STATE
+    ring.abort()
+    assert ring.resident() == -1
+    ring.zero_grads()
+    ring.flush()
+    with pytest.raises(B.RtpError) as e:                             # nothing resident: a backward pass cannot start
+        ring.begin(B.RTP_PASS_BWD)
+    assert e.value.status == B.RTP_ERR_STATE
+    ring.trace(clear=True)
+    ring.begin(B.RTP_PASS_FWD)                                       # ... but a forward pass starts from step 0 again
+    for t in range(n):
+        if t < n - 1:
+            ring.rotate_step(B.RTP_CW, t)
+        lin.fwd(t, None, None)
+    ring.end()
+    assert [(s, k) for (kind, p, s, k, b) in ring.trace() if kind == "fwd"] == [(t, orc.fwd_shard(1, t, n)) for t in range(n)]
+    ring.close()
+
+
 def test_create_rejects_bad_descriptions():
     def ring_status(**kw):
         args = dict(n=4, rank=0, mode=B.RTP_DOUBLE_BUFFER, w_bytes=64, g_bytes=64, flags=B.RTP_FLAG_DRY_RUN)
