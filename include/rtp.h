@@ -309,6 +309,26 @@ rtp_status rtp_linear_fwd(rtp_linear *lin, int step, const void *X_dev, void *Y_
  * input gradient.  Same state rules as rtp_linear_fwd, in a backward pass. */
 rtp_status rtp_linear_bwd(rtp_linear *lin, int step, const void *X_dev, const void *dY_dev, void *dX_dev);
 
+/* rtp_linear_fwd for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same steps, same kernels and same results as rtp_linear_fwd for an
+ * input-partitioned (RTP_SPLIT_IN) bf16 / fp16 layer, but the fp32 accumulator
+ * in which the n steps' partial products meet is a fixed array of
+ * RTP_NOALLOC_ACC_BYTES inside the library's device image (each GPU the
+ * library runs on holds it until the process ends) instead of
+ * rtp_linear_desc.acc_ws_dev, which may then be NULL at rtp_linear_create.
+ * The call itself allocates nothing (no hipMalloc, no hipFree, no allocating
+ * library routine).  X [T, I], Y [T, O] device, as rtp_linear_fwd.
+ * Errors: RTP_ERR_SHAPE if T * O * 4 exceeds RTP_NOALLOC_ACC_BYTES (nothing
+ * is enqueued); RTP_ERR_UNSUPPORTED for an output-partitioned or fp32 layer
+ * (they use no accumulator: call rtp_linear_fwd); otherwise rtp_linear_fwd's.
+ * Every call on a GPU shares that GPU's array.  A pass's step 0 overwrites it
+ * (nothing needs clearing), steps 1 .. n-1 add onto it and step n-1 rounds it
+ * into Y; so the n step calls of one layer's pass must not be interleaved or
+ * overlapped with those of another layer on the same GPU: such calls race. */
+#define RTP_NOALLOC_ACC_BYTES (16u << 20)
+rtp_status rtp_linear_fwd_noalloc(rtp_linear *lin, int step, const void *X_dev, void *Y_dev);
+
 /* ---- MLP unit: the whole N-step loop in one call ------------------------ */
 
 typedef struct {

@@ -25,6 +25,7 @@ RTP_PASS_IDLE, RTP_PASS_FWD, RTP_PASS_BWD = 0, 1, 2
 RTP_CW, RTP_CCW = 1, -1
 RTP_FLAG_DRY_RUN = 1
 RTP_FLAG_STEPWISE = 2
+RTP_NOALLOC_ACC_BYTES = 16 << 20
 LAYOUT_NT, LAYOUT_NN, LAYOUT_TN = 0, 1, 2
 
 TRACE_KINDS = {1: "fwd", 2: "bwd", 3: "w_in", 4: "w_out", 5: "g_in", 6: "g_out"}
@@ -109,6 +110,7 @@ SYMBOLS = {
     "rtp_linear_destroy": (C.c_int, [_P]),
     "rtp_linear_fwd": (C.c_int, [_P, C.c_int, _P, _P]),
     "rtp_linear_bwd": (C.c_int, [_P, C.c_int, _P, _P, _P]),
+    "rtp_linear_fwd_noalloc": (C.c_int, [_P, C.c_int, _P, _P]),
     "rtp_mlp_slot_w_bytes": (C.c_size_t, [C.POINTER(rtp_mlp_desc)]),
     "rtp_mlp_slot_g_bytes": (C.c_size_t, [C.POINTER(rtp_mlp_desc)]),
     "rtp_mlp_create": (C.c_int, [C.POINTER(_P), C.POINTER(rtp_mlp_desc)]),
@@ -284,6 +286,9 @@ class Linear:
 
     def bwd(self, step, X, dY, dX):
         check(lib.rtp_linear_bwd(self.handle, step, _ptr(X), _ptr(dY), _ptr(dX)), "rtp_linear_bwd")
+
+    def fwd_noalloc(self, step, X, Y):
+        check(lib.rtp_linear_fwd_noalloc(self.handle, step, _ptr(X), _ptr(Y)), "rtp_linear_fwd_noalloc")
 
     def close(self):
         if self.handle:

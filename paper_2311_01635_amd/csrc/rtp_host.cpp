@@ -874,6 +874,58 @@ extern "C" rtp_status rtp_linear_fwd(rtp_linear *l, int step, const void *X, voi
     return linear_fwd_step(l, step, X, Y, l->d.acc_ws_dev, "rtp_linear_fwd");
 }
 
+// ---- the forward step for callers that cannot allocate --------------------------------------
+// The fp32 cross-step accumulator of an input-partitioned layer is device memory beyond the
+// layer's inputs and outputs.  rtp_linear_fwd takes it from the caller (acc_ws_dev); this variant
+// takes it from a fixed array in the library's device image, so a caller that cannot call hipMalloc
+// (graph capture around its own allocation-free code, a tight serving loop, a harness that forbids
+// allocation) still gets the layer.  The array's name is a host-side stand-in for the symbol: only
+// the address hipGetSymbolAddress returns, looked up once per device with that device current, is a
+// device pointer, and only that address is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[RTP_NOALLOC_ACC_BYTES];
+
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static void *g_scratch_ptr[NOALLOC_MAX_DEVICES];
+static std::mutex g_scratch_lock;
+
+// device address of `scratch` on the current device
+static rtp_status noalloc_scratch(float **out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= NOALLOC_MAX_DEVICES)
+        return fail(RTP_ERR_UNSUPPORTED, "rtp_linear_fwd_noalloc: device ordinal %d is beyond the %d this entry point keeps a pointer for",
+                    dev, NOALLOC_MAX_DEVICES);
+    std::lock_guard<std::mutex> g(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(RTP_ERR_HIP, "rtp_linear_fwd_noalloc: hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = (float *)g_scratch_ptr[dev];
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_linear_fwd_noalloc(rtp_linear *l, int step, const void *X, void *Y)
+{
+    if (!l) return fail(RTP_ERR_INVALID, "rtp_linear_fwd_noalloc: null linear");
+    const rtp_linear_desc &d = l->d;
+    if (d.split != RTP_SPLIT_IN || d.dtype == RTP_F32)
+        return fail(RTP_ERR_UNSUPPORTED, "rtp_linear_fwd_noalloc: for input-partitioned 16-bit layers (the ones whose steps "
+                                         "meet in an fp32 accumulator); use rtp_linear_fwd for the others");
+    const size_t need = (size_t)d.T * (size_t)d.O * sizeof(float);
+    if (need > RTP_NOALLOC_ACC_BYTES)
+        return fail(RTP_ERR_SHAPE, "rtp_linear_fwd_noalloc: the fp32 accumulator [T=%lld, O=%lld] takes %zu bytes, the "
+                                   "library's fixed array holds %zu", (long long)d.T, (long long)d.O, need,
+                    (size_t)RTP_NOALLOC_ACC_BYTES);
+    float *acc = nullptr;
+    if (needs_acc(l)) RTP_TRY(noalloc_scratch(&acc));
+    // step 0 stores into the accumulator (EPI_ACC_FIRST), so nothing of the previous call's content
+    // has to be cleared; steps 1 .. n-1 add onto what step 0 .. of the same pass left there
+    return linear_fwd_step(l, step, X, Y, acc, "rtp_linear_fwd_noalloc");
+}
+
 extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, const void *dY, void *dX)
 {
     if (!l) return fail(RTP_ERR_INVALID, "rtp_linear_bwd: null linear");
