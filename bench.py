@@ -33,7 +33,13 @@ def parse():
     ap.add_argument("--workload", default="cfg4_llama7b_swiglu")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true", help="skip the three-run staging-overlap measurement")
-    ap.add_argument("--stepwise", action="store_true", help="one launch per linear and step instead of grouped launches")
+    ap.add_argument("--schedule", default="default", choices=["default", "pipelined", "grouped", "stepwise"],
+                    help="launch schedule of the MLP unit: default (forward: independent GEMMs of a step in one launch; "
+                         "backward: one launch per GEMM, weight gradients on the auxiliary stream), pipelined (two decoupled "
+                         "kernel chains on two streams), grouped (grouped launches in both passes), stepwise (one launch per "
+                         "linear and step)")
+    ap.add_argument("--stage-copy", default="kernel", choices=["kernel", "memcpy"],
+                    help="shard transfers by the library's copy kernel (default) or by hipMemcpyAsync device-to-device")
     ap.add_argument("--no-aux-stream", action="store_true", help="no second compute stream")
     ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens in the oracle's timed sample (0: sized for ~15 s)")
     return ap.parse_args()
@@ -116,19 +122,26 @@ def cpu_baseline_moe(w, inp, tokens):
                       f"{dt:.1f} s, fp64 triple loops"}
 
 
-def timed(torch, mlp, X, Y, dY, dX, steps, fwd=True, bwd=True):
-    """ms for `steps` fwd+bwd passes, HIP events on the compute stream."""
+def timed(torch, mlp, X, Y, dY, dX, steps, per_pass=None):
+    """ms for `steps` fwd+bwd passes between one pair of HIP events on the compute stream (every pass ends with
+    the stage and auxiliary streams joined into it).  With a list in `per_pass`, an event between passes as well:
+    the list receives each pass's own duration."""
     s = mlp.compute_stream
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1 if per_pass is not None else 2)]
     torch.cuda.synchronize()
-    e0.record(s)
-    for _ in range(steps):
+    marks[0].record(s)
+    for i in range(steps):
         mlp.forward(X, Y)
         mlp.backward(X, dY, dX)
-    e1.record(s)
+        if per_pass is not None:
+            marks[i + 1].record(s)
+    if per_pass is None:
+        marks[1].record(s)
     mlp.sync()
     torch.cuda.synchronize()
-    return e0.elapsed_time(e1)
+    if per_pass is not None:
+        per_pass.extend(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
+    return marks[0].elapsed_time(marks[-1])
 
 
 def algorithmic_bytes(w, staging_bytes):
@@ -213,14 +226,18 @@ def main():
         inp, weights, X, dY = build_inputs(w, torch, dev)
         act = B.RTP_ACT_SWIGLU if w.kind == "swiglu" else B.RTP_ACT_GELU_ERF
         mode = {"double_buffer": B.RTP_DOUBLE_BUFFER, "inplace_staged": B.RTP_INPLACE_STAGED}[w.mode]
-        mlp = RtpMlp(weights, w.T, w.n, 0, act, mode, B.RTP_BF16, stepwise=a.stepwise, aux_stream=not a.no_aux_stream)
+        mlp = RtpMlp(weights, w.T, w.n, 0, act, mode, B.RTP_BF16, stepwise=a.schedule == "stepwise",
+                     grouped=a.schedule == "grouped", pipelined=a.schedule == "pipelined", aux_stream=not a.no_aux_stream,
+                     stage_memcpy=a.stage_copy == "memcpy")
     Y = torch.empty(w.T, w.O2, device=dev, dtype=torch.bfloat16)
     dX = torch.empty(w.T, w.I, device=dev, dtype=torch.bfloat16)
     torch.cuda.synchronize()
 
     timed(torch, mlp, X, Y, dY, dX, a.warmup)
-    ms = timed(torch, mlp, X, Y, dY, dX, a.steps)
+    passes = []
+    ms = timed(torch, mlp, X, Y, dY, dX, a.steps, per_pass=passes)
     ms_step = ms / a.steps
+    passes.sort()
     tflops = w.flops / (ms_step * 1e-3) / 1e12
 
     # ---- the shader clock the chip sustains under this load (the MFMA peak scales with it) ----
@@ -275,7 +292,17 @@ def main():
         timed(torch, mlp, X, Y, dY, dX, 2)
         t_b = timed(torch, mlp, X, Y, dY, dX, k) / k
         hidden = 1.0 - max(0.0, t_b - t_c) / t_s if t_s > 0 else None
-        overlap = {"ms_compute_only": t_c, "ms_staging_only": t_s, "ms_both": t_b, "rotation_hidden_frac": hidden}
+        # what the fraction covers: the copies on the stage stream.  Per pass the weights make 2(n-1) rotations (each
+        # a copy out to the slot the shard travels to and a copy in from the slot it arrives in) after one initial
+        # load; the gradient shard comes in n times (n-1 rotations and the first load) by copy.  Its way OUT is not a
+        # copy in the timed run: the weight-gradient GEMM that completes a part stores `arriving + own` straight into
+        # the slot it travels to (a fused send); the staging-only run, which launches no GEMM, copies it instead.
+        n_, W_, G_ = w.n, mlp.w_bytes, mlp.g_bytes
+        overlap = {"ms_compute_only": t_c, "ms_staging_only": t_s, "ms_both": t_b, "rotation_hidden_frac": hidden,
+                   "ms_exposed": max(0.0, t_b - t_c),
+                   "staged_bytes": (4 * (n_ - 1) + 1) * W_ + n_ * G_, "g_out_fused": True,
+                   "g_out_bytes_stored_by_gemm_epilogues": (n_ - 1) * G_,
+                   "staging_only_run_bytes": (4 * (n_ - 1) + 1) * W_ + (2 * n_ - 1) * G_}
 
     cpu = None
     if not a.no_cpu_baseline:
@@ -291,12 +318,13 @@ def main():
                "unit": "GB/s", "frac": nbytes / (ms_step * 1e-3) / 1e9 / PEAK_HBM_GBS}
     out = {
         "metric": "TFLOP/s rotated-shard linear fwd+bwd per GPU", "value": tflops, "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step, "higher_is_better": True,
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step, "ms_per_step_median": passes[len(passes) // 2],
+        "ms_per_step_min": passes[0], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "T": w.T, "I": w.I, "O": w.O, "O2": w.O2, "n_shards": w.n, "mode": w.mode,
                    "grad_dtype": "f32", "flops_per_step": w.flops,
-                   "schedule": "expert rotation" if is_moe else "stepwise" if a.stepwise else "grouped",
-                   "aux_stream": not a.no_aux_stream,
+                   "schedule": "expert rotation" if is_moe else a.schedule,
+                   "aux_stream": not a.no_aux_stream, "stage_copy": a.stage_copy,
                    "worker_param_bytes": mlp.worker_bytes(),
                    "table1_rtp_worker_bytes": B.rtp_table1_worker_bytes(False, mlp.w_bytes, mlp.g_bytes)},
         "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,

@@ -82,6 +82,20 @@ typedef enum { RTP_PASS_IDLE = 0, RTP_PASS_FWD = 1, RTP_PASS_BWD = 2 } rtp_pass;
                                 exactly the rtp_rotate_step / rtp_linear_* call
                                 sequence (no grouped launches)                 */
 
+#define RTP_FLAG_GROUPED 4u  /* rtp_mlp_*: grouped launches in the backward pass too
+                                when an auxiliary stream is given (default then: one
+                                launch per GEMM, weight gradients on that stream)    */
+#define RTP_FLAG_PIPELINED 8u /* rtp_mlp_*: with an auxiliary stream, run each pass as
+                                two decoupled kernel chains (first linear's GEMMs /
+                                second linear's GEMMs forward; input gradients /
+                                weight gradients backward), shard parts moving as
+                                soon as their last reader is enqueued               */
+#define RTP_FLAG_STAGE_MEMCPY 16u /* shard transfers through hipMemcpyAsync (device to
+                                device) on the stage stream instead of the library's
+                                copy kernel: the runtime's own transfer path, for
+                                comparison (Rotating Communication Primitive section:
+                                communication on a stream of its own)                */
+
 typedef struct rtp_ring rtp_ring;
 typedef struct rtp_linear rtp_linear;
 typedef struct rtp_mlp rtp_mlp;

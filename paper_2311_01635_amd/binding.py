@@ -25,6 +25,9 @@ RTP_PASS_IDLE, RTP_PASS_FWD, RTP_PASS_BWD = 0, 1, 2
 RTP_CW, RTP_CCW = 1, -1
 RTP_FLAG_DRY_RUN = 1
 RTP_FLAG_STEPWISE = 2
+RTP_FLAG_GROUPED = 4
+RTP_FLAG_PIPELINED = 8
+RTP_FLAG_STAGE_MEMCPY = 16
 RTP_NOALLOC_ACC_BYTES = 16 << 20
 LAYOUT_NT, LAYOUT_NN, LAYOUT_TN = 0, 1, 2
 

@@ -22,11 +22,13 @@ def _newer(dst, srcs):
 
 def build(force: bool = True, verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    headers = [os.path.join(CSRC, "rtp_kernels.h"), os.path.join(CSRC, "rtp_gemm_epilogue.h"), os.path.join(CSRC, "rtp_gemm_pp.h"), os.path.join(HERE, "..", "include", "rtp.h")]
+    kernel_headers = [os.path.join(CSRC, h) for h in ("rtp_kernels.h", "rtp_gemm_epilogue.h", "rtp_gemm_pp.h")]
+    host_headers = [os.path.join(CSRC, "rtp_kernels.h"), os.path.join(HERE, "..", "include", "rtp.h")]
 
     def compile_one(src):
         s = os.path.join(CSRC, src)
         o = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+        headers = host_headers if src == "rtp_host.cpp" else kernel_headers
         if force or not _newer(o, [s] + headers):
             cmd = [HIPCC] + FLAGS + ["-c", s, "-o", o]
             tiled = src.startswith("rtp_gemm_pp_")

@@ -210,6 +210,8 @@ struct rtp_ring {
     std::vector<rtp_trace_rec> trace;
     hipEvent_t ev_free = nullptr, ev_free2 = nullptr, ev_join = nullptr, ev_aux = nullptr;
     hipEvent_t ev_w[2] = {nullptr, nullptr};
+    // the pipelined schedule of the MLP unit moves the two linears' shard parts separately
+    hipEvent_t ev_w2[2] = {nullptr, nullptr}, ev_g2[2] = {nullptr, nullptr}, ev_k[2] = {nullptr, nullptr};
     hipEvent_t ev_g[2] = {nullptr, nullptr};
 
     hipStream_t cs() const { return (hipStream_t)d.compute_stream; }
@@ -242,7 +244,8 @@ struct rtp_linear {
 static rtp_status ensure_events(rtp_ring *r)
 {
     if (r->dry || r->events_ready) return RTP_OK;
-    hipEvent_t *all[] = {&r->ev_free, &r->ev_free2, &r->ev_join, &r->ev_aux, &r->ev_w[0], &r->ev_w[1], &r->ev_g[0], &r->ev_g[1]};
+    hipEvent_t *all[] = {&r->ev_free, &r->ev_free2, &r->ev_join, &r->ev_aux, &r->ev_w[0], &r->ev_w[1], &r->ev_g[0], &r->ev_g[1],
+                         &r->ev_w2[0], &r->ev_w2[1], &r->ev_g2[0], &r->ev_g2[1], &r->ev_k[0], &r->ev_k[1]};
     for (hipEvent_t *e : all)
         HIP_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
     for (rtp_linear *l : r->linears) {
@@ -256,7 +259,10 @@ static rtp_status ensure_events(rtp_ring *r)
 static rtp_status copy_async(rtp_ring *r, void *dst, const void *src, size_t bytes, hipStream_t s)
 {
     if (r->dry || bytes == 0) return RTP_OK;
-    HIP_TRY(launch_copy(dst, src, bytes, s));
+    if (r->d.flags & RTP_FLAG_STAGE_MEMCPY)
+        HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s));
+    else
+        HIP_TRY(launch_copy(dst, src, bytes, s));
     return RTP_OK;
 }
 
@@ -267,9 +273,8 @@ static rtp_status copy_async(rtp_ring *r, void *dst, const void *src, size_t byt
 static rtp_status rotate_async(rtp_ring *r, void *out, const void *held, void *held_next, const void *in, size_t bytes,
                                hipStream_t s)
 {
-    if (r->dry || bytes == 0) return RTP_OK;
-    HIP_TRY(launch_copy(out, held, bytes, s));
-    HIP_TRY(launch_copy(held_next, in, bytes, s));
+    RTP_TRY(copy_async(r, out, held, bytes, s));
+    RTP_TRY(copy_async(r, held_next, in, bytes, s));
     return RTP_OK;
 }
 
@@ -347,7 +352,8 @@ extern "C" rtp_status rtp_ring_destroy(rtp_ring *r)
     if (!r) return RTP_OK;
     if (!r->linears.empty()) return fail(RTP_ERR_STATE, "rtp_ring_destroy: destroy the ring's linears first");
     if (r->events_ready) {
-        hipEvent_t all[] = {r->ev_free, r->ev_free2, r->ev_join, r->ev_aux, r->ev_w[0], r->ev_w[1], r->ev_g[0], r->ev_g[1]};
+        hipEvent_t all[] = {r->ev_free, r->ev_free2, r->ev_join, r->ev_aux, r->ev_w[0], r->ev_w[1], r->ev_g[0], r->ev_g[1],
+                            r->ev_w2[0], r->ev_w2[1], r->ev_g2[0], r->ev_g2[1], r->ev_k[0], r->ev_k[1]};
         for (hipEvent_t e : all)
             if (e) (void)hipEventDestroy(e);
     }
@@ -1493,9 +1499,204 @@ static rtp_status mlp_bwd_grouped(rtp_mlp *m, const void *X, const void *dY, voi
     return rtp_ring_end(r);
 }
 
+// ---- pipelined schedule of the MLP unit (two compute streams) ---------------------------
+// The unit's GEMMs form two chains that only touch through data: forward, Z_t = act(X W1_t^T) on
+// the compute stream and down_t = H_t W2_t^T on the auxiliary stream (down_t needs Z_t, nothing
+// needs down_t but the fp32 sum it adds to); backward, {dPre_s, dX_s} on the compute stream and
+// {dW2_s, dW1_s} on the auxiliary stream, where dPre_{s+1} = (dY W2_{s+1}) act'(.) needs nothing of
+// step s and is therefore issued BEFORE dX_s.  Each chain's next kernel then has its inputs ready
+// long before its predecessor ends, so a kernel that leaves compute units idle (a shard GEMM of 96
+// tiles on 256 units) runs beside the other chain's kernel instead of beside nothing, and no chain
+// waits for a transfer.  The shard parts move per buffer part: as soon as the last kernel that
+// reads a part of a weight buffer (W1 part: Z_t / dX_s; W2 part: down_t / dPre_s) or that adds onto
+// a part of a gradient buffer is enqueued, that part of the shard is sent on and the part of the
+// next shard that uses the same buffer (two steps on for the weights, `ng` steps on for the
+// gradients, ng = number of gradient buffers) is received into it.  Same buffers, same bytes and the
+// same N-1 sends and receives per part and pass as in the step-by-step schedule; same kernels.
+
+static rtp_status stream_after(hipEvent_t ev, hipStream_t later, hipStream_t earlier)
+{
+    HIP_TRY(hipEventRecord(ev, earlier));
+    HIP_TRY(hipStreamWaitEvent(later, ev, 0));
+    return RTP_OK;
+}
+
+// send shard k's part [off, off + bytes) of weight buffer `src` home (rotation `step`)
+static rtp_status w_part_out(rtp_ring *r, int step, int k, int src, size_t off, size_t bytes)
+{
+    RTP_TRY(copy_async(r, r->home_w(k) + off, (const char *)r->d.buf_w_dev[src] + off, bytes, r->ss()));
+    r->rec(TR_W_OUT, step, k, src);
+    return RTP_OK;
+}
+
+// receive shard kin's part into weight buffer `dst` (rotation `step`)
+static rtp_status w_part_in(rtp_ring *r, int step, int kin, int dst, size_t off, size_t bytes)
+{
+    RTP_TRY(copy_async(r, (char *)r->d.buf_w_dev[dst] + off, r->home_w(kin) + off, bytes, r->ss()));
+    r->rec(TR_W_IN, step, kin, dst);
+    return RTP_OK;
+}
+
+// After the last reader (step t) of part [off, off + bytes) of its weight buffer has been enqueued
+// on `reader`: that part of shard t goes home and the part of shard t+2 comes into the buffer.
+static rtp_status w_part_turnover(rtp_ring *r, int t, hipEvent_t scratch_ev, hipStream_t reader, size_t off, size_t bytes,
+                                  hipEvent_t landed)
+{
+    const int n = r->d.n;
+    if (t > n - 2 || bytes == 0) return RTP_OK; // the last shard of a pass stays
+    RTP_TRY(stream_after(scratch_ev, r->ss(), reader));
+    RTP_TRY(w_part_out(r, t, r->shard_at(t), r->w_idx(t), off, bytes));
+    if (t + 2 <= n - 1) {
+        RTP_TRY(w_part_in(r, t + 1, r->shard_at(t + 2), r->w_idx(t + 2), off, bytes));
+        HIP_TRY(hipEventRecord(landed, r->ss()));
+    }
+    return RTP_OK;
+}
+
+static rtp_status mlp_fwd_pipelined(rtp_mlp *m, const void *X, void *Y)
+{
+    rtp_ring *r = m->ring;
+    const int n = r->d.n;
+    const MlpShapes h = mlp_shapes(m);
+    RTP_TRY(rtp_ring_begin(r, RTP_PASS_FWD));
+    const bool rot = r->abl_rotate && n > 1;
+    hipStream_t cs = r->cs(), as = r->as();
+    const size_t w1_bytes = h.w_off2, w2_bytes = r->d.w_bytes - h.w_off2;
+    auto buf = [&](int step) { return (const char *)r->d.buf_w_dev[rot ? r->w_idx(step) : r->res_idx]; };
+    if (rot) {
+        // shard 1 comes into the free buffer at once (its readers belong to earlier passes, which
+        // rtp_ring_begin has ordered before everything enqueued from here on)
+        RTP_TRY(w_part_in(r, 0, r->shard_at(1), r->w_idx(1), 0, w1_bytes));
+        HIP_TRY(hipEventRecord(r->ev_w[1], r->ss()));
+        RTP_TRY(w_part_in(r, 0, r->shard_at(1), r->w_idx(1), h.w_off2, w2_bytes));
+        HIP_TRY(hipEventRecord(r->ev_w2[1], r->ss()));
+    }
+    for (int t = 0; t < n; ++t) {
+        const int k = r->shard_at(t);
+        // ---- Z_t on the compute stream
+        if (rot && t >= 1) HIP_TRY(hipStreamWaitEvent(cs, r->ev_w[t & 1], 0));
+        r->rec(TR_FWD, t, k, rot ? r->w_idx(t) : r->res_idx);
+        GemmArgs a = mlp_args_z(m, h, k, X, buf(t));
+        a.cu_share = 2;
+        RTP_TRY(gemm_group(r, LAY_NT, &a, 1, cs));
+        HIP_TRY(hipEventRecord(r->ev_k[t & 1], cs));
+        if (rot) RTP_TRY(w_part_turnover(r, t, r->ev_free, cs, 0, w1_bytes, r->ev_w[t & 1]));
+        // ---- down_t on the auxiliary stream (the own shard's initial load is ordered before Z_0)
+        HIP_TRY(hipStreamWaitEvent(as, r->ev_k[t & 1], 0));
+        if (rot && t >= 1) HIP_TRY(hipStreamWaitEvent(as, r->ev_w2[t & 1], 0));
+        a = mlp_args_down(m, h, k, t, buf(t), Y);
+        a.cu_share = 2;
+        RTP_TRY(gemm_group(r, LAY_NT, &a, 1, as));
+        if (rot) RTP_TRY(w_part_turnover(r, t, r->ev_free2, as, h.w_off2, w2_bytes, r->ev_w2[t & 1]));
+    }
+    mlp_close_pass(m);
+    return rtp_ring_end(r);
+}
+
+static rtp_status mlp_bwd_pipelined(rtp_mlp *m, const void *X, const void *dY, void *dX)
+{
+    rtp_ring *r = m->ring;
+    const int n = r->d.n;
+    const MlpShapes h = mlp_shapes(m);
+    RTP_TRY(rtp_ring_begin(r, RTP_PASS_BWD));
+    const bool rot = r->abl_rotate && n > 1;
+    const bool move_g = rot && r->d.g_bytes != 0;
+    const int ng = r->d.mode == RTP_DOUBLE_BUFFER ? 2 : 1;
+    hipStream_t cs = r->cs(), as = r->as(), ss = r->ss();
+    const size_t w1_bytes = h.w_off2, w2_bytes = r->d.w_bytes - h.w_off2;
+    const size_t g1_bytes = h.g_off2, g2_bytes = r->d.g_bytes - h.g_off2;
+    auto wbuf = [&](int step) { return (const char *)r->d.buf_w_dev[rot ? r->w_idx(step) : r->res_idx]; };
+    auto gidx = [&](int step) { return rot ? r->g_idx(step) : r->res_g_idx; };
+    auto gbuf = [&](int step) { return (char *)r->d.buf_g_dev[gidx(step)]; };
+
+    // receive the gradient part [off, off + bytes) of the shard step `c` adds onto, into its buffer
+    auto g_part_in = [&](int c, size_t off, size_t bytes, hipEvent_t landed) -> rtp_status {
+        const int kin = r->shard_at(c);
+        RTP_TRY(copy_async(r, gbuf(c) + off, r->home_g(kin) + off, bytes, ss));
+        r->rec(TR_G_IN, c - 1, kin, gidx(c));
+        HIP_TRY(hipEventRecord(landed, ss));
+        return RTP_OK;
+    };
+    // dPre_s on the compute stream, and the turnover of the W2 part it is the last reader of
+    auto emit_dpre = [&](int s) -> rtp_status {
+        if (rot && s >= 1) HIP_TRY(hipStreamWaitEvent(cs, r->ev_w2[s & 1], 0));
+        r->rec(TR_BWD, s, r->shard_at(s), rot ? r->w_idx(s) : r->res_idx);
+        GemmArgs a = mlp_args_dh(m, h, r->shard_at(s), wbuf(s), dY);
+        a.cu_share = 2;
+        RTP_TRY(gemm_group(r, LAY_NN, &a, 1, cs));
+        HIP_TRY(hipEventRecord(r->ev_k[s & 1], cs));
+        if (rot) RTP_TRY(w_part_turnover(r, s, r->ev_free, cs, h.w_off2, w2_bytes, r->ev_w2[s & 1]));
+        return RTP_OK;
+    };
+    // one weight-gradient kernel on the auxiliary stream, fused with the send of its part of the
+    // travelling gradient shard when the shard moves on, then the turnover of that part's buffer
+    auto emit_dw = [&](int s, GemmArgs a, size_t off, size_t bytes, hipEvent_t *landed) -> rtp_status {
+        if (move_g && s >= 1) HIP_TRY(hipStreamWaitEvent(as, landed[s & 1], 0));
+        const bool moves_on = move_g && s <= n - 2;
+        bool fused_send = moves_on && r->abl_compute;
+        if (fused_send) {
+            int ks = 1;
+            gemm_bf16_pp_plan(LAY_TN, &a, 1, nullptr, nullptr, &ks);
+            if (ks > 1) fused_send = false; // K-split partial sums need the plain `+=` form
+        }
+        if (fused_send) {
+            a.epi = EPI_ACC_LAST;
+            a.C = r->home_g(r->shard_at(s)) + off;
+        }
+        RTP_TRY(gemm_group(r, LAY_TN, &a, 1, as));
+        if (!move_g) return RTP_OK;
+        if (moves_on || s + ng <= n - 1) RTP_TRY(stream_after(r->ev_free2, ss, as));
+        if (moves_on) {
+            if (!fused_send) RTP_TRY(copy_async(r, r->home_g(r->shard_at(s)) + off, gbuf(s) + off, bytes, ss));
+            r->rec(TR_G_OUT, s, r->shard_at(s), gidx(s));
+        }
+        if (s + ng <= n - 1) RTP_TRY(g_part_in(s + ng, off, bytes, landed[(s + ng) & 1]));
+        return RTP_OK;
+    };
+
+    if (rot) {
+        // stage stream: after rtp_ring_begin's copies on the compute stream (the second gradient
+        // buffer may be the source of its write-back); then shard 1 comes into the free buffers
+        RTP_TRY(stream_after(r->ev_free, ss, cs));
+        RTP_TRY(w_part_in(r, 0, r->shard_at(1), r->w_idx(1), h.w_off2, w2_bytes));
+        HIP_TRY(hipEventRecord(r->ev_w2[1], ss));
+        RTP_TRY(w_part_in(r, 0, r->shard_at(1), r->w_idx(1), 0, w1_bytes));
+        HIP_TRY(hipEventRecord(r->ev_w[1], ss));
+        if (move_g && ng == 2) {
+            RTP_TRY(g_part_in(1, h.g_off2, g2_bytes, r->ev_g2[1]));
+            RTP_TRY(g_part_in(1, 0, g1_bytes, r->ev_g[1]));
+        }
+    }
+    // the auxiliary stream starts after rtp_ring_begin's load of the first gradient shard
+    RTP_TRY(stream_after(r->ev_aux, as, cs));
+    RTP_TRY(emit_dpre(0));
+    for (int s = 0; s < n; ++s) {
+        const int k = r->shard_at(s);
+        if (s + 1 < n) RTP_TRY(emit_dpre(s + 1));
+        // ---- dX_s (last reader of its buffer's W1 part)
+        if (rot && s >= 1) HIP_TRY(hipStreamWaitEvent(cs, r->ev_w[s & 1], 0));
+        GemmArgs a = mlp_args_dx(m, h, k, s, wbuf(s), dX);
+        a.cu_share = 2;
+        RTP_TRY(gemm_group(r, LAY_NN, &a, 1, cs));
+        if (rot) RTP_TRY(w_part_turnover(r, s, r->ev_free, cs, 0, w1_bytes, r->ev_w[s & 1]));
+        // ---- dW2_s, then dW1_s (needs dPre_s)
+        a = mlp_args_dw2(m, h, k, gbuf(s), dY);
+        a.cu_share = 2;
+        RTP_TRY(emit_dw(s, a, h.g_off2, g2_bytes, r->ev_g2));
+        HIP_TRY(hipStreamWaitEvent(as, r->ev_k[s & 1], 0));
+        a = mlp_args_dw1(m, h, k, gbuf(s), X);
+        a.cu_share = 2;
+        RTP_TRY(emit_dw(s, a, 0, g1_bytes, r->ev_g));
+    }
+    mlp_close_pass(m);
+    return rtp_ring_end(r);
+}
+
 static rtp_status mlp_fwd_pass(rtp_mlp *m, const void *X, void *Y)
 {
-    if (mlp_grouped_ok(m, X, Y, nullptr, nullptr)) return mlp_fwd_grouped(m, X, Y);
+    const bool have_aux = m->ring->as() != m->ring->cs();
+    if (mlp_grouped_ok(m, X, Y, nullptr, nullptr))
+        return have_aux && (m->d.flags & RTP_FLAG_PIPELINED) ? mlp_fwd_pipelined(m, X, Y) : mlp_fwd_grouped(m, X, Y);
     const int n = m->d.n;
     RTP_TRY(rtp_ring_begin(m->ring, RTP_PASS_FWD));
     for (int t = 0; t < n; ++t) {
@@ -1508,11 +1709,15 @@ static rtp_status mlp_fwd_pass(rtp_mlp *m, const void *X, void *Y)
 
 static rtp_status mlp_bwd_pass(rtp_mlp *m, const void *X, const void *dY, void *dX)
 {
-    // Measured on the Llama-shaped unit: with an auxiliary stream the four GEMMs of a backward
-    // step overlap freely when launched one by one (weight gradients on that stream), which beats
-    // the two grouped launches by 8 %; without one the grouped launches win by 6 %.
+    // Measured on the Llama-shaped unit (ms per backward pass, same box): with an auxiliary stream, one launch
+    // per GEMM with the weight gradients on that stream 3.15, the pipelined schedule 3.2-3.4, the two grouped
+    // launches per step 3.4-3.5; without one the grouped launches win (3.5 against 3.7).  Whatever the schedule,
+    // the kernels of a pass need ~4.26 ms of a machine that is busy throughout: see the design doc's schedule table.
     const bool have_aux = m->ring->as() != m->ring->cs();
-    if (dX && !have_aux && mlp_grouped_ok(m, X, nullptr, dY, dX)) return mlp_bwd_grouped(m, X, dY, dX);
+    if (dX && mlp_grouped_ok(m, X, nullptr, dY, dX)) {
+        if (have_aux && (m->d.flags & RTP_FLAG_PIPELINED)) return mlp_bwd_pipelined(m, X, dY, dX);
+        if (!have_aux || (m->d.flags & RTP_FLAG_GROUPED)) return mlp_bwd_grouped(m, X, dY, dX);
+    }
     const int n = m->d.n;
     RTP_TRY(rtp_ring_begin(m->ring, RTP_PASS_BWD));
     for (int s = 0; s < n; ++s) {

@@ -172,7 +172,7 @@ class RtpMlp(_PassStreams):
     by rtp_mlp_fwd / rtp_mlp_bwd: one library call per pass."""
 
     def __init__(self, weights, T, n, rank, act, mode=B.RTP_INPLACE_STAGED, dtype=B.RTP_BF16, G0=None,
-                 device="cuda:0", aux_stream=True, stepwise=False, biases=None, gb0=None):
+                 device="cuda:0", aux_stream=True, stepwise=False, biases=None, gb0=None, grouped=False, pipelined=False, stage_memcpy=False):
         self.dev = torch.device(device)
         td = _TORCH_DT[dtype]
         self.n, self.rank, self.T, self.act, self.mode, self.dtype = n, rank, T, act, mode, dtype
@@ -192,7 +192,8 @@ class RtpMlp(_PassStreams):
         d = B.rtp_mlp_desc()
         d.T, d.I, d.O, d.O2 = T, self.I, self.O, self.O2
         d.n, d.rank, d.mode, d.dtype, d.act = n, rank, mode, dtype, act
-        d.flags = B.RTP_FLAG_STEPWISE if stepwise else 0
+        d.flags = ((B.RTP_FLAG_STEPWISE if stepwise else 0) | (B.RTP_FLAG_GROUPED if grouped else 0) |
+                   (B.RTP_FLAG_PIPELINED if pipelined else 0) | (B.RTP_FLAG_STAGE_MEMCPY if stage_memcpy else 0))
         d.has_bias = int(self.has_bias)
         wb, gb = B.lib.rtp_mlp_slot_w_bytes(C.byref(d)), B.lib.rtp_mlp_slot_g_bytes(C.byref(d))
         g = None if G0 is None else [x.to(self.dev, torch.float32) for x in G0]

@@ -480,7 +480,20 @@ def test_empty_batch_is_a_no_op():
 
 # -------------------------------------------------------------------- MLP unit --
 
-def _mlp_case(w: wl.Workload, rank, mode, seed=0, grad0=True, stepwise=False, aux_stream=True):
+def _schedule(name):
+    """Keyword arguments of RtpMlp for a schedule name.  default: forward grouped (independent GEMMs of a step as
+    one launch), backward one launch per GEMM with the weight gradients on the auxiliary stream; pipelined: two
+    decoupled kernel chains on the compute and the auxiliary stream; grouped: grouped launches in both passes,
+    weight gradients on the auxiliary stream; grouped_one_stream: the same on one compute stream; stepwise*: one
+    launch per linear and step."""
+    return dict(stepwise=name.startswith("stepwise"), grouped=name.startswith("grouped"),
+                pipelined=name == "pipelined", aux_stream=not name.endswith("one_stream"))
+
+
+SCHEDULES = ["default", "pipelined", "grouped", "grouped_one_stream", "stepwise", "stepwise_one_stream"]
+
+
+def _mlp_case(w: wl.Workload, rank, mode, seed=0, grad0=True, **schedule):
     td, bd = _TD[w.dtype], _BD[w.dtype]
     inp = wl.make_inputs(w, seed, grad0=grad0)
     X, dY = inp["X"], inp["dY"]
@@ -496,8 +509,7 @@ def _mlp_case(w: wl.Workload, rank, mode, seed=0, grad0=True, stepwise=False, au
         ref = orc.rtp_mlp(f64(X), f64(inp["W1"]), f64(inp["W2"]), f64(dY), w.n, rank, kind, *g0)
         gkeys = ("dW1", "dW2")
     mlp = RtpMlp([dev(inp[k], td) for k in names], w.T, w.n, rank, act, mode, bd,
-                 G0=[dev(inp["G0_" + k], torch.float32) for k in names] if grad0 else None, stepwise=stepwise,
-                 aux_stream=aux_stream)
+                 G0=[dev(inp["G0_" + k], torch.float32) for k in names] if grad0 else None, **schedule)
     Xd, dYd = dev(X, td), dev(dY, td)
     Y = torch.full((w.T, w.O2), float("nan"), device=DEV, dtype=td)
     dX = torch.full((w.T, w.I), float("nan"), device=DEV, dtype=td)
@@ -529,33 +541,30 @@ def test_mlp_unit_small(kind, dtype, mode):
             assert relerr(out[key], ref[key]) <= tol, (key, relerr(out[key], ref[key]))
 
 
-@pytest.mark.parametrize("schedule", ["default", "grouped_one_stream", "stepwise", "stepwise_one_stream"])
+@pytest.mark.parametrize("schedule", SCHEDULES)
 @pytest.mark.parametrize("mode", [B.RTP_DOUBLE_BUFFER, B.RTP_INPLACE_STAGED])
-@pytest.mark.parametrize("kind,n", [("mlp_gelu", 4), ("swiglu", 4), ("swiglu", 3), ("swiglu", 1)])
+@pytest.mark.parametrize("kind,n", [("mlp_gelu", 4), ("swiglu", 4), ("swiglu", 3), ("swiglu", 2), ("swiglu", 1)])
 def test_mlp_unit_grouped_launches(kind, n, mode, schedule):
     """Shapes the tiled kernel takes (every contraction length a multiple of 32), so the unit can run
-    its grouped schedule (second linear one step behind the first); ragged tiles in every dimension.
-    default: forward grouped, backward step by step with weight gradients on the auxiliary stream;
-    grouped_one_stream: both passes grouped; stepwise*: one launch per linear and step."""
-    stepwise, aux = schedule.startswith("stepwise"), not schedule.endswith("one_stream")
+    its pipelined and grouped schedules; ragged tiles in every dimension.  Every schedule (see _schedule)
+    must give the oracle's results."""
     w = wl.Workload("mlp_grouped", kind, T=288, I=160, O=n * 128, O2=96, n=n, dtype="bf16", mode="x",
                     w_dist=("normal", 0.08))
     for rank in sorted({0, n - 1}):
         say(f"grouped mlp kind={kind} n={n} mode={mode} schedule={schedule} rank={rank}")
-        out, ref, gkeys = _mlp_case(w, rank, mode, stepwise=stepwise, aux_stream=aux)
+        out, ref, gkeys = _mlp_case(w, rank, mode, **_schedule(schedule))
         assert out["W_same"]
         for key in ("H", "Y", "dX") + tuple(gkeys):
             assert np.isfinite(out[key]).all(), key
             assert relerr(out[key], ref[key]) <= TOL_BF16, (key, relerr(out[key], ref[key]))
 
 
-@pytest.mark.parametrize("schedule", ["default", "grouped_one_stream", "stepwise"])
+@pytest.mark.parametrize("schedule", ["default", "pipelined", "grouped_one_stream", "stepwise"])
 @pytest.mark.parametrize("kind", ["mlp_gelu", "swiglu"])
 def test_mlp_unit_fp16(kind, schedule):
-    stepwise, aux = schedule.startswith("stepwise"), not schedule.endswith("one_stream")
     w = wl.Workload("mlp_f16", kind, T=288, I=160, O=4 * 128, O2=96, n=4, dtype="f16", mode="x", w_dist=("normal", 0.08))
     say(f"fp16 mlp kind={kind} schedule={schedule}")
-    out, ref, gkeys = _mlp_case(w, 2, B.RTP_INPLACE_STAGED, stepwise=stepwise, aux_stream=aux)
+    out, ref, gkeys = _mlp_case(w, 2, B.RTP_INPLACE_STAGED, **_schedule(schedule))
     assert out["W_same"]
     for key in ("H", "Y", "dX") + tuple(gkeys):
         assert np.isfinite(out[key]).all(), key
@@ -572,9 +581,9 @@ def test_mlp_grouped_and_stepwise_agree_bitwise_on_integers():
     Ws = [ints(inp[k].shape) for k in ("Wg", "Wu", "Wd")]
     X, dY = ints(inp["X"].shape), ints(inp["dY"].shape)
     res = []
-    for stepwise, aux in ((False, False), (False, True), (True, True)):
+    for sched in ("grouped_one_stream", "default", "pipelined", "grouped", "stepwise"):
         mlp = RtpMlp([dev(a, torch.bfloat16) for a in Ws], w.T, w.n, 1, B.RTP_ACT_SWIGLU, B.RTP_INPLACE_STAGED, B.RTP_BF16,
-                     stepwise=stepwise, aux_stream=aux)
+                     **_schedule(sched))
         Y = torch.empty(w.T, w.O2, device=DEV, dtype=torch.bfloat16)
         dX = torch.empty(w.T, w.I, device=DEV, dtype=torch.bfloat16)
         Xd, dYd = dev(X, torch.bfloat16), dev(dY, torch.bfloat16)
@@ -592,18 +601,17 @@ def test_mlp_grouped_and_stepwise_agree_bitwise_on_integers():
             assert torch.equal(a, b)
 
 
-@pytest.mark.parametrize("schedule", ["default", "grouped_one_stream", "stepwise"])
+@pytest.mark.parametrize("schedule", ["default", "pipelined", "grouped", "grouped_one_stream", "stepwise"])
 def test_mlp_gradients_accumulate_over_passes(schedule):
     """Two passes of the unit without reading the store in between add the pass's weight gradients twice
-    onto what arrived (all shards, the one the worker ends on included)."""
-    stepwise, aux = schedule.startswith("stepwise"), not schedule.endswith("one_stream")
+    onto what arrived (all shards, the one the worker ends on included): G = G0 + 2 dW, with dW the oracle's."""
     w = wl.Workload("mlp_twice", "swiglu", T=288, I=160, O=4 * 128, O2=96, n=4, dtype="bf16", mode="x", w_dist=("normal", 0.08))
     inp = wl.make_inputs(w, seed=12, grad0=True)
     names = ("Wg", "Wu", "Wd")
     res = []
     for passes in (1, 2):
         mlp = RtpMlp([dev(inp[k], torch.bfloat16) for k in names], w.T, w.n, 1, B.RTP_ACT_SWIGLU, B.RTP_INPLACE_STAGED,
-                     B.RTP_BF16, G0=[dev(inp["G0_" + k], torch.float32) for k in names], stepwise=stepwise, aux_stream=aux)
+                     B.RTP_BF16, G0=[dev(inp["G0_" + k], torch.float32) for k in names], **_schedule(schedule))
         X, dY = dev(inp["X"], torch.bfloat16), dev(inp["dY"], torch.bfloat16)
         Y = torch.empty(w.T, w.O2, device=DEV, dtype=torch.bfloat16)
         dX = torch.empty(w.T, w.I, device=DEV, dtype=torch.bfloat16)
@@ -614,8 +622,13 @@ def test_mlp_gradients_accumulate_over_passes(schedule):
         _, Gs = mlp.gathered()
         res.append([host(g) for g in Gs])
         mlp.close()
-    for k, g1, g2 in zip(names, *res):
+    # the oracle's one-pass result from the same arriving gradients: ref = G0 + dW, so two passes give 2 ref - G0
+    ref = orc.rtp_swiglu(f64(inp["X"]), *[f64(inp[k]) for k in names], f64(inp["dY"]), w.n, 1,
+                         *[f64(inp["G0_" + k]) for k in names])
+    for k, key, g1, g2 in zip(names, ("dWg", "dWu", "dWd"), *res):
         g0 = f64(inp["G0_" + k])
+        assert relerr(g1, ref[key]) <= TOL_BF16, (k, relerr(g1, ref[key]))
+        assert relerr(g2, 2.0 * ref[key] - g0) <= TOL_BF16, (k, relerr(g2, 2.0 * ref[key] - g0))
         assert relerr(g2 - g0, 2.0 * (g1 - g0)) <= 1e-5, (k, relerr(g2 - g0, 2.0 * (g1 - g0)))
 
 
