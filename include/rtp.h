@@ -129,6 +129,38 @@ int64_t rtp_shard_width(int64_t dim, int n, rtp_dtype dtype);
 size_t rtp_worker_bytes(rtp_mode mode, size_t w_bytes, size_t g_bytes);
 size_t rtp_table1_worker_bytes(int inplace, size_t w_bytes, size_t g_bytes);
 
+/* ---- the shard layout of the ring store (device kernels) ---------------- */
+
+/* Writes a full row-major matrix W[O, I] (device) into the ring store as its
+ * n shards (Partition Strategies section: Output-Partition and the
+ * input-dimension partition of the layer that follows it; FlatParameter
+ * paragraph: every parameter of the unit flattened into one slot, padded so
+ * that it divides evenly).  Shard k's part is written at
+ * home_dev + k * slot_bytes + offset:
+ *   RTP_SPLIT_OUT  rows [k w, (k+1) w) of W, stored [w, I];
+ *   RTP_SPLIT_IN   columns [k w, (k+1) w) of W, stored contiguously as [O, w];
+ * w = `width` (rtp_shard_width of the partitioned dimension; O / n or I / n
+ * when n divides it).  Elements of a shard that lie past the matrix (padded
+ * partition) are written as zeros.  `dtype` is the element type of W and of
+ * the store (RTP_F32 for a gradient store).  Nothing else of the slot is
+ * touched, so a unit's slot is built by one call per matrix with that
+ * matrix's offset: a (gate, up) pair is two output-partitioned matrices whose
+ * parts follow each other; a bias vector is a matrix with I = 1 (its shard
+ * entries follow its matrix, see rtp_linear_desc.has_bias; the pieces of an
+ * input-partitioned layer's bias are RTP_SPLIT_OUT with
+ * width = rtp_bias_piece_width).  With n = 1 the call copies one matrix into
+ * one slot (an expert of the expert partition).
+ * rtp_unpack_shards is the inverse: it reads the n parts back into W[O, I]
+ * and drops the padding.  Both enqueue one kernel on `stream` (a hipStream_t)
+ * and return.  All memory is the caller's.
+ * Errors: RTP_ERR_INVALID (null pointer, bad enum), RTP_ERR_SHAPE (sizes not
+ * positive, n * width short of the partitioned dimension, part beyond the
+ * slot, pointers / offset / slot size not multiples of the element size). */
+rtp_status rtp_pack_shards(void *home_dev, size_t slot_bytes, size_t offset, int n, rtp_split split,
+                           const void *W_dev, int64_t O, int64_t I, int64_t width, rtp_dtype dtype, void *stream);
+rtp_status rtp_unpack_shards(void *W_dev, const void *home_dev, size_t slot_bytes, size_t offset, int n,
+                             rtp_split split, int64_t O, int64_t I, int64_t width, rtp_dtype dtype, void *stream);
+
 const char *rtp_status_str(rtp_status s);
 const char *rtp_last_error(void);
 

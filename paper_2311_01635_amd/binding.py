@@ -93,6 +93,8 @@ SYMBOLS = {
     "rtp_linear_shard_g_bytes": (C.c_size_t, [C.POINTER(rtp_linear_desc), C.c_int]),
     "rtp_worker_bytes": (C.c_size_t, [C.c_int, C.c_size_t, C.c_size_t]),
     "rtp_table1_worker_bytes": (C.c_size_t, [C.c_int, C.c_size_t, C.c_size_t]),
+    "rtp_pack_shards": (C.c_int, [_P, C.c_size_t, C.c_size_t, C.c_int, C.c_int, _P, C.c_int64, C.c_int64, C.c_int64, C.c_int, _P]),
+    "rtp_unpack_shards": (C.c_int, [_P, _P, C.c_size_t, C.c_size_t, C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_int, _P]),
     "rtp_status_str": (C.c_char_p, [C.c_int]),
     "rtp_prof_begin_alone": (C.c_int, [C.c_int]),
     "rtp_clock_probe": (C.c_int, [_P, _P, C.c_int64, C.POINTER(C.c_int)]),
@@ -298,6 +300,17 @@ class Linear:
             check(lib.rtp_linear_destroy(self.handle), "rtp_linear_destroy")
             self.handle = C.c_void_p()
             self.ring.linears.remove(self)
+
+
+def rtp_pack_shards(home, slot_bytes, offset, n, split, W, O, I, width, dtype, stream=None):
+    """W[O, I] -> the n slots of `home` (a tensor or a raw device address), shard k's part at k * slot_bytes + offset."""
+    hp = home if isinstance(home, (int, C.c_void_p)) else _ptr(home)
+    check(lib.rtp_pack_shards(hp, slot_bytes, offset, n, split, _ptr(W), O, I, width, dtype, _stream(stream)), "rtp_pack_shards")
+
+
+def rtp_unpack_shards(W, home, slot_bytes, offset, n, split, O, I, width, dtype, stream=None):
+    hp = home if isinstance(home, (int, C.c_void_p)) else _ptr(home)
+    check(lib.rtp_unpack_shards(_ptr(W), hp, slot_bytes, offset, n, split, O, I, width, dtype, _stream(stream)), "rtp_unpack_shards")
 
 
 def rtp_gemm(layout, in_dtype, out_dtype, accumulate, A, lda, B, ldb, Cmat, ldc, M, N, K, variant=0, stream=None):

@@ -187,6 +187,42 @@ extern "C" size_t rtp_table1_worker_bytes(int inplace, size_t w, size_t g)
 }
 
 // ---------------------------------------------------------------------------
+// shard layout (Partition Strategies section; FlatParameter paragraph)
+// ---------------------------------------------------------------------------
+static rtp_status shard_layout(const char *who, void *home, size_t slot_bytes, size_t offset, int n, rtp_split split,
+                               void *W, int64_t O, int64_t I, int64_t width, rtp_dtype dtype, void *stream, int unpack)
+{
+    if (!home || !W) return fail(RTP_ERR_INVALID, "%s: null pointer", who);
+    if (split != RTP_SPLIT_OUT && split != RTP_SPLIT_IN) return fail(RTP_ERR_INVALID, "%s: bad split", who);
+    if (dtype != RTP_F32 && dtype != RTP_BF16 && dtype != RTP_F16) return fail(RTP_ERR_INVALID, "%s: bad dtype", who);
+    if (n < 1 || O <= 0 || I <= 0 || width <= 0) return fail(RTP_ERR_SHAPE, "%s: n, O, I and the shard width must be positive", who);
+    const int64_t part = split == RTP_SPLIT_OUT ? O : I, other = split == RTP_SPLIT_OUT ? I : O;
+    if ((int64_t)n * width < part)
+        return fail(RTP_ERR_SHAPE, "%s: %d shards of width %lld do not cover a dimension of %lld", who, n, (long long)width,
+                    (long long)part);
+    const size_t es = dtype == RTP_F32 ? 4 : 2;
+    if (offset % es || ((uintptr_t)home % es) || slot_bytes % es || ((uintptr_t)W % es))
+        return fail(RTP_ERR_SHAPE, "%s: pointers, the slot size and the offset must be multiples of the element size", who);
+    if (offset + (size_t)width * (size_t)other * es > slot_bytes)
+        return fail(RTP_ERR_SHAPE, "%s: the shard part does not fit the slot", who);
+    HIP_TRY(launch_shard_layout(home, slot_bytes, offset, n, split == RTP_SPLIT_IN, W, O, I, width, (int)es, unpack,
+                                (hipStream_t)stream));
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_pack_shards(void *home, size_t slot_bytes, size_t offset, int n, rtp_split split, const void *W,
+                                      int64_t O, int64_t I, int64_t width, rtp_dtype dtype, void *stream)
+{
+    return shard_layout("rtp_pack_shards", home, slot_bytes, offset, n, split, (void *)W, O, I, width, dtype, stream, 0);
+}
+
+extern "C" rtp_status rtp_unpack_shards(void *W, const void *home, size_t slot_bytes, size_t offset, int n, rtp_split split,
+                                        int64_t O, int64_t I, int64_t width, rtp_dtype dtype, void *stream)
+{
+    return shard_layout("rtp_unpack_shards", (void *)home, slot_bytes, offset, n, split, W, O, I, width, dtype, stream, 1);
+}
+
+// ---------------------------------------------------------------------------
 // ring
 // ---------------------------------------------------------------------------
 enum { TR_FWD = 1, TR_BWD = 2, TR_W_IN = 3, TR_W_OUT = 4, TR_G_IN = 5, TR_G_OUT = 6 };

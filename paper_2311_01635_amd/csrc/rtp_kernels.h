@@ -74,6 +74,11 @@ hipError_t launch_act_f32(int kind, const float *pre, int64_t ldpre, const float
 // device-to-device staging copy with a bounded number of workgroups
 hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
 hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s);
+// shard layout (pack: W -> slots, unpack: slots -> W): slot k's part at home + k * slot_bytes + off holds rows
+// [k w, (k+1) w) of W[O, I] as [w, I] (cols == 0) or columns [k w, (k+1) w) as [O, w] (cols != 0); elements past
+// the matrix are zero (pack) / skipped (unpack).  elem_bytes 2 or 4.
+hipError_t launch_shard_layout(void *home, size_t slot_bytes, size_t off, int n, int cols, void *W, int64_t O, int64_t I,
+                               int64_t w, int elem_bytes, int unpack, hipStream_t s);
 // bias gradient: out[c] = in[c] + sum over rows of Y[r, c], c < cols (fp32 in/out, which may be the same);
 // elem: -1 fp32, ELEM_BF16, ELEM_F16
 hipError_t launch_colsum(int elem, const void *Y, int64_t ld, int rows, int cols, const float *in, float *out, hipStream_t s);

@@ -202,6 +202,60 @@ hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s)
     return hipGetLastError();
 }
 
+// ---- shard layout: a full matrix into (out of) the N slots of the ring store --------------------
+// Shard k of W[O, I] is a row block [w, I] (rows k w .. of W; output partition) or a column block
+// stored contiguously as [O, w] (columns k w .. of W; input partition) at `off` bytes into slot k.
+// Elements of the shard that lie past the matrix (a padded partition) are written as zero when
+// packing and skipped when unpacking.  One thread per element of the shard grid, consecutive
+// threads on consecutive shard elements (the writes of a pack and the reads of an unpack coalesce;
+// the other side is row-contiguous for the row blocks and w-element runs for the column blocks).
+template <typename T, bool COLS, bool UNPACK>
+__global__ __launch_bounds__(256) void shard_layout_kernel(char *home, size_t slot_bytes, size_t off, T *W, int64_t O,
+                                                           int64_t I, int64_t w, int n)
+{
+    const int64_t per = COLS ? O * w : w * I; // elements of one shard
+    const int64_t total = per * n;
+    for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t k = e / per, i = e - k * per;
+        int64_t row, col;
+        if (COLS) {
+            row = i / w;
+            col = k * w + (i - row * w);
+        } else {
+            row = k * w + i / I;
+            col = i - (i / I) * I;
+        }
+        T *slot = (T *)(home + (size_t)k * slot_bytes + off) + i;
+        const bool inside = row < O && col < I;
+        if (UNPACK) {
+            if (inside) W[row * I + col] = *slot;
+        } else {
+            *slot = inside ? W[row * I + col] : (T)0;
+        }
+    }
+}
+
+hipError_t launch_shard_layout(void *home, size_t slot_bytes, size_t off, int n, int cols, void *W, int64_t O, int64_t I,
+                               int64_t w, int elem_bytes, int unpack, hipStream_t s)
+{
+    const int64_t total = (cols ? O * w : w * I) * n;
+    if (total <= 0) return hipSuccess;
+    const unsigned blocks = (unsigned)std::min<int64_t>((total + 255) / 256, 1 << 16);
+#define RTP_SHARD_LAYOUT(T, C, U) \
+    hipLaunchKernelGGL((shard_layout_kernel<T, C, U>), dim3(blocks), dim3(256), 0, s, (char *)home, slot_bytes, off, (T *)W, O, I, w, n)
+    if (elem_bytes == 2) {
+        if (cols) { if (unpack) RTP_SHARD_LAYOUT(uint16_t, true, true); else RTP_SHARD_LAYOUT(uint16_t, true, false); }
+        else { if (unpack) RTP_SHARD_LAYOUT(uint16_t, false, true); else RTP_SHARD_LAYOUT(uint16_t, false, false); }
+    } else if (elem_bytes == 4) {
+        if (cols) { if (unpack) RTP_SHARD_LAYOUT(uint32_t, true, true); else RTP_SHARD_LAYOUT(uint32_t, true, false); }
+        else { if (unpack) RTP_SHARD_LAYOUT(uint32_t, false, true); else RTP_SHARD_LAYOUT(uint32_t, false, false); }
+    } else {
+        return hipErrorInvalidValue;
+    }
+#undef RTP_SHARD_LAYOUT
+    return hipGetLastError();
+}
+
 // ---- bias piece of an input-partitioned layer, added onto a slice of the fp32 accumulator ----------
 template <typename T>
 __global__ __launch_bounds__(256) void bias_add_kernel(float *dst, int64_t ld, int rows, int cols, const T *bias)

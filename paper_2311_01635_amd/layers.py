@@ -27,45 +27,28 @@ class _PassStreams:
         torch.cuda.current_stream(self.dev).wait_stream(self.compute_stream)
 
 
-def pack_out_split(W, n, o=None):
-    """[O, I] -> [n, o*I]: shard k is rows [k o, (k+1) o); rows past O (padded partition) are zero."""
-    O, I = W.shape
-    o = O // n if o is None else o
-    if n * o != O:
-        W = torch.cat((W, W.new_zeros(n * o - O, I)), dim=0)
-    return W.reshape(n, o * I).clone()       # a store of its own: the ring writes into it
+class _Store:
+    """The ring store of one unit: `n` slots of `slot_bytes` each (a uint8 tensor), written and read through
+    rtp_pack_shards / rtp_unpack_shards.  `parts` remembers where each full matrix (or bias vector) lives."""
 
+    def __init__(self, n, slot_bytes, dtype, device):
+        self.n, self.slot_bytes, self.dtype = n, slot_bytes, dtype
+        self.es = _esize(dtype)
+        self.buf = torch.zeros(n, slot_bytes, dtype=torch.uint8, device=device)   # padding between parts stays zero
+        self.parts = {}
 
-def pack_in_split(W, n, o=None):
-    """[O, I] -> [n, O*o]: shard k is columns [k o, (k+1) o), stored [O, o]; columns past I are zero."""
-    O, I = W.shape
-    o = I // n if o is None else o
-    if n * o != I:
-        W = torch.cat((W, W.new_zeros(O, n * o - I)), dim=1)
-    return W.reshape(O, n, o).permute(1, 0, 2).clone(memory_format=torch.contiguous_format).reshape(n, O * o)
+    def pack(self, name, M, offset, split, width):
+        """Matrix M [O, I] (a vector counts as [O, 1]) into the store at `offset` bytes of every slot."""
+        M2 = M.reshape(M.shape[0], -1).to(self.buf.device, _TORCH_DT[self.dtype]).contiguous()
+        O, I = M2.shape
+        self.parts[name] = (offset, split, O, I, width, tuple(M.shape))
+        B.rtp_pack_shards(self.buf, self.slot_bytes, offset, self.n, split, M2, O, I, width, self.dtype)
 
-
-def unpack_out_split(P, n, O, I):
-    return P.reshape(-1, I)[:O].contiguous()
-
-
-def unpack_in_split(P, n, O, I):
-    o = P.shape[1] // O
-    return P.reshape(n, O, o).permute(1, 0, 2).reshape(O, n * o)[:, :I].contiguous()
-
-
-def stack_gate_up(Wg, Wu, n):
-    """[O, I] x 2 -> [2 O, I] with shard k = gate rows k followed by up rows k."""
-    O, I = Wg.shape
-    o = O // n
-    return torch.stack((Wg.reshape(n, o, I), Wu.reshape(n, o, I)), dim=1).reshape(2 * O, I).contiguous()
-
-
-def unstack_gate_up(Wgu, n):
-    O2, I = Wgu.shape
-    o = O2 // (2 * n)
-    v = Wgu.reshape(n, 2, o, I)
-    return v[:, 0].reshape(n * o, I).contiguous(), v[:, 1].reshape(n * o, I).contiguous()
+    def unpack(self, name):
+        offset, split, O, I, width, shape = self.parts[name]
+        out = torch.empty(O, I, dtype=_TORCH_DT[self.dtype], device=self.buf.device)
+        B.rtp_unpack_shards(out, self.buf, self.slot_bytes, offset, self.n, split, O, I, width, self.dtype)
+        return out.reshape(shape)
 
 
 class RtpLinear(_PassStreams):
@@ -79,35 +62,26 @@ class RtpLinear(_PassStreams):
         td = _TORCH_DT[dtype]
         W = W.to(self.dev, td).contiguous()
         self.O, self.I = W.shape
-        pack = pack_out_split if split == B.RTP_SPLIT_OUT else pack_in_split
         o = B.lib.rtp_shard_width(self.O if split == B.RTP_SPLIT_OUT else self.I, n, dtype)
         if o <= 0:
             raise ValueError("the partitioned dimension cannot be split into n non-empty aligned shards")
         self.o, self.has_bias = o, bias is not None
-        self.home_w = pack(W, n, o).contiguous()
-        G0 = torch.zeros(self.O, self.I, device=self.dev, dtype=torch.float32) if G0 is None else \
-            G0.to(self.dev, torch.float32)
-        self.home_g = pack(G0, n, o).contiguous()
-        self.n_mat = self.home_w.shape[1]                  # elements of a matrix shard
+        d = B.rtp_linear_desc()
+        d.T, d.I, d.O, d.split, d.dtype, d.grad_dtype, d.has_bias = T, self.I, self.O, split, dtype, B.RTP_F32, int(self.has_bias)
+        wb, gb = B.lib.rtp_linear_shard_w_bytes(C.byref(d), n), B.lib.rtp_linear_shard_g_bytes(C.byref(d), n)
+        # the shard layout is the library's (rtp_pack_shards): shard k of the flat parameter = its block of W,
+        # then (with a bias) its entries of b -- for an input-partitioned layer piece k of b
+        self.store_w, self.store_g = _Store(n, wb, dtype, self.dev), _Store(n, gb, B.RTP_F32, self.dev)
+        G0 = torch.zeros(self.O, self.I, device=self.dev, dtype=torch.float32) if G0 is None else G0
+        self.store_w.pack("W", W, 0, split, o)
+        self.store_g.pack("W", G0, 0, split, o)
+        n_mat = o * (self.I if split == B.RTP_SPLIT_OUT else self.O)      # elements of a matrix shard
         if self.has_bias:
-            # shard k of the flat parameter = its rows of W, then its entries of b, padded to 16 bytes
-            d = B.rtp_linear_desc()
-            d.T, d.I, d.O, d.split, d.dtype, d.grad_dtype, d.has_bias = T, self.I, self.O, split, dtype, B.RTP_F32, 1
-            wbytes, gbytes = B.lib.rtp_linear_shard_w_bytes(C.byref(d), n), B.lib.rtp_linear_shard_g_bytes(C.byref(d), n)
-            # (an input-partitioned layer spreads b over the shards in pieces of rtp_bias_piece_width entries)
-            pw = self.pw = o if split == B.RTP_SPLIT_OUT else B.lib.rtp_bias_piece_width(self.O, n, dtype)
-
-            def with_bias(mat, vec, total):
-                vec = torch.cat((vec, vec.new_zeros(n * pw - vec.numel()))).reshape(n, pw)
-                out = mat.new_zeros(n, total)
-                out[:, :self.n_mat] = mat
-                out[:, self.n_mat:self.n_mat + pw] = vec
-                return out.contiguous()
+            pw = o if split == B.RTP_SPLIT_OUT else B.lib.rtp_bias_piece_width(self.O, n, dtype)
             gb0 = torch.zeros(self.O, device=self.dev) if gb0 is None else gb0
-            self.home_w = with_bias(self.home_w, bias.to(self.dev, td), wbytes // _esize(dtype))
-            self.home_g = with_bias(self.home_g, gb0.to(self.dev, torch.float32), gbytes // 4)
-        wb = self.home_w.shape[1] * _esize(dtype)
-        gb = self.home_g.shape[1] * 4
+            self.store_w.pack("b", bias, n_mat * _esize(dtype), B.RTP_SPLIT_OUT, pw)
+            self.store_g.pack("b", gb0, n_mat * 4, B.RTP_SPLIT_OUT, pw)
+        self.home_w, self.home_g = self.store_w.buf, self.store_g.buf
         self.buf_w = [torch.empty(wb, dtype=torch.uint8, device=self.dev) for _ in range(2)]
         self.buf_g = [torch.empty(gb, dtype=torch.uint8, device=self.dev) for _ in range(2)]
         self.compute_stream = torch.cuda.Stream(self.dev)
@@ -154,14 +128,15 @@ class RtpLinear(_PassStreams):
         """(W, G) as full matrices, read back from the home store."""
         self.ring.flush()
         self.ring.sync()
-        un = unpack_out_split if self.split == B.RTP_SPLIT_OUT else unpack_in_split
-        return (un(self.home_w[:, :self.n_mat].contiguous(), self.n, self.O, self.I),
-                un(self.home_g[:, :self.n_mat].contiguous(), self.n, self.O, self.I))
+        out = self.store_w.unpack("W"), self.store_g.unpack("W")
+        torch.cuda.synchronize(self.dev)
+        return out
 
     def gathered_bias(self):
         """(b, gradient of b) read back from the home store (call gathered() first: it flushes)."""
-        sl = slice(self.n_mat, self.n_mat + self.pw)
-        return self.home_w[:, sl].reshape(-1)[:self.O].contiguous(), self.home_g[:, sl].reshape(-1)[:self.O].contiguous()
+        out = self.store_w.unpack("b"), self.store_g.unpack("b")
+        torch.cuda.synchronize(self.dev)
+        return out
 
     def close(self):
         self.ring.close()
@@ -179,16 +154,10 @@ class RtpMlp(_PassStreams):
         self.gated = act == B.RTP_ACT_SWIGLU
         self.has_bias = biases is not None
         ws = [w.to(self.dev, td).contiguous() for w in weights]
-        if self.gated:
-            Wg, Wu, Wd = ws
-            W1 = stack_gate_up(Wg, Wu, n)
-        else:
-            W1, Wd = ws
-        self.O, self.I = (W1.shape[0] // 2 if self.gated else W1.shape[0]), W1.shape[1]
-        self.O2 = Wd.shape[0]
+        self.names = ("Wg", "Wu", "Wd") if self.gated else ("W1", "W2")
+        self.O, self.I = ws[0].shape
+        self.O2 = ws[-1].shape[0]
         self.p = 2 if self.gated else 1
-        self.n1 = self.p * self.O * self.I // n           # elements of the first matrix's shard
-        self.n2 = self.O2 * self.O // n
         d = B.rtp_mlp_desc()
         d.T, d.I, d.O, d.O2 = T, self.I, self.O, self.O2
         d.n, d.rank, d.mode, d.dtype, d.act = n, rank, mode, dtype, act
@@ -196,41 +165,34 @@ class RtpMlp(_PassStreams):
                    (B.RTP_FLAG_PIPELINED if pipelined else 0) | (B.RTP_FLAG_STAGE_MEMCPY if stage_memcpy else 0))
         d.has_bias = int(self.has_bias)
         wb, gb = B.lib.rtp_mlp_slot_w_bytes(C.byref(d)), B.lib.rtp_mlp_slot_g_bytes(C.byref(d))
-        g = None if G0 is None else [x.to(self.dev, torch.float32) for x in G0]
-        G1 = None if g is None else (stack_gate_up(g[0], g[1], n) if self.gated else g[0])
-        if not self.has_bias:
-            self.off2 = self.n1                           # where the second linear's part starts, in elements
-            self.home_w = torch.cat((pack_out_split(W1, n), pack_in_split(Wd, n)), dim=1).contiguous()
-            if G0 is None:
-                self.home_g = torch.zeros(n, self.n1 + self.n2, dtype=torch.float32, device=self.dev)
-            else:
-                self.home_g = torch.cat((pack_out_split(G1, n), pack_in_split(g[-1], n)), dim=1).contiguous()
-        else:
-            # slot = [W1_k | b1_k | W2_k | piece k of b2]; each linear's part is padded to 16 bytes in the
-            # weight type and in fp32 alike, so one element offset serves both stores
-            self.o1 = self.O // n
-            self.pw2 = B.lib.rtp_bias_piece_width(self.O2, n, dtype)
-            l1 = B.rtp_linear_desc()
-            l1.T, l1.I, l1.O, l1.split, l1.dtype, l1.grad_dtype, l1.has_bias = T, self.I, self.O, B.RTP_SPLIT_OUT, dtype, B.RTP_F32, 1
-            self.off2 = B.lib.rtp_linear_shard_w_bytes(C.byref(l1), n) // _esize(dtype)
-            assert self.off2 * 4 == B.lib.rtp_linear_shard_g_bytes(C.byref(l1), n)
-            gb0 = [torch.zeros(self.O), torch.zeros(self.O2)] if gb0 is None else gb0
-
-            def slot(M1, v1, M2, v2, t, total):
-                out = torch.zeros(n, total, dtype=t, device=self.dev)
-                out[:, :self.n1] = pack_out_split(M1.to(self.dev, t), n)
-                out[:, self.n1:self.n1 + self.o1] = v1.to(self.dev, t).reshape(n, self.o1)
-                out[:, self.off2:self.off2 + self.n2] = pack_in_split(M2.to(self.dev, t), n)
-                v2 = v2.to(self.dev, t)
-                v2 = torch.cat((v2, v2.new_zeros(n * self.pw2 - v2.numel()))).reshape(n, self.pw2)
-                out[:, self.off2 + self.n2:self.off2 + self.n2 + self.pw2] = v2
-                return out.contiguous()
-
-            self.home_w = slot(W1, biases[0], Wd, biases[1], td, wb // _esize(dtype))
-            Z1, Z2 = torch.zeros(self.O, self.I), torch.zeros(self.O2, self.O)
-            self.home_g = slot(Z1 if g is None else G1, gb0[0], Z2 if g is None else g[-1], gb0[1], torch.float32, gb // 4)
-        assert wb == self.home_w.shape[1] * _esize(dtype) and gb == self.home_g.shape[1] * 4
+        if wb == 0 or gb == 0:
+            raise ValueError("rtp_mlp_slot_*_bytes rejects this unit (sizes, or a partition the unit does not take)")
         self.w_bytes, self.g_bytes = wb, gb
+        # Slot k = [first linear's shard | second linear's shard]; the first linear's shard is its row block of W1
+        # (gated unit: gate rows k, then up rows k), then its bias entries; the second's is its column block of
+        # W2 stored [O2, o], then piece k of its bias.  Offsets are the library's (rtp_linear_shard_*_bytes); the
+        # layout itself is written by rtp_pack_shards.  Gradient store: the same, fp32.
+        o = B.lib.rtp_shard_width(self.O, n, dtype)          # hidden units per shard
+        l1 = B.rtp_linear_desc()
+        l1.T, l1.I, l1.O, l1.split, l1.dtype, l1.grad_dtype = T, self.I, self.p * self.O, B.RTP_SPLIT_OUT, dtype, B.RTP_F32
+        l1.act, l1.has_bias = act, int(self.has_bias)
+        off2_w, off2_g = B.lib.rtp_linear_shard_w_bytes(C.byref(l1), n), B.lib.rtp_linear_shard_g_bytes(C.byref(l1), n)
+        assert off2_w // _esize(dtype) == off2_g // 4
+        self.store_w, self.store_g = _Store(n, wb, dtype, self.dev), _Store(n, gb, B.RTP_F32, self.dev)
+        zeros = lambda *shape: torch.zeros(*shape, dtype=torch.float32, device=self.dev)
+        g = [zeros(*w.shape) for w in ws] if G0 is None else list(G0)
+        bs = list(biases) if self.has_bias else []
+        gbs = ([zeros(b.numel()) for b in bs] if gb0 is None else list(gb0)) if self.has_bias else []
+        for store, mats, vecs, es, off2 in ((self.store_w, ws, bs, _esize(dtype), off2_w), (self.store_g, g, gbs, 4, off2_g)):
+            for j in range(self.p):                           # W1, or gate then up: o rows of I each
+                store.pack(self.names[j], mats[j], j * o * self.I * es, B.RTP_SPLIT_OUT, o)
+            store.pack(self.names[-1], mats[-1], off2, B.RTP_SPLIT_IN, o)
+            if self.has_bias:
+                for j in range(self.p):                       # the first linear's bias entries follow its rows
+                    store.pack("b" + self.names[j], vecs[j], (self.p * o * self.I + j * o) * es, B.RTP_SPLIT_OUT, o)
+                pw2 = B.lib.rtp_bias_piece_width(self.O2, n, dtype)
+                store.pack("b" + self.names[-1], vecs[-1], off2 + self.O2 * o * es, B.RTP_SPLIT_OUT, pw2)
+        self.home_w, self.home_g = self.store_w.buf, self.store_g.buf
         self.buf_w = [torch.empty(wb, dtype=torch.uint8, device=self.dev) for _ in range(2)]
         ng = 2 if mode == B.RTP_DOUBLE_BUFFER else 1
         self.buf_g = [torch.empty(gb, dtype=torch.uint8, device=self.dev) for _ in range(ng)] + [None] * (2 - ng)
@@ -281,22 +243,15 @@ class RtpMlp(_PassStreams):
         in the order they were given."""
         B.check(B.lib.rtp_mlp_flush(self.handle), "rtp_mlp_flush")
         self.sync()
-        out = []
-        for home in (self.home_w, self.home_g):
-            P1, P2 = home[:, :self.n1].contiguous(), home[:, self.off2:self.off2 + self.n2].contiguous()
-            M1 = unpack_out_split(P1, self.n, self.p * self.O, self.I)
-            M2 = unpack_in_split(P2, self.n, self.O2, self.O)
-            out.append((*unstack_gate_up(M1, self.n), M2) if self.gated else (M1, M2))
+        out = [tuple(store.unpack(nm) for nm in self.names) for store in (self.store_w, self.store_g)]
+        torch.cuda.synchronize(self.dev)
         return out
 
     def gathered_biases(self):
-        """((b1, b2), (gradient of b1, gradient of b2)) from the home store (call gathered() first: it flushes)."""
-        out = []
-        for home in (self.home_w, self.home_g):
-            v1 = home[:, self.n1:self.n1 + self.o1].reshape(-1).contiguous()
-            s2 = self.off2 + self.n2
-            v2 = home[:, s2:s2 + self.pw2].reshape(-1)[:self.O2].contiguous()
-            out.append((v1, v2))
+        """(biases, their gradients), each in the order the matrices were given, from the home store (call
+        gathered() first: it flushes)."""
+        out = [tuple(store.unpack("b" + nm) for nm in self.names) for store in (self.store_w, self.store_g)]
+        torch.cuda.synchronize(self.dev)
         return out
 
     def close(self):
@@ -321,20 +276,27 @@ class RtpMoe(_PassStreams):
         self.O2 = self.shapes[-1][0]
         self.p = 2 if self.gated else 1
 
-        def slot(mats, t):
-            # [W1_e | W2_e], W1_e = [gate_e ; up_e] for a gated expert: every matrix flattened row-major
-            return torch.cat([m.to(self.dev, t).contiguous().reshape(-1) for m in mats])
-
-        self.home_w = torch.stack([slot(ex, td) for ex in experts]).contiguous()
-        if G0 is None:
-            self.home_g = torch.zeros(n, self.home_w.shape[1], dtype=torch.float32, device=self.dev)
-        else:
-            self.home_g = torch.stack([slot(g, torch.float32) for g in G0]).contiguous()
         d = B.rtp_moe_desc()
         d.T, d.I, d.O, d.O2 = T, self.I, self.O, self.O2
         d.n, d.rank, d.mode, d.dtype, d.act, d.flags = n, rank, mode, dtype, act, 0
         wb, gb = B.lib.rtp_moe_slot_w_bytes(C.byref(d)), B.lib.rtp_moe_slot_g_bytes(C.byref(d))
-        assert wb == self.home_w.shape[1] * _esize(dtype) and gb == self.home_g.shape[1] * 4
+        # slot e = [W1_e | W2_e] (W1_e = [gate_e ; up_e] for a gated expert), every matrix whole and row-major:
+        # one rtp_pack_shards call per matrix with n = 1, aimed at the expert's slot
+        self.home_w = torch.zeros(n, wb, dtype=torch.uint8, device=self.dev)
+        self.home_g = torch.zeros(n, gb, dtype=torch.uint8, device=self.dev)
+        self._offsets = []
+        off = 0
+        for (r, c) in self.shapes:
+            self._offsets.append(off)
+            off += r * c
+        for e in range(n):
+            for j, (r, c) in enumerate(self.shapes):
+                B.rtp_pack_shards(self.home_w.data_ptr() + e * wb, wb, self._offsets[j] * _esize(dtype), 1, B.RTP_SPLIT_OUT,
+                                  experts[e][j].to(self.dev, td).contiguous(), r, c, r, dtype)
+                if G0 is not None:
+                    B.rtp_pack_shards(self.home_g.data_ptr() + e * gb, gb, self._offsets[j] * 4, 1, B.RTP_SPLIT_OUT,
+                                      G0[e][j].to(self.dev, torch.float32).contiguous(), r, c, r, B.RTP_F32)
+        torch.cuda.synchronize(self.dev)
         self.w_bytes, self.g_bytes = wb, gb
         self.buf_w = [torch.empty(wb, dtype=torch.uint8, device=self.dev) for _ in range(2)]
         ng = 2 if mode == B.RTP_DOUBLE_BUFFER else 1
@@ -397,15 +359,17 @@ class RtpMoe(_PassStreams):
         B.check(B.lib.rtp_moe_flush(self.handle), "rtp_moe_flush")
         self.sync()
         out = []
-        for home in (self.home_w, self.home_g):
+        for home, slot, dt, es in ((self.home_w, self.w_bytes, self.dtype, _esize(self.dtype)), (self.home_g, self.g_bytes, B.RTP_F32, 4)):
             per = []
             for e in range(self.n):
-                mats, off = [], 0
-                for (r, c) in self.shapes:
-                    mats.append(home[e, off:off + r * c].reshape(r, c).clone())
-                    off += r * c
+                mats = []
+                for j, (r, c) in enumerate(self.shapes):
+                    m = torch.empty(r, c, dtype=_TORCH_DT[dt], device=self.dev)
+                    B.rtp_unpack_shards(m, home.data_ptr() + e * slot, slot, self._offsets[j] * es, 1, B.RTP_SPLIT_OUT, r, c, r, dt)
+                    mats.append(m)
                 per.append(tuple(mats))
             out.append(per)
+        torch.cuda.synchronize(self.dev)
         return out
 
     def close(self):

@@ -451,3 +451,25 @@ def test_header_is_plain_c():
     subprocess.run(["g++", "-std=c++17", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", hdr], check=True)
     text = open(hdr).read()
     assert "torch" not in text.lower() and "hipStream_t " not in text.replace("/* hipStream_t", "")
+
+
+def test_shard_layout_calls_validate_before_they_launch():
+    """rtp_pack_shards / rtp_unpack_shards reject bad descriptions on the host (no kernel is launched)."""
+    import ctypes as C
+    p = C.c_void_p(4096)     # never dereferenced: every call below fails validation first
+
+    def st(home, slot, off, n, split, W, O, I, w, dt):
+        return B.lib.rtp_pack_shards(home, slot, off, n, split, W, O, I, w, dt, None)
+
+    assert st(None, 1024, 0, 4, B.RTP_SPLIT_OUT, p, 8, 8, 2, B.RTP_BF16) == B.RTP_ERR_INVALID
+    assert st(p, 1024, 0, 4, B.RTP_SPLIT_OUT, None, 8, 8, 2, B.RTP_BF16) == B.RTP_ERR_INVALID
+    assert st(p, 1024, 0, 4, 7, p, 8, 8, 2, B.RTP_BF16) == B.RTP_ERR_INVALID
+    assert st(p, 1024, 0, 4, B.RTP_SPLIT_OUT, p, 8, 8, 2, 9) == B.RTP_ERR_INVALID
+    assert st(p, 1024, 0, 0, B.RTP_SPLIT_OUT, p, 8, 8, 2, B.RTP_BF16) == B.RTP_ERR_SHAPE       # n < 1
+    assert st(p, 1024, 0, 4, B.RTP_SPLIT_OUT, p, 9, 8, 2, B.RTP_BF16) == B.RTP_ERR_SHAPE       # 4 x 2 rows do not cover 9
+    assert st(p, 1024, 0, 4, B.RTP_SPLIT_IN, p, 8, 9, 2, B.RTP_BF16) == B.RTP_ERR_SHAPE
+    assert st(p, 31, 0, 4, B.RTP_SPLIT_OUT, p, 8, 8, 2, B.RTP_BF16) == B.RTP_ERR_SHAPE         # part of 32 bytes, slot of 31
+    assert st(p, 1024, 1000, 4, B.RTP_SPLIT_OUT, p, 8, 8, 2, B.RTP_BF16) == B.RTP_ERR_SHAPE    # offset pushes it out
+    assert st(p, 1024, 1, 4, B.RTP_SPLIT_OUT, p, 8, 8, 2, B.RTP_BF16) == B.RTP_ERR_SHAPE       # offset not a whole element
+    assert B.lib.rtp_unpack_shards(p, None, 1024, 0, 4, B.RTP_SPLIT_OUT, 8, 8, 2, B.RTP_BF16, None) == B.RTP_ERR_INVALID
+    assert b"rtp_unpack_shards" in B.lib.rtp_last_error()

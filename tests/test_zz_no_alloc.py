@@ -12,7 +12,6 @@ import torch
 import oracle as orc
 import rtp_workloads as wl
 from paper_2311_01635_amd import binding as B
-from paper_2311_01635_amd.layers import pack_in_split
 
 pytestmark = pytest.mark.gpu
 
@@ -28,9 +27,10 @@ def _fwd_pass(T, I, O, n, rank, mode, seed, step_fn_name, with_acc):
     ref = orc.rtp_linear_in(f64(inp["X"]), f64(inp["W"]), f64(inp["dY"]), n, rank)["Y"]
     bf = torch.bfloat16
     to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV, bf)
-    home_w = pack_in_split(to(inp["W"]), n).contiguous()
-    wb = home_w.shape[1] * 2
-    home_g = torch.zeros(n, home_w.shape[1], dtype=torch.float32, device=DEV)
+    wb = O * (I // n) * 2
+    home_w = torch.zeros(n, wb // 2, dtype=bf, device=DEV)
+    B.rtp_pack_shards(home_w, wb, 0, n, B.RTP_SPLIT_IN, to(inp["W"]), O, I, I // n, B.RTP_BF16)
+    home_g = torch.zeros(n, wb // 2, dtype=torch.float32, device=DEV)
     buf_w = [torch.empty(wb, dtype=torch.uint8, device=DEV) for _ in range(2)]
     buf_g = [torch.empty(2 * wb, dtype=torch.uint8, device=DEV) for _ in range(2)]
     cs, ss = torch.cuda.Stream(DEV), torch.cuda.Stream(DEV)
