@@ -322,11 +322,12 @@ size_t rtp_linear_shard_g_bytes(const rtp_linear_desc *desc, int n);
  * [k*o/2, (k+1)*o/2) followed by the same rows of up; the forward output is
  * [T, O/2].  With SPLIT_IN and SWIGLU the backward output is [T, 2 I] in the
  * same shard-stacked column order.
- * A layer without an activation may have a partitioned dimension n does not
+ * A layer (not a gated one) may have a partitioned dimension n does not
  * divide: its shards are padded to rtp_shard_width() and stored at that width
- * ([w, I] rows for SPLIT_OUT, [O, w] columns for SPLIT_IN, padding zero).
+ * ([w, I] rows for SPLIT_OUT, [O, w] columns for SPLIT_IN, padding zero); the
+ * kernels only compute, read and write the columns that exist.
  * Errors: RTP_ERR_SHAPE (n does not divide the partitioned dimension of a
- * layer with an activation, or padding would leave a shard empty; bf16 or
+ * gated layer, or padding would leave a shard empty; bf16 or
  * fp16: I, O, o not multiples of 8; shard does not fit the slot),
  * RTP_ERR_INVALID, RTP_ERR_UNSUPPORTED (gradient dtype other than F32; fp16
  * with T, o or the unpartitioned dimension not a multiple of 32: fp16 inputs
@@ -387,18 +388,31 @@ typedef struct {
     /* slot = [W1_k | W2_k] or [gate_k | up_k | down_k]; gradients fp32         */
     void *home_w_dev, *home_g_dev;
     void *buf_w_dev[2], *buf_g_dev[2];
-    void *preact_dev;     /* [T, P*O], P = 2 for SWIGLU                            */
-    void *hidden_dev;     /* [T, O]                                                */
-    void *dpre_dev;       /* [T, P*O]                                              */
+    /* workspaces, Hw = rtp_mlp_hidden_width() columns per hidden unit row:    */
+    void *preact_dev;     /* [T, P*Hw], P = 2 for SWIGLU                           */
+    void *hidden_dev;     /* [T, Hw]                                               */
+    void *dpre_dev;       /* [T, P*Hw]                                             */
     float *acc_y_dev;     /* fp32 [T, O2]                                          */
     float *acc_dx_dev;    /* fp32 [T, I]                                           */
     void *compute_stream, *stage_stream;
     void *aux_stream;     /* optional, as in rtp_ring_desc                           */
-    int has_bias;         /* both linears carry a bias (GELU_* units only): slot =
-                             [W1_k | b1_k | W2_k | piece k of b2], each part padded to
-                             16 bytes as rtp_linear_shard_w_bytes gives it; such a
-                             unit runs step by step                                  */
+    int has_bias;         /* every linear of the unit carries a bias: slot =
+                             [W1_k | b1_k | W2_k | piece k of b2] (gated unit:
+                             [gate_k ; up_k | bgate_k | bup_k | down_k | piece k of
+                             bdown]), each linear's part padded to 16 bytes as
+                             rtp_linear_shard_w_bytes gives it                       */
 } rtp_mlp_desc;
+
+/* Hidden width the unit computes on (FlatParameter paragraph: the flat
+ * parameter is padded so that it divides evenly): O when n divides it,
+ * otherwise n * rtp_shard_width(O, n, dtype).  Shard k then holds hidden units
+ * [k w, (k+1) w); units past O are padding: their weights, biases and
+ * gradients are zeros in the store (rtp_pack_shards writes them), so their
+ * activations are act(0) = 0 and they change nothing.  The three hidden
+ * workspaces have this many columns (times P); columns past O of each shard's
+ * slice hold zeros after a pass.  -1 if the width cannot be split into n
+ * non-empty aligned shards. */
+int64_t rtp_mlp_hidden_width(const rtp_mlp_desc *d);
 
 size_t rtp_mlp_slot_w_bytes(const rtp_mlp_desc *d);
 size_t rtp_mlp_slot_g_bytes(const rtp_mlp_desc *d);
@@ -412,7 +426,9 @@ size_t rtp_mlp_slot_g_bytes(const rtp_mlp_desc *d);
  * second linear one step behind the first ({Z_t, down_{t-1}}), the shard
  * parts moving accordingly; so does the backward pass when no auxiliary
  * stream was given ({dX_{s-1}, dPre_s} and {dW1_s, dW2_s}).  Results, buffers
- * and bytes moved are the same.  RTP_FLAG_STEPWISE in `flags` keeps the
+ * and bytes moved are the same; so are they for a unit with biases (the
+ * pieces of the second linear's bias and the bias gradients are small kernels
+ * between the launches).  RTP_FLAG_STEPWISE in `flags` keeps the
  * step-by-step sequence everywhere.  `rotate` = 0 skips the rotation calls (the
  * resident shard is used for every step: timing of compute alone, results
  * are meaningless); `compute` = 0 skips the kernels (timing of the staging

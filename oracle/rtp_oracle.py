@@ -198,19 +198,20 @@ def plain_mlp(X, W1, W2, dY, kind=GELU_ERF, b1=None, b2=None):
     return dict(Z=Z, H=H, Y=Y, dH=dH, dZ=dZ, dX=dX, dW1=dW1, dW2=dW2, db1=plain_bias_grad(dZ), db2=plain_bias_grad(dY))
 
 
-def plain_swiglu(X, Wg, Wu, Wd, dY):
-    """Gated MLP: H = silu(X Wg^T) * (X Wu^T), Y = H Wd^T, and its gradients."""
-    A = plain_linear_fwd(X, Wg)
-    B = plain_linear_fwd(X, Wu)
+def plain_swiglu(X, Wg, Wu, Wd, dY, bg=None, bu=None, bd=None):
+    """Gated MLP: H = silu(X Wg^T + bg) * (X Wu^T + bu), Y = H Wd^T + bd, and its gradients (biases optional)."""
+    A = plain_linear_fwd(X, Wg, bg)
+    B = plain_linear_fwd(X, Wu, bu)
     sA = act(A, SILU)
     H = sA * B
-    Y = plain_linear_fwd(H, Wd)
+    Y = plain_linear_fwd(H, Wd, bd)
     dH, dWd = plain_linear_bwd(H, Wd, dY)
     dA = dH * B * act_grad(A, SILU)
     dB = dH * sA
     dXa, dWg = plain_linear_bwd(X, Wg, dA)
     dXb, dWu = plain_linear_bwd(X, Wu, dB)
-    return dict(A=A, B=B, H=H, Y=Y, dH=dH, dA=dA, dB=dB, dX=dXa + dXb, dWg=dWg, dWu=dWu, dWd=dWd)
+    return dict(A=A, B=B, H=H, Y=Y, dH=dH, dA=dA, dB=dB, dX=dXa + dXb, dWg=dWg, dWu=dWu, dWd=dWd,
+                dbg=plain_bias_grad(dA), dbu=plain_bias_grad(dB), dbd=plain_bias_grad(dY))
 
 
 # --------------------------------------------------------------------------
@@ -521,9 +522,12 @@ def rtp_mlp(X, W1, W2, dY, n, rank, kind=GELU_ERF, G1_0=None, G2_0=None, b1=None
     return out
 
 
-def rtp_swiglu(X, Wg, Wu, Wd, dY, n, rank, Gg0=None, Gu0=None, Gd0=None):
+def rtp_swiglu(X, Wg, Wu, Wd, dY, n, rank, Gg0=None, Gu0=None, Gd0=None, bg=None, bu=None, bd=None,
+               gbg0=None, gbu0=None, gbd0=None):
     """Gated MLP with gate and up output-partitioned and down
-    input-partitioned; unit k = (gate_k, up_k, down_k)."""
+    input-partitioned; unit k = (gate_k, up_k, down_k).  Optional biases (all
+    three or none), carried as in rtp_mlp: the gate's and the up matrix's
+    entries ride with their rows, the down matrix's is spread in pieces."""
     T, I = X.shape
     O1 = Wg.shape[0]
     O2 = Wd.shape[0]
@@ -533,39 +537,66 @@ def rtp_swiglu(X, Wg, Wu, Wd, dY, n, rank, Gg0=None, Gu0=None, Gd0=None):
     rg = _Ring(_split_rows(Wg, n), _split_rows(Gg0, n), rank)
     ru = _Ring(_split_rows(Wu, n), _split_rows(Gu0, n), rank)
     rd = _Ring(_split_cols(Wd, n), _split_cols(Gd0, n), rank)
+    rings = [rg, ru, rd]
+    biased = bg is not None
+    assert biased == (bu is not None) == (bd is not None)
+    if biased:
+        vec = lambda v, size: np.zeros(size) if v is None else np.asarray(v, dtype=np.float64)
+        bg, bu, bd = vec(bg, O1), vec(bu, O1), vec(bd, O2)
+        gbg0, gbu0, gbd0 = vec(gbg0, O1), vec(gbu0, O1), vec(gbd0, O2)
+        rows = [shard_rows(k, O1, n) for k in range(n)]
+        pieces = bias_pieces(O2, n)
+        rbg = _Ring([bg[lo:hi].copy() for lo, hi in rows], [gbg0[lo:hi].copy() for lo, hi in rows], rank)
+        rbu = _Ring([bu[lo:hi].copy() for lo, hi in rows], [gbu0[lo:hi].copy() for lo, hi in rows], rank)
+        rbd = _Ring(_padded_pieces(bd, pieces), _padded_pieces(gbd0, pieces), rank)
+        rings += [rbg, rbu, rbd]
     A = np.full((T, O1), np.nan)
     B = np.full((T, O1), np.nan)
     H = np.full((T, O1), np.nan)
     Y = np.zeros((T, O2))
     for t in range(n):
         k = rg.res_id
-        assert k == fwd_shard(rank, t, n)
+        assert all(r_.res_id == k for r_ in rings) and k == fwd_shard(rank, t, n)
         lo, hi = shard_rows(k, O1, n)
         gemm_nt(X, rg.res_w, A[:, lo:hi])
         gemm_nt(X, ru.res_w, B[:, lo:hi])
+        if biased:
+            for row in range(T):
+                A[row, lo:hi] += rbg.res_w
+                B[row, lo:hi] += rbu.res_w
         H[:, lo:hi] = act(A[:, lo:hi], SILU) * B[:, lo:hi]
         gemm_nt(np.ascontiguousarray(H[:, lo:hi]), rd.res_w, Y, accumulate=True)
+        if biased:
+            plo, phi = pieces[k]
+            for row in range(T):
+                Y[row, plo:phi] += rbd.res_w[:phi - plo]
         if t < n - 1:
-            for r_ in (rg, ru, rd):
+            for r_ in rings:
                 r_.rotate((k - 1) % n, with_grad=False)
     dX = np.zeros((T, I))
-    for r_ in (rg, ru, rd):
+    for r_ in rings:
         r_.begin_backward()
     for s in range(n):
         k = rg.res_id
-        assert k == bwd_shard(rank, s, n)
+        assert all(r_.res_id == k for r_ in rings) and k == bwd_shard(rank, s, n)
         lo, hi = shard_rows(k, O1, n)
         Hk = np.ascontiguousarray(H[:, lo:hi])
         gemm_tn(dY, Hk, rd.res_g, accumulate=True)
+        if biased:
+            plo, phi = pieces[k]
+            rbd.res_g[:phi - plo] += plain_bias_grad(np.ascontiguousarray(dY[:, plo:phi]))
         dHk = gemm_nn(dY, rd.res_w, np.empty((T, hi - lo)))
         dAk = dHk * B[:, lo:hi] * act_grad(A[:, lo:hi], SILU)
         dBk = dHk * act(A[:, lo:hi], SILU)
         gemm_tn(dAk, X, rg.res_g, accumulate=True)
         gemm_tn(dBk, X, ru.res_g, accumulate=True)
+        if biased:
+            rbg.res_g += plain_bias_grad(dAk)
+            rbu.res_g += plain_bias_grad(dBk)
         gemm_nn(dAk, rg.res_w, dX, accumulate=True)
         gemm_nn(dBk, ru.res_w, dX, accumulate=True)
         if s < n - 1:
-            for r_ in (rg, ru, rd):
+            for r_ in rings:
                 r_.rotate((k + 1) % n, with_grad=True)
 
     def gather(ring, axis):
@@ -573,8 +604,13 @@ def rtp_swiglu(X, Wg, Wu, Wd, dY, n, rank, Gg0=None, Gu0=None, Gd0=None):
         g[ring.res_id] = ring.res_g.copy()
         return np.concatenate(g, axis=axis)
 
-    return dict(A=A, B=B, H=H, Y=Y, dX=dX, dWg=gather(rg, 0), dWu=gather(ru, 0), dWd=gather(rd, 1),
-                resident_after_bwd=rg.res_id)
+    out = dict(A=A, B=B, H=H, Y=Y, dX=dX, dWg=gather(rg, 0), dWu=gather(ru, 0), dWd=gather(rd, 1),
+               resident_after_bwd=rg.res_id)
+    if biased:
+        gd = [x.copy() for x in rbd.home_g]
+        gd[rbd.res_id] = rbd.res_g.copy()
+        out["dbg"], out["dbu"], out["dbd"] = gather(rbg, 0), gather(rbu, 0), _unpad_pieces(gd, pieces)
+    return out
 
 
 # --------------------------------------------------------------------------

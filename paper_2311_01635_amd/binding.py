@@ -116,6 +116,7 @@ SYMBOLS = {
     "rtp_linear_fwd": (C.c_int, [_P, C.c_int, _P, _P]),
     "rtp_linear_bwd": (C.c_int, [_P, C.c_int, _P, _P, _P]),
     "rtp_linear_fwd_noalloc": (C.c_int, [_P, C.c_int, _P, _P]),
+    "rtp_mlp_hidden_width": (C.c_int64, [C.POINTER(rtp_mlp_desc)]),
     "rtp_mlp_slot_w_bytes": (C.c_size_t, [C.POINTER(rtp_mlp_desc)]),
     "rtp_mlp_slot_g_bytes": (C.c_size_t, [C.POINTER(rtp_mlp_desc)]),
     "rtp_mlp_create": (C.c_int, [C.POINTER(_P), C.POINTER(rtp_mlp_desc)]),

@@ -721,9 +721,9 @@ extern "C" rtp_status rtp_linear_create(rtp_linear **out, rtp_ring *ring, const 
     if (d->act < RTP_ACT_NONE || d->act > RTP_ACT_SWIGLU) return fail(RTP_ERR_INVALID, "bad activation");
     const int n = ring->d.n;
     const int64_t part = d->split == RTP_SPLIT_OUT ? d->O : d->I;
-    if (part % n != 0 && d->act != RTP_ACT_NONE)
-        return fail(RTP_ERR_SHAPE, "rtp_linear_create: n=%d does not divide the partitioned dimension %lld "
-                                   "(padded shards are built for layers without an activation)", n, (long long)part);
+    if (part % n != 0 && d->act == RTP_ACT_SWIGLU)
+        return fail(RTP_ERR_SHAPE, "rtp_linear_create: n=%d does not divide the partitioned dimension %lld of a gated layer "
+                                   "(the MLP unit pads its hidden width itself: rtp_mlp_hidden_width)", n, (long long)part);
     const int64_t o = rtp_shard_width(part, n, d->dtype);
     if (o <= 0)
         return fail(RTP_ERR_SHAPE, "rtp_linear_create: dimension %lld cannot be split into n=%d non-empty aligned shards",
@@ -847,9 +847,10 @@ static rtp_status linear_fwd_step(rtp_linear *l, int step, const void *X, void *
             RTP_TRY(gemm(l, LAY_NT, a, r->cs()));
         } else {
             const bool gated = d.act == RTP_ACT_SWIGLU;
-            const int64_t ow = gated ? o / 2 : o, Ow = gated ? d.O / 2 : d.O;
+            const int64_t ow = gated ? o / 2 : ov, Ow = gated ? d.O / 2 : d.O;   // (a gated layer is never padded)
             char *pre = (char *)d.preact_dev + (size_t)k * o * es;
-            char *Yk = (char *)Y + (size_t)k * ow * es;
+            char *Yk = (char *)Y + (size_t)k * (gated ? o / 2 : o) * es;
+            a.N = (int)ov;
             if (!f32) {
                 a.epi = fwd_act_epi(d.act);
                 a.half = (int)(o / 2);
@@ -1108,6 +1109,7 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
                 const int64_t P = gated ? 2 * d.I : d.I, po = gated ? 2 * o : o;
                 char *out = (char *)dX + (size_t)k * po * es;
                 const char *pre = (const char *)d.preact_dev + (size_t)k * po * es;
+                a.N = (int)ov;                                                   // (a gated layer is never padded)
                 if (!f32) {
                     a.epi = bwd_act_epi(d.act);
                     a.half = (int)o;
@@ -1123,7 +1125,7 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
                     RTP_TRY(gemm(l, LAY_NN, a, r->cs()));
                     if (!r->dry && r->abl_compute)
                         HIP_TRY(launch_act_f32(bwd_act_epi(d.act), (const float *)pre, P, tmp, P, (float *)out, P,
-                                               (int)d.T, (int)o, (int)o, r->cs()));
+                                               (int)d.T, (int)ov, (int)o, r->cs()));
                 }
             }
         }
@@ -1144,16 +1146,29 @@ struct rtp_mlp {
 static bool mlp_gated(const rtp_mlp_desc *d) { return d->act == RTP_ACT_SWIGLU; }
 
 // the unit's two linears: the first output-partitioned with the activation, the second input-partitioned
+// The hidden width the unit computes on: O when n divides it, else n shards of the smallest aligned
+// width that covers it (FlatParameter padding).  The padding units have zero weights and biases, so
+// their pre-activations are 0, their activations act(0) = 0 (also silu(0) * 0 for the gated form),
+// they add nothing to the second GEMM, and every gradient that belongs to them is an exact zero:
+// the unit simply runs on an evenly divided hidden dimension of this width.
+extern "C" int64_t rtp_mlp_hidden_width(const rtp_mlp_desc *d)
+{
+    if (!d || d->n < 1 || d->O <= 0) return -1;
+    const int64_t o = rtp_shard_width(d->O, d->n, d->dtype);
+    return o <= 0 ? -1 : o * d->n;
+}
+
 static void mlp_linear_descs(const rtp_mlp_desc *d, rtp_linear_desc *l1, rtp_linear_desc *l2)
 {
     const int64_t p = mlp_gated(d) ? 2 : 1;
+    const int64_t hw = rtp_mlp_hidden_width(d);
     memset(l1, 0, sizeof *l1);
-    l1->T = d->T; l1->I = d->I; l1->O = p * d->O;
+    l1->T = d->T; l1->I = d->I; l1->O = p * hw;
     l1->split = RTP_SPLIT_OUT; l1->dtype = d->dtype; l1->grad_dtype = RTP_F32; l1->act = d->act;
     l1->preact_dev = d->preact_dev; l1->acc_ws_dev = d->acc_dx_dev;
     l1->has_bias = d->has_bias;
     memset(l2, 0, sizeof *l2);
-    l2->T = d->T; l2->I = d->O; l2->O = d->O2;
+    l2->T = d->T; l2->I = hw; l2->O = d->O2;
     l2->split = RTP_SPLIT_IN; l2->dtype = d->dtype; l2->grad_dtype = RTP_F32; l2->act = d->act;
     l2->preact_dev = d->preact_dev; l2->acc_ws_dev = d->acc_y_dev;
     l2->has_bias = d->has_bias;
@@ -1163,7 +1178,7 @@ static void mlp_linear_descs(const rtp_mlp_desc *d, rtp_linear_desc *l1, rtp_lin
 
 extern "C" size_t rtp_mlp_slot_w_bytes(const rtp_mlp_desc *d)
 {
-    if (!d || d->n < 1 || d->O <= 0 || d->I <= 0 || d->O2 <= 0 || d->O % d->n != 0) return 0;
+    if (!d || d->n < 1 || d->O <= 0 || d->I <= 0 || d->O2 <= 0 || rtp_mlp_hidden_width(d) <= 0) return 0;
     rtp_linear_desc l1, l2;
     mlp_linear_descs(d, &l1, &l2);
     return l2.w_offset + rtp_linear_shard_w_bytes(&l2, d->n);
@@ -1171,7 +1186,7 @@ extern "C" size_t rtp_mlp_slot_w_bytes(const rtp_mlp_desc *d)
 
 extern "C" size_t rtp_mlp_slot_g_bytes(const rtp_mlp_desc *d)
 {
-    if (!d || d->n < 1 || d->O <= 0 || d->I <= 0 || d->O2 <= 0 || d->O % d->n != 0) return 0;
+    if (!d || d->n < 1 || d->O <= 0 || d->I <= 0 || d->O2 <= 0 || rtp_mlp_hidden_width(d) <= 0) return 0;
     rtp_linear_desc l1, l2;
     mlp_linear_descs(d, &l1, &l2);
     return l2.g_offset + rtp_linear_shard_g_bytes(&l2, d->n);
@@ -1182,10 +1197,11 @@ extern "C" rtp_status rtp_mlp_create(rtp_mlp **out, const rtp_mlp_desc *d)
     if (!out || !d) return fail(RTP_ERR_INVALID, "rtp_mlp_create: null argument");
     *out = nullptr;
     if (d->act == RTP_ACT_NONE) return fail(RTP_ERR_INVALID, "rtp_mlp_create: an MLP block has an activation");
-    if (d->n < 1 || d->O <= 0 || d->I <= 0 || d->O2 <= 0 || d->O % d->n != 0)
-        return fail(RTP_ERR_SHAPE, "rtp_mlp_create: n must divide the hidden width");
-    if (d->has_bias && mlp_gated(d))
-        return fail(RTP_ERR_UNSUPPORTED, "rtp_mlp_create: biases are built for the one-matrix activations");
+    if (d->n < 1 || d->O <= 0 || d->I <= 0 || d->O2 <= 0)
+        return fail(RTP_ERR_SHAPE, "rtp_mlp_create: n >= 1 and positive sizes needed");
+    if (rtp_mlp_hidden_width(d) <= 0)
+        return fail(RTP_ERR_SHAPE, "rtp_mlp_create: a hidden width of %lld cannot be split into n=%d non-empty aligned shards",
+                    (long long)d->O, d->n);
     rtp_ring_desc rd;
     memset(&rd, 0, sizeof rd);
     rd.n = d->n; rd.rank = d->rank; rd.mode = d->mode; rd.flags = d->flags;
@@ -1249,17 +1265,30 @@ extern "C" rtp_status rtp_mlp_set_ablation(rtp_mlp *m, int rotate, int compute)
 struct MlpShapes {
     int64_t T, I, O2, P1, o1, o2, Ohid;
     size_t es, w_off2, g_off2;
-    bool gated;
+    bool gated, has_bias;
+    int n, belem;
+    int64_t pb2;          // entries of the piece of the second linear's bias a shard carries
+    // valid entries of piece k (the last pieces may be short or empty)
+    int64_t pv2(int k) const { return std::max<int64_t>(0, std::min<int64_t>(pb2, O2 - (int64_t)k * pb2)); }
+    // byte offsets inside a weight slot / a gradient slot of the two bias parts
+    size_t wb1() const { return (size_t)o1 * I * es; }
+    size_t wb2() const { return w_off2 + (size_t)O2 * o2 * es; }
+    size_t gb1() const { return (size_t)o1 * I * 4; }
+    size_t gb2() const { return g_off2 + (size_t)O2 * o2 * 4; }
 };
 
 static MlpShapes mlp_shapes(const rtp_mlp *m)
 {
     MlpShapes h;
     h.gated = mlp_gated(&m->d);
-    h.T = m->d.T; h.I = m->d.I; h.O2 = m->d.O2; h.Ohid = m->d.O;
-    h.P1 = (h.gated ? 2 : 1) * m->d.O;
+    h.T = m->d.T; h.I = m->d.I; h.O2 = m->d.O2; h.Ohid = rtp_mlp_hidden_width(&m->d);
+    h.P1 = (h.gated ? 2 : 1) * h.Ohid;
     h.o1 = h.P1 / m->d.n;
-    h.o2 = m->d.O / m->d.n;
+    h.o2 = h.Ohid / m->d.n;
+    h.has_bias = m->d.has_bias != 0;
+    h.n = m->d.n;
+    h.belem = m->d.dtype == RTP_F16 ? ELEM_F16 : ELEM_BF16;
+    h.pb2 = h.has_bias ? rtp_bias_piece_width(m->d.O2, m->d.n, m->d.dtype) : 0;
     h.es = esize(m->d.dtype);
     h.w_off2 = m->l2->d.w_offset;
     h.g_off2 = m->l2->d.g_offset;
@@ -1280,6 +1309,7 @@ static GemmArgs mlp_args_z(const rtp_mlp *m, const MlpShapes &h, int k, const vo
     a.half = (int)(h.o1 / 2);
     a.aux = (char *)m->d.preact_dev + (size_t)k * h.o1 * h.es; a.ldaux = h.P1;
     a.C = (char *)m->d.hidden_dev + (size_t)k * ow * h.es; a.ldc = h.Ohid;
+    if (h.has_bias) a.bias = Wslot + h.wb1(); // the shard's bias entries follow its rows ((gate | up) order)
     return a;
 }
 
@@ -1295,7 +1325,36 @@ static GemmArgs mlp_args_down(const rtp_mlp *m, const MlpShapes &h, int k, int s
     a.C = Y; a.ldc = h.O2;
     a.epi = acc_epi(step, m->d.n);
     a.ws = m->d.acc_y_dev; a.ldws = h.O2;
+    if (h.has_bias && h.n == 1) a.bias = Wslot + h.wb2(); // one step: the whole bias, inside the kernel
     return a;
+}
+
+// Piece k of the second linear's bias onto the fp32 sum of the unit's output (n > 1): its place in the
+// stream is after the launch that starts the sum (step 0) and before the launch of any later step.
+static rtp_status mlp_bias2_add(rtp_mlp *m, const MlpShapes &h, int k, const char *Wslot, hipStream_t st)
+{
+    rtp_ring *r = m->ring;
+    if (!h.has_bias || h.n == 1 || h.pv2(k) <= 0 || r->dry || !r->abl_compute || h.T <= 0) return RTP_OK;
+    HIP_TRY(launch_bias_add(h.belem, m->d.acc_y_dev + (size_t)k * h.pb2, h.O2, (int)h.T, (int)h.pv2(k), Wslot + h.wb2(), st));
+    return RTP_OK;
+}
+
+// The two bias gradients of step s (shard k) onto the travelling gradient shard in `Gslot`: column sums of
+// dPre_k (first linear) and of the columns of dY that piece k of the second bias covers.  When the shard's
+// gradient parts are sent by the kernels that complete them, the sums go straight to `home` as well.
+static rtp_status mlp_bias_grads(rtp_mlp *m, const MlpShapes &h, int k, char *Gslot, char *home, const void *dY,
+                                 bool first, bool second, hipStream_t st)
+{
+    rtp_ring *r = m->ring;
+    if (!h.has_bias || r->dry || !r->abl_compute || h.T <= 0) return RTP_OK;
+    char *dst = home ? home : Gslot;
+    if (first)
+        HIP_TRY(launch_colsum(h.belem, (const char *)m->d.dpre_dev + (size_t)k * h.o1 * h.es, h.P1, (int)h.T, (int)h.o1,
+                              (const float *)(Gslot + h.gb1()), (float *)(dst + h.gb1()), st));
+    if (second && h.pv2(k) > 0)
+        HIP_TRY(launch_colsum(h.belem, (const char *)dY + (size_t)k * h.pb2 * h.es, h.O2, (int)h.T, (int)h.pv2(k),
+                              (const float *)(Gslot + h.gb2()), (float *)(dst + h.gb2()), st));
+    return RTP_OK;
 }
 
 // dPre_k = (dY W2_k) * act'(pre_k)
@@ -1365,7 +1424,6 @@ static bool mlp_grouped_ok(const rtp_mlp *m, const void *X, const void *Y, const
 {
     const rtp_ring *r = m->ring;
     if (r->dry || (m->d.flags & RTP_FLAG_STEPWISE) || m->d.dtype == RTP_F32 || m->d.T <= 0) return false;
-    if (m->d.has_bias) return false; // the grouped launches are built for units without biases
     if (r->d.mode == RTP_INPLACE_BLOCKING) return false;
     const MlpShapes h = mlp_shapes(m);
     const char *W = (const char *)r->d.buf_w_dev[0];
@@ -1459,7 +1517,9 @@ static rtp_status mlp_fwd_grouped(rtp_mlp *m, const void *X, void *Y)
             g[cnt++] = mlp_args_z(m, h, r->shard_at(t), X, buf(t));
         }
         if (t >= 1) g[cnt++] = mlp_args_down(m, h, r->shard_at(t - 1), t - 1, buf(t - 1), Y);
+        if (t >= 2) RTP_TRY(mlp_bias2_add(m, h, r->shard_at(t - 1), buf(t - 1), r->cs()));
         RTP_TRY(gemm_group(r, LAY_NT, g, cnt, r->cs()));
+        if (t == 1) RTP_TRY(mlp_bias2_add(m, h, r->shard_at(0), buf(0), r->cs())); // the sum exists from here on
     }
     mlp_close_pass(m);
     return rtp_ring_end(r);
@@ -1518,6 +1578,7 @@ static rtp_status mlp_bwd_grouped(rtp_mlp *m, const void *X, const void *dY, voi
             g[1].C = home + h.g_off2;
         }
         RTP_TRY(gemm_group(r, LAY_TN, g, 2, ws));
+        RTP_TRY(mlp_bias_grads(m, h, r->shard_at(s), gbuf(s), fused_send ? r->home_g(r->shard_at(s)) : nullptr, dY, true, true, ws));
         // ---- the gradient shard moves on as soon as both parts are complete; the next
         // input-gradient launch runs meanwhile
         if (move_g && s <= n - 2) {
@@ -1622,7 +1683,9 @@ static rtp_status mlp_fwd_pipelined(rtp_mlp *m, const void *X, void *Y)
         if (rot && t >= 1) HIP_TRY(hipStreamWaitEvent(as, r->ev_w2[t & 1], 0));
         a = mlp_args_down(m, h, k, t, buf(t), Y);
         a.cu_share = 2;
+        if (t >= 1) RTP_TRY(mlp_bias2_add(m, h, k, buf(t), as));
         RTP_TRY(gemm_group(r, LAY_NT, &a, 1, as));
+        if (t == 0) RTP_TRY(mlp_bias2_add(m, h, k, buf(t), as)); // the sum exists from here on
         if (rot) RTP_TRY(w_part_turnover(r, t, r->ev_free2, as, h.w_off2, w2_bytes, r->ev_w2[t & 1]));
     }
     mlp_close_pass(m);
@@ -1666,7 +1729,7 @@ static rtp_status mlp_bwd_pipelined(rtp_mlp *m, const void *X, const void *dY, v
     };
     // one weight-gradient kernel on the auxiliary stream, fused with the send of its part of the
     // travelling gradient shard when the shard moves on, then the turnover of that part's buffer
-    auto emit_dw = [&](int s, GemmArgs a, size_t off, size_t bytes, hipEvent_t *landed) -> rtp_status {
+    auto emit_dw = [&](int s, GemmArgs a, size_t off, size_t bytes, hipEvent_t *landed, bool first) -> rtp_status {
         if (move_g && s >= 1) HIP_TRY(hipStreamWaitEvent(as, landed[s & 1], 0));
         const bool moves_on = move_g && s <= n - 2;
         bool fused_send = moves_on && r->abl_compute;
@@ -1680,6 +1743,8 @@ static rtp_status mlp_bwd_pipelined(rtp_mlp *m, const void *X, const void *dY, v
             a.C = r->home_g(r->shard_at(s)) + off;
         }
         RTP_TRY(gemm_group(r, LAY_TN, &a, 1, as));
+        // this linear's bias gradient belongs to the same part of the gradient shard
+        RTP_TRY(mlp_bias_grads(m, h, r->shard_at(s), gbuf(s), fused_send ? r->home_g(r->shard_at(s)) : nullptr, dY, first, !first, as));
         if (!move_g) return RTP_OK;
         if (moves_on || s + ng <= n - 1) RTP_TRY(stream_after(r->ev_free2, ss, as));
         if (moves_on) {
@@ -1718,11 +1783,11 @@ static rtp_status mlp_bwd_pipelined(rtp_mlp *m, const void *X, const void *dY, v
         // ---- dW2_s, then dW1_s (needs dPre_s)
         a = mlp_args_dw2(m, h, k, gbuf(s), dY);
         a.cu_share = 2;
-        RTP_TRY(emit_dw(s, a, h.g_off2, g2_bytes, r->ev_g2));
+        RTP_TRY(emit_dw(s, a, h.g_off2, g2_bytes, r->ev_g2, false));
         HIP_TRY(hipStreamWaitEvent(as, r->ev_k[s & 1], 0));
         a = mlp_args_dw1(m, h, k, gbuf(s), X);
         a.cu_share = 2;
-        RTP_TRY(emit_dw(s, a, 0, g1_bytes, r->ev_g));
+        RTP_TRY(emit_dw(s, a, 0, g1_bytes, r->ev_g, true));
     }
     mlp_close_pass(m);
     return rtp_ring_end(r);

@@ -172,9 +172,10 @@ class RtpMlp(_PassStreams):
         # (gated unit: gate rows k, then up rows k), then its bias entries; the second's is its column block of
         # W2 stored [O2, o], then piece k of its bias.  Offsets are the library's (rtp_linear_shard_*_bytes); the
         # layout itself is written by rtp_pack_shards.  Gradient store: the same, fp32.
-        o = B.lib.rtp_shard_width(self.O, n, dtype)          # hidden units per shard
+        hw = self.hidden_width = B.lib.rtp_mlp_hidden_width(C.byref(d))   # O, or n shards of the padded width
+        o = hw // n                                          # hidden units per shard
         l1 = B.rtp_linear_desc()
-        l1.T, l1.I, l1.O, l1.split, l1.dtype, l1.grad_dtype = T, self.I, self.p * self.O, B.RTP_SPLIT_OUT, dtype, B.RTP_F32
+        l1.T, l1.I, l1.O, l1.split, l1.dtype, l1.grad_dtype = T, self.I, self.p * hw, B.RTP_SPLIT_OUT, dtype, B.RTP_F32
         l1.act, l1.has_bias = act, int(self.has_bias)
         off2_w, off2_g = B.lib.rtp_linear_shard_w_bytes(C.byref(l1), n), B.lib.rtp_linear_shard_g_bytes(C.byref(l1), n)
         assert off2_w // _esize(dtype) == off2_g // 4
@@ -196,9 +197,9 @@ class RtpMlp(_PassStreams):
         self.buf_w = [torch.empty(wb, dtype=torch.uint8, device=self.dev) for _ in range(2)]
         ng = 2 if mode == B.RTP_DOUBLE_BUFFER else 1
         self.buf_g = [torch.empty(gb, dtype=torch.uint8, device=self.dev) for _ in range(ng)] + [None] * (2 - ng)
-        self.preact = torch.empty(T, self.p * self.O, dtype=td, device=self.dev)
-        self.hidden = torch.empty(T, self.O, dtype=td, device=self.dev)
-        self.dpre = torch.empty(T, self.p * self.O, dtype=td, device=self.dev)
+        self.preact = torch.empty(T, self.p * hw, dtype=td, device=self.dev)
+        self.hidden = torch.empty(T, hw, dtype=td, device=self.dev)
+        self.dpre = torch.empty(T, self.p * hw, dtype=td, device=self.dev)
         self.acc_y = torch.empty(T, self.O2, dtype=torch.float32, device=self.dev)
         self.acc_dx = torch.empty(T, self.I, dtype=torch.float32, device=self.dev)
         self.compute_stream = torch.cuda.Stream(self.dev)

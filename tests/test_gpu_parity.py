@@ -312,15 +312,14 @@ def test_padded_partition(dtype, split, mode):
 def test_linear_with_bias(dtype, act, mode):
     """Y = act(X W^T + b) with the bias riding in the flat parameter: forward, input gradient, weight
     gradient and bias gradient (column sums of dY onto what arrives with the shard) against the oracle's
-    rotated layer with bias; weights and bias come back unchanged.  One case has a padded last shard."""
+    rotated layer with bias; weights and bias come back unchanged.  The fp32 and bf16 cases have a padded last
+    shard, with and without the activation."""
     if dtype == "f32":
-        T, I, O, n = 70, 36, 50, 3           # padded: shards of 17, 17, 16 rows
-    elif dtype == "bf16" and act == B.RTP_ACT_NONE:
-        T, I, O, n = 300, 264, 520, 3        # padded: 176, 176, 168
+        T, I, O, n = 70, 36, 50, 3           # padded: shards of 17, 17, 16 rows (with or without the activation)
+    elif dtype == "bf16":
+        T, I, O, n = 300, 264, 520, 3        # padded: 176, 176, 168 (with or without the activation)
     else:
         T, I, O, n = 320, 288, 4 * 160, 4
-    if act != B.RTP_ACT_NONE and O % n:
-        O = 48 if dtype == "f32" else O      # an activation needs n | O
     w = wl.Workload("bias", "linear", T=T, I=I, O=O, n=n, dtype=dtype, mode="x", w_dist=("uniform", 0.1))
     inp = wl.make_inputs(w, seed=21, grad0=True)
     rng = np.random.default_rng(22)
@@ -673,6 +672,101 @@ def test_mlp_unit_with_biases(dtype, act, mode):
         assert all(torch.equal(a, dev(inp[k], td)) for a, k in zip(Ws, ("W1", "W2")))
         assert torch.equal(bb1, dev(b1, td)) and torch.equal(bb2, dev(b2, td))
         got = dict(Y=Y, dX=dX, H=mlp.hidden, dW1=Gs[0], dW2=Gs[1], db1=g1, db2=g2)
+        for key, val in got.items():
+            assert torch.isfinite(val.float()).all(), key
+            assert relerr(host(val), ref[key]) <= tol, (key, relerr(host(val), ref[key]))
+        mlp.close()
+
+
+@pytest.mark.parametrize("schedule", ["default", "pipelined", "grouped", "grouped_one_stream", "stepwise"])
+@pytest.mark.parametrize("gated", [False, True])
+def test_mlp_unit_with_biases_in_every_schedule(gated, schedule):
+    """Biases of the unit's linears (for the gated unit: gate, up and down) in every launch schedule, shapes the
+    tiled kernel takes; arriving bias gradients are added onto."""
+    T, I, O, O2, n = 288, 160, 512, 96, 4
+    w = wl.Workload("mlp_bias_sched", "swiglu" if gated else "mlp_gelu", T=T, I=I, O=O, O2=O2, n=n, dtype="bf16", mode="x",
+                    w_dist=("normal", 0.08))
+    inp = wl.make_inputs(w, seed=51, grad0=True)
+    rng = np.random.default_rng(52)
+    names = ("Wg", "Wu", "Wd") if gated else ("W1", "W2")
+    sizes = [O] * (len(names) - 1) + [O2]
+    bs = [wl._store(rng.standard_normal(sz).astype(np.float32) * 0.3, "bf16") for sz in sizes]
+    gbs = [rng.standard_normal(sz).astype(np.float32) for sz in sizes]
+    for mode in (B.RTP_INPLACE_STAGED, B.RTP_DOUBLE_BUFFER):
+        rank = 2
+        say(f"biased mlp gated={gated} schedule={schedule} mode={mode}")
+        if gated:
+            ref = orc.rtp_swiglu(f64(inp["X"]), *[f64(inp[k]) for k in names], f64(inp["dY"]), n, rank,
+                                 *[f64(inp["G0_" + k]) for k in names], *[f64(b) for b in bs], *[f64(g) for g in gbs])
+            gkeys, bkeys = ("dWg", "dWu", "dWd"), ("dbg", "dbu", "dbd")
+        else:
+            ref = orc.rtp_mlp(f64(inp["X"]), f64(inp["W1"]), f64(inp["W2"]), f64(inp["dY"]), n, rank, orc.GELU_ERF,
+                              f64(inp["G0_W1"]), f64(inp["G0_W2"]), b1=f64(bs[0]), b2=f64(bs[1]), gb1_0=f64(gbs[0]), gb2_0=f64(gbs[1]))
+            gkeys, bkeys = ("dW1", "dW2"), ("db1", "db2")
+        mlp = RtpMlp([dev(inp[k], torch.bfloat16) for k in names], T, n, rank, B.RTP_ACT_SWIGLU if gated else B.RTP_ACT_GELU_ERF,
+                     mode, B.RTP_BF16, G0=[dev(inp["G0_" + k], torch.float32) for k in names],
+                     biases=[dev(b, torch.bfloat16) for b in bs], gb0=[dev(g, torch.float32) for g in gbs], **_schedule(schedule))
+        Xd, dYd = dev(inp["X"], torch.bfloat16), dev(inp["dY"], torch.bfloat16)
+        Y = torch.full((T, O2), float("nan"), device=DEV, dtype=torch.bfloat16)
+        dX = torch.full((T, I), float("nan"), device=DEV, dtype=torch.bfloat16)
+        torch.cuda.synchronize()
+        mlp.forward(Xd, Y)
+        mlp.backward(Xd, dYd, dX)
+        mlp.sync()
+        Ws, Gs = mlp.gathered()
+        bb, gg = mlp.gathered_biases()
+        assert all(torch.equal(a, dev(inp[k], torch.bfloat16)) for a, k in zip(Ws, names))
+        assert all(torch.equal(a, dev(b, torch.bfloat16)) for a, b in zip(bb, bs))
+        got = dict(Y=Y, dX=dX, H=mlp.hidden)
+        got.update(zip(gkeys, Gs))
+        got.update(zip(bkeys, gg))
+        for key, val in got.items():
+            assert torch.isfinite(val.float()).all(), key
+            assert relerr(host(val), ref[key]) <= TOL_BF16, (key, relerr(host(val), ref[key]))
+        mlp.close()
+
+
+@pytest.mark.parametrize("schedule", ["default", "pipelined", "stepwise"])
+@pytest.mark.parametrize("kind,dtype,O,n", [("mlp_gelu", "bf16", 232, 6), ("swiglu", "bf16", 232, 6), ("swiglu", "f16", 736, 6),
+                                            ("mlp_gelu", "f32", 50, 4), ("swiglu", "f32", 50, 4)])
+def test_mlp_unit_with_a_padded_partition(kind, dtype, O, n, schedule):
+    """A hidden width the partition factor does not divide: the unit runs on n shards of the padded width
+    (rtp_mlp_hidden_width); the padding units have zero weights, so act(0) = 0 and they change nothing.  The
+    reference is the unsharded definition (the rotated oracle needs an even partition)."""
+    if dtype == "f32" and schedule != "stepwise":
+        pytest.skip("the fp32 unit has one schedule")
+    T, I, O2 = (96, 64, 64) if dtype != "f32" else (40, 24, 20)
+    w = wl.Workload("mlp_padded", kind, T=T, I=I, O=O, O2=O2, n=n, dtype=dtype, mode="x", w_dist=("normal", 0.1))
+    inp = wl.make_inputs(w, seed=61, grad0=True)
+    td, bd = _TD[dtype], _BD[dtype]
+    tol = {"f32": TOL_F32, "bf16": TOL_BF16, "f16": TOL_F16}[dtype]
+    gated = kind == "swiglu"
+    names = ("Wg", "Wu", "Wd") if gated else ("W1", "W2")
+    if gated:
+        ref = orc.plain_swiglu(f64(inp["X"]), *[f64(inp[k]) for k in names], f64(inp["dY"]))
+        gkeys = ("dWg", "dWu", "dWd")
+    else:
+        ref = orc.plain_mlp(f64(inp["X"]), f64(inp["W1"]), f64(inp["W2"]), f64(inp["dY"]))
+        gkeys = ("dW1", "dW2")
+    for mode in (B.RTP_INPLACE_STAGED, B.RTP_DOUBLE_BUFFER, B.RTP_INPLACE_BLOCKING):
+        say(f"padded mlp kind={kind} dtype={dtype} O={O} n={n} schedule={schedule} mode={mode}")
+        mlp = RtpMlp([dev(inp[k], td) for k in names], T, n, n - 1, B.RTP_ACT_SWIGLU if gated else B.RTP_ACT_GELU_ERF, mode, bd,
+                     G0=[dev(inp["G0_" + k], torch.float32) for k in names], **_schedule(schedule))
+        assert mlp.hidden_width > O and mlp.hidden_width % n == 0
+        Xd, dYd = dev(inp["X"], td), dev(inp["dY"], td)
+        Y = torch.full((T, O2), float("nan"), device=DEV, dtype=td)
+        dX = torch.full((T, I), float("nan"), device=DEV, dtype=td)
+        torch.cuda.synchronize()
+        mlp.forward(Xd, Y)
+        mlp.backward(Xd, dYd, dX)
+        mlp.sync()
+        Ws, Gs = mlp.gathered()
+        assert all(torch.equal(a, dev(inp[k], td)) for a, k in zip(Ws, names)), "weights unchanged, padding dropped"
+        H = mlp.hidden
+        assert torch.count_nonzero(H[:, O:]) == 0, "padding units: act(0) = 0"
+        got = dict(Y=Y, dX=dX, H=H[:, :O])
+        for key, g, k in zip(gkeys, Gs, names):
+            got[key] = g.double().cpu() - torch.from_numpy(f64(inp["G0_" + k]))     # arriving + own, minus arriving
         for key, val in got.items():
             assert torch.isfinite(val.float()).all(), key
             assert relerr(host(val), ref[key]) <= tol, (key, relerr(host(val), ref[key]))

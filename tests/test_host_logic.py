@@ -288,6 +288,14 @@ def test_mlp_slot_sizes():
     d.act, d.I, d.O, d.O2, d.n, d.T = B.RTP_ACT_GELU_ERF, 8192, 28672, 8192, 16, 2048
     w, g = B.lib.rtp_mlp_slot_w_bytes(C.byref(d)), B.lib.rtp_mlp_slot_g_bytes(C.byref(d))
     assert (w, g) == (58720256, 117440512)
+    # a hidden width n does not divide: n shards of the aligned width that covers it
+    d2 = B.rtp_mlp_desc()
+    d2.T, d2.I, d2.O, d2.O2, d2.n, d2.dtype, d2.act = 64, 64, 232, 64, 6, B.RTP_BF16, B.RTP_ACT_SWIGLU
+    assert B.lib.rtp_mlp_hidden_width(C.byref(d2)) == 240
+    assert B.lib.rtp_mlp_slot_w_bytes(C.byref(d2)) == (2 * 40 * 64 + 64 * 40) * 2
+    d2.O = 200                                           # 5 shards of 40 would cover it: the last shard would be empty
+    assert B.lib.rtp_mlp_hidden_width(C.byref(d2)) == -1 and B.lib.rtp_mlp_slot_w_bytes(C.byref(d2)) == 0
+    assert B.lib.rtp_mlp_hidden_width(C.byref(d)) == 28672
     # the large config's footprint against the table's per-worker bound
     assert B.rtp_worker_bytes(B.RTP_INPLACE_STAGED, w, g) == 234881024
     assert B.rtp_table1_worker_bytes(False, w, g) == orc.worker_param_bytes("rtp", 939524096, 1879048192, 16)
@@ -327,8 +335,10 @@ def test_padded_linear_descriptions():
     ring = _dry_ring(3, 0, B.RTP_DOUBLE_BUFFER, w=176 * 64 * 2, g=176 * 64 * 4)
     ok = B.Linear(ring, T=8, I=64, O=520, split=B.RTP_SPLIT_OUT, dtype=B.RTP_BF16)      # shards of 176 rows, padded
     ok.close()
-    with pytest.raises(B.RtpError) as e:                                                  # an activation needs n | O
-        B.Linear(ring, T=8, I=64, O=520, split=B.RTP_SPLIT_OUT, dtype=B.RTP_BF16, act=B.RTP_ACT_GELU_ERF)
+    ok = B.Linear(ring, T=8, I=64, O=520, split=B.RTP_SPLIT_OUT, dtype=B.RTP_BF16, act=B.RTP_ACT_GELU_ERF)   # also with an activation
+    ok.close()
+    with pytest.raises(B.RtpError) as e:                                                  # but not a gated one: the unit pads itself
+        B.Linear(ring, T=8, I=64, O=520, split=B.RTP_SPLIT_OUT, dtype=B.RTP_BF16, act=B.RTP_ACT_SWIGLU)
     assert e.value.status == B.RTP_ERR_SHAPE
     with pytest.raises(B.RtpError) as e:                                                  # padded shard larger than the slot
         B.Linear(ring, T=8, I=64, O=536, split=B.RTP_SPLIT_OUT, dtype=B.RTP_BF16)

@@ -590,3 +590,36 @@ def test_mlp_with_biases_rotated_matches_plain_numpy_and_fd(kind):
         e1[j], e2[j] = h, h
         assert abs((loss(b1 + e1, b2) - loss(b1 - e1, b2)) / (2 * h) - out["db1"][j]) < 1e-6
         assert abs((loss(b1, b2 + e2) - loss(b1, b2 - e2)) / (2 * h) - out["db2"][j]) < 1e-6
+
+
+def test_gated_unit_with_biases_rotated_matches_plain_numpy_and_fd():
+    """Biases of the gated unit: the unsharded definition against a numpy forward and central differences in
+    every bias, and the rotated form against the unsharded one (arriving bias gradients added onto)."""
+    from scipy.special import expit
+    rng = np.random.default_rng(91)
+    n, T, I, O1, O2 = 4, 5, 6, 8, 7
+    X, dY = rng.standard_normal((T, I)), rng.standard_normal((T, O2))
+    Wg, Wu, Wd = 0.5 * rng.standard_normal((O1, I)), 0.5 * rng.standard_normal((O1, I)), 0.5 * rng.standard_normal((O2, O1))
+    bg, bu, bd = rng.standard_normal(O1), rng.standard_normal(O1), rng.standard_normal(O2)
+    g0 = [rng.standard_normal(O1), rng.standard_normal(O1), rng.standard_normal(O2)]
+    ref = orc.plain_swiglu(X, Wg, Wu, Wd, dY, bg, bu, bd)
+    a, b = X @ Wg.T + bg, X @ Wu.T + bu
+    np.testing.assert_allclose(ref["Y"], (a * expit(a) * b) @ Wd.T + bd, rtol=1e-12, atol=1e-12)
+    nobias = orc.plain_swiglu(X, Wg, Wu, Wd, dY)
+    zero = orc.plain_swiglu(X, Wg, Wu, Wd, dY, np.zeros(O1), np.zeros(O1), np.zeros(O2))
+    for key in ("Y", "dX", "dWg", "dWu", "dWd"):
+        assert np.array_equal(nobias[key], zero[key]), "zero biases change nothing"
+    for rank in (0, 3):
+        out = orc.rtp_swiglu(X, Wg, Wu, Wd, dY, n, rank, bg=bg, bu=bu, bd=bd, gbg0=g0[0], gbu0=g0[1], gbd0=g0[2])
+        for key in ("Y", "dX", "dWg", "dWu", "dWd"):
+            np.testing.assert_allclose(out[key], ref[key], rtol=1e-12, atol=1e-12)
+        for key, arriving in zip(("dbg", "dbu", "dbd"), g0):
+            np.testing.assert_allclose(out[key], arriving + ref[key], rtol=1e-12, atol=1e-12)
+    h = 1e-6
+    loss = lambda cg, cu, cd: float((orc.plain_swiglu(X, Wg, Wu, Wd, dY, cg, cu, cd)["Y"] * dY).sum())
+    for j in (0, 5):
+        e1, e2 = np.zeros(O1), np.zeros(O2)
+        e1[j], e2[j] = h, h
+        assert abs((loss(bg + e1, bu, bd) - loss(bg - e1, bu, bd)) / (2 * h) - ref["dbg"][j]) < 1e-6
+        assert abs((loss(bg, bu + e1, bd) - loss(bg, bu - e1, bd)) / (2 * h) - ref["dbu"][j]) < 1e-6
+        assert abs((loss(bg, bu, bd + e2) - loss(bg, bu, bd - e2)) / (2 * h) - ref["dbd"][j]) < 1e-6
