@@ -265,6 +265,18 @@ rtp_status rtp_ring_sync(rtp_ring *ring);
 /* Shard currently resident (after everything enqueued so far), or -1. */
 int rtp_ring_resident(const rtp_ring *ring);
 
+/* Test aid for the cross-stream ordering.  From now on the ring enqueues a
+ * bounded spin kernel (one wave that watches the wall clock for the given
+ * number of microseconds, at most 5000, and exits) ahead of every transfer on
+ * the stage stream (`stage_us`) and ahead of every GEMM on the auxiliary
+ * stream (`aux_us`), so that those streams run late against the compute
+ * stream: a result that only came out right because a transfer or a
+ * weight-gradient kernel happened to finish early no longer does.  Results
+ * must not change.  `scratch32_dev`: 32 bytes of caller-owned device memory
+ * the spin kernels write their clock readings to.  Zero for both switches it
+ * off.  Idle state only. */
+rtp_status rtp_ring_set_test_delay(rtp_ring *ring, void *scratch32_dev, int64_t stage_us, int64_t aux_us);
+
 /* Copies up to `cap` records of what the ring has enqueued since creation
  * (or the last call with clear != 0) and returns the total number recorded.
  * kind: 1 compute-fwd, 2 compute-bwd, 3 weights in, 4 weights out,

@@ -106,6 +106,7 @@ SYMBOLS = {
     "rtp_rotate_step": (C.c_int, [_P, C.c_int, C.c_int]),
     "rtp_ring_end": (C.c_int, [_P]),
     "rtp_ring_abort": (C.c_int, [_P]),
+    "rtp_ring_set_test_delay": (C.c_int, [_P, _P, C.c_int64, C.c_int64]),
     "rtp_ring_flush": (C.c_int, [_P]),
     "rtp_ring_zero_grads": (C.c_int, [_P]),
     "rtp_ring_sync": (C.c_int, [_P]),

@@ -242,6 +242,10 @@ struct rtp_ring {
     int base_idx = 0;    // weight buffer index at step 0 of the open pass
     int rotations = 0;   // rotate_step calls in the open pass
     int executed = 0;    // blocking mode: rotations already carried out
+    // test aid: a bounded spin kernel ahead of every transfer on the stage stream / every GEMM on the
+    // auxiliary stream stretches the windows in which a missing cross-stream wait would show
+    long long delay_stage_ticks = 0, delay_aux_ticks = 0;
+    long long *delay_out = nullptr;
     std::vector<rtp_linear *> linears;
     std::vector<rtp_trace_rec> trace;
     hipEvent_t ev_free = nullptr, ev_free2 = nullptr, ev_join = nullptr, ev_aux = nullptr;
@@ -295,6 +299,8 @@ static rtp_status ensure_events(rtp_ring *r)
 static rtp_status copy_async(rtp_ring *r, void *dst, const void *src, size_t bytes, hipStream_t s)
 {
     if (r->dry || bytes == 0) return RTP_OK;
+    if (r->delay_stage_ticks > 0 && s == r->ss() && r->ss() != r->cs())
+        HIP_TRY(launch_clock_probe(r->delay_out, r->delay_stage_ticks, s));
     if (r->d.flags & RTP_FLAG_STAGE_MEMCPY)
         HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s));
     else
@@ -414,6 +420,27 @@ static rtp_status set_ablation(rtp_ring *r, int rotate, int compute)
     if (r->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "ablation can only change between passes");
     r->abl_rotate = rotate != 0;
     r->abl_compute = compute != 0;
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_ring_set_test_delay(rtp_ring *r, void *scratch32_dev, int64_t stage_us, int64_t aux_us)
+{
+    if (!r) return fail(RTP_ERR_INVALID, "rtp_ring_set_test_delay: null ring");
+    if (r->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_ring_set_test_delay: a pass is open");
+    if (stage_us < 0 || aux_us < 0 || stage_us > 5000 || aux_us > 5000)
+        return fail(RTP_ERR_INVALID, "rtp_ring_set_test_delay: delays are 0 to 5000 microseconds");
+    r->delay_stage_ticks = r->delay_aux_ticks = 0;
+    r->delay_out = nullptr;
+    if (r->dry || (stage_us == 0 && aux_us == 0)) return RTP_OK;
+    if (!scratch32_dev || ((uintptr_t)scratch32_dev & 7))
+        return fail(RTP_ERR_INVALID, "rtp_ring_set_test_delay: the spin kernels need 32 bytes of 8-byte aligned device memory");
+    int dev = 0, khz = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev));
+    if (khz <= 0) return fail(RTP_ERR_UNSUPPORTED, "rtp_ring_set_test_delay: the device reports no wall clock rate");
+    r->delay_out = (long long *)scratch32_dev;
+    r->delay_stage_ticks = stage_us * (int64_t)khz / 1000;
+    r->delay_aux_ticks = aux_us * (int64_t)khz / 1000;
     return RTP_OK;
 }
 
@@ -795,10 +822,19 @@ static int bwd_act_epi(rtp_act a)
 // epilogue of a result that is summed over the n steps
 static int acc_epi(int step, int n) { return n == 1 ? EPI_STORE : step == 0 ? EPI_ACC_FIRST : step == n - 1 ? EPI_ACC_LAST : EPI_ACC_ADD; }
 
+// test aid (rtp_ring_set_test_delay): hold the auxiliary stream back ahead of a GEMM it is about to run
+static rtp_status aux_delay(rtp_ring *r, hipStream_t st)
+{
+    if (r->delay_aux_ticks > 0 && st == r->as() && r->as() != r->cs())
+        HIP_TRY(launch_clock_probe(r->delay_out + 2, r->delay_aux_ticks, st));
+    return RTP_OK;
+}
+
 static rtp_status gemm(rtp_linear *l, int layout, GemmArgs &a, hipStream_t st)
 {
     rtp_ring *r = l->ring;
     if (r->dry || !r->abl_compute) return RTP_OK;
+    RTP_TRY(aux_delay(r, st));
     if (l->d.dtype != RTP_F32) {
         a.elem = l->d.dtype == RTP_F16 ? ELEM_F16 : ELEM_BF16;
         HIP_TRY(timed_launch(layout, 2.0 * a.M * a.N * a.K, st, [&] { return launch_gemm_bf16(layout, a, 0, st); }));
@@ -1445,6 +1481,7 @@ static bool mlp_grouped_ok(const rtp_mlp *m, const void *X, const void *Y, const
 static rtp_status gemm_group(rtp_ring *r, int layout, const GemmArgs *a, int count, hipStream_t st)
 {
     if (r->dry || !r->abl_compute || count == 0) return RTP_OK;
+    RTP_TRY(aux_delay(r, st));
     double flops = 0.0;
     for (int i = 0; i < count; ++i) flops += 2.0 * a[i].M * a[i].N * a[i].K;
     HIP_TRY(timed_launch(layout, flops, st, [&] { return launch_gemm_bf16_pp_group(layout, a, count, nullptr, st); }));
@@ -1965,6 +2002,7 @@ static rtp_status moe_gemm(rtp_moe *m, int layout, GemmArgs &a, hipStream_t st)
 {
     rtp_ring *r = m->ring;
     if (!r->abl_compute || a.M <= 0 || a.N <= 0 || a.K <= 0) return RTP_OK;
+    RTP_TRY(aux_delay(r, st));
     a.elem = m->d.dtype == RTP_F16 ? ELEM_F16 : ELEM_BF16;
     HIP_TRY(timed_launch(layout, 2.0 * a.M * a.N * a.K, st, [&] { return launch_gemm_bf16(layout, a, 0, st); }));
     return RTP_OK;
