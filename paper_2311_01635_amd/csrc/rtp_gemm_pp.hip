@@ -25,6 +25,11 @@ bool gemm_bf16_pp_supported(int layout, const GemmArgs &a)
     if (a.K < 32 || (a.K & 31)) return false;
     if (layout == LAY_TN && a.M < 8) return false;
     if (layout != LAY_NT && a.N < 8) return false;
+    // the kernel addresses each operand through a buffer descriptor with 32-bit byte offsets
+    const bool a_kc = layout != LAY_TN, b_kc = layout == LAY_NT;
+    const int64_t a_elems = (int64_t)((a_kc ? a.M : a.K) - 1) * a.lda + (a_kc ? a.K : a.M);
+    const int64_t b_elems = (int64_t)((b_kc ? a.N : a.K) - 1) * a.ldb + (b_kc ? a.K : a.N);
+    if (a_elems * 2 >= (int64_t)1 << 31 || b_elems * 2 >= (int64_t)1 << 31) return false;
     return true;
 }
 
