@@ -51,21 +51,28 @@ def relerr(got, ref):
 
 
 def sample_rows(total, count, rng):
+    """First, last and `count` more rows, one drawn in each of `count` equal blocks: with count >= total / 128
+    every 128-row tile of an output holds a sampled row, and a sampled token's row is compared over ALL its
+    columns, so every output tile of Y, dX, H, the pre-activations and dPre is touched."""
     idx = {0, total - 1}
-    idx.update(int(i) for i in rng.choice(total, size=min(count, total), replace=False))
+    edges = np.linspace(0, total, min(count, total) + 1).astype(int)
+    idx.update(int(rng.integers(lo, hi)) for lo, hi in zip(edges[:-1], edges[1:]) if hi > lo)
     return np.array(sorted(idx))
 
 
 def sample_units(O, n, extra, rng):
+    """Every shard's first and last hidden unit plus `extra` more, one drawn in each of `extra` equal blocks of the
+    hidden width (a sampled unit's gradient row / column is compared over its whole length)."""
     o = O // n
     idx = set()
     for k in range(n):
         idx.update((k * o, (k + 1) * o - 1))
-    idx.update(int(i) for i in rng.choice(O, size=extra, replace=False))
+    edges = np.linspace(0, O, extra + 1).astype(int)
+    idx.update(int(rng.integers(lo, hi)) for lo, hi in zip(edges[:-1], edges[1:]) if hi > lo)
     return np.array(sorted(idx))
 
 
-def _mlp_fullsize(name, n_tokens, n_extra_units, rank=0):
+def _mlp_fullsize(name, n_tokens, n_extra_units, rank=0, **schedule):
     w = wl.CONFIGS[name]
     rng = np.random.default_rng(1234)
     say(f"{name}: drawing inputs")
@@ -74,12 +81,14 @@ def _mlp_fullsize(name, n_tokens, n_extra_units, rank=0):
     names = ("Wg", "Wu", "Wd") if gated else ("W1", "W2")
     act = B.RTP_ACT_SWIGLU if gated else B.RTP_ACT_GELU_ERF
     mode = {"double_buffer": B.RTP_DOUBLE_BUFFER, "inplace_staged": B.RTP_INPLACE_STAGED}[w.mode]
-    mlp = RtpMlp([dev(inp[k]) for k in names], w.T, w.n, rank, act, mode, B.RTP_BF16)
+    mlp = RtpMlp([dev(inp[k]) for k in names], w.T, w.n, rank, act, mode, B.RTP_BF16, **schedule)
     X, dY = dev(inp["X"]), dev(inp["dY"])
     Y = torch.full((w.T, w.O2), float("nan"), device=DEV, dtype=torch.bfloat16)
     dX = torch.full((w.T, w.I), float("nan"), device=DEV, dtype=torch.bfloat16)
     torch.cuda.synchronize()
-    say(f"{name}: GPU forward + backward, {w.n} rotation steps, mode {w.mode}")
+    say(f"{name}: GPU forward + backward, {w.n} rotation steps, mode {w.mode}, rank {rank}, schedule {schedule or 'default'}")
+    for t in (mlp.preact, mlp.hidden, mlp.dpre, mlp.acc_y, mlp.acc_dx):
+        t.view(torch.uint8).fill_(255)          # NaN everywhere: whatever is compared below was written by this pass
     mlp.forward(X, Y)
     mlp.backward(X, dY, dX)
     mlp.sync()
@@ -121,6 +130,16 @@ def _mlp_fullsize(name, n_tokens, n_extra_units, rank=0):
         got = {"dW1": host(Gs[0][J]), "dW2": host(Gs[1][:, J])}
     got.update(Y=host(Y[S]), dX=host(dX[S]), H=host(mlp.hidden[S]))
     refs = dict(refG, Y=ref["Y"], dX=ref["dX"], H=ref["H"])
+    # saved pre-activations and the gradient at them, stored shard by shard: [a_k | b_k] for the gated unit
+    o = w.O // w.n
+    pre, dpre = host(mlp.preact[S]), host(mlp.dpre[S])
+    if gated:
+        cols_a = np.concatenate([np.arange(k * 2 * o, k * 2 * o + o) for k in range(w.n)])
+        got.update(A=pre[:, cols_a], Bu=pre[:, cols_a + o], dA=dpre[:, cols_a], dB=dpre[:, cols_a + o])
+        refs.update(A=ref["A"], Bu=ref["B"], dA=ref["dA"], dB=ref["dB"])
+    else:
+        got.update(Z=pre, dZ=dpre)
+        refs.update(Z=ref["Z"], dZ=ref["dZ"])
     assert torch.isfinite(Y.float()).all() and torch.isfinite(dX.float()).all(), "an output element was never written"
     errs = {k: relerr(got[k], refs[k]) for k in refs}
     say(f"{name}: max-norm relative errors {errs}")
@@ -129,16 +148,22 @@ def _mlp_fullsize(name, n_tokens, n_extra_units, rank=0):
         assert e <= TOL, (k, e)
 
 
-def test_cfg4_llama7b_swiglu_fullsize():
-    _mlp_fullsize("cfg4_llama7b_swiglu", n_tokens=40, n_extra_units=8)
+@pytest.mark.parametrize("rank,schedule", [(0, {}), (5, dict(pipelined=True)), (3, dict(grouped=True)), (7, dict(stepwise=True)),
+                                           (2, dict(aux_stream=False))])
+def test_cfg4_llama7b_swiglu_fullsize(rank, schedule):
+    """The headline configuration, in the launch configuration bench.py times (rank 0, default schedule) and, on other
+    ranks, in every other launch schedule."""
+    _mlp_fullsize("cfg4_llama7b_swiglu", n_tokens=32, n_extra_units=10, rank=rank, **schedule)
 
 
-def test_cfg2_gpt2_small_mlp_fullsize():
-    _mlp_fullsize("cfg2_gpt2s_mlp", n_tokens=64, n_extra_units=16, rank=3)
+@pytest.mark.parametrize("rank,schedule", [(3, {}), (6, dict(pipelined=True)), (0, dict(stepwise=True))])
+def test_cfg2_gpt2_small_mlp_fullsize(rank, schedule):
+    _mlp_fullsize("cfg2_gpt2s_mlp", n_tokens=64, n_extra_units=16, rank=rank, **schedule)
 
 
-def test_cfg5_large_mlp_fullsize():
-    _mlp_fullsize("cfg5_large_mlp", n_tokens=14, n_extra_units=4, rank=0)
+@pytest.mark.parametrize("rank", [0, 9])
+def test_cfg5_large_mlp_fullsize(rank):
+    _mlp_fullsize("cfg5_large_mlp", n_tokens=16, n_extra_units=6, rank=rank)
 
 
 def test_cfg3_d2048_projections_fullsize():

@@ -242,6 +242,21 @@ def test_activation_closed_forms():
     assert np.abs(orc.act(x, orc.GELU_TANH) - orc.act(x, orc.GELU_ERF)).max() < 2e-3
 
 
+def test_tanh_gelu_value_and_derivative_against_a_library_routine():
+    """The tanh form pinned to rounding error: a library's own implementation of it in fp64 (value, and the
+    derivative through that library's automatic differentiation), the odd-part identity g(x) - g(-x) = x that
+    follows from tanh being odd, and the tails."""
+    import torch
+    x = np.linspace(-8, 8, 641)
+    xt = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+    yt = torch.nn.functional.gelu(xt, approximate="tanh")
+    yt.sum().backward()
+    np.testing.assert_allclose(orc.act(x, orc.GELU_TANH), yt.detach().numpy(), rtol=0, atol=1e-14)
+    np.testing.assert_allclose(orc.act_grad(x, orc.GELU_TANH), xt.grad.numpy(), rtol=0, atol=1e-13)
+    np.testing.assert_allclose(orc.act(x, orc.GELU_TANH) - orc.act(-x, orc.GELU_TANH), x, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(orc.act(np.array([30.0, -30.0]), orc.GELU_TANH), [30.0, 0.0], atol=1e-15)
+
+
 @pytest.mark.parametrize("kind", [orc.GELU_ERF, orc.GELU_TANH, orc.SILU])
 def test_activation_derivative_by_central_difference(kind):
     x = np.linspace(-5, 5, 101)
