@@ -22,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published)
+PEAK_F32_VECTOR_TFLOPS = 157.3   # fp32 vector ALU peak (the fp32 correctness path runs plain FMA kernels)
 PEAK_HBM_GBS = 8000.0
 
 
@@ -33,11 +34,11 @@ def parse():
     ap.add_argument("--workload", default="cfg4_llama7b_swiglu")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true", help="skip the three-run staging-overlap measurement")
-    ap.add_argument("--schedule", default="default", choices=["default", "pipelined", "grouped", "stepwise"],
+    ap.add_argument("--schedule", default="default", choices=["default", "pipelined", "grouped", "stepwise", "fused"],
                     help="launch schedule of the MLP unit: default (forward: independent GEMMs of a step in one launch; "
                          "backward: one launch per GEMM, weight gradients on the auxiliary stream), pipelined (two decoupled "
                          "kernel chains on two streams), grouped (grouped launches in both passes), stepwise (one launch per "
-                         "linear and step)")
+                         "linear and step), fused (the dependent GEMMs of a step as one launch)")
     ap.add_argument("--stage-copy", default="kernel", choices=["kernel", "memcpy"],
                     help="shard transfers by the library's copy kernel (default) or by hipMemcpyAsync device-to-device")
     ap.add_argument("--no-aux-stream", action="store_true", help="no second compute stream")
@@ -84,6 +85,85 @@ class MoeUnit:
         self.moe.close()
 
 
+class LinearsUnit:
+    """One or several independent rotated linear layers (the fp32 single layer; the four d=2048 projections) behind
+    the forward / backward calls of a unit: a pass runs every layer's N-step rotation, one layer after the other."""
+
+    def __init__(self, layers, torch):
+        self.layers, self.torch = layers, torch            # [(name, RtpLinear, X, dY, Y, dX)]
+        self.w_bytes = sum(l.ring.desc.w_bytes for _, l, *_ in layers)
+        self.g_bytes = sum(l.ring.desc.g_bytes for _, l, *_ in layers)
+
+    def forward(self, X, Y):
+        for _, l, x, dy, y, dx in self.layers:
+            l.forward(x, y)
+
+    def backward(self, X, dY, dX):
+        for _, l, x, dy, y, dx in self.layers:
+            l.backward(x, dy, dx)
+
+    def set_ablation(self, rotate=True, compute=True):
+        for _, l, *_ in self.layers:
+            l.set_ablation(rotate, compute)
+
+    def sync(self):
+        for _, l, *_ in self.layers:
+            l.sync()
+
+    def worker_bytes(self):
+        return sum(l.worker_bytes() for _, l, *_ in self.layers)
+
+    def close(self):
+        for _, l, *_ in self.layers:
+            l.close()
+
+
+def build_linears(w, torch, dev, aux_stream):
+    import numpy as np
+    import rtp_workloads as wl
+    from paper_2311_01635_amd import binding as B
+    from paper_2311_01635_amd.layers import RtpLinear
+    inp = wl.make_inputs(w, seed=0)
+    td, bd = (torch.float32, B.RTP_F32) if w.dtype == "f32" else (torch.bfloat16, B.RTP_BF16)
+    to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev, td)
+    mode = {"double_buffer": B.RTP_DOUBLE_BUFFER, "inplace_staged": B.RTP_INPLACE_STAGED}[w.mode]
+    mats = [("W", w.O, w.I)] if w.kind == "linear" else list(w.extra["matrices"])
+    layers = []
+    for (nm, O, I) in mats:
+        Wn, Xn, dYn = (inp["W"], inp["X"], inp["dY"]) if w.kind == "linear" else (inp[f"W_{nm}"], inp[f"X_{I}"], inp[f"dY_{nm}"])
+        layer = RtpLinear(to(Wn), w.T, w.n, 0, B.RTP_SPLIT_OUT, mode, bd, aux_stream=aux_stream)
+        layers.append((nm, layer, to(Xn), to(dYn), torch.empty(w.T, O, device=dev, dtype=td), torch.empty(w.T, I, device=dev, dtype=td)))
+    return inp, LinearsUnit(layers, torch)
+
+
+def cpu_baseline_linears(w, inp, tokens):
+    """The oracle's rotated linear layer(s), one worker, fwd+bwd, over the first `tokens` tokens (0: all of a small
+    workload, else a sample sized by two short probes for roughly 15 s)."""
+    import numpy as np
+    import oracle as orc
+    f64 = lambda a: np.ascontiguousarray(a, dtype=np.float64)
+    mats = [("W", w.O, w.I)] if w.kind == "linear" else list(w.extra["matrices"])
+
+    def run(nt):
+        t0 = time.perf_counter()
+        for (nm, O, I) in mats:
+            Wn, Xn, dYn = (inp["W"], inp["X"], inp["dY"]) if w.kind == "linear" else (inp[f"W_{nm}"], inp[f"X_{I}"], inp[f"dY_{nm}"])
+            orc.rtp_linear_out(f64(Xn[:nt]), f64(Wn), f64(dYn[:nt]), w.n, 0)
+        return time.perf_counter() - t0
+
+    if tokens <= 0 and w.flops < 1e9:
+        tokens = w.T
+    elif tokens <= 0:
+        t16, t64 = run(16), run(64)
+        per_token = max((t64 - t16) / 48.0, 1e-6)
+        tokens = int(min(w.T, max(64, (15.0 - max(t16 - 16 * per_token, 0.0)) / per_token))) // 16 * 16
+    dt = run(tokens)
+    flops = w.flops * tokens / w.T
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"first {tokens} of {w.T} tokens, full weights, all {w.n} rotation steps fwd+bwd of "
+                      f"{len(mats)} linear layer(s), {dt:.2f} s, fp64 triple loops"}
+
+
 def build_moe(w, torch, dev, aux_stream):
     import numpy as np
     import rtp_workloads as wl
@@ -123,10 +203,11 @@ def cpu_baseline_moe(w, inp, tokens):
 
 
 def timed(torch, mlp, X, Y, dY, dX, steps, per_pass=None):
-    """ms for `steps` fwd+bwd passes between one pair of HIP events on the compute stream (every pass ends with
-    the stage and auxiliary streams joined into it).  With a list in `per_pass`, an event between passes as well:
-    the list receives each pass's own duration."""
-    s = mlp.compute_stream
+    """ms for `steps` fwd+bwd passes between one pair of HIP events on the caller's stream: a pass starts after what
+    that stream holds and the stream continues after the pass (whose stage and auxiliary streams are joined into its
+    compute stream when it ends), so the pair brackets all the work of every stream.  With a list in `per_pass`, an
+    event between passes as well: the list receives each pass's own duration."""
+    s = torch.cuda.current_stream()
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1 if per_pass is not None else 2)]
     torch.cuda.synchronize()
     marks[0].record(s)
@@ -160,6 +241,24 @@ def algorithmic_bytes(w, staging_bytes):
     per_step_bwd += (P * T * o * a + P * o * I * a)                           # dX: dPre, W1_k -> the sum over steps
     sums = (2 * (n - 1)) * T * O2 * 4 + T * O2 * a + (2 * (n - 1)) * T * I * 4 + T * I * a
     return n * (per_step_fwd + per_step_bwd) + sums + staging_bytes
+
+
+def algorithmic_bytes_linears(w, unit):
+    """The same bound for independent output-partitioned linear layers: per step X, W_k and the output slice forward;
+    dY slice, X and the gradient shard read and written (weight gradient), dY slice, W_k and the fp32 input-gradient sum
+    read and written (input gradient) backward; plus the staging copies (each copy reads and writes its bytes)."""
+    a = 4 if w.dtype == "f32" else 2
+    n, T, total = w.n, w.T, 0
+    mats = [("W", w.O, w.I)] if w.kind == "linear" else list(w.extra["matrices"])
+    for (_, O, I) in mats:
+        o = O // n
+        fwd = T * I * a + o * I * a + T * o * a
+        bwd = (T * o * a + T * I * a + 2 * o * I * 4) + (T * o * a + o * I * a)
+        sums = (2 * (n - 1)) * T * I * 4 + T * I * a
+        total += n * (fwd + bwd) + sums
+    out_copied = w.dtype == "f32"              # the fp32 path copies the gradient shard out; the bf16 kernels store it home
+    stg = 2 * ((4 * (n - 1) + 1) * unit.w_bytes + (n + (n - 1 if out_copied else 0)) * unit.g_bytes)
+    return total + stg
 
 
 def measured_traffic(workload, layout):
@@ -220,17 +319,23 @@ def main():
     dev = torch.device("cuda:0")
     is_moe = a.workload in wl.MOE_CONFIGS
     w = wl.MOE_CONFIGS[a.workload] if is_moe else wl.CONFIGS[a.workload]
+    is_lin = w.kind in ("linear", "linears")
+    X = dY = None
     if is_moe:
         inp, mlp, X, dY = build_moe(w, torch, dev, not a.no_aux_stream)
+    elif is_lin:
+        inp, mlp = build_linears(w, torch, dev, not a.no_aux_stream)
     else:
         inp, weights, X, dY = build_inputs(w, torch, dev)
         act = B.RTP_ACT_SWIGLU if w.kind == "swiglu" else B.RTP_ACT_GELU_ERF
         mode = {"double_buffer": B.RTP_DOUBLE_BUFFER, "inplace_staged": B.RTP_INPLACE_STAGED}[w.mode]
         mlp = RtpMlp(weights, w.T, w.n, 0, act, mode, B.RTP_BF16, stepwise=a.schedule == "stepwise",
-                     grouped=a.schedule == "grouped", pipelined=a.schedule == "pipelined", aux_stream=not a.no_aux_stream,
+                     grouped=a.schedule == "grouped", pipelined=a.schedule == "pipelined", fused=a.schedule == "fused", aux_stream=not a.no_aux_stream,
                      stage_memcpy=a.stage_copy == "memcpy")
-    Y = torch.empty(w.T, w.O2, device=dev, dtype=torch.bfloat16)
-    dX = torch.empty(w.T, w.I, device=dev, dtype=torch.bfloat16)
+    Y = dX = None
+    if not is_lin:
+        Y = torch.empty(w.T, w.O2, device=dev, dtype=torch.bfloat16)
+        dX = torch.empty(w.T, w.I, device=dev, dtype=torch.bfloat16)
     torch.cuda.synchronize()
 
     timed(torch, mlp, X, Y, dY, dX, a.warmup)
@@ -259,8 +364,11 @@ def main():
     dom = max(prof, key=lambda k: prof[k][1])
     launches, tot_ms, tot_flops = prof[dom]
     achieved = tot_flops / (tot_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": B.rtp_gemm_kernel_name({"nt": 0, "nn": 1, "tn": 2}[dom], 4),
-                "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+    f32 = w.dtype == "f32"
+    peak = PEAK_F32_VECTOR_TFLOPS if f32 else PEAK_BF16_TFLOPS
+    roofline = {"bound": "alu" if f32 else "mfma",
+                "kernel": "gemm_f32_kernel" if f32 else B.rtp_gemm_kernel_name({"nt": 0, "nn": 1, "tn": 2}[dom], 4),
+                "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                 "avg_launch_us": tot_ms * 1e3 / launches, "launches_per_step": launches / a.steps,
                 "flops_per_launch": tot_flops / launches, "traffic": measured_traffic(w.name, dom),
                 # launches on the compute and the auxiliary stream overlap, so a launch's duration includes the
@@ -276,7 +384,7 @@ def main():
     timed(torch, mlp, X, Y, dY, dX, k_alone)
     prof_alone = B.rtp_prof_end()
     roofline["alone"] = {k: {"avg_us": v[1] * 1e3 / max(v[0], 1), "tflops": v[2] / max(v[1], 1e-9) / 1e9,
-                             "frac": v[2] / max(v[1], 1e-9) / 1e9 / PEAK_BF16_TFLOPS} for k, v in prof_alone.items()}
+                             "frac": v[2] / max(v[1], 1e-9) / 1e9 / peak} for k, v in prof_alone.items()}
 
     # ---- how much of the shard staging hides under compute -------------------------
     overlap = None
@@ -298,18 +406,34 @@ def main():
         # copy in the timed run: the weight-gradient GEMM that completes a part stores `arriving + own` straight into
         # the slot it travels to (a fused send); the staging-only run, which launches no GEMM, copies it instead.
         n_, W_, G_ = w.n, mlp.w_bytes, mlp.g_bytes
+        fused = w.dtype != "f32"                # the fp32 path copies the gradient shard out like the weights
         overlap = {"ms_compute_only": t_c, "ms_staging_only": t_s, "ms_both": t_b, "rotation_hidden_frac": hidden,
                    "ms_exposed": max(0.0, t_b - t_c),
-                   "staged_bytes": (4 * (n_ - 1) + 1) * W_ + n_ * G_, "g_out_fused": True,
-                   "g_out_bytes_stored_by_gemm_epilogues": (n_ - 1) * G_,
+                   "staged_bytes": (4 * (n_ - 1) + 1) * W_ + (n_ if fused else 2 * n_ - 1) * G_, "g_out_fused": fused,
+                   "g_out_bytes_stored_by_gemm_epilogues": (n_ - 1) * G_ if fused else 0,
                    "staging_only_run_bytes": (4 * (n_ - 1) + 1) * W_ + (2 * n_ - 1) * G_}
 
     cpu = None
     if not a.no_cpu_baseline:
-        cpu = cpu_baseline_moe(w, inp, a.cpu_tokens) if is_moe else cpu_baseline(w, inp, a.cpu_tokens)
+        cpu = (cpu_baseline_moe if is_moe else cpu_baseline_linears if is_lin else cpu_baseline)(w, inp, a.cpu_tokens)
+
+    # ---- each matrix of a multi-layer workload on its own: K passes of that layer alone -------------
+    per_matrix = None
+    if is_lin and len(mlp.layers) > 1:
+        per_matrix = {}
+        for (nm, layer, x, dy, y, dx) in mlp.layers:
+            one = LinearsUnit([(nm, layer, x, dy, y, dx)], torch)
+            timed(torch, one, None, None, None, None, 2)
+            ms_one = timed(torch, one, None, None, None, None, max(3, a.steps // 2)) / max(3, a.steps // 2)
+            fl = 6.0 * w.T * x.shape[1] * y.shape[1]
+            per_matrix[nm] = {"O": y.shape[1], "I": x.shape[1], "ms_per_pass": ms_one, "tflops": fl / (ms_one * 1e-3) / 1e12}
 
     hbm = None
-    if not is_moe:
+    if is_lin:
+        nbytes = algorithmic_bytes_linears(w, mlp)
+        hbm = {"algorithmic_bytes_per_step": nbytes, "achieved": nbytes / (ms_step * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+               "unit": "GB/s", "frac": nbytes / (ms_step * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    elif not is_moe:
         # staging: every copy reads and writes its bytes; per pass 2(n-1) weight rotations (out + in), one initial
         # load, and per backward rotation the gradient shard in (its way out is a GEMM's store, counted above)
         stg = 2 * (2 * (2 * (w.n - 1)) + 1) * mlp.w_bytes + 2 * (w.n - 1 + 1) * mlp.g_bytes
@@ -320,16 +444,17 @@ def main():
         "metric": "TFLOP/s rotated-shard linear fwd+bwd per GPU", "value": tflops, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step, "ms_per_step_median": passes[len(passes) // 2],
         "ms_per_step_min": passes[0], "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "T": w.T, "I": w.I, "O": w.O, "O2": w.O2, "n_shards": w.n, "mode": w.mode,
                    "grad_dtype": "f32", "flops_per_step": w.flops,
-                   "schedule": "expert rotation" if is_moe else a.schedule,
+                   "schedule": "expert rotation" if is_moe else "one launch per layer and step" if is_lin else a.schedule,
                    "aux_stream": not a.no_aux_stream, "stage_copy": a.stage_copy,
                    "worker_param_bytes": mlp.worker_bytes(),
                    "table1_rtp_worker_bytes": B.rtp_table1_worker_bytes(False, mlp.w_bytes, mlp.g_bytes)},
-        "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
+        "per_matrix": per_matrix,
+        "frac_of_bf16_mfma_peak": None if f32 else tflops / PEAK_BF16_TFLOPS,
         "sustained_clock_ghz": clock_ghz, "nominal_clock_ghz": 2.4,
-        "frac_of_peak_at_sustained_clock": tflops / (PEAK_BF16_TFLOPS * clock_ghz / 2.4) if clock_ghz > 0 else None,
+        "frac_of_peak_at_sustained_clock": tflops / (peak * clock_ghz / 2.4) if clock_ghz > 0 else None,
         "roofline": roofline, "hbm_algorithmic": hbm, "overlap": overlap, "cpu_baseline": cpu,
     }
     mlp.close()

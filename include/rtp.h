@@ -90,6 +90,12 @@ typedef enum { RTP_PASS_IDLE = 0, RTP_PASS_FWD = 1, RTP_PASS_BWD = 2 } rtp_pass;
                                 second linear's GEMMs forward; input gradients /
                                 weight gradients backward), shard parts moving as
                                 soon as their last reader is enqueued               */
+#define RTP_FLAG_FUSED_STEP 32u /* rtp_mlp_*: the dependent GEMMs of a rotation step as one
+                                launch (RTP Transformers section, linear-block item: the
+                                first GEMM, its activation and the second GEMM of the
+                                block): forward Z_t -> down_t, backward dPre_s -> dX_s; the
+                                second GEMM's tiles start as their rows of the first are
+                                done.  Needs rtp_mlp_desc.step_sync_dev                  */
 #define RTP_FLAG_STAGE_MEMCPY 16u /* shard transfers through hipMemcpyAsync (device to
                                 device) on the stage stream instead of the library's
                                 copy kernel: the runtime's own transfer path, for
@@ -265,6 +271,13 @@ rtp_status rtp_ring_sync(rtp_ring *ring);
 /* Shard currently resident (after everything enqueued so far), or -1. */
 int rtp_ring_resident(const rtp_ring *ring);
 
+/* Timing aid (the three-run measurement of how much of the staging hides
+ * under compute): `rotate` = 0 skips the transfers (every step computes on the
+ * shard that is resident: results are meaningless), `compute` = 0 skips the
+ * kernels of the ring's layers (the staging traffic alone).  Idle state only.
+ * rtp_mlp_set_ablation / rtp_moe_set_ablation do the same for a unit. */
+rtp_status rtp_ring_set_ablation(rtp_ring *ring, int rotate, int compute);
+
 /* Test aid for the cross-stream ordering.  From now on the ring enqueues a
  * bounded spin kernel (one wave that watches the wall clock for the given
  * number of microseconds, at most 5000, and exits) ahead of every transfer on
@@ -408,6 +421,9 @@ typedef struct {
     float *acc_dx_dev;    /* fp32 [T, I]                                           */
     void *compute_stream, *stage_stream;
     void *aux_stream;     /* optional, as in rtp_ring_desc                           */
+    void *step_sync_dev;  /* RTP_FLAG_FUSED_STEP only: rtp_mlp_step_sync_bytes() bytes of
+                             device memory for the per-row-block counters of a fused
+                             step (the library clears them when a pass begins)       */
     int has_bias;         /* every linear of the unit carries a bias: slot =
                              [W1_k | b1_k | W2_k | piece k of b2] (gated unit:
                              [gate_k ; up_k | bgate_k | bup_k | down_k | piece k of
@@ -426,6 +442,10 @@ typedef struct {
  * non-empty aligned shards. */
 int64_t rtp_mlp_hidden_width(const rtp_mlp_desc *d);
 
+/* Bytes of rtp_mlp_desc.step_sync_dev: one int32 per 64 tokens and an error
+ * word (rtp_mlp_sync returns RTP_ERR_HIP if a tile of a fused step ever gave
+ * up its bounded wait). */
+size_t rtp_mlp_step_sync_bytes(const rtp_mlp_desc *d);
 size_t rtp_mlp_slot_w_bytes(const rtp_mlp_desc *d);
 size_t rtp_mlp_slot_g_bytes(const rtp_mlp_desc *d);
 
@@ -541,7 +561,7 @@ const char *rtp_gemm_kernel_name(int layout, int variant);
 
 /* ---- per-launch timing of the bf16 GEMM kernels -------------------------- */
 
-/* Between rtp_prof_begin() and rtp_prof_end() every bf16 GEMM launch the
+/* Between rtp_prof_begin() and rtp_prof_end() every GEMM launch the
  * library makes (from any entry point) is bracketed by HIP events on the
  * stream it is launched on.  rtp_prof_end() waits for them and fills
  * out[layout] (0 NT, 1 NN, 2 TN) with the number of launches, the sum of

@@ -28,6 +28,7 @@ RTP_FLAG_STEPWISE = 2
 RTP_FLAG_GROUPED = 4
 RTP_FLAG_PIPELINED = 8
 RTP_FLAG_STAGE_MEMCPY = 16
+RTP_FLAG_FUSED_STEP = 32
 RTP_NOALLOC_ACC_BYTES = 16 << 20
 LAYOUT_NT, LAYOUT_NN, LAYOUT_TN = 0, 1, 2
 
@@ -58,7 +59,7 @@ class rtp_mlp_desc(C.Structure):
                 ("preact_dev", C.c_void_p), ("hidden_dev", C.c_void_p), ("dpre_dev", C.c_void_p),
                 ("acc_y_dev", C.c_void_p), ("acc_dx_dev", C.c_void_p),
                 ("compute_stream", C.c_void_p), ("stage_stream", C.c_void_p), ("aux_stream", C.c_void_p),
-                ("has_bias", C.c_int)]
+                ("step_sync_dev", C.c_void_p), ("has_bias", C.c_int)]
 
 
 class rtp_moe_desc(C.Structure):
@@ -107,6 +108,7 @@ SYMBOLS = {
     "rtp_ring_end": (C.c_int, [_P]),
     "rtp_ring_abort": (C.c_int, [_P]),
     "rtp_ring_set_test_delay": (C.c_int, [_P, _P, C.c_int64, C.c_int64]),
+    "rtp_ring_set_ablation": (C.c_int, [_P, C.c_int, C.c_int]),
     "rtp_ring_flush": (C.c_int, [_P]),
     "rtp_ring_zero_grads": (C.c_int, [_P]),
     "rtp_ring_sync": (C.c_int, [_P]),
@@ -118,6 +120,7 @@ SYMBOLS = {
     "rtp_linear_bwd": (C.c_int, [_P, C.c_int, _P, _P, _P]),
     "rtp_linear_fwd_noalloc": (C.c_int, [_P, C.c_int, _P, _P]),
     "rtp_mlp_hidden_width": (C.c_int64, [C.POINTER(rtp_mlp_desc)]),
+    "rtp_mlp_step_sync_bytes": (C.c_size_t, [C.POINTER(rtp_mlp_desc)]),
     "rtp_mlp_slot_w_bytes": (C.c_size_t, [C.POINTER(rtp_mlp_desc)]),
     "rtp_mlp_slot_g_bytes": (C.c_size_t, [C.POINTER(rtp_mlp_desc)]),
     "rtp_mlp_create": (C.c_int, [C.POINTER(_P), C.POINTER(rtp_mlp_desc)]),
@@ -246,6 +249,9 @@ class Ring:
 
     def abort(self):
         check(lib.rtp_ring_abort(self.handle), "rtp_ring_abort")
+
+    def set_ablation(self, rotate=True, compute=True):
+        check(lib.rtp_ring_set_ablation(self.handle, int(rotate), int(compute)), "rtp_ring_set_ablation")
 
     def flush(self):
         check(lib.rtp_ring_flush(self.handle), "rtp_ring_flush")

@@ -116,6 +116,28 @@ __device__ __forceinline__ void pp_tile(const GemmArgs &p, const int tiles_m, co
 
     const bool paired = (p.epi == EPI_SWIGLU_FWD);
     const int m0 = tm * BM;
+    const int sync_b0 = m0 / SYNC_ROWS, sync_b1 = (min(m0 + BM, p.M) + SYNC_ROWS - 1) / SYNC_ROWS; // row blocks of this tile
+
+    // ---- consumer of another problem of this launch: wait until its producer tiles are done.  The producer's
+    // workgroups precede this one in dispatch order, so they are running or finished; the wait is bounded all
+    // the same, and a tile that gives up says so in the error word instead of hanging the launch.
+    if (p.sync_wait > 0) {
+        if (tid == 0) {
+            const int blocks_total = (p.M + SYNC_ROWS - 1) / SYNC_ROWS;
+            for (int b = sync_b0; b < sync_b1; ++b) {
+                int spins = 0;
+                while (__hip_atomic_load(p.sync + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < p.sync_wait) {
+                    __builtin_amdgcn_s_sleep(8);
+                    if (++spins > (1 << 21)) {
+                        __hip_atomic_store(p.sync + blocks_total, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        break;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); // what the producers stored is read from memory, not from a stale line
+    }
     const int n0 = paired ? tn * (BN / 2) : tn * BN;
     const int M = p.M, N = p.N, K = p.K;
     const int half = p.half;
@@ -294,6 +316,14 @@ __device__ __forceinline__ void pp_tile(const GemmArgs &p, const int tiles_m, co
                                               m0 + wm * (BM / WM), n0, wn * 32, lane);
     else
         gemm_epilogue<E, FM, FN, WN * 32>(p, acc, m0 + wm * (BM / WM) + 4 * (lane >> 5), n0, wn * 32 + (lane & 31));
+
+    // ---- producer: the tile's results are visible device-wide before the counters say so
+    if (p.sync_signal) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        __syncthreads();
+        if (tid == 0)
+            for (int b = sync_b0; b < sync_b1; ++b) __hip_atomic_fetch_add(p.sync + b, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 // Workgroup ids are dealt round-robin to the 8 XCDs.  XCD x works through its own list: its

@@ -54,6 +54,8 @@ static int tiles_n_of(const GemmArgs &a)
     return (ncols + bn - 1) / bn;
 }
 
+int gemm_bf16_pp_tiles_n(const GemmArgs &a) { return tiles_n_of(a); }
+
 // ---- run-time estimate of a launch ------------------------------------------------------
 // Unit: one K sub-tile (32) of a 256 x 256 tile.  A tile costs its K loop plus its epilogue,
 // scaled by its height; the shorter tiles carry a small handicap because they move more
@@ -88,6 +90,7 @@ static double tile_cost(const GemmArgs &a, int bm, int ksplit)
 // GEMM of a narrow shard contracts over all T tokens into an output of a few tiles.
 static bool may_split_k(const GemmArgs &a)
 {
+    if (a.sync) return false; // the counters count whole tiles
     return a.epi == EPI_ACC_ADD && a.c_is_f32 && a.C == (void *)a.ws && a.ldc == a.ldws;
 }
 
@@ -135,7 +138,7 @@ static Plan plan_group(int layout, const GemmArgs *a, int count, const int *bm_o
     key.layout = layout; key.count = count; key.cu_share = cu_share;
     for (int q = 0; q < count; ++q) {
         const int forced = bm_override ? bm_override[q] : 0;
-        const int d[6] = {a[q].M, a[q].N, a[q].K, a[q].epi, forced, may_split_k(a[q]) ? 1 : 0};
+        const int d[6] = {a[q].M, a[q].N, a[q].K, a[q].epi + (a[q].sync ? 64 : 0), forced, may_split_k(a[q]) ? 1 : 0};
         memcpy(key.dims[q], d, sizeof d);
     }
     {
@@ -175,8 +178,11 @@ static Plan plan_group(int layout, const GemmArgs *a, int count, const int *bm_o
             ks[q] = oks[q][idx[q]];
             order[q] = q;
         }
-        std::stable_sort(order, order + count,
-                         [&](int i, int j) { return tile_cost(a[i], bm[i], ks[i]) > tile_cost(a[j], bm[j], ks[j]); });
+        bool ordered = false; // a producer / consumer pair keeps the order it was given in
+        for (int q = 0; q < count; ++q) ordered = ordered || a[q].sync != nullptr;
+        if (!ordered)
+            std::stable_sort(order, order + count,
+                             [&](int i, int j) { return tile_cost(a[i], bm[i], ks[i]) > tile_cost(a[j], bm[j], ks[j]); });
         const double t = makespan(a, bm, ks, order, count, cus_per_xcd);
         if (t < best - 1e-9) {
             best = t;

@@ -444,6 +444,12 @@ extern "C" rtp_status rtp_ring_set_test_delay(rtp_ring *r, void *scratch32_dev, 
     return RTP_OK;
 }
 
+extern "C" rtp_status rtp_ring_set_ablation(rtp_ring *r, int rotate, int compute)
+{
+    if (!r) return fail(RTP_ERR_INVALID, "rtp_ring_set_ablation: null ring");
+    return set_ablation(r, rotate, compute);
+}
+
 extern "C" rtp_status rtp_ring_begin(rtp_ring *r, rtp_pass pass)
 {
     if (!r) return fail(RTP_ERR_INVALID, "rtp_ring_begin: null ring");
@@ -839,7 +845,7 @@ static rtp_status gemm(rtp_linear *l, int layout, GemmArgs &a, hipStream_t st)
         a.elem = l->d.dtype == RTP_F16 ? ELEM_F16 : ELEM_BF16;
         HIP_TRY(timed_launch(layout, 2.0 * a.M * a.N * a.K, st, [&] { return launch_gemm_bf16(layout, a, 0, st); }));
     } else {
-        HIP_TRY(launch_gemm_f32(layout, a, st));
+        HIP_TRY(timed_launch(layout, 2.0 * a.M * a.N * a.K, st, [&] { return launch_gemm_f32(layout, a, st); }));
     }
     return RTP_OK;
 }
@@ -1633,6 +1639,103 @@ static rtp_status mlp_bwd_grouped(rtp_mlp *m, const void *X, const void *dY, voi
     return rtp_ring_end(r);
 }
 
+// ---- fused step: the unit's dependent GEMMs of a rotation step as ONE launch ---------------------
+// Forward, Z_t = act(X W1_t^T) and down_t = H_t W2_t^T of the SAME step go out as one launch of the
+// tiled kernel: the tiles of down_t follow those of Z_t in the grid and each starts as soon as the Z
+// tiles of its rows are done (a counter per 64 rows in device memory), so the hidden activations
+// are read back while they are still in the cache they were written through, and a step is one
+// kernel.  (They are still stored: the backward pass needs them.  Keeping them in LDS instead
+// would need a workgroup to own all `o` columns of its rows: 64-row tiles at most, a quarter of the
+// operand reuse of the 256-row tile.)  Backward the same holds for dPre_s -> dX_s; the weight
+// gradients stay two launches on the auxiliary stream.  Rotation, buffers, events: the step-by-step
+// schedule's, in all three modes.
+static size_t mlp_sync_words(const rtp_mlp_desc *d)
+{
+    const size_t blocks = ((size_t)std::max<int64_t>(d->T, 0) + SYNC_ROWS - 1) / SYNC_ROWS;
+    return (blocks + 1 + 3) / 4 * 4; // one counter per row block, the error word, whole 16-byte units
+}
+
+extern "C" size_t rtp_mlp_step_sync_bytes(const rtp_mlp_desc *d) { return d ? mlp_sync_words(d) * sizeof(int) : 0; }
+
+static bool mlp_fused_ok(const rtp_mlp *m, const void *X, const void *Y, const void *dY, const void *dX)
+{
+    if (!(m->d.flags & RTP_FLAG_FUSED_STEP) || !m->d.step_sync_dev) return false;
+    // same shape rules as the grouped launches (16-bit inputs, every GEMM within the tiled kernel's reach);
+    // the blocking mode is fine here: the rotation is the step-by-step schedule's
+    const rtp_ring *r = m->ring;
+    if (r->dry || m->d.dtype == RTP_F32 || m->d.T <= 0) return false;
+    const MlpShapes h = mlp_shapes(m);
+    const char *W = (const char *)r->d.buf_w_dev[0];
+    const void *x = X ? X : m->d.hidden_dev, *dy = dY ? dY : m->d.hidden_dev;
+    void *y = Y ? (void *)Y : m->d.hidden_dev, *dx = dX ? (void *)dX : m->d.hidden_dev;
+    const GemmArgs nt[2] = {mlp_args_z(m, h, 0, x, W), mlp_args_down(m, h, 0, 0, W, y)};
+    const GemmArgs nn[2] = {mlp_args_dh(m, h, 0, W, dy), mlp_args_dx(m, h, 0, 0, W, dx)};
+    for (int i = 0; i < 2; ++i) {
+        if (!gemm_bf16_args_ok(LAY_NT, nt[i]) || !gemm_bf16_pp_supported(LAY_NT, nt[i])) return false;
+        if (!gemm_bf16_args_ok(LAY_NN, nn[i]) || !gemm_bf16_pp_supported(LAY_NN, nn[i])) return false;
+    }
+    return true;
+}
+
+static rtp_status mlp_sync_reset(rtp_mlp *m)
+{
+    rtp_ring *r = m->ring;
+    if (r->dry || !r->abl_compute) return RTP_OK;
+    HIP_TRY(launch_fill_zero(m->d.step_sync_dev, mlp_sync_words(&m->d) * sizeof(int), r->cs()));
+    return RTP_OK;
+}
+
+static rtp_status mlp_fwd_fused(rtp_mlp *m, const void *X, void *Y)
+{
+    rtp_ring *r = m->ring;
+    const int n = r->d.n;
+    const MlpShapes h = mlp_shapes(m);
+    RTP_TRY(rtp_ring_begin(r, RTP_PASS_FWD));
+    RTP_TRY(mlp_sync_reset(m));
+    for (int t = 0; t < n; ++t) {
+        if (t < n - 1) RTP_TRY(rtp_rotate_step(r, RTP_CW, t));
+        RTP_TRY(enter_step(r, t, t, RTP_PASS_FWD, "rtp_mlp_fwd"));
+        const int k = r->abl_rotate ? r->resident : rtp_fwd_shard(r->d.rank, t, n);
+        const char *W = (const char *)r->d.buf_w_dev[r->res_idx];
+        r->rec(TR_FWD, t, k, r->res_idx);
+        GemmArgs g[2] = {mlp_args_z(m, h, k, X, W), mlp_args_down(m, h, k, t, W, Y)};
+        g[0].sync = g[1].sync = (int *)m->d.step_sync_dev;
+        g[0].sync_signal = 1;
+        g[1].sync_wait = (t + 1) * gemm_bf16_pp_tiles_n(g[0]); // every Z tile of the rows, of this and the earlier steps
+        if (t >= 1) RTP_TRY(mlp_bias2_add(m, h, k, W, r->cs()));
+        RTP_TRY(gemm_group(r, LAY_NT, g, 2, r->cs()));
+        if (t == 0) RTP_TRY(mlp_bias2_add(m, h, k, W, r->cs()));
+        m->l1->next_step = m->l2->next_step = t + 1;
+    }
+    return rtp_ring_end(r);
+}
+
+static rtp_status mlp_bwd_fused(rtp_mlp *m, const void *X, const void *dY, void *dX)
+{
+    rtp_ring *r = m->ring;
+    const int n = r->d.n;
+    const MlpShapes h = mlp_shapes(m);
+    RTP_TRY(rtp_ring_begin(r, RTP_PASS_BWD));
+    RTP_TRY(mlp_sync_reset(m));
+    for (int s = 0; s < n; ++s) {
+        if (s < n - 1) RTP_TRY(rtp_rotate_step(r, RTP_CCW, s));
+        // the second linear's weight gradient (auxiliary stream, gradient part handed on), no input gradient yet
+        RTP_TRY(rtp_linear_bwd(m->l2, s, m->d.hidden_dev, dY, nullptr));
+        // dPre_s and dX_s as one launch: the tiles of dX_s wait for the dPre tiles of their rows
+        const int k = r->abl_rotate ? r->resident : rtp_bwd_shard(r->d.rank, s, n);
+        const char *W = (const char *)r->d.buf_w_dev[r->res_idx];
+        GemmArgs g[2] = {mlp_args_dh(m, h, k, W, dY), mlp_args_dx(m, h, k, s, W, dX)};
+        g[0].sync = g[1].sync = (int *)m->d.step_sync_dev;
+        g[0].sync_signal = 1;
+        g[1].sync_wait = (s + 1) * gemm_bf16_pp_tiles_n(g[0]);
+        g[0].cu_share = g[1].cu_share = r->as() != r->cs() ? 2 : 1;
+        RTP_TRY(gemm_group(r, LAY_NN, g, 2, r->cs()));
+        // the first linear's weight gradient needs dPre_s: ordered after the launch above
+        RTP_TRY(rtp_linear_bwd(m->l1, s, X, m->d.dpre_dev, nullptr));
+    }
+    return rtp_ring_end(r);
+}
+
 // ---- pipelined schedule of the MLP unit (two compute streams) ---------------------------
 // The unit's GEMMs form two chains that only touch through data: forward, Z_t = act(X W1_t^T) on
 // the compute stream and down_t = H_t W2_t^T on the auxiliary stream (down_t needs Z_t, nothing
@@ -1833,6 +1936,7 @@ static rtp_status mlp_bwd_pipelined(rtp_mlp *m, const void *X, const void *dY, v
 static rtp_status mlp_fwd_pass(rtp_mlp *m, const void *X, void *Y)
 {
     const bool have_aux = m->ring->as() != m->ring->cs();
+    if (mlp_fused_ok(m, X, Y, nullptr, nullptr)) return mlp_fwd_fused(m, X, Y);
     if (mlp_grouped_ok(m, X, Y, nullptr, nullptr))
         return have_aux && (m->d.flags & RTP_FLAG_PIPELINED) ? mlp_fwd_pipelined(m, X, Y) : mlp_fwd_grouped(m, X, Y);
     const int n = m->d.n;
@@ -1852,6 +1956,7 @@ static rtp_status mlp_bwd_pass(rtp_mlp *m, const void *X, const void *dY, void *
     // launches per step 3.4-3.5; without one the grouped launches win (3.5 against 3.7).  Whatever the schedule,
     // the kernels of a pass need ~4.26 ms of a machine that is busy throughout: see the design doc's schedule table.
     const bool have_aux = m->ring->as() != m->ring->cs();
+    if (dX && mlp_fused_ok(m, X, nullptr, dY, dX)) return mlp_bwd_fused(m, X, dY, dX);
     if (dX && mlp_grouped_ok(m, X, nullptr, dY, dX)) {
         if (have_aux && (m->d.flags & RTP_FLAG_PIPELINED)) return mlp_bwd_pipelined(m, X, dY, dX);
         if (!have_aux || (m->d.flags & RTP_FLAG_GROUPED)) return mlp_bwd_grouped(m, X, dY, dX);
@@ -1884,7 +1989,20 @@ extern "C" rtp_status rtp_mlp_bwd(rtp_mlp *m, const void *X, const void *dY, voi
 }
 
 extern "C" rtp_status rtp_mlp_flush(rtp_mlp *m) { return m ? rtp_ring_flush(m->ring) : fail(RTP_ERR_INVALID, "null mlp"); }
-extern "C" rtp_status rtp_mlp_sync(rtp_mlp *m) { return m ? rtp_ring_sync(m->ring) : fail(RTP_ERR_INVALID, "null mlp"); }
+extern "C" rtp_status rtp_mlp_sync(rtp_mlp *m)
+{
+    if (!m) return fail(RTP_ERR_INVALID, "null mlp");
+    RTP_TRY(rtp_ring_sync(m->ring));
+    if ((m->d.flags & RTP_FLAG_FUSED_STEP) && m->d.step_sync_dev && !m->ring->dry) {
+        // a consumer tile that gave up waiting for its producers has raised the word after the counters
+        const size_t blocks = ((size_t)m->d.T + SYNC_ROWS - 1) / SYNC_ROWS;
+        int flag = 0;
+        HIP_TRY(hipMemcpy(&flag, (const int *)m->d.step_sync_dev + blocks, sizeof flag, hipMemcpyDeviceToHost));
+        if (flag) return fail(RTP_ERR_HIP, "rtp_mlp_sync: a tile of a fused step gave up waiting for the tiles it depends on; "
+                                            "the results of that pass are not valid");
+    }
+    return RTP_OK;
+}
 
 // ---------------------------------------------------------------------------
 // expert partition: the ring's shard is one whole expert

@@ -42,7 +42,16 @@ struct GemmArgs {
     int elem;           // ELEM_BF16 or ELEM_F16 (the ping-pong kernel only; the register-staged one is bf16)
     int cu_share;       // > 1: this launch runs beside cu_share - 1 others of similar size, so the
                         // tile height is picked for 1/cu_share of the compute units (0, 1: all)
+    // Producer / consumer GEMMs inside one group launch of the tiled kernel (a rotation step as one launch):
+    // `sync` points at one int32 counter per SYNC_ROWS rows of M, followed by one error word.  A tile of a
+    // problem with sync_signal != 0 adds 1 to the counter of every row block it covers once its results are
+    // visible device-wide; a tile of a problem with sync_wait > 0 starts only when the counter of every row
+    // block it covers has reached sync_wait (a bounded wait: on giving up it raises the error word and
+    // goes on).  The consumer must follow its producer in the group (the launcher keeps the given order).
+    int *sync;
+    int sync_signal, sync_wait;
 };
+constexpr int SYNC_ROWS = 64;
 
 // bf16 inputs, fp32 MFMA accumulation.  variant: 0 = pick by shape; 1, 2, 3 = register-staged
 // tiles (256x256/8 waves, 128x128/4 waves, 256x256/4 waves); 4 = the ping-pong kernel with the
@@ -61,6 +70,8 @@ constexpr int PP_MAX_GROUP = 4;
 hipError_t launch_gemm_bf16_pp_group(int layout, const GemmArgs *a, int count, const int *bm_override, hipStream_t s);
 // the tile heights and K splits that launch would use (either output may be null)
 void gemm_bf16_pp_plan(int layout, const GemmArgs *a, int count, const int *bm_override, int *bm_out, int *ksplit_out);
+// column tiles the tiled kernel cuts a problem into (what a producer problem adds to each row block's counter)
+int gemm_bf16_pp_tiles_n(const GemmArgs &a);
 const char *gemm_bf16_kernel_name(int layout, int variant);
 
 // fp32 inputs and outputs (epi: EPI_STORE, EPI_ACC_ADD with ws == C).

@@ -121,6 +121,12 @@ class RtpLinear(_PassStreams):
     def sync(self):
         self.ring.sync()
 
+    def set_ablation(self, rotate=True, compute=True):
+        self.ring.set_ablation(rotate, compute)
+
+    def worker_bytes(self):
+        return B.rtp_worker_bytes(self.mode, self.ring.desc.w_bytes, self.ring.desc.g_bytes)
+
     def zero_grads(self):
         self.ring.zero_grads()
 
@@ -147,7 +153,7 @@ class RtpMlp(_PassStreams):
     by rtp_mlp_fwd / rtp_mlp_bwd: one library call per pass."""
 
     def __init__(self, weights, T, n, rank, act, mode=B.RTP_INPLACE_STAGED, dtype=B.RTP_BF16, G0=None,
-                 device="cuda:0", aux_stream=True, stepwise=False, biases=None, gb0=None, grouped=False, pipelined=False, stage_memcpy=False):
+                 device="cuda:0", aux_stream=True, stepwise=False, biases=None, gb0=None, grouped=False, pipelined=False, stage_memcpy=False, fused=False):
         self.dev = torch.device(device)
         td = _TORCH_DT[dtype]
         self.n, self.rank, self.T, self.act, self.mode, self.dtype = n, rank, T, act, mode, dtype
@@ -162,7 +168,8 @@ class RtpMlp(_PassStreams):
         d.T, d.I, d.O, d.O2 = T, self.I, self.O, self.O2
         d.n, d.rank, d.mode, d.dtype, d.act = n, rank, mode, dtype, act
         d.flags = ((B.RTP_FLAG_STEPWISE if stepwise else 0) | (B.RTP_FLAG_GROUPED if grouped else 0) |
-                   (B.RTP_FLAG_PIPELINED if pipelined else 0) | (B.RTP_FLAG_STAGE_MEMCPY if stage_memcpy else 0))
+                   (B.RTP_FLAG_PIPELINED if pipelined else 0) | (B.RTP_FLAG_STAGE_MEMCPY if stage_memcpy else 0) |
+                   (B.RTP_FLAG_FUSED_STEP if fused else 0))
         d.has_bias = int(self.has_bias)
         wb, gb = B.lib.rtp_mlp_slot_w_bytes(C.byref(d)), B.lib.rtp_mlp_slot_g_bytes(C.byref(d))
         if wb == 0 or gb == 0:
@@ -212,6 +219,8 @@ class RtpMlp(_PassStreams):
         d.compute_stream, d.stage_stream = B._stream(self.compute_stream), B._stream(self.stage_stream)
         self.aux_stream = torch.cuda.Stream(self.dev) if aux_stream else None
         d.aux_stream = B._stream(self.aux_stream)
+        self.step_sync = torch.zeros(B.lib.rtp_mlp_step_sync_bytes(C.byref(d)), dtype=torch.uint8, device=self.dev) if fused else None
+        d.step_sync_dev = B._ptr(self.step_sync)
         self.desc = d
         self.handle = C.c_void_p()
         B.check(B.lib.rtp_mlp_create(C.byref(self.handle), C.byref(d)), "rtp_mlp_create")

@@ -149,14 +149,14 @@ def _mlp_fullsize(name, n_tokens, n_extra_units, rank=0, **schedule):
 
 
 @pytest.mark.parametrize("rank,schedule", [(0, {}), (5, dict(pipelined=True)), (3, dict(grouped=True)), (7, dict(stepwise=True)),
-                                           (2, dict(aux_stream=False))])
+                                           (2, dict(aux_stream=False)), (6, dict(fused=True))])
 def test_cfg4_llama7b_swiglu_fullsize(rank, schedule):
     """The headline configuration, in the launch configuration bench.py times (rank 0, default schedule) and, on other
     ranks, in every other launch schedule."""
     _mlp_fullsize("cfg4_llama7b_swiglu", n_tokens=32, n_extra_units=10, rank=rank, **schedule)
 
 
-@pytest.mark.parametrize("rank,schedule", [(3, {}), (6, dict(pipelined=True)), (0, dict(stepwise=True))])
+@pytest.mark.parametrize("rank,schedule", [(3, {}), (6, dict(pipelined=True)), (0, dict(stepwise=True)), (5, dict(fused=True))])
 def test_cfg2_gpt2_small_mlp_fullsize(rank, schedule):
     _mlp_fullsize("cfg2_gpt2s_mlp", n_tokens=64, n_extra_units=16, rank=rank, **schedule)
 

@@ -87,18 +87,19 @@ def test_linear_layer_with_poisoned_buffers_and_late_streams(split, mode, stage_
 
 
 @pytest.mark.parametrize("stage_us,aux_us", DELAYS)
-@pytest.mark.parametrize("schedule", ["default", "pipelined", "grouped", "stepwise"])
+@pytest.mark.parametrize("schedule", ["default", "pipelined", "grouped", "stepwise", "fused"])
 @pytest.mark.parametrize("mode", MODES)
 def test_mlp_unit_with_poisoned_buffers_and_late_streams(mode, schedule, stage_us, aux_us):
-    if mode == B.RTP_INPLACE_BLOCKING and schedule != "stepwise":
-        pytest.skip("the blocking mode has one schedule")
+    if mode == B.RTP_INPLACE_BLOCKING and schedule not in ("stepwise", "fused"):
+        pytest.skip("the blocking mode runs step by step (plain or fused)")
     T, I, O, O2, n, rank = 288, 160, 4 * 128, 96, 4, 3
     w = wl.Workload("hz_mlp", "swiglu", T=T, I=I, O=O, O2=O2, n=n, dtype="bf16", mode="x", w_dist=("normal", 0.08))
     inp = wl.make_inputs(w, seed=72, grad0=True)
     names = ("Wg", "Wu", "Wd")
     ref = orc.rtp_swiglu(f64(inp["X"]), *[f64(inp[k]) for k in names], f64(inp["dY"]), n, rank,
                          *[f64(inp["G0_" + k]) for k in names])
-    sched = dict(stepwise=schedule == "stepwise", grouped=schedule == "grouped", pipelined=schedule == "pipelined")
+    sched = dict(stepwise=schedule == "stepwise", grouped=schedule == "grouped", pipelined=schedule == "pipelined",
+                 fused=schedule == "fused")
     mlp = RtpMlp([dev(inp[k]) for k in names], T, n, rank, B.RTP_ACT_SWIGLU, mode, B.RTP_BF16,
                  G0=[dev(inp["G0_" + k], torch.float32) for k in names], **sched)
     scratch = torch.zeros(4, dtype=torch.int64, device=DEV)

@@ -486,10 +486,10 @@ def _schedule(name):
     weight gradients on the auxiliary stream; grouped_one_stream: the same on one compute stream; stepwise*: one
     launch per linear and step."""
     return dict(stepwise=name.startswith("stepwise"), grouped=name.startswith("grouped"),
-                pipelined=name == "pipelined", aux_stream=not name.endswith("one_stream"))
+                pipelined=name == "pipelined", fused=name.startswith("fused"), aux_stream=not name.endswith("one_stream"))
 
 
-SCHEDULES = ["default", "pipelined", "grouped", "grouped_one_stream", "stepwise", "stepwise_one_stream"]
+SCHEDULES = ["default", "pipelined", "grouped", "grouped_one_stream", "stepwise", "stepwise_one_stream", "fused", "fused_one_stream"]
 
 
 def _mlp_case(w: wl.Workload, rank, mode, seed=0, grad0=True, **schedule):
@@ -558,7 +558,7 @@ def test_mlp_unit_grouped_launches(kind, n, mode, schedule):
             assert relerr(out[key], ref[key]) <= TOL_BF16, (key, relerr(out[key], ref[key]))
 
 
-@pytest.mark.parametrize("schedule", ["default", "pipelined", "grouped_one_stream", "stepwise"])
+@pytest.mark.parametrize("schedule", ["default", "pipelined", "grouped_one_stream", "stepwise", "fused"])
 @pytest.mark.parametrize("kind", ["mlp_gelu", "swiglu"])
 def test_mlp_unit_fp16(kind, schedule):
     w = wl.Workload("mlp_f16", kind, T=288, I=160, O=4 * 128, O2=96, n=4, dtype="f16", mode="x", w_dist=("normal", 0.08))
@@ -580,7 +580,7 @@ def test_mlp_grouped_and_stepwise_agree_bitwise_on_integers():
     Ws = [ints(inp[k].shape) for k in ("Wg", "Wu", "Wd")]
     X, dY = ints(inp["X"].shape), ints(inp["dY"].shape)
     res = []
-    for sched in ("grouped_one_stream", "default", "pipelined", "grouped", "stepwise"):
+    for sched in ("grouped_one_stream", "default", "pipelined", "grouped", "stepwise", "fused"):
         mlp = RtpMlp([dev(a, torch.bfloat16) for a in Ws], w.T, w.n, 1, B.RTP_ACT_SWIGLU, B.RTP_INPLACE_STAGED, B.RTP_BF16,
                      **_schedule(sched))
         Y = torch.empty(w.T, w.O2, device=DEV, dtype=torch.bfloat16)
@@ -600,7 +600,7 @@ def test_mlp_grouped_and_stepwise_agree_bitwise_on_integers():
             assert torch.equal(a, b)
 
 
-@pytest.mark.parametrize("schedule", ["default", "pipelined", "grouped", "grouped_one_stream", "stepwise"])
+@pytest.mark.parametrize("schedule", ["default", "pipelined", "grouped", "grouped_one_stream", "stepwise", "fused"])
 def test_mlp_gradients_accumulate_over_passes(schedule):
     """Two passes of the unit without reading the store in between add the pass's weight gradients twice
     onto what arrived (all shards, the one the worker ends on included): G = G0 + 2 dW, with dW the oracle's."""
@@ -678,7 +678,7 @@ def test_mlp_unit_with_biases(dtype, act, mode):
         mlp.close()
 
 
-@pytest.mark.parametrize("schedule", ["default", "pipelined", "grouped", "grouped_one_stream", "stepwise"])
+@pytest.mark.parametrize("schedule", ["default", "pipelined", "grouped", "grouped_one_stream", "stepwise", "fused"])
 @pytest.mark.parametrize("gated", [False, True])
 def test_mlp_unit_with_biases_in_every_schedule(gated, schedule):
     """Biases of the unit's linears (for the gated unit: gate, up and down) in every launch schedule, shapes the
@@ -692,7 +692,7 @@ def test_mlp_unit_with_biases_in_every_schedule(gated, schedule):
     sizes = [O] * (len(names) - 1) + [O2]
     bs = [wl._store(rng.standard_normal(sz).astype(np.float32) * 0.3, "bf16") for sz in sizes]
     gbs = [rng.standard_normal(sz).astype(np.float32) for sz in sizes]
-    for mode in (B.RTP_INPLACE_STAGED, B.RTP_DOUBLE_BUFFER):
+    for mode in (B.RTP_INPLACE_STAGED, B.RTP_DOUBLE_BUFFER) + ((B.RTP_INPLACE_BLOCKING,) if schedule == "fused" else ()):
         rank = 2
         say(f"biased mlp gated={gated} schedule={schedule} mode={mode}")
         if gated:
@@ -726,7 +726,7 @@ def test_mlp_unit_with_biases_in_every_schedule(gated, schedule):
         mlp.close()
 
 
-@pytest.mark.parametrize("schedule", ["default", "pipelined", "stepwise"])
+@pytest.mark.parametrize("schedule", ["default", "pipelined", "stepwise", "fused"])
 @pytest.mark.parametrize("kind,dtype,O,n", [("mlp_gelu", "bf16", 232, 6), ("swiglu", "bf16", 232, 6), ("swiglu", "f16", 736, 6),
                                             ("mlp_gelu", "f32", 50, 4), ("swiglu", "f32", 50, 4)])
 def test_mlp_unit_with_a_padded_partition(kind, dtype, O, n, schedule):
