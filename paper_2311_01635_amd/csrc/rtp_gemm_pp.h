@@ -100,7 +100,10 @@ __device__ __forceinline__ void pp_tile(const GemmArgs &p, const int tiles_m, co
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    // the wave index as a scalar: everything derived from it (LDS destinations of the direct loads, hence the
+    // M0 values; which pieces a wave fetches) then stays in scalar registers instead of costing vector
+    // instructions and readfirstlanes in the loop
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
     const int group = wave >> 2; // waves 0-3 and 4-7 sit on SIMDs 0-3 respectively
 
@@ -187,9 +190,11 @@ __device__ __forceinline__ void pp_tile(const GemmArgs &p, const int tiles_m, co
             ob[i] = (unsigned)(((int64_t)kr * p.ldb + b_col(c * 8)) * 2);
         }
     }
-    // byte ranges of the operands (the launcher has checked that they stay below 2^31)
-    const unsigned a_bytes = (unsigned)(((int64_t)((A_KC ? M : K) - 1) * p.lda + (A_KC ? K : M)) * 2);
-    const unsigned b_bytes = (unsigned)(((int64_t)((B_KC ? N : K) - 1) * p.ldb + (B_KC ? K : N)) * 2);
+    // byte ranges of the operands (the launcher has checked that they stay below 2^31: 32-bit scalar arithmetic,
+    // so that the descriptors live in scalar registers; a 64-bit product would be computed on the vector unit and
+    // every load would then run inside a loop that re-reads the descriptor lane by lane)
+    const unsigned a_bytes = __builtin_amdgcn_readfirstlane(((unsigned)((A_KC ? M : K) - 1) * (unsigned)p.lda + (unsigned)(A_KC ? K : M)) * 2u);
+    const unsigned b_bytes = __builtin_amdgcn_readfirstlane(((unsigned)((B_KC ? N : K) - 1) * (unsigned)p.ldb + (unsigned)(B_KC ? K : N)) * 2u);
     const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc((void *)p.A, 0, a_bytes, BUFFER_RSRC_FLAGS);
     const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc((void *)p.B, 0, b_bytes, BUFFER_RSRC_FLAGS);
     const int stepA = A_KC ? BK * 2 : (int)(BK * p.lda * 2);
