@@ -78,6 +78,30 @@ struct PpGroup {
     PpProblem p[PP_MAX_GROUP];
 };
 
+// The transposing fragment read, issued as an instruction of our own.  Through the builtin the compiler puts a
+// wait for ALL outstanding direct loads in front of these reads (it cannot tell that the LDS stage being read is
+// not the one a load in flight is writing), which empties the ring of sub-tiles in flight at every slot; the slot
+// ends with an explicit wait for the stage that is read next, and that wait is the one that is needed.
+// addr: LDS byte address; OFF: immediate byte offset.
+template <int OFF> __device__ __forceinline__ s16x4 ds_read_tr16_b64(unsigned addr)
+{
+    s16x4 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+// 8 consecutive k (sub-tile half KS) of one column of an M- or N-contiguous stage with K-rows of ROWB bytes:
+// two transposing reads of 4 K-rows x 16 columns (K-rows 16*KS + 8*(lane/32) + 0..3 and + 4..7)
+template <typename V8, int KS, int ROWB> __device__ __forceinline__ V8 frag_mc_read(unsigned addr)
+{
+    union {
+        s16x4 h[2];
+        V8 v;
+    } u;
+    u.h[0] = ds_read_tr16_b64<KS * 16 * ROWB>(addr);
+    u.h[1] = ds_read_tr16_b64<KS * 16 * ROWB + 4 * ROWB>(addr);
+    return u.v;
+}
+
 // One BM x 256 tile over the K sub-tiles [kt_begin, kt_begin + kt_count): `pid` is the tile's index inside its
 // problem, `smem` the workgroup's LDS.
 template <int LAY, int BM, typename E>
@@ -252,20 +276,15 @@ __device__ __forceinline__ void pp_tile(const GemmArgs &p, const int tiles_m, co
     }
     // 8 consecutive k of one row (K-contiguous stage) ...
     auto frag_kc = [](const char *opnd, int off, int ks) { return *(const frag8 *)(opnd + (off ^ (ks << 5))); };
-    // ... or the same 8 k of one column through two transposing reads of 4 K-rows x 16 columns
-    // (K-rows 16*ks + 8*(lane/32) + 0..3 and + 4..7: the row index changes by multiples of 4, so
-    // the chunk permutation of the lane's row stays the one a_off / b_off were built with)
-    auto frag_mc = [](const char *opnd, int off, int ks, int rowb) {
-        typedef s16x4 __attribute__((address_space(3))) * lp;
-        const char *q = opnd + off + ks * 16 * rowb;
-        union {
-            s16x4 h[2];
-            frag8 v;
-        } u;
-        u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(q));
-        u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(q + 4 * rowb));
-        return u.v;
-    };
+    // ... or the same 8 k of one column through two transposing reads (frag_mc_read): the row index changes by
+    // multiples of 4 between them, so the chunk permutation of the lane's row stays the one a_off / b_off were built with
+    auto lds_addr = [](const char *q) { return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const char *)q; };
+    const unsigned smem_lds = lds_addr(smem); // the ring's LDS address, folded into the transposing reads' lane addresses once
+    unsigned a_tr[FM], b_tr[FN];
+#pragma unroll
+    for (int f = 0; f < FM; ++f) a_tr[f] = smem_lds + (unsigned)a_off[f];
+#pragma unroll
+    for (int f = 0; f < FN; ++f) b_tr[f] = smem_lds + (unsigned)(A_BYTES + b_off[f]);
 
     f32x16 acc[FM][FN];
 #pragma unroll
@@ -285,14 +304,28 @@ __device__ __forceinline__ void pp_tile(const GemmArgs &p, const int tiles_m, co
     frag8 af[2][FM], bf[2][FN];
     for (int kt = 0; kt < KT; ++kt) {
         // ---- memory slot ------------------------------------------------------------------
-        const char *sa = smem + (kt % STAGES) * STAGE;
+        const unsigned stage_off = (unsigned)((kt % STAGES) * STAGE);
+        const char *sa = smem + stage_off;
         const char *sb = sa + A_BYTES;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int f = 0; f < FM; ++f) {
+            if (A_KC) {
+                af[0][f] = frag_kc(sa, a_off[f], 0);
+                af[1][f] = frag_kc(sa, a_off[f], 1);
+            } else {
+                af[0][f] = frag_mc_read<frag8, 0, A_ROWB>(a_tr[f] + stage_off);
+                af[1][f] = frag_mc_read<frag8, 1, A_ROWB>(a_tr[f] + stage_off);
+            }
+        }
 #pragma unroll
-            for (int f = 0; f < FM; ++f) af[ks][f] = A_KC ? frag_kc(sa, a_off[f], ks) : frag_mc(sa, a_off[f], ks, A_ROWB);
-#pragma unroll
-            for (int f = 0; f < FN; ++f) bf[ks][f] = B_KC ? frag_kc(sb, b_off[f], ks) : frag_mc(sb, b_off[f], ks, 512);
+        for (int f = 0; f < FN; ++f) {
+            if (B_KC) {
+                bf[0][f] = frag_kc(sb, b_off[f], 0);
+                bf[1][f] = frag_kc(sb, b_off[f], 1);
+            } else {
+                bf[0][f] = frag_mc_read<frag8, 0, 512>(b_tr[f] + stage_off);
+                bf[1][f] = frag_mc_read<frag8, 1, 512>(b_tr[f] + stage_off);
+            }
         }
         issue(kt + PF);
         // own loads of sub-tile kt+1 have landed, fragments are in registers
