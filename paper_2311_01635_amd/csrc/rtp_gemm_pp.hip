@@ -183,7 +183,12 @@ static Plan plan_group(int layout, const GemmArgs *a, int count, const int *bm_o
         if (!ordered)
             std::stable_sort(order, order + count,
                              [&](int i, int j) { return tile_cost(a[i], bm[i], ks[i]) > tile_cost(a[j], bm[j], ks[j]); });
-        const double t = makespan(a, bm, ks, order, count, cus_per_xcd);
+        // A launch that shares the machine (cu_share > 1) seldom gets exactly its share: its partner on the other
+        // stream may be a GEMM of a hundred tiles, or done already.  The estimate is the mean of the two ends, its
+        // share of the compute units and all of them, which is what the in-situ sweeps of the tile heights favour
+        // (a 96-tile GEMM planned for half the machine kept its 256-high tiles and left compute units idle).
+        double t = makespan(a, bm, ks, order, count, cus_per_xcd);
+        if (cu_share > 1) t = 0.5 * (t + makespan(a, bm, ks, order, count, std::max(1, compute_units() / 8)));
         if (t < best - 1e-9) {
             best = t;
             for (int q = 0; q < count; ++q) {
