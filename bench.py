@@ -257,7 +257,9 @@ def algorithmic_bytes_linears(w, unit):
         sums = (2 * (n - 1)) * T * I * 4 + T * I * a
         total += n * (fwd + bwd) + sums
     out_copied = w.dtype == "f32"              # the fp32 path copies the gradient shard out; the bf16 kernels store it home
-    stg = 2 * ((4 * (n - 1) + 1) * unit.w_bytes + (n + (n - 1 if out_copied else 0)) * unit.g_bytes)
+    # gradient shard: n copies in, one copy out (the shard the pass ends on goes back to its slot when the next
+    # backward pass begins), and n - 1 more out where the weight-gradient kernels do not store it home themselves
+    stg = 2 * ((4 * (n - 1) + 1) * unit.w_bytes + (n + 1 + (n - 1 if out_copied else 0)) * unit.g_bytes)
     return total + stg
 
 
@@ -402,16 +404,17 @@ def main():
         hidden = 1.0 - max(0.0, t_b - t_c) / t_s if t_s > 0 else None
         # what the fraction covers: the copies on the stage stream.  Per pass the weights make 2(n-1) rotations (each
         # a copy out to the slot the shard travels to and a copy in from the slot it arrives in) after one initial
-        # load; the gradient shard comes in n times (n-1 rotations and the first load) by copy.  Its way OUT is not a
-        # copy in the timed run: the weight-gradient GEMM that completes a part stores `arriving + own` straight into
-        # the slot it travels to (a fused send); the staging-only run, which launches no GEMM, copies it instead.
+        # load; the gradient shard comes in n times by copy (n-1 rotations and the first load) and goes out once by
+        # copy (the shard a pass ends on, written back when the next backward pass begins).  Its other n-1 ways OUT
+        # are not copies in the timed run: the weight-gradient GEMM that completes a part stores `arriving + own`
+        # straight into the slot it travels to (a fused send); the staging-only run, which launches no GEMM, copies.
         n_, W_, G_ = w.n, mlp.w_bytes, mlp.g_bytes
         fused = w.dtype != "f32"                # the fp32 path copies the gradient shard out like the weights
         overlap = {"ms_compute_only": t_c, "ms_staging_only": t_s, "ms_both": t_b, "rotation_hidden_frac": hidden,
                    "ms_exposed": max(0.0, t_b - t_c),
-                   "staged_bytes": (4 * (n_ - 1) + 1) * W_ + (n_ if fused else 2 * n_ - 1) * G_, "g_out_fused": fused,
+                   "staged_bytes": (4 * (n_ - 1) + 1) * W_ + (n_ + 1 if fused else 2 * n_) * G_, "g_out_fused": fused,
                    "g_out_bytes_stored_by_gemm_epilogues": (n_ - 1) * G_ if fused else 0,
-                   "staging_only_run_bytes": (4 * (n_ - 1) + 1) * W_ + (2 * n_ - 1) * G_}
+                   "staging_only_run_bytes": (4 * (n_ - 1) + 1) * W_ + 2 * n_ * G_}
 
     cpu = None
     if not a.no_cpu_baseline:
