@@ -259,7 +259,7 @@ def algorithmic_bytes_linears(w, unit):
     out_copied = w.dtype == "f32"              # the fp32 path copies the gradient shard out; the bf16 kernels store it home
     # gradient shard: n copies in, one copy out (the shard the pass ends on goes back to its slot when the next
     # backward pass begins), and n - 1 more out where the weight-gradient kernels do not store it home themselves
-    stg = 2 * ((4 * (n - 1) + 1) * unit.w_bytes + (n + 1 + (n - 1 if out_copied else 0)) * unit.g_bytes)
+    stg = 2 * (4 * (n - 1) * unit.w_bytes + (n + 1 + (n - 1 if out_copied else 0)) * unit.g_bytes)
     return total + stg
 
 
@@ -403,8 +403,8 @@ def main():
         t_b = timed(torch, mlp, X, Y, dY, dX, k) / k
         hidden = 1.0 - max(0.0, t_b - t_c) / t_s if t_s > 0 else None
         # what the fraction covers: the copies on the stage stream.  Per pass the weights make 2(n-1) rotations (each
-        # a copy out to the slot the shard travels to and a copy in from the slot it arrives in) after one initial
-        # load; the gradient shard comes in n times by copy (n-1 rotations and the first load) and goes out once by
+        # a copy out to the slot the shard travels to and a copy in from the slot it arrives in; no initial load in a
+        # loop of passes: a backward pass ends on the worker's own shard); the gradient shard comes in n times by copy (n-1 rotations and the first load) and goes out once by
         # copy (the shard a pass ends on, written back when the next backward pass begins).  Its other n-1 ways OUT
         # are not copies in the timed run: the weight-gradient GEMM that completes a part stores `arriving + own`
         # straight into the slot it travels to (a fused send); the staging-only run, which launches no GEMM, copies.
@@ -412,9 +412,9 @@ def main():
         fused = w.dtype != "f32"                # the fp32 path copies the gradient shard out like the weights
         overlap = {"ms_compute_only": t_c, "ms_staging_only": t_s, "ms_both": t_b, "rotation_hidden_frac": hidden,
                    "ms_exposed": max(0.0, t_b - t_c),
-                   "staged_bytes": (4 * (n_ - 1) + 1) * W_ + (n_ + 1 if fused else 2 * n_) * G_, "g_out_fused": fused,
+                   "staged_bytes": 4 * (n_ - 1) * W_ + (n_ + 1 if fused else 2 * n_) * G_, "g_out_fused": fused,
                    "g_out_bytes_stored_by_gemm_epilogues": (n_ - 1) * G_ if fused else 0,
-                   "staging_only_run_bytes": (4 * (n_ - 1) + 1) * W_ + 2 * n_ * G_}
+                   "staging_only_run_bytes": 4 * (n_ - 1) * W_ + 2 * n_ * G_}
 
     cpu = None
     if not a.no_cpu_baseline:
@@ -437,9 +437,10 @@ def main():
         hbm = {"algorithmic_bytes_per_step": nbytes, "achieved": nbytes / (ms_step * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                "unit": "GB/s", "frac": nbytes / (ms_step * 1e-3) / 1e9 / PEAK_HBM_GBS}
     elif not is_moe:
-        # staging: every copy reads and writes its bytes; per pass 2(n-1) weight rotations (out + in), one initial
-        # load, and per backward rotation the gradient shard in (its way out is a GEMM's store, counted above)
-        stg = 2 * (2 * (2 * (w.n - 1)) + 1) * mlp.w_bytes + 2 * (w.n - 1 + 1) * mlp.g_bytes
+        # staging: every copy reads and writes its bytes; per pass 2(n-1) weight rotations (out + in), the gradient
+        # shard in at the start and per backward rotation (its way out is a GEMM's store, counted above) and out
+        # once by copy (the shard the pass ends on, written back when the next backward pass begins)
+        stg = 2 * 4 * (w.n - 1) * mlp.w_bytes + 2 * (w.n + 1) * mlp.g_bytes
         nbytes = algorithmic_bytes(w, stg)
         hbm = {"algorithmic_bytes_per_step": nbytes, "achieved": nbytes / (ms_step * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                "unit": "GB/s", "frac": nbytes / (ms_step * 1e-3) / 1e9 / PEAK_HBM_GBS}

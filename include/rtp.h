@@ -199,14 +199,21 @@ typedef struct {
 rtp_status rtp_ring_create(rtp_ring **out, const rtp_ring_desc *desc);
 rtp_status rtp_ring_destroy(rtp_ring *ring);
 
-/* Starts a pass.  RTP_PASS_FWD: copies home slot `rank` into the resident
- * buffer (weights) -- the worker's own shard.  RTP_PASS_BWD: must follow a
+/* Starts a pass.  RTP_PASS_FWD: the worker starts on its own shard (Design
+ * section, workflow paragraph).  If a completed backward pass has left that
+ * shard in the worker's buffer, it is used where it is; otherwise (first
+ * pass, after a forward pass, after rtp_ring_flush or rtp_ring_abort) home
+ * slot `rank` is copied into the resident buffer.  The caller therefore must
+ * not touch the worker's weight buffers between passes, and calls
+ * rtp_ring_flush before it writes to the weight store (an optimizer step).
+ * RTP_PASS_BWD: must follow a
  * completed forward pass (the worker holds shard (rank+1) mod n) or, with
  * n == 1 or after rtp_ring_seek_bwd_start(), any idle state; loads that shard's
  * gradient part, after writing the gradient shard an earlier backward pass
  * left in the buffer (the worker's own) back to its slot: gradients
- * accumulate over any number of passes.  RTP_ERR_STATE if a pass is in
- * progress.
+ * accumulate over any number of passes.  These two gradient transfers run on
+ * the stage stream; only the weight-gradient kernels wait for them.
+ * RTP_ERR_STATE if a pass is in progress.
  * Stream capture of a pass is not supported: the calls decide on the host,
  * when they are made, what a pass enqueues (the write-back above, for one),
  * and use three streams.  RTP_ERR_UNSUPPORTED, before anything is enqueued,

@@ -237,6 +237,8 @@ struct rtp_ring {
     rtp_pass pass = RTP_PASS_IDLE;
     int resident = -1;   // shard whose weights are in buf_w[res_idx]
     int res_idx = 0;
+    bool w_held = false; // buf_w[res_idx] really holds shard `resident` as the store has it (not after a flush,
+                         // an abort, or a pass run with the rotation switched off)
     int res_g = -1;      // shard whose gradients are in buf_g[res_g_idx]
     int res_g_idx = 0;
     int base_idx = 0;    // weight buffer index at step 0 of the open pass
@@ -253,6 +255,7 @@ struct rtp_ring {
     // the pipelined schedule of the MLP unit moves the two linears' shard parts separately
     hipEvent_t ev_w2[2] = {nullptr, nullptr}, ev_g2[2] = {nullptr, nullptr}, ev_k[2] = {nullptr, nullptr};
     hipEvent_t ev_g[2] = {nullptr, nullptr};
+    hipEvent_t ev_g0 = nullptr; // the gradient shard a backward pass starts on has landed
 
     hipStream_t cs() const { return (hipStream_t)d.compute_stream; }
     hipStream_t ss() const { return d.mode == RTP_INPLACE_BLOCKING ? cs() : (hipStream_t)d.stage_stream; }
@@ -285,7 +288,7 @@ static rtp_status ensure_events(rtp_ring *r)
 {
     if (r->dry || r->events_ready) return RTP_OK;
     hipEvent_t *all[] = {&r->ev_free, &r->ev_free2, &r->ev_join, &r->ev_aux, &r->ev_w[0], &r->ev_w[1], &r->ev_g[0], &r->ev_g[1],
-                         &r->ev_w2[0], &r->ev_w2[1], &r->ev_g2[0], &r->ev_g2[1], &r->ev_k[0], &r->ev_k[1]};
+                         &r->ev_w2[0], &r->ev_w2[1], &r->ev_g2[0], &r->ev_g2[1], &r->ev_k[0], &r->ev_k[1], &r->ev_g0};
     for (hipEvent_t *e : all)
         HIP_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
     for (rtp_linear *l : r->linears) {
@@ -420,6 +423,7 @@ static rtp_status set_ablation(rtp_ring *r, int rotate, int compute)
     if (r->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "ablation can only change between passes");
     r->abl_rotate = rotate != 0;
     r->abl_compute = compute != 0;
+    r->w_held = false;
     return RTP_OK;
 }
 
@@ -467,26 +471,40 @@ extern "C" rtp_status rtp_ring_begin(rtp_ring *r, rtp_pass pass)
     r->executed = 0;
     for (rtp_linear *l : r->linears) l->next_step = 0;
     if (pass == RTP_PASS_FWD) {
-        // the worker starts on its own shard
-        r->res_idx = 0;
-        r->base_idx = 0;
-        r->resident = rank;
-        RTP_TRY(copy_async(r, r->d.buf_w_dev[0], r->home_w(rank), r->d.w_bytes, r->cs()));
-        r->rec(TR_W_IN, -1, rank, 0);
+        // the worker starts on its own shard: the one a backward pass ended on, if it is still in its buffer
+        // (Design section, workflow paragraph: the backward rotation ends on the worker's own shard)
+        if (r->w_held && r->resident == rank && r->abl_rotate) {
+            r->base_idx = r->res_idx;
+        } else {
+            r->res_idx = 0;
+            r->base_idx = 0;
+            r->resident = rank;
+            RTP_TRY(copy_async(r, r->d.buf_w_dev[0], r->home_w(rank), r->d.w_bytes, r->cs()));
+            r->rec(TR_W_IN, -1, rank, 0);
+            r->w_held = r->abl_rotate;
+        }
     } else {
         // gradient shards come into being where the weights ended the forward pass
         r->base_idx = r->res_idx;
+        // The gradient transfers of the pass's start run on the stage stream: only the weight-gradient kernels
+        // (auxiliary stream, or the compute stream when there is none) wait for them, the first input-gradient
+        // kernels do not.  cross_join above has ordered the stage stream after everything enqueued so far.
+        hipStream_t gs = r->ss();
         if (r->d.g_bytes && r->res_g >= 0) {
             // the gradient shard the previous backward pass ended on (the worker's own) is still in the
             // buffer: it goes back to its slot before the buffer takes the shard this pass starts with
-            RTP_TRY(copy_async(r, r->home_g(r->res_g), r->d.buf_g_dev[r->res_g_idx], r->d.g_bytes, r->cs()));
+            RTP_TRY(copy_async(r, r->home_g(r->res_g), r->d.buf_g_dev[r->res_g_idx], r->d.g_bytes, gs));
             r->rec(TR_G_OUT, -1, r->res_g, r->res_g_idx);
         }
         r->res_g_idx = 0;
         r->res_g = r->resident;
         if (r->d.g_bytes) {
-            RTP_TRY(copy_async(r, r->d.buf_g_dev[0], r->home_g(r->resident), r->d.g_bytes, r->cs()));
+            RTP_TRY(copy_async(r, r->d.buf_g_dev[0], r->home_g(r->resident), r->d.g_bytes, gs));
             r->rec(TR_G_IN, -1, r->resident, 0);
+            if (!r->dry && gs != r->cs()) {
+                HIP_TRY(hipEventRecord(r->ev_g0, gs));
+                HIP_TRY(hipStreamWaitEvent(r->as(), r->ev_g0, 0));
+            }
         }
     }
     return RTP_OK;
@@ -504,6 +522,7 @@ extern "C" rtp_status rtp_ring_seek_bwd_start(rtp_ring *r)
     r->resident = k;
     RTP_TRY(copy_async(r, r->d.buf_w_dev[0], r->home_w(k), r->d.w_bytes, r->cs()));
     r->rec(TR_W_IN, -1, k, 0);
+    r->w_held = r->abl_rotate;
     return RTP_OK;
 }
 
@@ -627,6 +646,7 @@ extern "C" rtp_status rtp_ring_end(rtp_ring *r)
     if (!r->abl_rotate) {
         // keep the shard ids consistent even though nothing moved
         r->resident = r->shard_at(r->d.n - 1);
+        r->w_held = false;
     }
     r->pass = RTP_PASS_IDLE;
     // the pass is complete on the compute stream only once the stage stream's last transfers are:
@@ -652,6 +672,7 @@ extern "C" rtp_status rtp_ring_abort(rtp_ring *r)
     rtp_status st = (r->dry || !r->events_ready) ? RTP_OK : cross_join(r);
     r->pass = RTP_PASS_IDLE;
     r->resident = -1;
+    r->w_held = false;
     r->res_g = -1;
     r->rotations = 0;
     r->executed = 0;
@@ -680,6 +701,7 @@ extern "C" rtp_status rtp_ring_flush(rtp_ring *r)
     RTP_TRY(cross_join(r));
     RTP_TRY(copy_async(r, r->home_w(r->resident), r->d.buf_w_dev[r->res_idx], r->d.w_bytes, r->cs()));
     r->rec(TR_W_OUT, -1, r->resident, r->res_idx);
+    r->w_held = false; // the store may be written from here on (an optimizer step): the next forward pass loads anew
     if (r->d.g_bytes && r->res_g >= 0) {
         RTP_TRY(copy_async(r, r->home_g(r->res_g), r->d.buf_g_dev[r->res_g_idx], r->d.g_bytes, r->cs()));
         r->rec(TR_G_OUT, -1, r->res_g, r->res_g_idx);

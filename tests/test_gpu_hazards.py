@@ -72,8 +72,8 @@ def test_linear_layer_with_poisoned_buffers_and_late_streams(split, mode, stage_
     dX = torch.empty(T, I, device=DEV, dtype=torch.bfloat16)
     for p in range(2):
         print(f"linear split={split} mode={mode} delays=({stage_us},{aux_us}) pass {p}", flush=True)
-        poison(Y, dX, layer.acc_ws, *layer.buf_w, *([] if p else layer.buf_g))   # (the gradient buffer holds the
-        torch.cuda.synchronize()                                                 #  worker's own shard after pass 0)
+        poison(Y, dX, layer.acc_ws, *([] if p else layer.buf_w + layer.buf_g))   # (after pass 0 the buffers hold the
+        torch.cuda.synchronize()                                                 #  worker's own weight and gradient shard)
         layer.forward(X, Y)
         layer.backward(X, dY, dX)
         layer.sync()
@@ -109,7 +109,7 @@ def test_mlp_unit_with_poisoned_buffers_and_late_streams(mode, schedule, stage_u
     dX = torch.empty(T, I, device=DEV, dtype=torch.bfloat16)
     for p in range(2):
         print(f"mlp mode={mode} schedule={schedule} delays=({stage_us},{aux_us}) pass {p}", flush=True)
-        poison(Y, dX, mlp.acc_y, mlp.acc_dx, mlp.preact, mlp.hidden, mlp.dpre, *mlp.buf_w, *([] if p else mlp.buf_g))
+        poison(Y, dX, mlp.acc_y, mlp.acc_dx, mlp.preact, mlp.hidden, mlp.dpre, *([] if p else mlp.buf_w + mlp.buf_g))
         torch.cuda.synchronize()
         mlp.forward(X, Y)
         mlp.backward(X, dY, dX)

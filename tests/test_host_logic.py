@@ -119,6 +119,67 @@ def test_dry_run_trace_matches_oracle_schedule(n, mode):
                     assert b != comp[(p, s)] and b == comp[(p, s + 1)]
 
 
+@pytest.mark.parametrize("mode", [B.RTP_DOUBLE_BUFFER, B.RTP_INPLACE_STAGED, B.RTP_INPLACE_BLOCKING])
+@pytest.mark.parametrize("between", ["nothing", "flush", "abort", "forward_only", "ablation"])
+def test_own_weight_shard_left_in_the_buffer_is_not_loaded_again(between, mode):
+    """A backward pass ends on the worker's own shard (Design section, workflow paragraph): the next forward
+    pass starts on it where it is -- same buffer, no load -- unless the store may have changed (flush), the
+    ring forgot what it holds (abort, a pass without rotation) or the last pass was a forward pass."""
+    n, rank = 4, 1
+    ring = _dry_ring(n, rank, mode, w=16 * 8 * n * 4, g=16 * 8 * n * 4)
+    lin = B.Linear(ring, 4, 8, 8 * n, B.RTP_SPLIT_OUT, B.RTP_F32)
+
+    def fwd():
+        ring.begin(B.RTP_PASS_FWD)
+        for t in range(n):
+            if t < n - 1:
+                ring.rotate_step(B.RTP_CW, t)
+            lin.fwd(t, None, None)
+        ring.end()
+
+    def bwd():
+        ring.begin(B.RTP_PASS_BWD)
+        for s in range(n):
+            if s < n - 1:
+                ring.rotate_step(B.RTP_CCW, s)
+            lin.bwd(s, None, None, None)
+        ring.end()
+
+    fwd()
+    first = ring.trace(clear=True)
+    assert [r[3] for r in first if r[0] == "w_in" and r[2] < 0] == [rank], "first pass loads the own shard"
+    bwd()
+    last_bwd = [r for r in ring.trace(clear=True) if r[0] == "bwd"][-1]
+    assert last_bwd[3] == rank
+    if between == "flush":
+        ring.flush()
+    elif between == "abort":
+        ring.begin(B.RTP_PASS_FWD)
+        ring.abort()
+    elif between == "forward_only":
+        fwd()
+    elif between == "ablation":
+        ring.set_ablation(True, True)
+    ring.trace(clear=True)
+    fwd()
+    tr = ring.trace(clear=True)
+    loads = [r[3] for r in tr if r[0] == "w_in" and r[2] < 0]
+    assert loads == ([] if between == "nothing" else [rank])
+    step0 = [r for r in tr if r[0] == "fwd"][0]
+    assert step0[3] == rank
+    if between == "nothing":
+        assert step0[4] == last_bwd[4], "step 0 computes on the buffer the backward pass ended in"
+    # the schedule that follows is the same either way
+    assert [r[3] for r in tr if r[0] == "fwd"] == [B.rtp_fwd_shard(rank, t, n) for t in range(n)]
+    if mode != B.RTP_INPLACE_BLOCKING:
+        comp = {r[2]: r[4] for r in tr if r[0] == "fwd"}
+        for r in tr:
+            if r[0] == "w_in" and r[2] >= 0:
+                assert r[4] != comp[r[2]] and r[4] == comp[r[2] + 1]
+    lin.close()
+    ring.close()
+
+
 @pytest.mark.parametrize("between", ["nothing", "flush", "zero_grads"])
 def test_gradient_shard_left_in_the_buffer_goes_home_once(between):
     """A second backward pass first sends the worker's own gradient shard, still in its buffer from
