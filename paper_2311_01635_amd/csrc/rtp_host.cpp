@@ -311,16 +311,66 @@ static rtp_status copy_async(rtp_ring *r, void *dst, const void *src, size_t byt
     return RTP_OK;
 }
 
-// One rotation of a shard part: the held part goes out, then the next one comes in (held_next may
-// be the buffer it just left: stream order keeps the two copies apart).  A single kernel doing
-// both directions at once was measured 40 % slower than the two plain copies: four interleaved
-// streams of addresses use HBM worse than two.
+// Transfers that do not depend on one another, gathered so that they go out as ONE launch: the host pays for
+// every launch (and every cross-stream wait) of a pass, and the narrow-shard units are bound by exactly that.
+// The workgroups of the launch are dealt segment by segment, so the copies still pass through the machine one
+// after the other.  (A kernel in which every thread served both directions of a rotation at once was measured
+// 40 % slower than two plain copies: four interleaved address streams use HBM worse than two.)
+constexpr size_t COPY_BATCH_MAX_BYTES = (size_t)16 << 20;
+struct CopyBatch {
+    int n = 0;
+    void *dst[COPY_MAX_SEGS];
+    const void *src[COPY_MAX_SEGS];
+    size_t bytes[COPY_MAX_SEGS];
+};
+
+static rtp_status copy_batch_flush(rtp_ring *r, CopyBatch &b, hipStream_t s)
+{
+    if (b.n == 0) return RTP_OK;
+    const int n = b.n;
+    b.n = 0;
+    if (r->dry) return RTP_OK;
+    // Large transfers go out one by one, in the order they were added (callers add the transfer a kernel waits for
+    // first): beside a GEMM that fills the machine, copies that follow one another disturb it less than the same
+    // bytes all at once (Llama-shaped unit: 4.31 against 4.39 ms per pass, expert unit 16.9 against 17.2; the
+    // large unit with its few tokens per shard is the exception, 9.1 against 8.9), and a launch is nothing beside them.
+    size_t total = 0;
+    for (int i = 0; i < n; ++i) total += b.bytes[i];
+    if (n == 1 || (r->d.flags & RTP_FLAG_STAGE_MEMCPY) || total >= COPY_BATCH_MAX_BYTES) {
+        for (int i = 0; i < n; ++i) RTP_TRY(copy_async(r, b.dst[i], b.src[i], b.bytes[i], s));
+        return RTP_OK;
+    }
+    if (r->delay_stage_ticks > 0 && s == r->ss() && r->ss() != r->cs())
+        HIP_TRY(launch_clock_probe(r->delay_out, r->delay_stage_ticks, s));
+    HIP_TRY(launch_copy_multi(b.dst, b.src, b.bytes, n, s));
+    return RTP_OK;
+}
+
+// adds a transfer to the batch; the caller guarantees that it overlaps none of those already in it
+static rtp_status copy_batch_add(rtp_ring *r, CopyBatch &b, void *dst, const void *src, size_t bytes, hipStream_t s)
+{
+    if (bytes == 0) return RTP_OK;
+    if (b.n == COPY_MAX_SEGS) RTP_TRY(copy_batch_flush(r, b, s));
+    b.dst[b.n] = dst; b.src[b.n] = src; b.bytes[b.n] = bytes;
+    b.n++;
+    return RTP_OK;
+}
+
+// One rotation of a shard part: the held part goes out and the next one comes in.  held_next may be the
+// buffer the held part just left (the in-place exchange): then stream order keeps the two copies apart;
+// otherwise they are one launch.
 static rtp_status rotate_async(rtp_ring *r, void *out, const void *held, void *held_next, const void *in, size_t bytes,
                                hipStream_t s)
 {
-    RTP_TRY(copy_async(r, out, held, bytes, s));
-    RTP_TRY(copy_async(r, held_next, in, bytes, s));
-    return RTP_OK;
+    if (held_next == held || out == in) {
+        RTP_TRY(copy_async(r, out, held, bytes, s));
+        RTP_TRY(copy_async(r, held_next, in, bytes, s));
+        return RTP_OK;
+    }
+    CopyBatch b;
+    RTP_TRY(copy_batch_add(r, b, held_next, in, bytes, s)); // the incoming part first: a kernel waits for it
+    RTP_TRY(copy_batch_add(r, b, out, held, bytes, s));
+    return copy_batch_flush(r, b, s);
 }
 
 // make each stream wait for everything enqueued so far on the other
@@ -552,7 +602,24 @@ static rtp_status do_rotation(rtp_ring *r, int step)
         HIP_TRY(hipEventRecord(r->ev_join, r->as()));
         HIP_TRY(hipStreamWaitEvent(r->cs(), r->ev_join, 0));
     }
-    // send the held weights to their next holder, receive the next shard
+    // send the held weights to their next holder, receive the next shard; with two gradient buffers the next
+    // gradient shard comes in with them (one launch for the three transfers)
+    if (bwd && r->d.g_bytes && r->d.mode == RTP_DOUBLE_BUFFER && src != dst) {
+        const int gdst = r->g_idx(step + 1);
+        CopyBatch b;
+        RTP_TRY(copy_batch_add(r, b, r->d.buf_w_dev[dst], r->home_w(kin), r->d.w_bytes, s));
+        RTP_TRY(copy_batch_add(r, b, r->d.buf_g_dev[gdst], r->home_g(kin), r->d.g_bytes, s));
+        RTP_TRY(copy_batch_add(r, b, r->home_w(k), r->d.buf_w_dev[src], r->d.w_bytes, s));
+        RTP_TRY(copy_batch_flush(r, b, s));
+        r->rec(TR_W_OUT, step, k, src);
+        r->rec(TR_W_IN, step, kin, dst);
+        r->rec(TR_G_IN, step, kin, gdst);
+        if (!r->dry) {
+            HIP_TRY(hipEventRecord(r->ev_w[(step + 1) & 1], s));
+            HIP_TRY(hipEventRecord(r->ev_g[(step + 1) & 1], s));
+        }
+        return RTP_OK;
+    }
     RTP_TRY(rotate_async(r, r->home_w(k), r->d.buf_w_dev[src], r->d.buf_w_dev[dst], r->home_w(kin), r->d.w_bytes, s));
     r->rec(TR_W_OUT, step, k, src);
     r->rec(TR_W_IN, step, kin, dst);
@@ -1516,6 +1583,13 @@ static rtp_status gemm_group(rtp_ring *r, int layout, const GemmArgs *a, int cou
     return RTP_OK;
 }
 
+static rtp_status stream_after(hipEvent_t ev, hipStream_t later, hipStream_t earlier)
+{
+    HIP_TRY(hipEventRecord(ev, earlier));
+    HIP_TRY(hipStreamWaitEvent(later, ev, 0));
+    return RTP_OK;
+}
+
 // stage stream: wait for everything enqueued so far on the compute stream
 static rtp_status stage_after_compute(rtp_ring *r)
 {
@@ -1530,6 +1604,16 @@ static rtp_status rotate_w_part(rtp_ring *r, int step, int k, int kin, int src, 
 {
     RTP_TRY(rotate_async(r, r->home_w(k) + off, (char *)r->d.buf_w_dev[src] + off, (char *)r->d.buf_w_dev[dst] + off,
                          r->home_w(kin) + off, bytes, r->ss()));
+    r->rec(TR_W_OUT, step, k, src);
+    r->rec(TR_W_IN, step, kin, dst);
+    return RTP_OK;
+}
+
+// the same into a batch (src != dst: the staged modes)
+static rtp_status rotate_w_part(rtp_ring *r, CopyBatch &b, int step, int k, int kin, int src, int dst, size_t off, size_t bytes)
+{
+    RTP_TRY(copy_batch_add(r, b, (char *)r->d.buf_w_dev[dst] + off, r->home_w(kin) + off, bytes, r->ss()));
+    RTP_TRY(copy_batch_add(r, b, r->home_w(k) + off, (char *)r->d.buf_w_dev[src] + off, bytes, r->ss()));
     r->rec(TR_W_OUT, step, k, src);
     r->rec(TR_W_IN, step, kin, dst);
     return RTP_OK;
@@ -1568,10 +1652,12 @@ static rtp_status mlp_fwd_grouped(rtp_mlp *m, const void *X, void *Y)
         const bool move_w2 = rot && t >= 1 && t <= n - 1, move_w1 = rot && t <= n - 2;
         if (move_w1 || move_w2) {
             RTP_TRY(stage_after_compute(r));
+            CopyBatch b; // four transfers, no two on the same bytes: one launch
             if (move_w2)
-                RTP_TRY(rotate_w_part(r, t - 1, r->shard_at(t - 1), r->shard_at(t), r->w_idx(t - 1), r->w_idx(t), h.w_off2, w2_bytes));
+                RTP_TRY(rotate_w_part(r, b, t - 1, r->shard_at(t - 1), r->shard_at(t), r->w_idx(t - 1), r->w_idx(t), h.w_off2, w2_bytes));
             if (move_w1)
-                RTP_TRY(rotate_w_part(r, t, r->shard_at(t), r->shard_at(t + 1), r->w_idx(t), r->w_idx(t + 1), 0, w1_bytes));
+                RTP_TRY(rotate_w_part(r, b, t, r->shard_at(t), r->shard_at(t + 1), r->w_idx(t), r->w_idx(t + 1), 0, w1_bytes));
+            RTP_TRY(copy_batch_flush(r, b, r->ss()));
             HIP_TRY(hipEventRecord(r->ev_w[(t + 1) & 1], r->ss()));
         }
         if (rot && t >= 1) HIP_TRY(hipStreamWaitEvent(r->cs(), r->ev_w[t & 1], 0));
@@ -1655,6 +1741,123 @@ static rtp_status mlp_bwd_grouped(rtp_mlp *m, const void *X, const void *dY, voi
             RTP_TRY(copy_async(r, r->d.buf_g_dev[r->g_idx(s + 1)], r->home_g(kin), r->d.g_bytes, r->ss()));
             r->rec(TR_G_IN, s, kin, r->g_idx(s + 1));
             HIP_TRY(hipEventRecord(r->ev_g[(s + 1) & 1], r->ss()));
+        }
+    }
+    mlp_close_pass(m);
+    return rtp_ring_end(r);
+}
+
+// The default backward pass beside an auxiliary stream: one launch per GEMM, the input gradients (dPre_s, dX_s)
+// on the compute stream and the weight gradients (dW2_s, dW1_s) on the auxiliary stream, exactly the kernels and
+// the order of the step-by-step calls, but with the cross-stream waits and transfer launches of a step cut to what
+// the data flow needs (the host pays ~5 us for each of them, and units with narrow shards are bound by the host):
+//   stage stream   waits for the compute stream's last readers of the staging weight buffer, then moves
+//                  shard s out and shard s+1 in as one launch; waits for the weight-gradient kernel(s) that
+//                  complete a gradient part, then exchanges that part (two buffers: the whole shard at once
+//                  into the other buffer; one buffer: part by part, in place);
+//   compute stream waits for the weights of step s;
+//   auxiliary      waits for the gradient part it adds onto, and dW1_s for dPre_s.
+static rtp_status mlp_bwd_two_stream(rtp_mlp *m, const void *X, const void *dY, void *dX)
+{
+    rtp_ring *r = m->ring;
+    const int n = r->d.n;
+    const MlpShapes h = mlp_shapes(m);
+    RTP_TRY(rtp_ring_begin(r, RTP_PASS_BWD));
+    const bool rot = r->abl_rotate && n > 1;
+    const bool move_g = rot && r->d.g_bytes != 0;
+    const bool two_g = r->d.mode == RTP_DOUBLE_BUFFER;
+    hipStream_t cs = r->cs(), as = r->as(), ss = r->ss();
+    const size_t g1_bytes = h.g_off2, g2_bytes = r->d.g_bytes - h.g_off2;
+    auto wbuf = [&](int step) { return (const char *)r->d.buf_w_dev[rot ? r->w_idx(step) : r->res_idx]; };
+    auto gidx = [&](int step) { return rot ? r->g_idx(step) : r->res_g_idx; };
+    auto gbuf = [&](int step) { return (char *)r->d.buf_g_dev[gidx(step)]; };
+
+    // a weight-gradient kernel; the send of its part of the gradient shard is fused into it when the shard moves on
+    auto emit_dw = [&](int s, GemmArgs a, size_t off, bool first, bool *fused) -> rtp_status {
+        const bool moves_on = move_g && s <= n - 2;
+        bool fused_send = moves_on && r->abl_compute;
+        if (fused_send) {
+            int ks = 1;
+            gemm_bf16_pp_plan(LAY_TN, &a, 1, nullptr, nullptr, &ks);
+            if (ks > 1) fused_send = false; // K-split partial sums need the plain `+=` form
+        }
+        if (fused_send) {
+            a.epi = EPI_ACC_LAST;
+            a.C = r->home_g(r->shard_at(s)) + off;
+        }
+        a.cu_share = 2;
+        RTP_TRY(gemm_group(r, LAY_TN, &a, 1, as));
+        RTP_TRY(mlp_bias_grads(m, h, r->shard_at(s), gbuf(s), fused_send ? r->home_g(r->shard_at(s)) : nullptr, dY, first, !first, as));
+        *fused = fused_send;
+        return RTP_OK;
+    };
+    // stage stream, after the auxiliary stream's kernels so far: part [off, off + bytes) of gradient shard s goes
+    // out (unless its kernel has sent it) and the same part of shard s+1 comes into buffer gidx(s+1)
+    auto exchange_g = [&](int s, size_t off, size_t bytes, bool out_by_copy, hipEvent_t landed, bool whole) -> rtp_status {
+        const int k = r->shard_at(s), kin = r->shard_at(s + 1);
+        RTP_TRY(stream_after(r->ev_free2, ss, as));
+        CopyBatch b;
+        if (two_g) {
+            RTP_TRY(copy_batch_add(r, b, gbuf(s + 1) + off, r->home_g(kin) + off, bytes, ss));
+            if (out_by_copy) RTP_TRY(copy_batch_add(r, b, r->home_g(k) + off, gbuf(s) + off, bytes, ss));
+        } else {
+            // in place: the part comes into the buffer it just left
+            if (out_by_copy) RTP_TRY(copy_async(r, r->home_g(k) + off, gbuf(s) + off, bytes, ss));
+            RTP_TRY(copy_batch_add(r, b, gbuf(s + 1) + off, r->home_g(kin) + off, bytes, ss));
+        }
+        RTP_TRY(copy_batch_flush(r, b, ss));
+        if (whole || off != 0) r->rec(TR_G_OUT, s, k, gidx(s));
+        if (whole || off != 0) r->rec(TR_G_IN, s, kin, gidx(s + 1));
+        HIP_TRY(hipEventRecord(landed, ss));
+        return RTP_OK;
+    };
+
+    for (int s = 0; s < n; ++s) {
+        const int k = r->shard_at(s);
+        // ---- weights of step s+1: their buffer was last read by dPre_{s-1} and dX_{s-1}
+        if (rot && s <= n - 2) {
+            if (s >= 1) RTP_TRY(stream_after(r->ev_free, ss, cs)); // (step 0: rtp_ring_begin has ordered the streams)
+            CopyBatch b;
+            RTP_TRY(rotate_w_part(r, b, s, k, r->shard_at(s + 1), r->w_idx(s), r->w_idx(s + 1), 0, r->d.w_bytes));
+            RTP_TRY(copy_batch_flush(r, b, ss));
+            HIP_TRY(hipEventRecord(r->ev_w[(s + 1) & 1], ss));
+        }
+        // ---- input gradients
+        if (rot && s >= 1) HIP_TRY(hipStreamWaitEvent(cs, r->ev_w[s & 1], 0));
+        r->rec(TR_BWD, s, k, rot ? r->w_idx(s) : r->res_idx);
+        GemmArgs a = mlp_args_dh(m, h, k, wbuf(s), dY);
+        a.cu_share = 2;
+        RTP_TRY(gemm_group(r, LAY_NN, &a, 1, cs));
+        HIP_TRY(hipEventRecord(r->ev_k[s & 1], cs));
+        a = mlp_args_dx(m, h, k, s, wbuf(s), dX);
+        a.cu_share = 2;
+        RTP_TRY(gemm_group(r, LAY_NN, &a, 1, cs));
+        // ---- weight gradients, onto the travelling gradient shard
+        const bool moves_on = move_g && s <= n - 2;
+        bool sent2 = false, sent1 = false;
+        if (move_g && s >= 1) HIP_TRY(hipStreamWaitEvent(as, (two_g ? r->ev_g : r->ev_g2)[s & 1], 0));
+        RTP_TRY(emit_dw(s, mlp_args_dw2(m, h, k, gbuf(s), dY), h.g_off2, false, &sent2));
+        if (moves_on && !two_g) RTP_TRY(exchange_g(s, h.g_off2, g2_bytes, !sent2, r->ev_g2[(s + 1) & 1], false));
+        HIP_TRY(hipStreamWaitEvent(as, r->ev_k[s & 1], 0));
+        if (move_g && s >= 1 && !two_g) HIP_TRY(hipStreamWaitEvent(as, r->ev_g[s & 1], 0));
+        RTP_TRY(emit_dw(s, mlp_args_dw1(m, h, k, gbuf(s), X), 0, true, &sent1));
+        if (moves_on && !two_g) RTP_TRY(exchange_g(s, 0, g1_bytes, !sent1, r->ev_g[(s + 1) & 1], false));
+        if (moves_on && two_g) {
+            // two buffers: the whole shard at once (a part its kernel did not send goes out by copy)
+            if (sent1 == sent2) {
+                RTP_TRY(exchange_g(s, 0, r->d.g_bytes, !sent1, r->ev_g[(s + 1) & 1], true));
+            } else {
+                const int kk = r->shard_at(s), kin = r->shard_at(s + 1);
+                RTP_TRY(stream_after(r->ev_free2, ss, as));
+                CopyBatch b;
+                RTP_TRY(copy_batch_add(r, b, gbuf(s + 1), r->home_g(kin), r->d.g_bytes, ss));
+                if (!sent1) RTP_TRY(copy_batch_add(r, b, r->home_g(kk), gbuf(s), g1_bytes, ss));
+                if (!sent2) RTP_TRY(copy_batch_add(r, b, r->home_g(kk) + h.g_off2, gbuf(s) + h.g_off2, g2_bytes, ss));
+                RTP_TRY(copy_batch_flush(r, b, ss));
+                r->rec(TR_G_OUT, s, kk, gidx(s));
+                r->rec(TR_G_IN, s, kin, gidx(s + 1));
+                HIP_TRY(hipEventRecord(r->ev_g[(s + 1) & 1], ss));
+            }
         }
     }
     mlp_close_pass(m);
@@ -1773,12 +1976,6 @@ static rtp_status mlp_bwd_fused(rtp_mlp *m, const void *X, const void *dY, void 
 // gradients, ng = number of gradient buffers) is received into it.  Same buffers, same bytes and the
 // same N-1 sends and receives per part and pass as in the step-by-step schedule; same kernels.
 
-static rtp_status stream_after(hipEvent_t ev, hipStream_t later, hipStream_t earlier)
-{
-    HIP_TRY(hipEventRecord(ev, earlier));
-    HIP_TRY(hipStreamWaitEvent(later, ev, 0));
-    return RTP_OK;
-}
 
 // send shard k's part [off, off + bytes) of weight buffer `src` home (rotation `step`)
 static rtp_status w_part_out(rtp_ring *r, int step, int k, int src, size_t off, size_t bytes)
@@ -1976,12 +2173,13 @@ static rtp_status mlp_bwd_pass(rtp_mlp *m, const void *X, const void *dY, void *
     // Measured on the Llama-shaped unit (ms per backward pass, same box): with an auxiliary stream, one launch
     // per GEMM with the weight gradients on that stream 3.15, the pipelined schedule 3.2-3.4, the two grouped
     // launches per step 3.4-3.5; without one the grouped launches win (3.5 against 3.7).  Whatever the schedule,
-    // the kernels of a pass need ~4.26 ms of a machine that is busy throughout: see the design doc's schedule table.
+    // the kernels of a pass need the same time of a machine that is busy throughout.
     const bool have_aux = m->ring->as() != m->ring->cs();
     if (dX && mlp_fused_ok(m, X, nullptr, dY, dX)) return mlp_bwd_fused(m, X, dY, dX);
     if (dX && mlp_grouped_ok(m, X, nullptr, dY, dX)) {
         if (have_aux && (m->d.flags & RTP_FLAG_PIPELINED)) return mlp_bwd_pipelined(m, X, dY, dX);
         if (!have_aux || (m->d.flags & RTP_FLAG_GROUPED)) return mlp_bwd_grouped(m, X, dY, dX);
+        return mlp_bwd_two_stream(m, X, dY, dX);
     }
     const int n = m->d.n;
     RTP_TRY(rtp_ring_begin(m->ring, RTP_PASS_BWD));

@@ -1,6 +1,7 @@
 // fp32 path of the partition GEMM (the small fp32 configuration), the
 // elementwise activation kernels that path uses, and the shard-staging copy.
 #include "rtp_kernels.h"
+#include <cstring>
 #include <algorithm>
 
 namespace rtp {
@@ -182,6 +183,63 @@ hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s)
     const int64_t per = COPY_THREADS * COPY_PER_THREAD;
     const unsigned blocks = (unsigned)((n16 + per - 1) / per);
     hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(COPY_THREADS), 0, s, (u32x4 *)dst, (const u32x4 *)src, n16);
+    return hipGetLastError();
+}
+
+// Up to COPY_MAX_SEGS independent copies as one launch: workgroups [first[i], first[i + 1]) move segment i, 64 KB
+// each as above, so the segments go through the machine one after the other as separate launches would, for one
+// launch's worth of host time.  The segments must not overlap one another (no order among them).
+struct CopySegs {
+    u32x4 *dst[COPY_MAX_SEGS];
+    const u32x4 *src[COPY_MAX_SEGS];
+    int64_t n16[COPY_MAX_SEGS];
+    unsigned first[COPY_MAX_SEGS + 1];
+    int count;
+};
+
+__global__ __launch_bounds__(COPY_THREADS) void copy_multi_kernel(const CopySegs g)
+{
+    int i = 0;
+    while (i + 1 < g.count && blockIdx.x >= g.first[i + 1]) ++i;
+    const u32x4 *__restrict__ src = g.src[i];
+    u32x4 *__restrict__ dst = g.dst[i];
+    const int64_t n16 = g.n16[i];
+    const int64_t base = (int64_t)(blockIdx.x - g.first[i]) * (COPY_THREADS * COPY_PER_THREAD) + threadIdx.x;
+    u32x4 v[COPY_PER_THREAD];
+#pragma unroll
+    for (int j = 0; j < COPY_PER_THREAD; ++j) {
+        const int64_t e = base + (int64_t)j * COPY_THREADS;
+        if (e < n16) v[j] = __builtin_nontemporal_load(src + e);
+    }
+#pragma unroll
+    for (int j = 0; j < COPY_PER_THREAD; ++j) {
+        const int64_t e = base + (int64_t)j * COPY_THREADS;
+        if (e < n16) __builtin_nontemporal_store(v[j], dst + e);
+    }
+}
+
+hipError_t launch_copy_multi(void *const *dst, const void *const *src, const size_t *bytes, int count, hipStream_t s)
+{
+    if (count < 0 || count > COPY_MAX_SEGS) return hipErrorInvalidValue;
+    CopySegs g;
+    memset(&g, 0, sizeof g);
+    const int64_t per = COPY_THREADS * COPY_PER_THREAD;
+    unsigned blocks = 0;
+    for (int i = 0; i < count; ++i) {
+        if (bytes[i] == 0) continue;
+        if ((bytes[i] & 15) || ((uintptr_t)dst[i] & 15) || ((uintptr_t)src[i] & 15)) return hipErrorInvalidValue;
+        const int64_t n16 = (int64_t)(bytes[i] >> 4);
+        g.dst[g.count] = (u32x4 *)dst[i];
+        g.src[g.count] = (const u32x4 *)src[i];
+        g.n16[g.count] = n16;
+        g.first[g.count] = blocks;
+        blocks += (unsigned)((n16 + per - 1) / per);
+        g.count++;
+    }
+    if (g.count == 0) return hipSuccess;
+    g.first[g.count] = blocks;
+    if (g.count == 1) return launch_copy(g.dst[0], g.src[0], (size_t)g.n16[0] << 4, s);
+    hipLaunchKernelGGL(copy_multi_kernel, dim3(blocks), dim3(COPY_THREADS), 0, s, g);
     return hipGetLastError();
 }
 
