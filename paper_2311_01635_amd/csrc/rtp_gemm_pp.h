@@ -49,6 +49,7 @@
 // stored), K must be a multiple of 32.
 #pragma once
 #include "rtp_gemm_epilogue.h"
+#include <hip/hip_ext.h>
 
 namespace rtp {
 
@@ -402,10 +403,15 @@ __global__ __launch_bounds__(pp::NTHR) void gemm_pp_kernel(const PpGroup g)
     }
 }
 
+// done: an event that completes with the kernel (its completion signal is the event's: no packet of its own in
+// the queue, which a separate record costs ~4 us of queue time between two dependent launches), or null.
 template <int LAY, typename E>
-static hipError_t launch_gemm_pp_layout(const PpGroup &g, unsigned blocks, hipStream_t s)
+static hipError_t launch_gemm_pp_layout(const PpGroup &g, unsigned blocks, hipStream_t s, hipEvent_t done)
 {
-    hipLaunchKernelGGL((gemm_pp_kernel<LAY, E>), dim3(blocks), dim3(pp::NTHR), 0, s, g);
+    if (done)
+        hipExtLaunchKernelGGL((gemm_pp_kernel<LAY, E>), dim3(blocks), dim3(pp::NTHR), 0, s, nullptr, done, 0, g);
+    else
+        hipLaunchKernelGGL((gemm_pp_kernel<LAY, E>), dim3(blocks), dim3(pp::NTHR), 0, s, g);
     return hipGetLastError();
 }
 

@@ -13,12 +13,12 @@
 
 namespace rtp {
 
-hipError_t launch_gemm_pp_nt_bf16(const PpGroup &g, unsigned blocks, hipStream_t s);
-hipError_t launch_gemm_pp_nn_bf16(const PpGroup &g, unsigned blocks, hipStream_t s);
-hipError_t launch_gemm_pp_tn_bf16(const PpGroup &g, unsigned blocks, hipStream_t s);
-hipError_t launch_gemm_pp_nt_f16(const PpGroup &g, unsigned blocks, hipStream_t s);
-hipError_t launch_gemm_pp_nn_f16(const PpGroup &g, unsigned blocks, hipStream_t s);
-hipError_t launch_gemm_pp_tn_f16(const PpGroup &g, unsigned blocks, hipStream_t s);
+hipError_t launch_gemm_pp_nt_bf16(const PpGroup &g, unsigned blocks, hipStream_t s, hipEvent_t done);
+hipError_t launch_gemm_pp_nn_bf16(const PpGroup &g, unsigned blocks, hipStream_t s, hipEvent_t done);
+hipError_t launch_gemm_pp_tn_bf16(const PpGroup &g, unsigned blocks, hipStream_t s, hipEvent_t done);
+hipError_t launch_gemm_pp_nt_f16(const PpGroup &g, unsigned blocks, hipStream_t s, hipEvent_t done);
+hipError_t launch_gemm_pp_nn_f16(const PpGroup &g, unsigned blocks, hipStream_t s, hipEvent_t done);
+hipError_t launch_gemm_pp_tn_f16(const PpGroup &g, unsigned blocks, hipStream_t s, hipEvent_t done);
 
 bool gemm_bf16_pp_supported(int layout, const GemmArgs &a)
 {
@@ -216,7 +216,8 @@ void gemm_bf16_pp_plan(int layout, const GemmArgs *a, int count, const int *bm_o
     }
 }
 
-hipError_t launch_gemm_bf16_pp_group(int layout, const GemmArgs *a_in, int count_in, const int *bm_override, hipStream_t s)
+hipError_t launch_gemm_bf16_pp_group(int layout, const GemmArgs *a_in, int count_in, const int *bm_override, hipStream_t s,
+                                     hipEvent_t done)
 {
     if (count_in < 0 || count_in > PP_MAX_GROUP) return hipErrorInvalidValue;
     GemmArgs a[PP_MAX_GROUP];
@@ -229,7 +230,7 @@ hipError_t launch_gemm_bf16_pp_group(int layout, const GemmArgs *a_in, int count
         forced[count] = bm_override ? bm_override[q] : 0;
         a[count++] = a_in[q];
     }
-    if (count == 0) return hipSuccess;
+    if (count == 0) return done ? hipEventRecord(done, s) : hipSuccess; // nothing to launch: the event still marks this point
     const Plan pl = plan_group(layout, a, count, forced, count == 1 ? a[0].cu_share : 1);
     const int *bm = pl.bm, *order = pl.order;
 
@@ -254,16 +255,16 @@ hipError_t launch_gemm_bf16_pp_group(int layout, const GemmArgs *a_in, int count
     const unsigned blocks = per_xcd * 8;
     const bool f16 = a[0].elem == ELEM_F16;
     switch (layout) {
-    case LAY_NT: return f16 ? launch_gemm_pp_nt_f16(g, blocks, s) : launch_gemm_pp_nt_bf16(g, blocks, s);
-    case LAY_NN: return f16 ? launch_gemm_pp_nn_f16(g, blocks, s) : launch_gemm_pp_nn_bf16(g, blocks, s);
-    case LAY_TN: return f16 ? launch_gemm_pp_tn_f16(g, blocks, s) : launch_gemm_pp_tn_bf16(g, blocks, s);
+    case LAY_NT: return f16 ? launch_gemm_pp_nt_f16(g, blocks, s, done) : launch_gemm_pp_nt_bf16(g, blocks, s, done);
+    case LAY_NN: return f16 ? launch_gemm_pp_nn_f16(g, blocks, s, done) : launch_gemm_pp_nn_bf16(g, blocks, s, done);
+    case LAY_TN: return f16 ? launch_gemm_pp_tn_f16(g, blocks, s, done) : launch_gemm_pp_tn_bf16(g, blocks, s, done);
     default: return hipErrorInvalidValue;
     }
 }
 
 hipError_t launch_gemm_bf16_pp(int layout, const GemmArgs &a, int bm_override, hipStream_t s)
 {
-    return launch_gemm_bf16_pp_group(layout, &a, 1, &bm_override, s);
+    return launch_gemm_bf16_pp_group(layout, &a, 1, &bm_override, s, nullptr);
 }
 
 } // namespace rtp

@@ -2,8 +2,8 @@
 #include "rtp_gemm_pp.h"
 
 namespace rtp {
-hipError_t launch_gemm_pp_nt_bf16(const PpGroup &g, unsigned blocks, hipStream_t s)
+hipError_t launch_gemm_pp_nt_bf16(const PpGroup &g, unsigned blocks, hipStream_t s, hipEvent_t done)
 {
-    return launch_gemm_pp_layout<LAY_NT, __bf16>(g, blocks, s);
+    return launch_gemm_pp_layout<LAY_NT, __bf16>(g, blocks, s, done);
 }
 } // namespace rtp

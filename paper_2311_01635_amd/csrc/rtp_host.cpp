@@ -1573,13 +1573,24 @@ static bool mlp_grouped_ok(const rtp_mlp *m, const void *X, const void *Y, const
     return true;
 }
 
-static rtp_status gemm_group(rtp_ring *r, int layout, const GemmArgs *a, int count, hipStream_t st)
+// done (may be null): an event that marks the end of this launch on its stream, as a record right after the
+// launch would, but carried by the kernel's own completion signal when there is a kernel
+static rtp_status gemm_group(rtp_ring *r, int layout, const GemmArgs *a, int count, hipStream_t st, hipEvent_t done = nullptr)
 {
-    if (r->dry || !r->abl_compute || count == 0) return RTP_OK;
+    if (r->dry) return RTP_OK;
+    if (!r->abl_compute || count == 0) {
+        if (done) HIP_TRY(hipEventRecord(done, st));
+        return RTP_OK;
+    }
     RTP_TRY(aux_delay(r, st));
     double flops = 0.0;
     for (int i = 0; i < count; ++i) flops += 2.0 * a[i].M * a[i].N * a[i].K;
-    HIP_TRY(timed_launch(layout, flops, st, [&] { return launch_gemm_bf16_pp_group(layout, a, count, nullptr, st); }));
+    if (g_prof_on) { // the timing events bracket the launch; the caller's event follows them
+        HIP_TRY(timed_launch(layout, flops, st, [&] { return launch_gemm_bf16_pp_group(layout, a, count, nullptr, st); }));
+        if (done) HIP_TRY(hipEventRecord(done, st));
+        return RTP_OK;
+    }
+    HIP_TRY(launch_gemm_bf16_pp_group(layout, a, count, nullptr, st, done));
     return RTP_OK;
 }
 
@@ -1650,8 +1661,13 @@ static rtp_status mlp_fwd_grouped(rtp_mlp *m, const void *X, void *Y)
         // the lagging linear's part of shard t (its buffer was last read by down_{t-2}) and the
         // leading linear's part of shard t+1 (last reader of its buffer: Z_{t-1})
         const bool move_w2 = rot && t >= 1 && t <= n - 1, move_w1 = rot && t <= n - 2;
+        if (rot && t >= 1) HIP_TRY(hipStreamWaitEvent(r->cs(), r->ev_w[t & 1], 0));
         if (move_w1 || move_w2) {
-            RTP_TRY(stage_after_compute(r));
+            // after launch t-1, which carries ev_free (t = 0: after the load of the own shard, if there was one)
+            if (t >= 1)
+                HIP_TRY(hipStreamWaitEvent(r->ss(), r->ev_free, 0));
+            else
+                RTP_TRY(stage_after_compute(r));
             CopyBatch b; // four transfers, no two on the same bytes: one launch
             if (move_w2)
                 RTP_TRY(rotate_w_part(r, b, t - 1, r->shard_at(t - 1), r->shard_at(t), r->w_idx(t - 1), r->w_idx(t), h.w_off2, w2_bytes));
@@ -1660,7 +1676,6 @@ static rtp_status mlp_fwd_grouped(rtp_mlp *m, const void *X, void *Y)
             RTP_TRY(copy_batch_flush(r, b, r->ss()));
             HIP_TRY(hipEventRecord(r->ev_w[(t + 1) & 1], r->ss()));
         }
-        if (rot && t >= 1) HIP_TRY(hipStreamWaitEvent(r->cs(), r->ev_w[t & 1], 0));
         GemmArgs g[2];
         int cnt = 0;
         if (t < n) {
@@ -1669,8 +1684,10 @@ static rtp_status mlp_fwd_grouped(rtp_mlp *m, const void *X, void *Y)
         }
         if (t >= 1) g[cnt++] = mlp_args_down(m, h, r->shard_at(t - 1), t - 1, buf(t - 1), Y);
         if (t >= 2) RTP_TRY(mlp_bias2_add(m, h, r->shard_at(t - 1), buf(t - 1), r->cs()));
-        RTP_TRY(gemm_group(r, LAY_NT, g, cnt, r->cs()));
+        const bool bias_after = t == 1 && h.has_bias && h.n > 1;
+        RTP_TRY(gemm_group(r, LAY_NT, g, cnt, r->cs(), rot && !bias_after ? r->ev_free : nullptr));
         if (t == 1) RTP_TRY(mlp_bias2_add(m, h, r->shard_at(0), buf(0), r->cs())); // the sum exists from here on
+        if (rot && bias_after) HIP_TRY(hipEventRecord(r->ev_free, r->cs()));
     }
     mlp_close_pass(m);
     return rtp_ring_end(r);
@@ -1701,7 +1718,9 @@ static rtp_status mlp_bwd_grouped(rtp_mlp *m, const void *X, const void *dY, voi
         // ---- weights of shard s+1: their buffer was last read by dX_{s-1}, just enqueued ----
         if (rot && s <= n - 2) {
             RTP_TRY(stage_after_compute(r));
-            RTP_TRY(rotate_w_part(r, s, r->shard_at(s), r->shard_at(s + 1), r->w_idx(s), r->w_idx(s + 1), 0, r->d.w_bytes));
+            CopyBatch b;
+            RTP_TRY(rotate_w_part(r, b, s, r->shard_at(s), r->shard_at(s + 1), r->w_idx(s), r->w_idx(s + 1), 0, r->d.w_bytes));
+            RTP_TRY(copy_batch_flush(r, b, r->ss()));
             HIP_TRY(hipEventRecord(r->ev_w[(s + 1) & 1], r->ss()));
         }
         // ---- weight-gradient launch s = {G1_s, G2_s}, onto the travelling gradient shard ----
@@ -1736,9 +1755,17 @@ static rtp_status mlp_bwd_grouped(rtp_mlp *m, const void *X, const void *dY, voi
             const int k = r->shard_at(s), kin = r->shard_at(s + 1);
             HIP_TRY(hipEventRecord(r->ev_free2, ws));
             HIP_TRY(hipStreamWaitEvent(r->ss(), r->ev_free2, 0));
-            if (!fused_send) RTP_TRY(copy_async(r, r->home_g(k), r->d.buf_g_dev[r->g_idx(s)], r->d.g_bytes, r->ss()));
+            if (r->g_idx(s) != r->g_idx(s + 1)) {
+                // two buffers: the next shard comes into the other one, the two transfers are one launch
+                CopyBatch b;
+                RTP_TRY(copy_batch_add(r, b, r->d.buf_g_dev[r->g_idx(s + 1)], r->home_g(kin), r->d.g_bytes, r->ss()));
+                if (!fused_send) RTP_TRY(copy_batch_add(r, b, r->home_g(k), r->d.buf_g_dev[r->g_idx(s)], r->d.g_bytes, r->ss()));
+                RTP_TRY(copy_batch_flush(r, b, r->ss()));
+            } else {
+                if (!fused_send) RTP_TRY(copy_async(r, r->home_g(k), r->d.buf_g_dev[r->g_idx(s)], r->d.g_bytes, r->ss()));
+                RTP_TRY(copy_async(r, r->d.buf_g_dev[r->g_idx(s + 1)], r->home_g(kin), r->d.g_bytes, r->ss()));
+            }
             r->rec(TR_G_OUT, s, k, r->g_idx(s));
-            RTP_TRY(copy_async(r, r->d.buf_g_dev[r->g_idx(s + 1)], r->home_g(kin), r->d.g_bytes, r->ss()));
             r->rec(TR_G_IN, s, kin, r->g_idx(s + 1));
             HIP_TRY(hipEventRecord(r->ev_g[(s + 1) & 1], r->ss()));
         }
@@ -1773,7 +1800,8 @@ static rtp_status mlp_bwd_two_stream(rtp_mlp *m, const void *X, const void *dY, 
     auto gbuf = [&](int step) { return (char *)r->d.buf_g_dev[gidx(step)]; };
 
     // a weight-gradient kernel; the send of its part of the gradient shard is fused into it when the shard moves on
-    auto emit_dw = [&](int s, GemmArgs a, size_t off, bool first, bool *fused) -> rtp_status {
+    // (mark: ev_free2 completes with the kernel, or with the bias sums that follow it, when a transfer waits for it)
+    auto emit_dw = [&](int s, GemmArgs a, size_t off, bool first, bool *fused, bool mark) -> rtp_status {
         const bool moves_on = move_g && s <= n - 2;
         bool fused_send = moves_on && r->abl_compute;
         if (fused_send) {
@@ -1786,16 +1814,17 @@ static rtp_status mlp_bwd_two_stream(rtp_mlp *m, const void *X, const void *dY, 
             a.C = r->home_g(r->shard_at(s)) + off;
         }
         a.cu_share = 2;
-        RTP_TRY(gemm_group(r, LAY_TN, &a, 1, as));
+        RTP_TRY(gemm_group(r, LAY_TN, &a, 1, as, mark && !h.has_bias ? r->ev_free2 : nullptr));
         RTP_TRY(mlp_bias_grads(m, h, r->shard_at(s), gbuf(s), fused_send ? r->home_g(r->shard_at(s)) : nullptr, dY, first, !first, as));
+        if (mark && h.has_bias && !r->dry) HIP_TRY(hipEventRecord(r->ev_free2, as));
         *fused = fused_send;
         return RTP_OK;
     };
-    // stage stream, after the auxiliary stream's kernels so far: part [off, off + bytes) of gradient shard s goes
+    // stage stream, after the weight-gradient kernel that carries ev_free2: part [off, off + bytes) of gradient shard s goes
     // out (unless its kernel has sent it) and the same part of shard s+1 comes into buffer gidx(s+1)
     auto exchange_g = [&](int s, size_t off, size_t bytes, bool out_by_copy, hipEvent_t landed, bool whole) -> rtp_status {
         const int k = r->shard_at(s), kin = r->shard_at(s + 1);
-        RTP_TRY(stream_after(r->ev_free2, ss, as));
+        HIP_TRY(hipStreamWaitEvent(ss, r->ev_free2, 0));
         CopyBatch b;
         if (two_g) {
             RTP_TRY(copy_batch_add(r, b, gbuf(s + 1) + off, r->home_g(kin) + off, bytes, ss));
@@ -1816,7 +1845,7 @@ static rtp_status mlp_bwd_two_stream(rtp_mlp *m, const void *X, const void *dY, 
         const int k = r->shard_at(s);
         // ---- weights of step s+1: their buffer was last read by dPre_{s-1} and dX_{s-1}
         if (rot && s <= n - 2) {
-            if (s >= 1) RTP_TRY(stream_after(r->ev_free, ss, cs)); // (step 0: rtp_ring_begin has ordered the streams)
+            if (s >= 1) HIP_TRY(hipStreamWaitEvent(ss, r->ev_free, 0)); // dX_{s-1} carries ev_free (step 0: rtp_ring_begin has ordered the streams)
             CopyBatch b;
             RTP_TRY(rotate_w_part(r, b, s, k, r->shard_at(s + 1), r->w_idx(s), r->w_idx(s + 1), 0, r->d.w_bytes));
             RTP_TRY(copy_batch_flush(r, b, ss));
@@ -1827,20 +1856,19 @@ static rtp_status mlp_bwd_two_stream(rtp_mlp *m, const void *X, const void *dY, 
         r->rec(TR_BWD, s, k, rot ? r->w_idx(s) : r->res_idx);
         GemmArgs a = mlp_args_dh(m, h, k, wbuf(s), dY);
         a.cu_share = 2;
-        RTP_TRY(gemm_group(r, LAY_NN, &a, 1, cs));
-        HIP_TRY(hipEventRecord(r->ev_k[s & 1], cs));
+        RTP_TRY(gemm_group(r, LAY_NN, &a, 1, cs, r->ev_k[s & 1]));
         a = mlp_args_dx(m, h, k, s, wbuf(s), dX);
         a.cu_share = 2;
-        RTP_TRY(gemm_group(r, LAY_NN, &a, 1, cs));
+        RTP_TRY(gemm_group(r, LAY_NN, &a, 1, cs, rot && s <= n - 2 ? r->ev_free : nullptr));
         // ---- weight gradients, onto the travelling gradient shard
         const bool moves_on = move_g && s <= n - 2;
         bool sent2 = false, sent1 = false;
         if (move_g && s >= 1) HIP_TRY(hipStreamWaitEvent(as, (two_g ? r->ev_g : r->ev_g2)[s & 1], 0));
-        RTP_TRY(emit_dw(s, mlp_args_dw2(m, h, k, gbuf(s), dY), h.g_off2, false, &sent2));
+        RTP_TRY(emit_dw(s, mlp_args_dw2(m, h, k, gbuf(s), dY), h.g_off2, false, &sent2, moves_on && !two_g));
         if (moves_on && !two_g) RTP_TRY(exchange_g(s, h.g_off2, g2_bytes, !sent2, r->ev_g2[(s + 1) & 1], false));
         HIP_TRY(hipStreamWaitEvent(as, r->ev_k[s & 1], 0));
         if (move_g && s >= 1 && !two_g) HIP_TRY(hipStreamWaitEvent(as, r->ev_g[s & 1], 0));
-        RTP_TRY(emit_dw(s, mlp_args_dw1(m, h, k, gbuf(s), X), 0, true, &sent1));
+        RTP_TRY(emit_dw(s, mlp_args_dw1(m, h, k, gbuf(s), X), 0, true, &sent1, moves_on));
         if (moves_on && !two_g) RTP_TRY(exchange_g(s, 0, g1_bytes, !sent1, r->ev_g[(s + 1) & 1], false));
         if (moves_on && two_g) {
             // two buffers: the whole shard at once (a part its kernel did not send goes out by copy)
@@ -1848,7 +1876,7 @@ static rtp_status mlp_bwd_two_stream(rtp_mlp *m, const void *X, const void *dY, 
                 RTP_TRY(exchange_g(s, 0, r->d.g_bytes, !sent1, r->ev_g[(s + 1) & 1], true));
             } else {
                 const int kk = r->shard_at(s), kin = r->shard_at(s + 1);
-                RTP_TRY(stream_after(r->ev_free2, ss, as));
+                HIP_TRY(hipStreamWaitEvent(ss, r->ev_free2, 0));
                 CopyBatch b;
                 RTP_TRY(copy_batch_add(r, b, gbuf(s + 1), r->home_g(kin), r->d.g_bytes, ss));
                 if (!sent1) RTP_TRY(copy_batch_add(r, b, r->home_g(kk), gbuf(s), g1_bytes, ss));

@@ -67,7 +67,9 @@ hipError_t launch_gemm_bf16_pp(int layout, const GemmArgs &a, int bm_override, h
 // adds, so the order of that sum is not fixed), are picked for the group as a whole (bm_override: null, or one forced height per problem, 0 = pick).
 // hipErrorInvalidValue if a problem does not meet gemm_bf16_pp_supported.
 constexpr int PP_MAX_GROUP = 4;
-hipError_t launch_gemm_bf16_pp_group(int layout, const GemmArgs *a, int count, const int *bm_override, hipStream_t s);
+// done (may be null): an event that completes when the launch does, as if recorded right after it
+hipError_t launch_gemm_bf16_pp_group(int layout, const GemmArgs *a, int count, const int *bm_override, hipStream_t s,
+                                     hipEvent_t done = nullptr);
 // the tile heights and K splits that launch would use (either output may be null)
 void gemm_bf16_pp_plan(int layout, const GemmArgs *a, int count, const int *bm_override, int *bm_out, int *ksplit_out);
 // column tiles the tiled kernel cuts a problem into (what a producer problem adds to each row block's counter)
