@@ -49,6 +49,7 @@
 // stored), K must be a multiple of 32.
 #pragma once
 #include "rtp_gemm_epilogue.h"
+#include <type_traits>
 #include <hip/hip_ext.h>
 
 namespace rtp {
@@ -302,50 +303,90 @@ __device__ __forceinline__ void pp_tile(const GemmArgs &p, const int tiles_m, co
     end_slot_after_loads();
     if (group == 1) asm volatile("s_barrier" ::: "memory"); // start one slot late
 
+    // ---- which of this wave's fragments hold anything: a tile on the matrix edge (N = 1376 is 5.4 tile columns)
+    // has fragment rows / columns that lie wholly outside; their MFMAs and LDS reads are skipped.  On a part whose
+    // clock follows the switching activity that is energy for the other tiles, and the edge tile itself ends sooner.
+    // All of it is wave-uniform scalar state; interior waves run the loop without a single test.
+    const int iv = max(0, min(FM, (M - (m0 + wm * (BM / WM)) + 31) / 32)); // valid fragment rows: 0 .. iv-1
+    bool jv[FN];
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+        jv[j] = paired ? (n0 + wn * 32 < half) : (n0 + j * (WN * 32) + wn * 32 < N);
+    const bool interior = iv == FM && jv[0] && jv[FN - 1];
+
     frag8 af[2][FM], bf[2][FN];
-    for (int kt = 0; kt < KT; ++kt) {
-        // ---- memory slot ------------------------------------------------------------------
-        const unsigned stage_off = (unsigned)((kt % STAGES) * STAGE);
-        const char *sa = smem + stage_off;
-        const char *sb = sa + A_BYTES;
+    auto k_loop = [&](auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        if (!FULL) {
+            // fragments that are never read must still be defined where the compiler sees them used
 #pragma unroll
-        for (int f = 0; f < FM; ++f) {
-            if (A_KC) {
-                af[0][f] = frag_kc(sa, a_off[f], 0);
-                af[1][f] = frag_kc(sa, a_off[f], 1);
-            } else {
-                af[0][f] = frag_mc_read<frag8, 0, A_ROWB>(a_tr[f] + stage_off);
-                af[1][f] = frag_mc_read<frag8, 1, A_ROWB>(a_tr[f] + stage_off);
-            }
+            for (int f = 0; f < FM; ++f) af[0][f] = af[1][f] = frag8{};
+#pragma unroll
+            for (int f = 0; f < FN; ++f) bf[0][f] = bf[1][f] = frag8{};
         }
+        for (int kt = 0; kt < KT; ++kt) {
+            // ---- memory slot ------------------------------------------------------------------
+            const unsigned stage_off = (unsigned)((kt % STAGES) * STAGE);
+            const char *sa = smem + stage_off;
+            const char *sb = sa + A_BYTES;
 #pragma unroll
-        for (int f = 0; f < FN; ++f) {
-            if (B_KC) {
-                bf[0][f] = frag_kc(sb, b_off[f], 0);
-                bf[1][f] = frag_kc(sb, b_off[f], 1);
-            } else {
-                bf[0][f] = frag_mc_read<frag8, 0, 512>(b_tr[f] + stage_off);
-                bf[1][f] = frag_mc_read<frag8, 1, 512>(b_tr[f] + stage_off);
+            for (int f = 0; f < FM; ++f) {
+                if (!FULL && f >= iv) continue;
+                if (A_KC) {
+                    af[0][f] = frag_kc(sa, a_off[f], 0);
+                    af[1][f] = frag_kc(sa, a_off[f], 1);
+                } else {
+                    af[0][f] = frag_mc_read<frag8, 0, A_ROWB>(a_tr[f] + stage_off);
+                    af[1][f] = frag_mc_read<frag8, 1, A_ROWB>(a_tr[f] + stage_off);
+                }
             }
-        }
-        issue(kt + PF);
-        // own loads of sub-tile kt+1 have landed, fragments are in registers
-        end_slot_after_loads();
-        __builtin_amdgcn_sched_barrier(0); // nothing may drift across a slot boundary
-        // ---- compute slot -------------------------------------------------------------------
-        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
+            for (int f = 0; f < FN; ++f) {
+                if (!FULL && !jv[f]) continue;
+                if (B_KC) {
+                    bf[0][f] = frag_kc(sb, b_off[f], 0);
+                    bf[1][f] = frag_kc(sb, b_off[f], 1);
+                } else {
+                    bf[0][f] = frag_mc_read<frag8, 0, 512>(b_tr[f] + stage_off);
+                    bf[1][f] = frag_mc_read<frag8, 1, 512>(b_tr[f] + stage_off);
+                }
+            }
+            issue(kt + PF);
+            // own loads of sub-tile kt+1 have landed, fragments are in registers
+            end_slot_after_loads();
+            __builtin_amdgcn_sched_barrier(0); // nothing may drift across a slot boundary
+            // ---- compute slot -------------------------------------------------------------------
+            __builtin_amdgcn_s_setprio(1);
+            if (FULL) {
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
+                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                    for (int i = 0; i < FM; ++i)
+#pragma unroll
+                        for (int j = 0; j < FN; ++j)
+                            acc[i][j] = mfma_32x32x16(af[ks][i], bf[ks][j], acc[i][j]);
+            } else {
 #pragma unroll
                 for (int j = 0; j < FN; ++j)
-                    acc[i][j] = mfma_32x32x16(af[ks][i], bf[ks][j], acc[i][j]);
-        __builtin_amdgcn_s_setprio(0);
-        __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_barrier" ::: "memory");
-        __builtin_amdgcn_sched_barrier(0);
-    }
+                    if (jv[j]) {
+#pragma unroll
+                        for (int i = 0; i < FM; ++i)
+                            if (i < iv) {
+                                acc[i][j] = mfma_32x32x16(af[0][i], bf[0][j], acc[i][j]);
+                                acc[i][j] = mfma_32x32x16(af[1][i], bf[1][j], acc[i][j]);
+                            }
+                    }
+            }
+            __builtin_amdgcn_s_setprio(0);
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_barrier" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    if (interior)
+        k_loop(std::true_type{});
+    else
+        k_loop(std::false_type{});
     if (group == 0) asm volatile("s_barrier" ::: "memory"); // every wave passes the same number of barriers
     // the refetches past the end may still be landing in LDS: drain everybody's before LDS is reused
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
