@@ -78,11 +78,31 @@ static double epilogue_steps(int epi, int c_is_f32)
     }
 }
 
-static double tile_cost(const GemmArgs &a, int bm, int ksplit)
+// frac: the share of the K loop's MFMA time an edge tile still needs (1 for an interior tile), area: the share
+// of the tile that exists (scales the epilogue's traffic)
+static double tile_cost(const GemmArgs &a, int bm, int ksplit, double frac = 1.0, double area = 1.0)
 {
     const double handicap = bm == 256 ? 1.0 : bm == 192 ? 1.04 : 1.12;
     const int kt = a.K / 32, each = (kt + ksplit - 1) / ksplit;
-    return handicap * (bm / 256.0) * (each + epilogue_steps(ksplit > 1 ? EPI_ACC_ATOMIC : a.epi, a.c_is_f32));
+    // (an edge tile still fetches whole sub-tiles and passes every barrier: a floor under its loop time)
+    const double loop = each * std::max(frac, 0.35);
+    return handicap * (bm / 256.0) * (loop + area * epilogue_steps(ksplit > 1 ? EPI_ACC_ATOMIC : a.epi, a.c_is_f32));
+}
+
+// The kernel skips the fragments of an edge tile that lie wholly outside the matrix; the tile then runs as long
+// as its busiest wave.  Waves split the tile's rows in two halves (BM / 64 fragment rows each) and hold two
+// fragment columns 128 apart (gate / up halves of the paired epilogue: always both or none).
+static void edge_shares(const GemmArgs &a, int bm, double *frac_m, double *area_m, double *frac_n, double *area_n)
+{
+    const int tm = (a.M + bm - 1) / bm, vr = a.M - (tm - 1) * bm; // valid rows of the last tile row
+    const int fm = bm / 64;
+    *frac_m = vr >= bm / 2 ? 1.0 : (double)((vr + 31) / 32) / fm;
+    *area_m = (double)vr / bm;
+    const bool paired = a.epi == EPI_SWIGLU_FWD;
+    const int ncols = paired ? a.half : a.N, bn = paired ? 128 : 256;
+    const int tn = (ncols + bn - 1) / bn, vc = ncols - (tn - 1) * bn;
+    *frac_n = paired || vc > 128 ? 1.0 : 0.5;
+    *area_n = (double)vc / bn;
 }
 
 // A problem may have its K loop cut into chunks when its result is an fp32 sum onto an accumulator
@@ -104,15 +124,29 @@ static double makespan(const GemmArgs *a, const int *bm, const int *ks, const in
     for (int i = 0; i < count; ++i) {
         const int q = order[i];
         const int kt = a[q].K / 32, each = (kt + ks[q] - 1) / ks[q], chunks = (kt + each - 1) / each;
-        const long tiles = (long)((a[q].M + bm[q] - 1) / bm[q]) * tiles_n_of(a[q]) * chunks;
+        const long tm = (a[q].M + bm[q] - 1) / bm[q], tn = tiles_n_of(a[q]);
+        const long tiles = tm * tn * chunks;
         const long mine = (tiles + 7) / 8;
-        const double c = tile_cost(a[q], bm[q], ks[q]);
-        for (long t = 0; t < mine; ++t) {
-            const double start = free_at.top();
-            free_at.pop();
-            free_at.push(start + c);
-            end = std::max(end, start + c);
+        // interior tiles, then the last tile column, the last tile row and the corner, each with its own cost
+        double fm, am, fn, an;
+        edge_shares(a[q], bm[q], &fm, &am, &fn, &an);
+        const double cost[4] = {tile_cost(a[q], bm[q], ks[q]), tile_cost(a[q], bm[q], ks[q], fn, an),
+                                tile_cost(a[q], bm[q], ks[q], fm, am), tile_cost(a[q], bm[q], ks[q], fm * fn, am * an)};
+        const long cls[4] = {(tm - 1) * (tn - 1) * chunks, (tm - 1) * chunks, (tn - 1) * chunks, (long)chunks};
+        // this XCD's share of each class: the edge classes rounded up, the interior takes the rest
+        long cnt[4] = {0, 0, 0, 0}, left = mine;
+        for (int c = 3; c >= 1; --c) {
+            cnt[c] = std::min(left, (cls[c] * mine + tiles - 1) / tiles);
+            left -= cnt[c];
         }
+        cnt[0] = left;
+        for (int c = 0; c < 4; ++c)
+            for (long t = 0; t < cnt[c]; ++t) {
+                const double start = free_at.top();
+                free_at.pop();
+                free_at.push(start + cost[c]);
+                end = std::max(end, start + cost[c]);
+            }
     }
     return end;
 }
