@@ -207,17 +207,20 @@ def timed(torch, mlp, X, Y, dY, dX, steps, per_pass=None):
     that stream holds and the stream continues after the pass (whose stage and auxiliary streams are joined into its
     compute stream when it ends), so the pair brackets all the work of every stream.  With a list in `per_pass`, an
     event between passes as well: the list receives each pass's own duration."""
-    s = torch.cuda.current_stream()
+    # The caller runs on the unit's own compute stream (as a training loop that owns the layer would): the pass then
+    # needs no hop between the caller's stream and the layer's.  A unit of several layers has no single such stream.
+    s = getattr(mlp, "compute_stream", None) or torch.cuda.current_stream()
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1 if per_pass is not None else 2)]
     torch.cuda.synchronize()
-    marks[0].record(s)
-    for i in range(steps):
-        mlp.forward(X, Y)
-        mlp.backward(X, dY, dX)
-        if per_pass is not None:
-            marks[i + 1].record(s)
-    if per_pass is None:
-        marks[1].record(s)
+    with torch.cuda.stream(s):
+        marks[0].record(s)
+        for i in range(steps):
+            mlp.forward(X, Y)
+            mlp.backward(X, dY, dX)
+            if per_pass is not None:
+                marks[i + 1].record(s)
+        if per_pass is None:
+            marks[1].record(s)
     mlp.sync()
     torch.cuda.synchronize()
     if per_pass is not None:

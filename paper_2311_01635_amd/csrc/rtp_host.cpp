@@ -237,6 +237,8 @@ struct rtp_ring {
     rtp_pass pass = RTP_PASS_IDLE;
     int resident = -1;   // shard whose weights are in buf_w[res_idx]
     int res_idx = 0;
+    bool joined = false;      // nothing has been enqueued on the stage / auxiliary stream since rtp_ring_end joined them
+    bool pass_uses_as = true; // the open pass enqueues on the auxiliary stream (a schedule that does not says so)
     bool w_held = false; // buf_w[res_idx] really holds shard `resident` as the store has it (not after a flush,
                          // an abort, or a pass run with the rotation switched off)
     int res_g = -1;      // shard whose gradients are in buf_g[res_g_idx]
@@ -391,6 +393,20 @@ static rtp_status cross_join(rtp_ring *r)
     return RTP_OK;
 }
 
+// Start of a pass: the stage and auxiliary streams wait for everything the compute stream holds (the caller's
+// inputs were produced there); the other direction only if they may hold work the compute stream has not yet
+// waited for (rtp_ring_end joins them, and only passes enqueue on them).
+static rtp_status begin_join(rtp_ring *r)
+{
+    if (r->dry) return RTP_OK;
+    if (!r->joined) return cross_join(r);
+    r->joined = false;
+    HIP_TRY(hipEventRecord(r->ev_join, r->cs()));
+    if (r->ss() != r->cs()) HIP_TRY(hipStreamWaitEvent(r->ss(), r->ev_join, 0));
+    if (r->as() != r->cs()) HIP_TRY(hipStreamWaitEvent(r->as(), r->ev_join, 0));
+    return RTP_OK;
+}
+
 // A pass cannot be recorded into a HIP graph (the calls decide on the host what they enqueue, on
 // three streams): refuse, before anything is enqueued, when one of the ring's streams is capturing.
 static rtp_status refuse_capture(const rtp_ring *r, const char *who)
@@ -515,7 +531,8 @@ extern "C" rtp_status rtp_ring_begin(rtp_ring *r, rtp_pass pass)
                     (rank + 1) % n, r->resident);
     RTP_TRY(refuse_capture(r, "rtp_ring_begin"));
     RTP_TRY(ensure_events(r));
-    RTP_TRY(cross_join(r));
+    RTP_TRY(begin_join(r));
+    r->joined = false;
     r->pass = pass;
     r->rotations = 0;
     r->executed = 0;
@@ -723,11 +740,13 @@ extern "C" rtp_status rtp_ring_end(rtp_ring *r)
             HIP_TRY(hipEventRecord(r->ev_join, r->ss()));
             HIP_TRY(hipStreamWaitEvent(r->cs(), r->ev_join, 0));
         }
-        if (r->cs() != r->as()) {
+        if (r->cs() != r->as() && r->pass_uses_as) {
             HIP_TRY(hipEventRecord(r->ev_join, r->as()));
             HIP_TRY(hipStreamWaitEvent(r->cs(), r->ev_join, 0));
         }
+        r->joined = true;
     }
+    r->pass_uses_as = true;
     return RTP_OK;
 }
 
@@ -738,6 +757,8 @@ extern "C" rtp_status rtp_ring_abort(rtp_ring *r)
     // whatever the streams still hold runs to its end before anybody reuses the buffers
     rtp_status st = (r->dry || !r->events_ready) ? RTP_OK : cross_join(r);
     r->pass = RTP_PASS_IDLE;
+    r->joined = false;
+    r->pass_uses_as = true;
     r->resident = -1;
     r->w_held = false;
     r->res_g = -1;
@@ -1652,6 +1673,7 @@ static rtp_status mlp_fwd_grouped(rtp_mlp *m, const void *X, void *Y)
     const int n = r->d.n;
     const MlpShapes h = mlp_shapes(m);
     RTP_TRY(rtp_ring_begin(r, RTP_PASS_FWD));
+    r->pass_uses_as = false; // everything below runs on the compute and the stage stream
     const bool rot = r->abl_rotate && n > 1;
     const size_t w1_bytes = h.w_off2, w2_bytes = r->d.w_bytes - h.w_off2;
     auto buf = [&](int step) { return (const char *)r->d.buf_w_dev[rot ? r->w_idx(step) : r->res_idx]; };

@@ -18,13 +18,18 @@ class _PassStreams:
     """Orders a layer's private streams with the caller's: a pass starts after everything the
     caller's current stream holds (X, dY or the routing may just have been produced there) and the
     caller's stream continues after the pass (rtp_ring_end has joined the stage and auxiliary
-    streams into the compute stream)."""
+    streams into the compute stream).  A caller whose current stream IS the layer's compute stream
+    (`with torch.cuda.stream(layer.compute_stream):`) skips both hops."""
 
     def _enter(self):
-        self.compute_stream.wait_stream(torch.cuda.current_stream(self.dev))
+        cur = torch.cuda.current_stream(self.dev)
+        if cur != self.compute_stream:        # a caller that runs on the layer's compute stream needs no hop
+            self.compute_stream.wait_stream(cur)
 
     def _leave(self):
-        torch.cuda.current_stream(self.dev).wait_stream(self.compute_stream)
+        cur = torch.cuda.current_stream(self.dev)
+        if cur != self.compute_stream:
+            cur.wait_stream(self.compute_stream)
 
 
 class _Store:
