@@ -1826,6 +1826,7 @@ static rtp_status mlp_bwd_two_stream(rtp_mlp *m, const void *X, const void *dY, 
     auto emit_dw = [&](int s, GemmArgs a, size_t off, bool first, bool *fused, bool mark) -> rtp_status {
         const bool moves_on = move_g && s <= n - 2;
         bool fused_send = moves_on && r->abl_compute;
+        a.cu_share = 2; // (before the plan is asked for: the launcher plans with it)
         if (fused_send) {
             int ks = 1;
             gemm_bf16_pp_plan(LAY_TN, &a, 1, nullptr, nullptr, &ks);
@@ -1835,7 +1836,6 @@ static rtp_status mlp_bwd_two_stream(rtp_mlp *m, const void *X, const void *dY, 
             a.epi = EPI_ACC_LAST;
             a.C = r->home_g(r->shard_at(s)) + off;
         }
-        a.cu_share = 2;
         RTP_TRY(gemm_group(r, LAY_TN, &a, 1, as, mark && !h.has_bias ? r->ev_free2 : nullptr));
         RTP_TRY(mlp_bias_grads(m, h, r->shard_at(s), gbuf(s), fused_send ? r->home_g(r->shard_at(s)) : nullptr, dY, first, !first, as));
         if (mark && h.has_bias && !r->dry) HIP_TRY(hipEventRecord(r->ev_free2, as));
