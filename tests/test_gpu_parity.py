@@ -450,6 +450,39 @@ def test_cleared_gradients_start_from_zero(mode, how):
     layer.close()
 
 
+@pytest.mark.parametrize("mode", [B.RTP_DOUBLE_BUFFER, B.RTP_INPLACE_STAGED, B.RTP_INPLACE_BLOCKING])
+def test_weights_written_after_a_flush_are_the_ones_the_next_pass_uses(mode):
+    """An optimizer step on the weights: a backward pass leaves the worker's own shard in its buffer and the
+    next forward pass starts on it without loading it; after rtp_ring_flush the caller may write to the weight
+    store, and the next pass must compute with what it wrote, own shard included (integer inputs: bit-exact)."""
+    T, I, O, n, rank = 256, 512, 1024, 4, 2
+    g = torch.Generator(device="cpu").manual_seed(6)
+    ri = lambda lo, hi, shape: torch.randint(lo, hi, shape, generator=g).float()
+    W, X, dY = ri(-2, 3, (O, I)), ri(-2, 3, (T, I)), ri(-2, 3, (T, O))
+    layer = RtpLinear(W.to(DEV, torch.bfloat16), T, n, rank, B.RTP_SPLIT_OUT, mode, B.RTP_BF16)
+    Xd, dYd = X.to(DEV, torch.bfloat16), dY.to(DEV, torch.bfloat16)
+    Y = torch.empty(T, O, device=DEV, dtype=torch.bfloat16)
+    dX = torch.empty(T, I, device=DEV, dtype=torch.bfloat16)
+    for _ in range(2):                                   # the second pass starts on the shard the first one ended on
+        layer.forward(Xd, Y)
+        layer.backward(Xd, dYd, dX)
+    layer.sync()
+    assert torch.equal(Y.cpu(), (X.double() @ W.double().T).to(torch.bfloat16))
+    layer.ring.flush()
+    layer.sync()
+    W2 = W - ri(-1, 2, (O, I))                           # "W -= lr * G", every shard touched
+    layer.store_w.pack("W", W2.to(DEV, torch.bfloat16), 0, B.RTP_SPLIT_OUT, layer.o)
+    torch.cuda.synchronize()
+    layer.forward(Xd, Y)
+    layer.backward(Xd, dYd, dX)
+    layer.sync()
+    assert torch.equal(Y.cpu(), (X.double() @ W2.double().T).to(torch.bfloat16))
+    assert torch.equal(dX.cpu(), (dY.double() @ W2.double()).to(torch.bfloat16))
+    Wb, _ = layer.gathered()
+    assert torch.equal(Wb.cpu().float(), W2)
+    layer.close()
+
+
 def test_degenerate_partitions():
     # n = 1 is the plain linear; one token; n equal to the number of 8-wide column groups
     for (T, I, O, n) in ((40, 64, 72, 1), (1, 64, 64, 2), (33, 16, 64, 8)):
