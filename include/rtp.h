@@ -185,7 +185,10 @@ typedef struct {
     void *buf_w_dev[2]; /* w_bytes each; [1] unused (may be NULL) when blocking   */
     void *buf_g_dev[2]; /* g_bytes each; [1] used by RTP_DOUBLE_BUFFER only       */
     void *compute_stream; /* hipStream_t */
-    void *stage_stream;   /* hipStream_t, != compute_stream unless blocking       */
+    void *stage_stream;   /* hipStream_t, != compute_stream unless blocking.  The
+                             stage and the auxiliary stream are the ring's alone
+                             from create to destroy: the caller enqueues nothing on
+                             them (a pass relies on finding them as it left them)  */
     void *aux_stream;     /* optional second compute stream (hipStream_t, distinct):
                              the weight-gradient kernels run there, beside the
                              input-gradient kernels, since one shard GEMM seldom fills
