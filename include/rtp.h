@@ -300,6 +300,15 @@ rtp_status rtp_ring_set_ablation(rtp_ring *ring, int rotate, int compute);
  * off.  Idle state only. */
 rtp_status rtp_ring_set_test_delay(rtp_ring *ring, void *scratch32_dev, int64_t stage_us, int64_t aux_us);
 
+/* The same for the compute stream: a bounded spin kernel ahead of every GEMM
+ * on it (`compute_us`, at most 5000; `scratch16_dev`: 16 bytes of device
+ * memory), so that the compute stream runs late against the stage and the
+ * auxiliary stream: a transfer that did not really wait for the kernels
+ * reading its destination, or a weight-gradient kernel that did not wait for
+ * the input-gradient kernel it depends on, shows.  Zero switches it off.
+ * Idle state only. */
+rtp_status rtp_ring_set_test_delay_compute(rtp_ring *ring, void *scratch16_dev, int64_t compute_us);
+
 /* Copies up to `cap` records of what the ring has enqueued since creation
  * (or the last call with clear != 0) and returns the total number recorded.
  * kind: 1 compute-fwd, 2 compute-bwd, 3 weights in, 4 weights out,

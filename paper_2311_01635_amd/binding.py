@@ -108,6 +108,7 @@ SYMBOLS = {
     "rtp_ring_end": (C.c_int, [_P]),
     "rtp_ring_abort": (C.c_int, [_P]),
     "rtp_ring_set_test_delay": (C.c_int, [_P, _P, C.c_int64, C.c_int64]),
+    "rtp_ring_set_test_delay_compute": (C.c_int, [_P, _P, C.c_int64]),
     "rtp_ring_set_ablation": (C.c_int, [_P, C.c_int, C.c_int]),
     "rtp_ring_flush": (C.c_int, [_P]),
     "rtp_ring_zero_grads": (C.c_int, [_P]),

@@ -248,8 +248,8 @@ struct rtp_ring {
     int executed = 0;    // blocking mode: rotations already carried out
     // test aid: a bounded spin kernel ahead of every transfer on the stage stream / every GEMM on the
     // auxiliary stream stretches the windows in which a missing cross-stream wait would show
-    long long delay_stage_ticks = 0, delay_aux_ticks = 0;
-    long long *delay_out = nullptr;
+    long long delay_stage_ticks = 0, delay_aux_ticks = 0, delay_compute_ticks = 0;
+    long long *delay_out = nullptr, *delay_compute_out = nullptr;
     std::vector<rtp_linear *> linears;
     std::vector<rtp_trace_rec> trace;
     hipEvent_t ev_free = nullptr, ev_free2 = nullptr, ev_join = nullptr, ev_aux = nullptr;
@@ -511,6 +511,26 @@ extern "C" rtp_status rtp_ring_set_test_delay(rtp_ring *r, void *scratch32_dev, 
     r->delay_out = (long long *)scratch32_dev;
     r->delay_stage_ticks = stage_us * (int64_t)khz / 1000;
     r->delay_aux_ticks = aux_us * (int64_t)khz / 1000;
+    return RTP_OK;
+}
+
+extern "C" rtp_status rtp_ring_set_test_delay_compute(rtp_ring *r, void *scratch16_dev, int64_t compute_us)
+{
+    if (!r) return fail(RTP_ERR_INVALID, "rtp_ring_set_test_delay_compute: null ring");
+    if (r->pass != RTP_PASS_IDLE) return fail(RTP_ERR_STATE, "rtp_ring_set_test_delay_compute: a pass is open");
+    if (compute_us < 0 || compute_us > 5000)
+        return fail(RTP_ERR_INVALID, "rtp_ring_set_test_delay_compute: the delay is 0 to 5000 microseconds");
+    r->delay_compute_ticks = 0;
+    r->delay_compute_out = nullptr;
+    if (r->dry || compute_us == 0) return RTP_OK;
+    if (!scratch16_dev || ((uintptr_t)scratch16_dev & 7))
+        return fail(RTP_ERR_INVALID, "rtp_ring_set_test_delay_compute: the spin kernels need 16 bytes of 8-byte aligned device memory");
+    int dev = 0, khz = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev));
+    if (khz <= 0) return fail(RTP_ERR_UNSUPPORTED, "rtp_ring_set_test_delay_compute: the device reports no wall clock rate");
+    r->delay_compute_out = (long long *)scratch16_dev;
+    r->delay_compute_ticks = compute_us * (int64_t)khz / 1000;
     return RTP_OK;
 }
 
@@ -938,11 +958,14 @@ static int bwd_act_epi(rtp_act a)
 // epilogue of a result that is summed over the n steps
 static int acc_epi(int step, int n) { return n == 1 ? EPI_STORE : step == 0 ? EPI_ACC_FIRST : step == n - 1 ? EPI_ACC_LAST : EPI_ACC_ADD; }
 
-// test aid (rtp_ring_set_test_delay): hold the auxiliary stream back ahead of a GEMM it is about to run
+// test aid (rtp_ring_set_test_delay, rtp_ring_set_test_delay_compute): hold the auxiliary or the compute stream
+// back ahead of a GEMM it is about to run
 static rtp_status aux_delay(rtp_ring *r, hipStream_t st)
 {
     if (r->delay_aux_ticks > 0 && st == r->as() && r->as() != r->cs())
         HIP_TRY(launch_clock_probe(r->delay_out + 2, r->delay_aux_ticks, st));
+    if (r->delay_compute_ticks > 0 && st == r->cs())
+        HIP_TRY(launch_clock_probe(r->delay_compute_out, r->delay_compute_ticks, st));
     return RTP_OK;
 }
 
