@@ -42,6 +42,12 @@ def build(force: bool = True, verbose: bool = False) -> str:
                 spills = [ln for ln in res.stderr.splitlines() if "ScratchSize" in ln and not ln.rstrip().endswith(": 0 [-Rpass-analysis=kernel-resource-usage]")]
                 if spills:
                     raise RuntimeError(f"{src}: the tiled GEMM kernel spills registers to scratch memory:\n" + "\n".join(spills))
+                # ... and leave room for a wave of the staging copy kernel (96 registers) beside its own two waves on a
+                # SIMD (512 registers): above 208 the copies only run where no GEMM wave sits, and the steps wait for them
+                import re
+                fat = [ln for ln in res.stderr.splitlines() if (m := re.search(r" VGPRs: (\d+)", ln)) and int(m.group(1)) > 208]
+                if fat:
+                    raise RuntimeError(f"{src}: the tiled GEMM kernel uses more than 208 vector registers:\n" + "\n".join(fat))
         return o
 
     with ThreadPoolExecutor(max_workers=8) as ex:

@@ -321,6 +321,40 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
             __builtin_amdgcn_wave_barrier();
         }
     };
+    // The same for an epilogue that READS global memory (an fp32 sum it adds onto, saved pre-activations): the reads
+    // of a fragment row are issued four at a time before the first of their results is stored.  Written load -
+    // compute - store group by group, each read waits behind the previous group's store (the compiler cannot tell
+    // the addresses apart), i.e. 8 x FM memory round trips in a row per tile instead of 2 x FM.  The reads use clamped
+    // coordinates, so that they are legal and unconditional (a vector epilogue has M >= 1 and N >= 4); what they
+    // fetch for a group outside the matrix is not used.
+    auto each_rw = [&](auto load, auto op) {
+        constexpr int DEPTH = 4; // reads in flight per lane: 16 registers (eight at once push the kernel past the
+                                 // register count at which the staging copies' waves still fit beside its own)
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            park(i);
+#pragma unroll
+            for (int r0 = 0; r0 < 8; r0 += DEPTH) {
+                decltype(load(0, 0)) in[DEPTH];
+#pragma unroll
+                for (int r = r0; r < r0 + DEPTH; ++r) {
+                    const int c4 = lane & 15;
+                    const int grow = rbase_wave + i * 32 + 4 * r + (lane >> 4);
+                    const int col = n0 + (c4 >> 3) * NSTRIDE + wn32 + (c4 & 7) * 4;
+                    in[r - r0] = load(min(grow, M - 1), min(col, N - 4));
+                }
+#pragma unroll
+                for (int r = r0; r < r0 + DEPTH; ++r) {
+                    const int row = 4 * r + (lane >> 4), c4 = lane & 15;
+                    const f32x4 x = *(const f32x4 *)(wlds + row * EPI_LDS_PITCH + c4 * 4);
+                    const int grow = rbase_wave + i * 32 + row;
+                    const int col = n0 + (c4 >> 3) * NSTRIDE + wn32 + (c4 & 7) * 4;
+                    if (grow < M && col < N) op(grow, col, x, in[r - r0]);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    };
     switch (p.epi) {
     case EPI_STORE:
         if (p.c_is_f32)
@@ -332,10 +366,8 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
         each([&](int r, int c, f32x4 x) { *(f32x4 *)(ws + (int64_t)r * ldws + c) = x; });
         break;
     case EPI_ACC_ADD:
-        each([&](int r, int c, f32x4 x) {
-            f32x4 *q = (f32x4 *)(ws + (int64_t)r * ldws + c);
-            *q = *q + x;
-        });
+        each_rw([&](int r, int c) { return *(const f32x4 *)(ws + (int64_t)r * ldws + c); },
+                [&](int r, int c, f32x4 x, f32x4 old) { *(f32x4 *)(ws + (int64_t)r * ldws + c) = old + x; });
         break;
     case EPI_ACC_ATOMIC:
         // one float per lane, 32 consecutive lanes on 32 consecutive columns: an atomic instruction
@@ -356,13 +388,11 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
         break;
     case EPI_ACC_LAST:
         if (p.c_is_f32)
-            each([&](int r, int c, f32x4 x) {
-                *(f32x4 *)(Cf + (int64_t)r * ldc + c) = *(const f32x4 *)(ws + (int64_t)r * ldws + c) + x;
-            });
+            each_rw([&](int r, int c) { return *(const f32x4 *)(ws + (int64_t)r * ldws + c); },
+                    [&](int r, int c, f32x4 x, f32x4 old) { *(f32x4 *)(Cf + (int64_t)r * ldc + c) = old + x; });
         else
-            each([&](int r, int c, f32x4 x) {
-                *(out4 *)(Cb + (int64_t)r * ldc + c) = to_elem4<E>(*(const f32x4 *)(ws + (int64_t)r * ldws + c) + x);
-            });
+            each_rw([&](int r, int c) { return *(const f32x4 *)(ws + (int64_t)r * ldws + c); },
+                    [&](int r, int c, f32x4 x, f32x4 old) { *(out4 *)(Cb + (int64_t)r * ldc + c) = to_elem4<E>(old + x); });
         break;
     case EPI_GELU_ERF_FWD:
         each([&](int r, int c, f32x4 x) {
@@ -377,25 +407,33 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
         });
         break;
     case EPI_GELU_ERF_BWD:
-        each([&](int r, int c, f32x4 x) {
-            const f32x4 z = from_elem4<E>(*(const out4 *)(aux + (int64_t)r * ldaux + c));
-            *(out4 *)(Cb + (int64_t)r * ldc + c) = to_elem4<E>(x * map4(z, [](float t) { return gelu_erf_grad(t); }));
-        });
+        each_rw([&](int r, int c) { return *(const out4 *)(aux + (int64_t)r * ldaux + c); },
+                [&](int r, int c, f32x4 x, out4 zz) {
+                    const f32x4 z = from_elem4<E>(zz);
+                    *(out4 *)(Cb + (int64_t)r * ldc + c) = to_elem4<E>(x * map4(z, [](float t) { return gelu_erf_grad(t); }));
+                });
         break;
     case EPI_GELU_TANH_BWD:
-        each([&](int r, int c, f32x4 x) {
-            const f32x4 z = from_elem4<E>(*(const out4 *)(aux + (int64_t)r * ldaux + c));
-            *(out4 *)(Cb + (int64_t)r * ldc + c) = to_elem4<E>(x * map4(z, [](float t) { return gelu_tanh_grad(t); }));
-        });
+        each_rw([&](int r, int c) { return *(const out4 *)(aux + (int64_t)r * ldaux + c); },
+                [&](int r, int c, f32x4 x, out4 zz) {
+                    const f32x4 z = from_elem4<E>(zz);
+                    *(out4 *)(Cb + (int64_t)r * ldc + c) = to_elem4<E>(x * map4(z, [](float t) { return gelu_tanh_grad(t); }));
+                });
         break;
-    case EPI_SWIGLU_BWD:
-        each([&](int r, int c, f32x4 x) {
-            const f32x4 a = from_elem4<E>(*(const out4 *)(aux + (int64_t)r * ldaux + c));
-            const f32x4 b = from_elem4<E>(*(const out4 *)(aux + (int64_t)r * ldaux + half + c));
-            *(out4 *)(Cb + (int64_t)r * ldc + c) = to_elem4<E>(x * b * map4(a, [](float t) { return silu_grad(t); }));
-            *(out4 *)(Cb + (int64_t)r * ldc + half + c) = to_elem4<E>(x * map4(a, [](float t) { return silu(t); }));
-        });
+    case EPI_SWIGLU_BWD: {
+        struct GateUp {
+            out4 a, b;
+        };
+        each_rw([&](int r, int c) {
+                    return GateUp{*(const out4 *)(aux + (int64_t)r * ldaux + c), *(const out4 *)(aux + (int64_t)r * ldaux + half + c)};
+                },
+                [&](int r, int c, f32x4 x, GateUp g) {
+                    const f32x4 a = from_elem4<E>(g.a), b = from_elem4<E>(g.b);
+                    *(out4 *)(Cb + (int64_t)r * ldc + c) = to_elem4<E>(x * b * map4(a, [](float t) { return silu_grad(t); }));
+                    *(out4 *)(Cb + (int64_t)r * ldc + half + c) = to_elem4<E>(x * map4(a, [](float t) { return silu(t); }));
+                });
         break;
+    }
     default:
         break;
     }

@@ -140,7 +140,10 @@ static double makespan(const GemmArgs *a, const int *bm, const int *ks, const in
             left -= cnt[c];
         }
         cnt[0] = left;
-        for (int c = 0; c < 4; ++c)
+        // cheap tiles first: the grid hands tiles out in index order, not longest first, so the tile that starts a
+        // further round is as likely a full one as not; an estimate that kept the cheap ones for last favoured plans
+        // whose last round never comes out that short (a K split that spilled 8 tiles into a second round)
+        for (int c = 3; c >= 0; --c)
             for (long t = 0; t < cnt[c]; ++t) {
                 const double start = free_at.top();
                 free_at.pop();
