@@ -219,6 +219,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, f32x16 (&acc)[F
 // otherwise.  No workgroup barrier: a wave only reads what it wrote.
 constexpr int EPI_LDS_PITCH = 72;                       // floats per staged row (64 columns + pad)
 constexpr int EPI_LDS_BYTES_PER_WAVE = 32 * EPI_LDS_PITCH * 4;
+constexpr int EPI_LAND_ROUNDS = 8;                                   // reads of an fp32 sum in flight per wave ...
+constexpr int EPI_LAND_BYTES_PER_WAVE = EPI_LAND_ROUNDS * 64 * 16;   // ... landing in LDS, 16 bytes per lane each
 
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
@@ -255,7 +257,7 @@ __host__ __device__ inline bool gemm_epilogue_vec_ok(const GemmArgs &p)
 
 template <typename E, int FM, int FN, int NSTRIDE>
 __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (&acc)[FM][FN], float *wlds,
-                                                     int rbase_wave, int n0, int wn32, int lane)
+                                                     int rbase_wave, int n0, int wn32, int lane, char *land = nullptr)
 {
     typedef typename ElemVec<E>::v4 out4; // four consecutive elements of the 16-bit output type
     static_assert(FN == 2, "staging layout is written for two 32-column fragments per wave");
@@ -355,6 +357,44 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
             __builtin_amdgcn_wave_barrier();
         }
     };
+    // The same for the fp32 sum `ws`, read straight into LDS (`land`: EPI_LAND_BYTES_PER_WAVE of the wave's own) instead
+    // of into registers: the eight reads of a fragment row are in flight at once at no register cost, and the reads
+    // of the next fragment row are on their way while this one's accumulators are parked.  Each lane's 16 bytes land
+    // at land + 1024 * round + 16 * lane.  Byte offsets into `ws` are 32-bit: the caller checks the range.
+    auto each_rw_landed = [&](auto op) {
+        typedef __attribute__((address_space(3))) void *lds_vp;
+        const unsigned ws_bytes = __builtin_amdgcn_readfirstlane((unsigned)(((int64_t)(M - 1) * ldws + N) * 4));
+        const __amdgpu_buffer_rsrc_t rws = __builtin_amdgcn_make_buffer_rsrc((void *)ws, 0, ws_bytes, 0x00020000);
+        auto fetch = [&](int i) {
+#pragma unroll
+            for (int r = 0; r < EPI_LAND_ROUNDS; ++r) {
+                const int c4 = lane & 15;
+                const int grow = rbase_wave + i * 32 + 4 * r + (lane >> 4);
+                const int col = n0 + (c4 >> 3) * NSTRIDE + wn32 + (c4 & 7) * 4;
+                const unsigned off = ((unsigned)min(grow, M - 1) * (unsigned)ldws + (unsigned)min(col, N - 4)) * 4u;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rws, (lds_vp)(land + r * 1024), 16, off, 0, 0, 0);
+            }
+        };
+        fetch(0);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            park(i);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this fragment row's reads have landed
+#pragma unroll
+            for (int r = 0; r < EPI_LAND_ROUNDS; ++r) {
+                const int row = 4 * r + (lane >> 4), c4 = lane & 15;
+                const f32x4 x = *(const f32x4 *)(wlds + row * EPI_LDS_PITCH + c4 * 4);
+                const f32x4 old = *(const f32x4 *)(land + r * 1024 + lane * 16);
+                const int grow = rbase_wave + i * 32 + row;
+                const int col = n0 + (c4 >> 3) * NSTRIDE + wn32 + (c4 & 7) * 4;
+                if (grow < M && col < N) op(grow, col, x, old);
+            }
+            __builtin_amdgcn_s_waitcnt(0xc07f); // lgkmcnt(0): the landing area has been read ...
+            __builtin_amdgcn_wave_barrier();
+            if (i + 1 < FM) fetch(i + 1);       // ... before the next reads are sent into it
+        }
+    };
+    const bool landed = land != nullptr && ((int64_t)(M - 1) * ldws + N) * 4 < ((int64_t)1 << 32);
     switch (p.epi) {
     case EPI_STORE:
         if (p.c_is_f32)
@@ -366,8 +406,11 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
         each([&](int r, int c, f32x4 x) { *(f32x4 *)(ws + (int64_t)r * ldws + c) = x; });
         break;
     case EPI_ACC_ADD:
-        each_rw([&](int r, int c) { return *(const f32x4 *)(ws + (int64_t)r * ldws + c); },
-                [&](int r, int c, f32x4 x, f32x4 old) { *(f32x4 *)(ws + (int64_t)r * ldws + c) = old + x; });
+        if (landed)
+            each_rw_landed([&](int r, int c, f32x4 x, f32x4 old) { *(f32x4 *)(ws + (int64_t)r * ldws + c) = old + x; });
+        else
+            each_rw([&](int r, int c) { return *(const f32x4 *)(ws + (int64_t)r * ldws + c); },
+                    [&](int r, int c, f32x4 x, f32x4 old) { *(f32x4 *)(ws + (int64_t)r * ldws + c) = old + x; });
         break;
     case EPI_ACC_ATOMIC:
         // one float per lane, 32 consecutive lanes on 32 consecutive columns: an atomic instruction
@@ -387,7 +430,11 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs &p, f32x16 (
         }
         break;
     case EPI_ACC_LAST:
-        if (p.c_is_f32)
+        if (landed && p.c_is_f32)
+            each_rw_landed([&](int r, int c, f32x4 x, f32x4 old) { *(f32x4 *)(Cf + (int64_t)r * ldc + c) = old + x; });
+        else if (landed)
+            each_rw_landed([&](int r, int c, f32x4 x, f32x4 old) { *(out4 *)(Cb + (int64_t)r * ldc + c) = to_elem4<E>(old + x); });
+        else if (p.c_is_f32)
             each_rw([&](int r, int c) { return *(const f32x4 *)(ws + (int64_t)r * ldws + c); },
                     [&](int r, int c, f32x4 x, f32x4 old) { *(f32x4 *)(Cf + (int64_t)r * ldc + c) = old + x; });
         else

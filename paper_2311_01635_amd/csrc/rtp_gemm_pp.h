@@ -60,7 +60,11 @@ constexpr int WM = 2, WN = 4, NTHR = 512;
 constexpr int FN = BN / (WN * 32);   // 2 fragments of 32 columns per wave
 constexpr int B_BYTES = BN * BK * 2; // 16 KB of B per stage
 constexpr int STAGES = 4; // deeper rings (5 or 6 stages fit the 160 KB LDS) measured no faster
-constexpr int SMEM_BYTES = STAGES * (256 * BK * 2 + B_BYTES); // the tallest tile's ring: 128 KB
+constexpr int RING_BYTES = STAGES * (256 * BK * 2 + B_BYTES); // the tallest tile's ring: 128 KB
+// the epilogue reuses the ring: per wave, one parked fragment row and the landing area of its fp32 reads (136 KB)
+constexpr int EPI_BYTES = NTHR / 64 * (EPI_LDS_BYTES_PER_WAVE + EPI_LAND_BYTES_PER_WAVE);
+constexpr int SMEM_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
+static_assert(SMEM_BYTES <= 160 * 1024, "one workgroup per compute unit: 160 KB of LDS");
 typedef __attribute__((address_space(3))) void *lds_vp;
 // fourth word of a raw buffer descriptor on gfx9-family parts: 32-bit data format, no swizzle, no stride
 constexpr int BUFFER_RSRC_FLAGS = 0x00020000;
@@ -393,7 +397,8 @@ __device__ __forceinline__ void pp_tile(const GemmArgs &p, const int tiles_m, co
 
     if (vec_epilogue)
         gemm_epilogue_staged<E, FM, FN, WN * 32>(p, acc, (float *)(smem + wave * EPI_LDS_BYTES_PER_WAVE),
-                                              m0 + wm * (BM / WM), n0, wn * 32, lane);
+                                              m0 + wm * (BM / WM), n0, wn * 32, lane,
+                                              smem + (pp::NTHR / 64) * EPI_LDS_BYTES_PER_WAVE + wave * EPI_LAND_BYTES_PER_WAVE);
     else
         gemm_epilogue<E, FM, FN, WN * 32>(p, acc, m0 + wm * (BM / WM) + 4 * (lane >> 5), n0, wn * 32 + (lane & 31));
 

@@ -141,6 +141,30 @@ def test_gemm_split_k_accumulate(layout, dtype):
     assert torch.equal(dC.cpu(), ref)
 
 
+def test_gemm_accumulates_onto_a_sum_beyond_32_bit_byte_offsets():
+    """fp32 `C += A B` where C's rows lie 128 MiB apart, 5 GiB from first to last: the tiled kernel reads the sum it
+    adds onto through 32-bit byte offsets where they reach, and through 64-bit addresses where, as here, they do not."""
+    M, N, K, ldc = 40, 64, 64, 1 << 25
+    rng = np.random.default_rng(91)
+    A = wl._store(rng.standard_normal((M, K), dtype=np.float32), "bf16")
+    Bm = wl._store(rng.standard_normal((N, K), dtype=np.float32), "bf16")
+    C0 = rng.standard_normal((M, N), dtype=np.float32)
+    ref = np.zeros((M, N))
+    orc.gemm_nt(f64(A), f64(Bm), ref)
+    ref += f64(C0)
+    big = torch.zeros((M - 1) * ldc + N, device=DEV, dtype=torch.float32)
+    view = torch.as_strided(big, (M, N), (ldc, 1))
+    view.copy_(torch.from_numpy(C0))
+    say(f"gemm NT M={M} N={N} K={K} ldc={ldc} accumulate")
+    B.rtp_gemm(B.LAYOUT_NT, B.RTP_BF16, B.RTP_F32, True, dev(A, torch.bfloat16), K, dev(Bm, torch.bfloat16), K, big, ldc,
+               M, N, K, 4)
+    torch.cuda.synchronize()
+    assert relerr(host(view), ref) <= TOL_F32
+    assert float(big[N:ldc].abs().max()) == 0.0          # nothing written between the rows
+    del big, view
+    torch.cuda.empty_cache()
+
+
 def test_gemm_fp16_needs_the_tiled_kernel():
     a = torch.zeros(64, 72, device=DEV, dtype=torch.float16)
     c = torch.zeros(64, 64, device=DEV, dtype=torch.float32)
