@@ -266,6 +266,16 @@ def algorithmic_bytes_linears(w, unit):
     return total + stg
 
 
+def grad_shard_held(B, unit):
+    """Whether, after a backward pass, a gradient shard is still in the worker's buffer and not in its slot."""
+    if hasattr(unit, "layers"):
+        rings = [l.ring.handle for _, l, *_ in unit.layers]
+    else:
+        get = B.lib.rtp_moe_ring if unit.__class__.__name__ == "RtpMoe" else B.lib.rtp_mlp_ring
+        rings = [get(unit.handle)]
+    return any(B.lib.rtp_ring_resident_grad(h) >= 0 for h in rings)
+
+
 def measured_traffic(workload, layout):
     """HBM bytes per launch of a GEMM kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs whose
     summary is kept under profiles/ (counters cannot be read from inside this process); None if absent."""
@@ -407,15 +417,19 @@ def main():
         hidden = 1.0 - max(0.0, t_b - t_c) / t_s if t_s > 0 else None
         # what the fraction covers: the copies on the stage stream.  Per pass the weights make 2(n-1) rotations (each
         # a copy out to the slot the shard travels to and a copy in from the slot it arrives in; no initial load in a
-        # loop of passes: a backward pass ends on the worker's own shard); the gradient shard comes in n times by copy (n-1 rotations and the first load) and goes out once by
-        # copy (the shard a pass ends on, written back when the next backward pass begins).  Its other n-1 ways OUT
+        # loop of passes: a backward pass ends on the worker's own shard); the gradient shard comes in n times by copy (n-1 rotations and the first load); the shard a pass
+        # ends on is the worker's own and goes to its slot by copy only where the last kernels do not store it there.  Its other n-1 ways OUT
         # are not copies in the timed run: the weight-gradient GEMM that completes a part stores `arriving + own`
         # straight into the slot it travels to (a fused send); the staging-only run, which launches no GEMM, copies.
         n_, W_, G_ = w.n, mlp.w_bytes, mlp.g_bytes
         fused = w.dtype != "f32"                # the fp32 path copies the gradient shard out like the weights
+        # the worker's own shard, on which a backward pass ends, travels no further: it is either stored straight into
+        # its slot by the last step's kernels or left in the buffer and copied there when the next backward pass begins
+        own_by_copy = 1 if grad_shard_held(B, mlp) else 0
         overlap = {"ms_compute_only": t_c, "ms_staging_only": t_s, "ms_both": t_b, "rotation_hidden_frac": hidden,
                    "ms_exposed": max(0.0, t_b - t_c),
-                   "staged_bytes": 4 * (n_ - 1) * W_ + (n_ + 1 if fused else 2 * n_) * G_, "g_out_fused": fused,
+                   "staged_bytes": 4 * (n_ - 1) * W_ + (n_ + own_by_copy if fused else 2 * n_) * G_, "g_out_fused": fused,
+                   "own_grad_shard_written_back_by_copy": bool(own_by_copy),
                    "g_out_bytes_stored_by_gemm_epilogues": (n_ - 1) * G_ if fused else 0,
                    "staging_only_run_bytes": 4 * (n_ - 1) * W_ + 2 * n_ * G_}
 
@@ -441,9 +455,9 @@ def main():
                "unit": "GB/s", "frac": nbytes / (ms_step * 1e-3) / 1e9 / PEAK_HBM_GBS}
     elif not is_moe:
         # staging: every copy reads and writes its bytes; per pass 2(n-1) weight rotations (out + in), the gradient
-        # shard in at the start and per backward rotation (its way out is a GEMM's store, counted above) and out
-        # once by copy (the shard the pass ends on, written back when the next backward pass begins)
-        stg = 2 * 4 * (w.n - 1) * mlp.w_bytes + 2 * (w.n + 1) * mlp.g_bytes
+        # shard in at the start and per backward rotation (its way out is a GEMM's store, counted above) and, where
+        # the last step's kernels leave the worker's own shard in the buffer, out once by copy
+        stg = 2 * 4 * (w.n - 1) * mlp.w_bytes + 2 * (w.n + (1 if grad_shard_held(B, mlp) else 0)) * mlp.g_bytes
         nbytes = algorithmic_bytes(w, stg)
         hbm = {"algorithmic_bytes_per_step": nbytes, "achieved": nbytes / (ms_step * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                "unit": "GB/s", "frac": nbytes / (ms_step * 1e-3) / 1e9 / PEAK_HBM_GBS}

@@ -213,8 +213,8 @@ rtp_status rtp_ring_destroy(rtp_ring *ring);
  * completed forward pass (the worker holds shard (rank+1) mod n) or, with
  * n == 1 or after rtp_ring_seek_bwd_start(), any idle state; loads that shard's
  * gradient part, after writing the gradient shard an earlier backward pass
- * left in the buffer (the worker's own) back to its slot: gradients
- * accumulate over any number of passes.  These two gradient transfers run on
+ * left in the buffer (the worker's own; see rtp_ring_resident_grad) back to
+ * its slot: gradients accumulate over any number of passes.  These two gradient transfers run on
  * the stage stream; only the weight-gradient kernels wait for them.
  * RTP_ERR_STATE if a pass is in progress.
  * Stream capture of a pass is not supported: the calls decide on the host,
@@ -280,6 +280,15 @@ rtp_status rtp_ring_sync(rtp_ring *ring);
 
 /* Shard currently resident (after everything enqueued so far), or -1. */
 int rtp_ring_resident(const rtp_ring *ring);
+
+/* Gradient shard the worker's buffer still holds that is NOT yet in its slot
+ * of the home store (the next backward pass or rtp_ring_flush writes it
+ * back), or -1 when every slot is current.  A backward pass ends on the
+ * worker's own shard (Design section, workflow paragraph), which travels no
+ * further: the MLP unit's default schedule stores `arrived + own` straight
+ * into the own slot and leaves -1; the other schedules, the bare linear
+ * layers and K-split weight-gradient kernels leave the shard in the buffer. */
+int rtp_ring_resident_grad(const rtp_ring *ring);
 
 /* Timing aid (the three-run measurement of how much of the staging hides
  * under compute): `rotate` = 0 skips the transfers (every step computes on the

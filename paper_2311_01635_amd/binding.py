@@ -114,6 +114,7 @@ SYMBOLS = {
     "rtp_ring_zero_grads": (C.c_int, [_P]),
     "rtp_ring_sync": (C.c_int, [_P]),
     "rtp_ring_resident": (C.c_int, [_P]),
+    "rtp_ring_resident_grad": (C.c_int, [_P]),
     "rtp_ring_trace": (C.c_int64, [_P, C.POINTER(rtp_trace_rec), C.c_int64, C.c_int]),
     "rtp_linear_create": (C.c_int, [C.POINTER(_P), _P, C.POINTER(rtp_linear_desc)]),
     "rtp_linear_destroy": (C.c_int, [_P]),
@@ -265,6 +266,9 @@ class Ring:
 
     def resident(self):
         return lib.rtp_ring_resident(self.handle)
+
+    def resident_grad(self):
+        return lib.rtp_ring_resident_grad(self.handle)
 
     def trace(self, clear=False):
         total = lib.rtp_ring_trace(self.handle, None, 0, 0)

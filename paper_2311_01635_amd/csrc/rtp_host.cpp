@@ -473,6 +473,7 @@ extern "C" rtp_status rtp_ring_destroy(rtp_ring *r)
 }
 
 extern "C" int rtp_ring_resident(const rtp_ring *r) { return r ? r->resident : -1; }
+extern "C" int rtp_ring_resident_grad(const rtp_ring *r) { return r && r->d.g_bytes ? r->res_g : -1; }
 
 extern "C" int64_t rtp_ring_trace(rtp_ring *r, rtp_trace_rec *out, int64_t cap, int clear)
 {
@@ -1844,13 +1845,27 @@ static rtp_status mlp_bwd_two_stream(rtp_mlp *m, const void *X, const void *dY, 
     auto gidx = [&](int step) { return rot ? r->g_idx(step) : r->res_g_idx; };
     auto gbuf = [&](int step) { return (char *)r->d.buf_g_dev[gidx(step)]; };
 
+    // The shard of the last step is the worker's own and goes nowhere (Design section, workflow paragraph): its two
+    // kernels store `arrived + own` straight into the shard's slot, and nothing is left in the buffer for the next
+    // backward pass (or a flush) to write back.  Both parts or neither: a write-back of the whole buffer would
+    // overwrite a part that is current in the slot only.
+    bool own_to_slot = false;
+    if (move_g && r->abl_compute && !r->dry) {
+        const int k = r->shard_at(n - 1);
+        GemmArgs a2 = mlp_args_dw2(m, h, k, gbuf(n - 1), dY), a1 = mlp_args_dw1(m, h, k, gbuf(n - 1), X);
+        a1.cu_share = a2.cu_share = 2;
+        int ks1 = 1, ks2 = 1;
+        gemm_bf16_pp_plan(LAY_TN, &a2, 1, nullptr, nullptr, &ks2);
+        gemm_bf16_pp_plan(LAY_TN, &a1, 1, nullptr, nullptr, &ks1);
+        own_to_slot = ks1 == 1 && ks2 == 1;
+    }
     // a weight-gradient kernel; the send of its part of the gradient shard is fused into it when the shard moves on
     // (mark: ev_free2 completes with the kernel, or with the bias sums that follow it, when a transfer waits for it)
     auto emit_dw = [&](int s, GemmArgs a, size_t off, bool first, bool *fused, bool mark) -> rtp_status {
         const bool moves_on = move_g && s <= n - 2;
-        bool fused_send = moves_on && r->abl_compute;
+        bool fused_send = (moves_on && r->abl_compute) || (own_to_slot && s == n - 1);
         a.cu_share = 2; // (before the plan is asked for: the launcher plans with it)
-        if (fused_send) {
+        if (fused_send && moves_on) {
             int ks = 1;
             gemm_bf16_pp_plan(LAY_TN, &a, 1, nullptr, nullptr, &ks);
             if (ks > 1) fused_send = false; // K-split partial sums need the plain `+=` form
@@ -1934,6 +1949,7 @@ static rtp_status mlp_bwd_two_stream(rtp_mlp *m, const void *X, const void *dY, 
         }
     }
     mlp_close_pass(m);
+    if (own_to_slot) r->res_g = -1; // the slot is current
     return rtp_ring_end(r);
 }
 

@@ -507,6 +507,45 @@ def test_weights_written_after_a_flush_are_the_ones_the_next_pass_uses(mode):
     layer.close()
 
 
+@pytest.mark.parametrize("mode", [B.RTP_DOUBLE_BUFFER, B.RTP_INPLACE_STAGED])
+@pytest.mark.parametrize("schedule", ["default", "grouped"])
+def test_own_gradient_shard_reaches_its_slot(schedule, mode):
+    """A backward pass ends on the worker's own shard, which travels no further.  The unit's default schedule has the
+    last step's kernels store `arrived + own` straight into the own slot: the store is current without a flush and
+    the ring holds nothing back.  The grouped schedule leaves the shard in the buffer: the ring says so, and the next
+    backward pass (or a flush) writes it back.  Either way two passes give the oracle's `2 x own + arrived`."""
+    T, I, O, O2, n, rank = 192, 128, 4 * 128, 96, 4, 1
+    w = wl.Workload("own_g", "swiglu", T=T, I=I, O=O, O2=O2, n=n, dtype="bf16", mode="x", w_dist=("normal", 0.08))
+    inp = wl.make_inputs(w, seed=83, grad0=True)
+    names = ("Wg", "Wu", "Wd")
+    ref = orc.rtp_swiglu(f64(inp["X"]), *[f64(inp[k]) for k in names], f64(inp["dY"]), n, rank,
+                         *[f64(inp["G0_" + k]) for k in names])
+    mlp = RtpMlp([dev(inp[k], torch.bfloat16) for k in names], T, n, rank, B.RTP_ACT_SWIGLU, mode, B.RTP_BF16,
+                 G0=[dev(inp["G0_" + k], torch.float32) for k in names], grouped=schedule == "grouped")
+    ring = B.lib.rtp_mlp_ring(mlp.handle)
+    X, dY = dev(inp["X"], torch.bfloat16), dev(inp["dY"], torch.bfloat16)
+    Y = torch.empty(T, O2, device=DEV, dtype=torch.bfloat16)
+    dX = torch.empty(T, I, device=DEV, dtype=torch.bfloat16)
+    for p in (1, 2):
+        say(f"own gradient shard schedule={schedule} mode={mode} pass {p}")
+        mlp.forward(X, Y)
+        mlp.backward(X, dY, dX)
+        mlp.sync()
+        held = B.lib.rtp_ring_resident_grad(ring)
+        assert held == (-1 if schedule == "default" else rank)
+        if held < 0:                                          # no flush: read the store as it is
+            rows = slice(rank * (O // n), (rank + 1) * (O // n))
+            for key, k, g in zip(("dWg", "dWu", "dWd"), names, [mlp.store_g.unpack(nm) for nm in names]):
+                want = p * ref[key] - (p - 1) * f64(inp["G0_" + k])
+                got, want = (host(g)[rows], want[rows]) if k != "Wd" else (host(g)[:, rows], want[:, rows])
+                assert relerr(got, want) <= TOL_BF16, (key, p)
+    _, Gs = mlp.gathered()
+    assert B.lib.rtp_ring_resident_grad(ring) == -1
+    for key, k, g in zip(("dWg", "dWu", "dWd"), names, Gs):
+        assert relerr(host(g), 2.0 * ref[key] - f64(inp["G0_" + k])) <= TOL_BF16, key
+    mlp.close()
+
+
 def test_degenerate_partitions():
     # n = 1 is the plain linear; one token; n equal to the number of 8-wide column groups
     for (T, I, O, n) in ((40, 64, 72, 1), (1, 64, 64, 2), (33, 16, 64, 8)):

@@ -202,13 +202,17 @@ def test_gradient_shard_left_in_the_buffer_goes_home_once(between):
             lin.bwd(s, None, None, None)
         ring.end()
 
+    assert ring.resident_grad() == -1
     one_pass()
     assert [r for r in ring.trace(clear=True) if r[0] == "g_out" and r[2] < 0] == [], "first pass: nothing to write back"
+    assert ring.resident_grad() == rank, "the own shard's gradients are in the buffer, not yet in their slot"
     if between == "flush":
         ring.flush()
         assert [r[3] for r in ring.trace(clear=True) if r[0] == "g_out"] == [rank]
+        assert ring.resident_grad() == -1
     elif between == "zero_grads":
         ring.zero_grads()
+        assert ring.resident_grad() == -1
     one_pass()
     early = [r[3] for r in ring.trace(clear=True) if r[0] == "g_out" and r[2] < 0]
     assert early == ([rank] if between == "nothing" else [])
