@@ -270,9 +270,10 @@ def grad_shard_held(B, unit):
     """Whether, after a backward pass, a gradient shard is still in the worker's buffer and not in its slot."""
     if hasattr(unit, "layers"):
         rings = [l.ring.handle for _, l, *_ in unit.layers]
+    elif hasattr(unit, "moe"):
+        rings = [B.lib.rtp_moe_ring(unit.moe.handle)]
     else:
-        get = B.lib.rtp_moe_ring if unit.__class__.__name__ == "RtpMoe" else B.lib.rtp_mlp_ring
-        rings = [get(unit.handle)]
+        rings = [B.lib.rtp_mlp_ring(unit.handle)]
     return any(B.lib.rtp_ring_resident_grad(h) >= 0 for h in rings)
 
 

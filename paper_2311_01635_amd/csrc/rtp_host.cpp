@@ -2531,6 +2531,7 @@ static rtp_status moe_bwd_pass(rtp_moe *m, const void *dY, void *dX)
 
     RTP_TRY(rtp_ring_begin(r, RTP_PASS_BWD));
     m->next_step = 0;
+    bool own_to_slot = false;
     for (int s = 0; s < n; ++s) {
         if (s < n - 1) RTP_TRY(rtp_rotate_step(r, RTP_CCW, s));
         RTP_TRY(enter_step(r, m->next_step, s, RTP_PASS_BWD, "rtp_moe_bwd"));
@@ -2564,29 +2565,43 @@ static rtp_status moe_bwd_pass(rtp_moe *m, const void *dY, void *dX)
         // back into the buffer; not for a group without tokens (no kernel runs) or when the launcher
         // would cut the contraction into chunks (their partial sums need the plain `+=` form).
         const bool moves_on = rotating && r->d.g_bytes && r->d.mode != RTP_INPLACE_BLOCKING;
+        auto whole_k = [&](const GemmArgs &g) {
+            int ks = 1;
+            if (gemm_bf16_pp_supported(LAY_TN, g)) gemm_bf16_pp_plan(LAY_TN, &g, 1, nullptr, nullptr, &ks);
+            return ks == 1;
+        };
+        const size_t g1_bytes = (size_t)PO * d.I * 4, g2_bytes = (size_t)d.O2 * d.O * 4;
+        // G2_e += dY_e^T H_e and G1_e += dPre_e^T X_e
+        GemmArgs a2, a1;
+        memset(&a2, 0, sizeof a2);
+        a2.A = dYe; a2.lda = d.O2;
+        a2.B = He; a2.ldb = d.O;
+        a2.M = (int)d.O2; a2.N = (int)d.O; a2.K = (int)rows_e;
+        a2.epi = EPI_ACC_ADD; a2.c_is_f32 = 1;
+        a2.ws = G2; a2.ldws = d.O; a2.C = G2; a2.ldc = d.O;
+        a2.cu_share = split ? 2 : 1;
+        memset(&a1, 0, sizeof a1);
+        a1.A = dPe; a1.lda = PO;
+        a1.B = Xe; a1.ldb = d.I;
+        a1.M = (int)PO; a1.N = (int)d.I; a1.K = (int)rows_e;
+        a1.epi = EPI_ACC_ADD; a1.c_is_f32 = 1;
+        a1.ws = G1; a1.ldws = d.I; a1.C = G1; a1.ldc = d.I;
+        a1.cu_share = split ? 2 : 1;
+        // The expert of the last step is the worker's own and goes nowhere (Design section, workflow paragraph): its
+        // kernels store the sum straight into the own slot and nothing stays behind in the buffer.  Both matrices or
+        // neither: a write-back of the whole buffer would overwrite the one that is current in the slot only.
+        const bool stays = s == n - 1 && r->abl_rotate && n > 1 && r->d.g_bytes && r->d.mode != RTP_INPLACE_BLOCKING &&
+                           r->abl_compute && rows_e > 0 && whole_k(a2) && whole_k(a1);
+        own_to_slot = stays;
         auto send_fused = [&](GemmArgs &g, size_t g_off) {
-            if (!moves_on || !r->abl_compute || rows_e <= 0) return false;
-            if (gemm_bf16_pp_supported(LAY_TN, g)) {
-                int ks = 1;
-                gemm_bf16_pp_plan(LAY_TN, &g, 1, nullptr, nullptr, &ks);
-                if (ks > 1) return false;
-            }
+            if (!stays && (!moves_on || !r->abl_compute || rows_e <= 0 || !whole_k(g))) return false;
             g.epi = EPI_ACC_LAST;
             g.C = r->home_g(e) + g_off;
             return true;
         };
-        const size_t g1_bytes = (size_t)PO * d.I * 4, g2_bytes = (size_t)d.O2 * d.O * 4;
         GemmArgs a;
-        // G2_e += dY_e^T H_e
-        memset(&a, 0, sizeof a);
-        a.A = dYe; a.lda = d.O2;
-        a.B = He; a.ldb = d.O;
-        a.M = (int)d.O2; a.N = (int)d.O; a.K = (int)rows_e;
-        a.epi = EPI_ACC_ADD; a.c_is_f32 = 1;
-        a.ws = G2; a.ldws = d.O; a.C = G2; a.ldc = d.O;
-        a.cu_share = split ? 2 : 1;
-        const bool sent2 = send_fused(a, g1_bytes);
-        RTP_TRY(moe_gemm(m, LAY_TN, a, ws));
+        const bool sent2 = send_fused(a2, g1_bytes);
+        RTP_TRY(moe_gemm(m, LAY_TN, a2, ws));
         // dPre_e = (dY_e W2_e) * act'(pre_e)
         memset(&a, 0, sizeof a);
         a.A = dYe; a.lda = d.O2;
@@ -2602,16 +2617,8 @@ static rtp_status moe_bwd_pass(rtp_moe *m, const void *dY, void *dX)
             HIP_TRY(hipEventRecord(m->ev_dpre, cs));
             HIP_TRY(hipStreamWaitEvent(ws, m->ev_dpre, 0));
         }
-        // G1_e += dPre_e^T X_e
-        memset(&a, 0, sizeof a);
-        a.A = dPe; a.lda = PO;
-        a.B = Xe; a.ldb = d.I;
-        a.M = (int)PO; a.N = (int)d.I; a.K = (int)rows_e;
-        a.epi = EPI_ACC_ADD; a.c_is_f32 = 1;
-        a.ws = G1; a.ldws = d.I; a.C = G1; a.ldc = d.I;
-        a.cu_share = split ? 2 : 1;
-        const bool sent1 = send_fused(a, 0);
-        RTP_TRY(moe_gemm(m, LAY_TN, a, ws));
+        const bool sent1 = send_fused(a1, 0);
+        RTP_TRY(moe_gemm(m, LAY_TN, a1, ws));
         // the expert's gradients move on with it: handed to the stage stream once both kernels are done
         if (moves_on) {
             const int ein = rtp_bwd_shard(d.rank, s + 1, n);
@@ -2638,6 +2645,7 @@ static rtp_status moe_bwd_pass(rtp_moe *m, const void *dY, void *dX)
         RTP_TRY(moe_gemm(m, LAY_NN, a, cs));
         m->next_step = s + 1;
     }
+    if (own_to_slot) r->res_g = -1; // the slot is current
     RTP_TRY(rtp_ring_end(r));
     if (r->abl_compute) HIP_TRY(launch_scatter_rows(dX, d.dxp_dev, d.perm_dev, (int)rows, (size_t)d.I * es, cs));
     return RTP_OK;

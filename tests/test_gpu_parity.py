@@ -1102,6 +1102,46 @@ def test_moe_gradients_accumulate_over_passes():
     _check_moe(out, ref, inp, 4, TOL_BF16, passes=2)
 
 
+@pytest.mark.parametrize("mode", [B.RTP_DOUBLE_BUFFER, B.RTP_INPLACE_STAGED, B.RTP_INPLACE_BLOCKING])
+def test_moe_own_experts_gradients_reach_their_slot(mode):
+    """The backward pass ends on the worker's own expert, which travels no further: its weight-gradient kernels store
+    `arrived + own` straight into the own slot (staged modes, an expert with tokens), so the store is current
+    without a flush; the blocking mode leaves the shard in the buffer, and the ring says so."""
+    n, T, rank = 4, 300, 2
+    mi = wl.make_moe_inputs(T, 64, 96, 64, n, seed=87)
+    ex64 = [tuple(f64(m) for m in ex) for ex in mi["experts"]]
+    g64 = [tuple(f64(g) for g in ex) for ex in mi["G0"]]
+    ref = orc.rtp_moe(f64(mi["X"]), mi["route"], ex64, f64(mi["dY"]), n, rank, G0=g64)
+    assert ref["counts"][rank] > 0
+    moe = RtpMoe([tuple(dev(m, torch.bfloat16) for m in ex) for ex in mi["experts"]], T, rank, B.RTP_ACT_GELU_ERF, mode,
+                 G0=[tuple(dev(g, torch.float32) for g in ex) for ex in mi["G0"]])
+    ring = B.lib.rtp_moe_ring(moe.handle)
+    X, dY, route = dev(mi["X"], torch.bfloat16), dev(mi["dY"], torch.bfloat16), dev(mi["route"], torch.int32)
+    Y = torch.empty(T, 64, device=DEV, dtype=torch.bfloat16)
+    dX = torch.empty(T, 64, device=DEV, dtype=torch.bfloat16)
+    for p in (1, 2):
+        say(f"moe own expert mode={mode} pass {p}")
+        moe.forward(X, route, Y)
+        moe.backward(dY, dX)
+        moe.sync()
+        held = B.lib.rtp_ring_resident_grad(ring)
+        assert held == (rank if mode == B.RTP_INPLACE_BLOCKING else -1)
+        if held < 0:                                          # no flush: the store as it is
+            for j, (rows, cols) in enumerate(moe.shapes):
+                got = torch.empty(rows, cols, dtype=torch.float32, device=DEV)
+                B.rtp_unpack_shards(got, moe.home_g.data_ptr() + rank * moe.g_bytes, moe.g_bytes, moe._offsets[j] * 4, 1,
+                                    B.RTP_SPLIT_OUT, rows, cols, rows, B.RTP_F32)
+                torch.cuda.synchronize()
+                want = g64[rank][j] + p * (ref["G"][rank][j] - g64[rank][j])
+                assert relerr(host(got), want) <= TOL_BF16, (j, p)
+    _, Gs = moe.gathered()
+    assert B.lib.rtp_ring_resident_grad(ring) == -1
+    for e in range(n):
+        for j in range(2):
+            assert relerr(host(Gs[e][j]), g64[e][j] + 2 * (ref["G"][e][j] - g64[e][j])) <= TOL_BF16, (e, j)
+    moe.close()
+
+
 def test_moe_rejects_an_expert_id_out_of_range_and_goes_on():
     n, T = 4, 64
     inp = wl.make_moe_inputs(T, 64, 64, 64, n, seed=9)
