@@ -285,9 +285,10 @@ int rtp_ring_resident(const rtp_ring *ring);
  * of the home store (the next backward pass or rtp_ring_flush writes it
  * back), or -1 when every slot is current.  A backward pass ends on the
  * worker's own shard (Design section, workflow paragraph), which travels no
- * further: the MLP unit's default schedule stores `arrived + own` straight
- * into the own slot and leaves -1; the other schedules, the bare linear
- * layers and K-split weight-gradient kernels leave the shard in the buffer. */
+ * further: the MLP unit's default schedule and the expert layer (staged
+ * modes, own expert with tokens) store `arrived + own` straight into the own
+ * slot and leave -1; the other schedules, the bare linear layers and K-split
+ * weight-gradient kernels leave the shard in the buffer. */
 int rtp_ring_resident_grad(const rtp_ring *ring);
 
 /* Timing aid (the three-run measurement of how much of the staging hides
