@@ -87,20 +87,34 @@ class MoeUnit:
 
 class LinearsUnit:
     """One or several independent rotated linear layers (the fp32 single layer; the four d=2048 projections) behind
-    the forward / backward calls of a unit: a pass runs every layer's N-step rotation, one layer after the other."""
+    the forward / backward calls of a unit: a pass runs every layer's N-step rotation."""
 
     def __init__(self, layers, torch):
         self.layers, self.torch = layers, torch            # [(name, RtpLinear, X, dY, Y, dX)]
         self.w_bytes = sum(l.ring.desc.w_bytes for _, l, *_ in layers)
         self.g_bytes = sum(l.ring.desc.g_bytes for _, l, *_ in layers)
 
+    # The layers are independent of one another (own inputs, own streams): each one's pass is enqueued on its own
+    # compute stream, ordered after the caller's stream, and the caller's stream waits for all of them at the end, so
+    # that layers may share the chip (a shard GEMM of a 256-row shard is 64 tiles for 256 compute units).
+    def _each(self, call):
+        torch = self.torch
+        cur = torch.cuda.current_stream()
+        for item in self.layers:
+            s = item[1].compute_stream
+            if s != cur:
+                s.wait_stream(cur)
+            with torch.cuda.stream(s):
+                call(*item)
+        for item in self.layers:
+            if item[1].compute_stream != cur:
+                cur.wait_stream(item[1].compute_stream)
+
     def forward(self, X, Y):
-        for _, l, x, dy, y, dx in self.layers:
-            l.forward(x, y)
+        self._each(lambda _, l, x, dy, y, dx: l.forward(x, y))
 
     def backward(self, X, dY, dX):
-        for _, l, x, dy, y, dx in self.layers:
-            l.backward(x, dy, dx)
+        self._each(lambda _, l, x, dy, y, dx: l.backward(x, dy, dx))
 
     def set_ablation(self, rotate=True, compute=True):
         for _, l, *_ in self.layers:
