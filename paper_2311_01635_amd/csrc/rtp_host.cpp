@@ -301,15 +301,23 @@ static rtp_status ensure_events(rtp_ring *r)
     return RTP_OK;
 }
 
-static rtp_status copy_async(rtp_ring *r, void *dst, const void *src, size_t bytes, hipStream_t s)
+// done: an event recorded on `s` behind the transfer; a copy kernel carries it as its completion signal (one host
+// call and one packet in the queue less than a record of its own).  A dry ring has no events.
+static rtp_status copy_async(rtp_ring *r, void *dst, const void *src, size_t bytes, hipStream_t s, hipEvent_t done = nullptr)
 {
-    if (r->dry || bytes == 0) return RTP_OK;
+    if (r->dry) return RTP_OK;
+    if (bytes == 0) {
+        if (done) HIP_TRY(hipEventRecord(done, s));
+        return RTP_OK;
+    }
     if (r->delay_stage_ticks > 0 && s == r->ss() && r->ss() != r->cs())
         HIP_TRY(launch_clock_probe(r->delay_out, r->delay_stage_ticks, s));
-    if (r->d.flags & RTP_FLAG_STAGE_MEMCPY)
+    if (r->d.flags & RTP_FLAG_STAGE_MEMCPY) {
         HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s));
-    else
-        HIP_TRY(launch_copy(dst, src, bytes, s));
+        if (done) HIP_TRY(hipEventRecord(done, s));
+    } else {
+        HIP_TRY(launch_copy(dst, src, bytes, s, done));
+    }
     return RTP_OK;
 }
 
@@ -326,12 +334,18 @@ struct CopyBatch {
     size_t bytes[COPY_MAX_SEGS];
 };
 
-static rtp_status copy_batch_flush(rtp_ring *r, CopyBatch &b, hipStream_t s)
+static rtp_status copy_batch_flush(rtp_ring *r, CopyBatch &b, hipStream_t s, hipEvent_t done = nullptr)
 {
-    if (b.n == 0) return RTP_OK;
+    if (r->dry) {
+        b.n = 0;
+        return RTP_OK;
+    }
+    if (b.n == 0) {
+        if (done) HIP_TRY(hipEventRecord(done, s));
+        return RTP_OK;
+    }
     const int n = b.n;
     b.n = 0;
-    if (r->dry) return RTP_OK;
     // Large transfers go out one by one, in the order they were added (callers add the transfer a kernel waits for
     // first): beside a GEMM that fills the machine, copies that follow one another disturb it less than the same
     // bytes all at once (Llama-shaped unit: 4.31 against 4.39 ms per pass, expert unit 16.9 against 17.2; the
@@ -339,12 +353,12 @@ static rtp_status copy_batch_flush(rtp_ring *r, CopyBatch &b, hipStream_t s)
     size_t total = 0;
     for (int i = 0; i < n; ++i) total += b.bytes[i];
     if (n == 1 || (r->d.flags & RTP_FLAG_STAGE_MEMCPY) || total >= COPY_BATCH_MAX_BYTES) {
-        for (int i = 0; i < n; ++i) RTP_TRY(copy_async(r, b.dst[i], b.src[i], b.bytes[i], s));
+        for (int i = 0; i < n; ++i) RTP_TRY(copy_async(r, b.dst[i], b.src[i], b.bytes[i], s, i == n - 1 ? done : nullptr));
         return RTP_OK;
     }
     if (r->delay_stage_ticks > 0 && s == r->ss() && r->ss() != r->cs())
         HIP_TRY(launch_clock_probe(r->delay_out, r->delay_stage_ticks, s));
-    HIP_TRY(launch_copy_multi(b.dst, b.src, b.bytes, n, s));
+    HIP_TRY(launch_copy_multi(b.dst, b.src, b.bytes, n, s, done));
     return RTP_OK;
 }
 
@@ -362,17 +376,17 @@ static rtp_status copy_batch_add(rtp_ring *r, CopyBatch &b, void *dst, const voi
 // buffer the held part just left (the in-place exchange): then stream order keeps the two copies apart;
 // otherwise they are one launch.
 static rtp_status rotate_async(rtp_ring *r, void *out, const void *held, void *held_next, const void *in, size_t bytes,
-                               hipStream_t s)
+                               hipStream_t s, hipEvent_t done = nullptr)
 {
     if (held_next == held || out == in) {
         RTP_TRY(copy_async(r, out, held, bytes, s));
-        RTP_TRY(copy_async(r, held_next, in, bytes, s));
+        RTP_TRY(copy_async(r, held_next, in, bytes, s, done));
         return RTP_OK;
     }
     CopyBatch b;
     RTP_TRY(copy_batch_add(r, b, held_next, in, bytes, s)); // the incoming part first: a kernel waits for it
     RTP_TRY(copy_batch_add(r, b, out, held, bytes, s));
-    return copy_batch_flush(r, b, s);
+    return copy_batch_flush(r, b, s, done);
 }
 
 // make each stream wait for everything enqueued so far on the other
@@ -648,26 +662,22 @@ static rtp_status do_rotation(rtp_ring *r, int step)
         RTP_TRY(copy_batch_add(r, b, r->d.buf_w_dev[dst], r->home_w(kin), r->d.w_bytes, s));
         RTP_TRY(copy_batch_add(r, b, r->d.buf_g_dev[gdst], r->home_g(kin), r->d.g_bytes, s));
         RTP_TRY(copy_batch_add(r, b, r->home_w(k), r->d.buf_w_dev[src], r->d.w_bytes, s));
-        RTP_TRY(copy_batch_flush(r, b, s));
+        RTP_TRY(copy_batch_flush(r, b, s, r->ev_w[(step + 1) & 1]));
         r->rec(TR_W_OUT, step, k, src);
         r->rec(TR_W_IN, step, kin, dst);
         r->rec(TR_G_IN, step, kin, gdst);
-        if (!r->dry) {
-            HIP_TRY(hipEventRecord(r->ev_w[(step + 1) & 1], s));
-            HIP_TRY(hipEventRecord(r->ev_g[(step + 1) & 1], s));
-        }
+        if (!r->dry) HIP_TRY(hipEventRecord(r->ev_g[(step + 1) & 1], s));
         return RTP_OK;
     }
-    RTP_TRY(rotate_async(r, r->home_w(k), r->d.buf_w_dev[src], r->d.buf_w_dev[dst], r->home_w(kin), r->d.w_bytes, s));
+    RTP_TRY(rotate_async(r, r->home_w(k), r->d.buf_w_dev[src], r->d.buf_w_dev[dst], r->home_w(kin), r->d.w_bytes, s,
+                         blocking ? nullptr : r->ev_w[(step + 1) & 1]));
     r->rec(TR_W_OUT, step, k, src);
     r->rec(TR_W_IN, step, kin, dst);
-    if (!r->dry && !blocking) HIP_TRY(hipEventRecord(r->ev_w[(step + 1) & 1], s));
     if (bwd && r->d.g_bytes) {
         if (r->d.mode == RTP_DOUBLE_BUFFER) {
             const int gdst = r->g_idx(step + 1);
-            RTP_TRY(copy_async(r, r->d.buf_g_dev[gdst], r->home_g(kin), r->d.g_bytes, s));
+            RTP_TRY(copy_async(r, r->d.buf_g_dev[gdst], r->home_g(kin), r->d.g_bytes, s, r->ev_g[(step + 1) & 1]));
             r->rec(TR_G_IN, step, kin, gdst);
-            if (!r->dry) HIP_TRY(hipEventRecord(r->ev_g[(step + 1) & 1], s));
         } else if (blocking) {
             RTP_TRY(rotate_async(r, r->home_g(k), r->d.buf_g_dev[0], r->d.buf_g_dev[0], r->home_g(kin), r->d.g_bytes, s));
             r->rec(TR_G_OUT, step, k, 0);
@@ -1248,9 +1258,8 @@ extern "C" rtp_status rtp_linear_bwd(rtp_linear *l, int step, const void *X, con
         r->rec(TR_G_OUT, step, k, gi);
         if (staged_g) {
             // in place: the next shard's part comes into the buffer the kernel has just finished with
-            RTP_TRY(copy_async(r, part, r->home_g(kin) + d.g_offset, l->g_shard_bytes, r->ss()));
+            RTP_TRY(copy_async(r, part, r->home_g(kin) + d.g_offset, l->g_shard_bytes, r->ss(), l->ev_g_in));
             r->rec(TR_G_IN, step, kin, gi);
-            if (!r->dry) HIP_TRY(hipEventRecord(l->ev_g_in, r->ss()));
         }
     }
 
@@ -1719,8 +1728,7 @@ static rtp_status mlp_fwd_grouped(rtp_mlp *m, const void *X, void *Y)
                 RTP_TRY(rotate_w_part(r, b, t - 1, r->shard_at(t - 1), r->shard_at(t), r->w_idx(t - 1), r->w_idx(t), h.w_off2, w2_bytes));
             if (move_w1)
                 RTP_TRY(rotate_w_part(r, b, t, r->shard_at(t), r->shard_at(t + 1), r->w_idx(t), r->w_idx(t + 1), 0, w1_bytes));
-            RTP_TRY(copy_batch_flush(r, b, r->ss()));
-            HIP_TRY(hipEventRecord(r->ev_w[(t + 1) & 1], r->ss()));
+            RTP_TRY(copy_batch_flush(r, b, r->ss(), r->ev_w[(t + 1) & 1]));
         }
         GemmArgs g[2];
         int cnt = 0;
@@ -1766,8 +1774,7 @@ static rtp_status mlp_bwd_grouped(rtp_mlp *m, const void *X, const void *dY, voi
             RTP_TRY(stage_after_compute(r));
             CopyBatch b;
             RTP_TRY(rotate_w_part(r, b, s, r->shard_at(s), r->shard_at(s + 1), r->w_idx(s), r->w_idx(s + 1), 0, r->d.w_bytes));
-            RTP_TRY(copy_batch_flush(r, b, r->ss()));
-            HIP_TRY(hipEventRecord(r->ev_w[(s + 1) & 1], r->ss()));
+            RTP_TRY(copy_batch_flush(r, b, r->ss(), r->ev_w[(s + 1) & 1]));
         }
         // ---- weight-gradient launch s = {G1_s, G2_s}, onto the travelling gradient shard ----
         // (on the auxiliary stream when there is one: it only has to follow dPre_s, so it runs
@@ -1806,14 +1813,13 @@ static rtp_status mlp_bwd_grouped(rtp_mlp *m, const void *X, const void *dY, voi
                 CopyBatch b;
                 RTP_TRY(copy_batch_add(r, b, r->d.buf_g_dev[r->g_idx(s + 1)], r->home_g(kin), r->d.g_bytes, r->ss()));
                 if (!fused_send) RTP_TRY(copy_batch_add(r, b, r->home_g(k), r->d.buf_g_dev[r->g_idx(s)], r->d.g_bytes, r->ss()));
-                RTP_TRY(copy_batch_flush(r, b, r->ss()));
+                RTP_TRY(copy_batch_flush(r, b, r->ss(), r->ev_g[(s + 1) & 1]));
             } else {
                 if (!fused_send) RTP_TRY(copy_async(r, r->home_g(k), r->d.buf_g_dev[r->g_idx(s)], r->d.g_bytes, r->ss()));
-                RTP_TRY(copy_async(r, r->d.buf_g_dev[r->g_idx(s + 1)], r->home_g(kin), r->d.g_bytes, r->ss()));
+                RTP_TRY(copy_async(r, r->d.buf_g_dev[r->g_idx(s + 1)], r->home_g(kin), r->d.g_bytes, r->ss(), r->ev_g[(s + 1) & 1]));
             }
             r->rec(TR_G_OUT, s, k, r->g_idx(s));
             r->rec(TR_G_IN, s, kin, r->g_idx(s + 1));
-            HIP_TRY(hipEventRecord(r->ev_g[(s + 1) & 1], r->ss()));
         }
     }
     mlp_close_pass(m);
@@ -1894,10 +1900,9 @@ static rtp_status mlp_bwd_two_stream(rtp_mlp *m, const void *X, const void *dY, 
             if (out_by_copy) RTP_TRY(copy_async(r, r->home_g(k) + off, gbuf(s) + off, bytes, ss));
             RTP_TRY(copy_batch_add(r, b, gbuf(s + 1) + off, r->home_g(kin) + off, bytes, ss));
         }
-        RTP_TRY(copy_batch_flush(r, b, ss));
+        RTP_TRY(copy_batch_flush(r, b, ss, landed));
         if (whole || off != 0) r->rec(TR_G_OUT, s, k, gidx(s));
         if (whole || off != 0) r->rec(TR_G_IN, s, kin, gidx(s + 1));
-        HIP_TRY(hipEventRecord(landed, ss));
         return RTP_OK;
     };
 
@@ -1908,8 +1913,7 @@ static rtp_status mlp_bwd_two_stream(rtp_mlp *m, const void *X, const void *dY, 
             if (s >= 1) HIP_TRY(hipStreamWaitEvent(ss, r->ev_free, 0)); // dX_{s-1} carries ev_free (step 0: rtp_ring_begin has ordered the streams)
             CopyBatch b;
             RTP_TRY(rotate_w_part(r, b, s, k, r->shard_at(s + 1), r->w_idx(s), r->w_idx(s + 1), 0, r->d.w_bytes));
-            RTP_TRY(copy_batch_flush(r, b, ss));
-            HIP_TRY(hipEventRecord(r->ev_w[(s + 1) & 1], ss));
+            RTP_TRY(copy_batch_flush(r, b, ss, r->ev_w[(s + 1) & 1]));
         }
         // ---- input gradients
         if (rot && s >= 1) HIP_TRY(hipStreamWaitEvent(cs, r->ev_w[s & 1], 0));
@@ -1941,10 +1945,9 @@ static rtp_status mlp_bwd_two_stream(rtp_mlp *m, const void *X, const void *dY, 
                 RTP_TRY(copy_batch_add(r, b, gbuf(s + 1), r->home_g(kin), r->d.g_bytes, ss));
                 if (!sent1) RTP_TRY(copy_batch_add(r, b, r->home_g(kk), gbuf(s), g1_bytes, ss));
                 if (!sent2) RTP_TRY(copy_batch_add(r, b, r->home_g(kk) + h.g_off2, gbuf(s) + h.g_off2, g2_bytes, ss));
-                RTP_TRY(copy_batch_flush(r, b, ss));
+                RTP_TRY(copy_batch_flush(r, b, ss, r->ev_g[(s + 1) & 1]));
                 r->rec(TR_G_OUT, s, kk, gidx(s));
                 r->rec(TR_G_IN, s, kin, gidx(s + 1));
-                HIP_TRY(hipEventRecord(r->ev_g[(s + 1) & 1], ss));
             }
         }
     }
@@ -2629,9 +2632,8 @@ static rtp_status moe_bwd_pass(rtp_moe *m, const void *dY, void *dX)
             if (!sent2) RTP_TRY(copy_async(r, r->home_g(e) + g1_bytes, buf + g1_bytes, g2_bytes, r->ss()));
             r->rec(TR_G_OUT, s, e, gi);
             if (staged_g) {
-                RTP_TRY(copy_async(r, r->d.buf_g_dev[gi], r->home_g(ein), r->d.g_bytes, r->ss()));
+                RTP_TRY(copy_async(r, r->d.buf_g_dev[gi], r->home_g(ein), r->d.g_bytes, r->ss(), m->ev_g_in));
                 r->rec(TR_G_IN, s, ein, gi);
-                HIP_TRY(hipEventRecord(m->ev_g_in, r->ss()));
             }
         }
         // dX_e = dPre_e W1_e

@@ -85,10 +85,11 @@ hipError_t launch_act_f32(int kind, const float *pre, int64_t ldpre, const float
                           float *out, int64_t ldout, int rows, int cols, int half, hipStream_t s);
 
 // device-to-device staging copy with a bounded number of workgroups
-hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
+hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s, hipEvent_t done = nullptr);
 // up to COPY_MAX_SEGS copies that do not overlap one another, as one launch (no order among them)
 constexpr int COPY_MAX_SEGS = 4;
-hipError_t launch_copy_multi(void *const *dst, const void *const *src, const size_t *bytes, int count, hipStream_t s);
+hipError_t launch_copy_multi(void *const *dst, const void *const *src, const size_t *bytes, int count, hipStream_t s,
+                             hipEvent_t done = nullptr);
 hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s);
 // shard layout (pack: W -> slots, unpack: slots -> W): slot k's part at home + k * slot_bytes + off holds rows
 // [k w, (k+1) w) of W[O, I] as [w, I] (cols == 0) or columns [k w, (k+1) w) as [O, w] (cols != 0); elements past

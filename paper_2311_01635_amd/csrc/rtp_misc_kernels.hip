@@ -1,6 +1,7 @@
 // fp32 path of the partition GEMM (the small fp32 configuration), the
 // elementwise activation kernels that path uses, and the shard-staging copy.
 #include "rtp_kernels.h"
+#include <hip/hip_ext.h>
 #include <cstring>
 #include <algorithm>
 
@@ -174,15 +175,20 @@ __global__ __launch_bounds__(COPY_THREADS) void copy_kernel(u32x4 *__restrict__ 
     }
 }
 
-hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s)
+// done: an event that completes with the copy (the kernel's completion signal is the event's: no record packet of
+// its own in the queue, and one host call less), or null.  Recorded the plain way when there is nothing to copy.
+hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s, hipEvent_t done)
 {
-
-    if (bytes == 0) return hipSuccess;
+    if (bytes == 0) return done ? hipEventRecord(done, s) : hipSuccess;
     if ((bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return hipErrorInvalidValue;
     const int64_t n16 = (int64_t)(bytes >> 4);
     const int64_t per = COPY_THREADS * COPY_PER_THREAD;
     const unsigned blocks = (unsigned)((n16 + per - 1) / per);
-    hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(COPY_THREADS), 0, s, (u32x4 *)dst, (const u32x4 *)src, n16);
+    if (done)
+        hipExtLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(COPY_THREADS), 0, s, nullptr, done, 0, (u32x4 *)dst,
+                              (const u32x4 *)src, n16);
+    else
+        hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(COPY_THREADS), 0, s, (u32x4 *)dst, (const u32x4 *)src, n16);
     return hipGetLastError();
 }
 
@@ -218,7 +224,8 @@ __global__ __launch_bounds__(COPY_THREADS) void copy_multi_kernel(const CopySegs
     }
 }
 
-hipError_t launch_copy_multi(void *const *dst, const void *const *src, const size_t *bytes, int count, hipStream_t s)
+hipError_t launch_copy_multi(void *const *dst, const void *const *src, const size_t *bytes, int count, hipStream_t s,
+                             hipEvent_t done)
 {
     if (count < 0 || count > COPY_MAX_SEGS) return hipErrorInvalidValue;
     CopySegs g;
@@ -236,10 +243,13 @@ hipError_t launch_copy_multi(void *const *dst, const void *const *src, const siz
         blocks += (unsigned)((n16 + per - 1) / per);
         g.count++;
     }
-    if (g.count == 0) return hipSuccess;
+    if (g.count == 0) return done ? hipEventRecord(done, s) : hipSuccess;
     g.first[g.count] = blocks;
-    if (g.count == 1) return launch_copy(g.dst[0], g.src[0], (size_t)g.n16[0] << 4, s);
-    hipLaunchKernelGGL(copy_multi_kernel, dim3(blocks), dim3(COPY_THREADS), 0, s, g);
+    if (g.count == 1) return launch_copy(g.dst[0], g.src[0], (size_t)g.n16[0] << 4, s, done);
+    if (done)
+        hipExtLaunchKernelGGL(copy_multi_kernel, dim3(blocks), dim3(COPY_THREADS), 0, s, nullptr, done, 0, g);
+    else
+        hipLaunchKernelGGL(copy_multi_kernel, dim3(blocks), dim3(COPY_THREADS), 0, s, g);
     return hipGetLastError();
 }
 
